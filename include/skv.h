@@ -1,0 +1,172 @@
+/*
+ * skv -- routed grouped-query attention over a depth-shared KV cache, for AMD MI355X (gfx950).
+ *
+ * Layer l of a decoder reads the K/V cache of a source layer route[l] <= l (cross-layer
+ * attention, paper Eq. (3.1)); only layers with route[l] == l ("owners", the cache-sharing
+ * strategy S of Sec. 3.1.3) hold a cache slot, so cache memory is proportional to the number
+ * of distinct slots instead of the number of layers.  This library holds the slot cache and
+ * runs the three operations of the paper's inference loop (Alg. 2): the cache update for owner
+ * layers, attention of one new token against the routed slot (sampling phase, Sec. 3.1.1) and
+ * causal attention of many tokens against it (pre-fill phase).
+ *
+ * Conventions
+ *   - C linkage, plain pointers and sizes only.  "host" / "device" on every pointer says where
+ *     the memory lives.  Device pointers are ordinary HIP allocations (for example the storage
+ *     of a PyTorch-ROCm tensor).  `stream` is a hipStream_t passed as void* (NULL = default).
+ *   - Every compute call only ENQUEUES work on `stream`: no synchronisation, no allocation.
+ *     Caller-owned buffers must stay alive until that work has run.
+ *   - Layers, heads, positions and slots are 0-based (the paper counts layers from 1).
+ *   - Query head h reads kv head h / (n_q_heads / n_kv_heads).
+ *   - The query at absolute position p sees cached positions 0..p.
+ *   - Every function returns a status; on any status other than SKV_OK nothing was enqueued
+ *     and the cache is unchanged.  There is no CPU compute path: without a usable HIP device
+ *     the compute calls return SKV_ERR_HIP.
+ *   - Lengths and positions live on the device and cannot be checked by the host without a
+ *     synchronisation.  Kernels never touch memory outside the cache: a position beyond the
+ *     capacity, or a block id outside [0, n_blocks), is skipped and recorded in a per-cache
+ *     fault word (skv_cache_device_faults).
+ *
+ * Cache layout (element type = dtype of the descriptor)
+ *   contiguous (block_size == 0):  K and V pools are [n_slots][batch][max_ctx][n_kv_heads][head_dim]
+ *   paged      (block_size  > 0):  K and V pools are [n_slots][n_blocks][block_size][n_kv_heads][head_dim];
+ *       logical (b, pos) lives in physical block table[b][pos / block_size] at offset
+ *       pos % block_size.  One table serves every slot.
+ */
+#ifndef SKV_H
+#define SKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct skv_cache skv_cache_t; /* opaque, owned by the library */
+
+typedef enum {
+    SKV_OK = 0,
+    SKV_ERR_INVALID_ARG = 1, /* null pointer, negative size, layer out of range, small workspace */
+    SKV_ERR_BAD_ROUTE = 2,   /* route violates 0 <= route[l] <= l or route[route[l]] == route[l] */
+    SKV_ERR_NOT_OWNER = 3,   /* cache update asked for a layer that owns no slot */
+    SKV_ERR_CAPACITY = 4,    /* a host-side length exceeds the cache capacity */
+    SKV_ERR_OOM = 5,         /* device or host allocation failed */
+    SKV_ERR_UNSUPPORTED = 6, /* head_dim / dtype / head grouping / block size not supported */
+    SKV_ERR_HIP = 7          /* a HIP call failed; see skv_last_hip_error */
+} skv_status_t;
+
+typedef enum { SKV_F32 = 0, SKV_F16 = 1, SKV_BF16 = 2 } skv_dtype_t;
+
+/* Bits of the per-cache device fault word. */
+enum {
+    SKV_FAULT_APPEND_RANGE = 1, /* an append row fell outside the capacity and was dropped */
+    SKV_FAULT_BLOCK_ID = 2,     /* a block-table entry was outside [0, n_blocks) */
+    SKV_FAULT_KV_LEN = 4        /* a kv length was < 1, above the hint/capacity, or < q length */
+};
+
+typedef struct {
+    int32_t n_layers;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;  /* must divide n_q_heads; group size n_q_heads / n_kv_heads in {1,2,4,8,16} */
+    int32_t head_dim;    /* 64, 128 or 256 */
+    int32_t batch;       /* number of sequences */
+    int32_t max_ctx;     /* capacity in positions per sequence (contiguous: pool extent;
+                            paged: max_blocks_per_seq * block_size is the effective bound) */
+    int32_t dtype;       /* skv_dtype_t */
+    int32_t block_size;  /* 0 = contiguous, else tokens per physical block (power of two, 8..256) */
+    int32_t n_blocks;    /* paged: physical blocks per slot pool; ignored when contiguous */
+    const int32_t *route; /* host, n_layers entries, copied by skv_cache_alloc */
+    void *k_pool;        /* device, optional caller-owned storage for K; NULL = library allocates */
+    void *v_pool;        /* device, same for V; both or neither */
+    size_t pool_bytes;   /* size of EACH caller pool; must be >= skv_cache_bytes / 2 */
+} skv_cache_desc_t;
+
+/* ---- routing (host only, no device needed) ------------------------------------------------ */
+
+/* Eq. (3.2): route[l] = l if l is in the strategy, else the largest strategy layer below l.
+ * owners: host, n_owners distinct layers in any order.  route_out: host, n_layers.
+ * SKV_ERR_BAD_ROUTE if layer 0 is not an owner (the map is undefined for the layers before the
+ * first owner), or an owner is outside [0, n_layers) or repeated. */
+skv_status_t skv_route_from_strategy(const int32_t *owners, int32_t n_owners, int32_t n_layers,
+                                     int32_t *route_out);
+
+/* Checks a route (any l' <= l that owns a slot is allowed, Eq. (3.1)) and derives the slot map:
+ * slot_of_layer[l] = rank of route[l] among the owners in ascending order.
+ * slot_of_layer (host, n_layers) and n_slots may be NULL. */
+skv_status_t skv_route_validate(const int32_t *route, int32_t n_layers, int32_t *slot_of_layer,
+                                int32_t *n_slots);
+
+/* Total bytes of the K and V pools together:
+ * 2 * n_slots * batch * max_ctx * n_kv_heads * head_dim * sizeof(dtype)   (contiguous)
+ * 2 * n_slots * n_blocks * block_size * n_kv_heads * head_dim * sizeof(dtype)   (paged)
+ * i.e. the footprint M = L x (T + t) x S of Sec. 3.1.1 with L replaced by |S|. */
+skv_status_t skv_cache_bytes(const skv_cache_desc_t *desc, size_t *total_bytes);
+
+/* ---- cache object --------------------------------------------------------------------------- */
+
+/* Validates the descriptor, copies the route, allocates the pools unless the caller gave them,
+ * and zero-fills library-allocated pools.  *out is set only on SKV_OK.  Synchronous. */
+skv_status_t skv_cache_alloc(const skv_cache_desc_t *desc, skv_cache_t **out);
+
+/* Frees the handle and library-allocated pools (never caller pools).  NULL is accepted.
+ * The caller must have synchronised all streams that still use the cache. */
+skv_status_t skv_cache_free(skv_cache_t *cache);
+
+/* Introspection (host values).  Any out pointer may be NULL. */
+skv_status_t skv_cache_info(const skv_cache_t *cache, int32_t *n_slots, void **k_pool_device,
+                            void **v_pool_device, size_t *pool_bytes_each);
+skv_status_t skv_cache_slot_of_layer(const skv_cache_t *cache, int32_t layer, int32_t *slot,
+                                     int32_t *is_owner);
+
+/* Paged caches: borrow the block table, device int32 [batch][max_blocks_per_seq].  Must be set
+ * before the first append / attention call and stay alive while the cache is used. */
+skv_status_t skv_cache_set_block_table(skv_cache_t *cache, const int32_t *table_device,
+                                       int32_t max_blocks_per_seq);
+
+/* Reads and clears the device fault word (synchronises the device). */
+skv_status_t skv_cache_device_faults(skv_cache_t *cache, uint32_t *faults);
+
+/* ---- the three operations of the inference loop (Alg. 2) ----------------------------------- */
+
+/* "Update K_l, V_l", allowed only if layer owns a slot (else SKV_ERR_NOT_OWNER, cache untouched).
+ * k_new, v_new: device [batch][max_new][n_kv_heads][head_dim]; row i < new_lens[b] of sequence b
+ * is written, bit for bit, to position start_pos[b] + i of the layer's slot; other rows are
+ * ignored.  start_pos, new_lens: device int32[batch]. */
+skv_status_t skv_kv_append(skv_cache_t *cache, int32_t layer, const void *k_new, const void *v_new,
+                           const int32_t *start_pos, const int32_t *new_lens, int32_t max_new,
+                           void *stream);
+
+/* Scratch bytes skv_attn_decode needs for sequences of up to max_kv_len positions. */
+skv_status_t skv_decode_workspace_bytes(const skv_cache_t *cache, int32_t max_kv_len, size_t *bytes);
+
+/* Sampling-phase attention, Eq. (3.1) for one query token per sequence:
+ *   out[b][h] = sum_j softmax_j(scale * <q[b][h], K[j]>) V[j],  j < kv_lens[b],
+ * over the slot of route[layer].  q, out: device [batch][n_q_heads][head_dim], dtype of the
+ * cache; fp32 accumulation; out rounded to nearest even.  kv_lens: device int32[batch], each in
+ * [1, max_kv_len]; max_kv_len (host) only sizes the launch and must be >= every kv_lens[b]
+ * (positions beyond it are not read).  workspace: device, >= skv_decode_workspace_bytes. */
+skv_status_t skv_attn_decode(skv_cache_t *cache, int32_t layer, const void *q, void *out,
+                             const int32_t *kv_lens, int32_t max_kv_len, float scale,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
+/* Pre-fill-phase attention: q_lens[b] query rows per sequence; row i sits at absolute position
+ * kv_lens[b] - q_lens[b] + i and sees cached positions 0..that position of the routed slot.
+ * q, out: device [batch][max_q][n_q_heads][head_dim]; rows i >= q_lens[b] are neither read nor
+ * written.  q_lens, kv_lens: device int32[batch], 0 <= q_lens[b] <= min(max_q, kv_lens[b]),
+ * kv_lens[b] <= max_kv_len. */
+skv_status_t skv_attn_prefill(skv_cache_t *cache, int32_t layer, const void *q, void *out,
+                              const int32_t *q_lens, const int32_t *kv_lens, int32_t max_q,
+                              int32_t max_kv_len, float scale, void *stream);
+
+/* ---- diagnostics ---------------------------------------------------------------------------- */
+const char *skv_status_str(skv_status_t status);
+/* Code of the last failing HIP call seen by this thread's skv_* calls (0 = none). */
+int32_t skv_last_hip_error(void);
+/* Name of the kernel the last successful skv_attn_* call on this thread launched (static string),
+ * for profiling scripts that have to find it in a trace. */
+const char *skv_last_kernel_name(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SKV_H */

@@ -1,0 +1,365 @@
+// C ABI of libskv: validation, route -> slot map, sizing, launch configuration.
+// Every entry point is documented in include/skv.h; nothing here computes attention on the host.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "skv_internal.h"
+
+struct skv_cache {
+    skv_cache_desc_t d;          // route pointer inside is not used after alloc
+    std::vector<int32_t> route;  // host copy
+    std::vector<int32_t> slot;   // slot_of_layer
+    int32_t n_slots = 0;
+    void *k_pool = nullptr, *v_pool = nullptr;
+    bool owns_pools = false;
+    size_t pool_bytes_each = 0;
+    size_t slot_bytes = 0;       // bytes of one slot inside a pool
+    const int32_t *block_table = nullptr;
+    int32_t max_blocks_per_seq = 0;
+    int32_t block_shift = 0;
+    uint32_t *faults = nullptr;  // device word
+};
+
+namespace {
+
+thread_local int32_t g_last_hip_error = 0;
+thread_local const char *g_last_kernel = "";
+
+skv_status_t hip_fail(hipError_t e) {
+    g_last_hip_error = (int32_t)e;
+    (void)hipGetLastError(); // clear the sticky per-thread error
+    return e == hipErrorOutOfMemory ? SKV_ERR_OOM : SKV_ERR_HIP;
+}
+
+int elem_bytes(int dtype) { return dtype == SKV_F32 ? 4 : 2; }
+
+int ilog2_exact(int v) {
+    for (int s = 0; s < 31; ++s)
+        if ((1 << s) == v) return s;
+    return -1;
+}
+
+skv_status_t check_desc(const skv_cache_desc_t *d, int32_t *n_slots, std::vector<int32_t> *slot) {
+    if (!d || !d->route) return SKV_ERR_INVALID_ARG;
+    if (d->n_layers <= 0 || d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->batch <= 0 || d->max_ctx <= 0)
+        return SKV_ERR_INVALID_ARG;
+    if (d->dtype != SKV_F32 && d->dtype != SKV_F16 && d->dtype != SKV_BF16) return SKV_ERR_UNSUPPORTED;
+    if (d->head_dim != 64 && d->head_dim != 128 && d->head_dim != 256) return SKV_ERR_UNSUPPORTED;
+    if (d->n_q_heads % d->n_kv_heads) return SKV_ERR_UNSUPPORTED;
+    const int g = d->n_q_heads / d->n_kv_heads;
+    if (g != 1 && g != 2 && g != 4 && g != 8 && g != 16) return SKV_ERR_UNSUPPORTED;
+    if (d->block_size < 0) return SKV_ERR_INVALID_ARG;
+    if (d->block_size > 0) {
+        if (ilog2_exact(d->block_size) < 3 || d->block_size > 256) return SKV_ERR_UNSUPPORTED;
+        if (d->n_blocks <= 0) return SKV_ERR_INVALID_ARG;
+    }
+    if ((d->k_pool == nullptr) != (d->v_pool == nullptr)) return SKV_ERR_INVALID_ARG;
+    std::vector<int32_t> tmp((size_t)d->n_layers);
+    int32_t ns = 0;
+    skv_status_t st = skv_route_validate(d->route, d->n_layers, tmp.data(), &ns);
+    if (st != SKV_OK) return st;
+    if (n_slots) *n_slots = ns;
+    if (slot) slot->swap(tmp);
+    return SKV_OK;
+}
+
+size_t slot_bytes_of(const skv_cache_desc_t *d) {
+    const size_t row = (size_t)d->n_kv_heads * d->head_dim * elem_bytes(d->dtype);
+    const size_t rows = d->block_size > 0 ? (size_t)d->n_blocks * d->block_size
+                                          : (size_t)d->batch * d->max_ctx;
+    return rows * row;
+}
+
+skv::SlotView view_of(const skv_cache *c, int slot) {
+    skv::SlotView v;
+    v.k = (const char *)c->k_pool + (size_t)slot * c->slot_bytes;
+    v.v = (const char *)c->v_pool + (size_t)slot * c->slot_bytes;
+    v.block_table = c->block_table;
+    v.faults = c->faults;
+    v.max_blocks_per_seq = c->max_blocks_per_seq;
+    v.block_shift = c->block_shift;
+    v.n_blocks = c->d.n_blocks;
+    v.max_ctx = c->d.block_size > 0
+                    ? (int32_t)std::min<int64_t>((int64_t)c->max_blocks_per_seq << c->block_shift, INT32_MAX)
+                    : c->d.max_ctx;
+    v.n_kv_heads = c->d.n_kv_heads;
+    v.head_dim = c->d.head_dim;
+    return v;
+}
+
+// Key-axis chunk covered by one work item of the decode kernels.  Deterministic in
+// (batch, n_kv_heads, max_kv_len) so that the workspace size and the launch agree.
+int32_t decode_keys_per_split(const skv_cache *c, int32_t max_kv_len) {
+    const int64_t units = (int64_t)c->d.batch * c->d.n_kv_heads;
+    const int64_t want_items = 256 * 8; // about eight work groups per compute unit
+    const int64_t splits = std::max<int64_t>(1, (want_items + units - 1) / units);
+    int64_t kps = (max_kv_len + splits - 1) / splits;
+    kps = ((kps + 255) / 256) * 256;
+    return (int32_t)std::max<int64_t>(256, kps);
+}
+
+bool paged_ready(const skv_cache *c) { return c->d.block_size == 0 || c->block_table != nullptr; }
+
+} // namespace
+
+namespace skv {
+void set_last_kernel_name(const char *name) { g_last_kernel = name; }
+} // namespace skv
+
+extern "C" {
+
+skv_status_t skv_route_from_strategy(const int32_t *owners, int32_t n_owners, int32_t n_layers,
+                                     int32_t *route_out) {
+    if (!owners || !route_out || n_layers <= 0 || n_owners <= 0) return SKV_ERR_INVALID_ARG;
+    std::vector<char> is_owner((size_t)n_layers, 0);
+    for (int i = 0; i < n_owners; ++i) {
+        if (owners[i] < 0 || owners[i] >= n_layers || is_owner[owners[i]]) return SKV_ERR_BAD_ROUTE;
+        is_owner[owners[i]] = 1;
+    }
+    if (!is_owner[0]) return SKV_ERR_BAD_ROUTE;
+    int32_t last = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        if (is_owner[l]) last = l;
+        route_out[l] = last;
+    }
+    return SKV_OK;
+}
+
+skv_status_t skv_route_validate(const int32_t *route, int32_t n_layers, int32_t *slot_of_layer,
+                                int32_t *n_slots) {
+    if (!route || n_layers <= 0) return SKV_ERR_INVALID_ARG;
+    for (int l = 0; l < n_layers; ++l) {
+        const int32_t r = route[l];
+        if (r < 0 || r > l) return SKV_ERR_BAD_ROUTE;
+        if (route[r] != r) return SKV_ERR_BAD_ROUTE;
+    }
+    std::vector<int32_t> rank((size_t)n_layers, -1);
+    int32_t ns = 0;
+    for (int l = 0; l < n_layers; ++l)
+        if (route[l] == l) rank[l] = ns++;
+    if (slot_of_layer)
+        for (int l = 0; l < n_layers; ++l) slot_of_layer[l] = rank[route[l]];
+    if (n_slots) *n_slots = ns;
+    return SKV_OK;
+}
+
+skv_status_t skv_cache_bytes(const skv_cache_desc_t *desc, size_t *total_bytes) {
+    if (!total_bytes) return SKV_ERR_INVALID_ARG;
+    int32_t ns = 0;
+    skv_status_t st = check_desc(desc, &ns, nullptr);
+    if (st != SKV_OK) return st;
+    *total_bytes = 2 * (size_t)ns * slot_bytes_of(desc);
+    return SKV_OK;
+}
+
+skv_status_t skv_cache_alloc(const skv_cache_desc_t *desc, skv_cache_t **out) {
+    if (!out) return SKV_ERR_INVALID_ARG;
+    int32_t ns = 0;
+    std::vector<int32_t> slot;
+    skv_status_t st = check_desc(desc, &ns, &slot);
+    if (st != SKV_OK) return st;
+    const size_t each = (size_t)ns * slot_bytes_of(desc);
+    if (desc->k_pool && desc->pool_bytes < each) return SKV_ERR_CAPACITY;
+
+    skv_cache *c = new (std::nothrow) skv_cache();
+    if (!c) return SKV_ERR_OOM;
+    c->d = *desc;
+    c->route.assign(desc->route, desc->route + desc->n_layers);
+    c->d.route = nullptr;
+    c->slot.swap(slot);
+    c->n_slots = ns;
+    c->pool_bytes_each = each;
+    c->slot_bytes = slot_bytes_of(desc);
+    c->block_shift = desc->block_size > 0 ? ilog2_exact(desc->block_size) : 0;
+
+    hipError_t e = hipMalloc((void **)&c->faults, 256);
+    if (e == hipSuccess) e = hipMemset(c->faults, 0, 256);
+    if (e != hipSuccess) {
+        if (c->faults) (void)hipFree(c->faults);
+        delete c;
+        return hip_fail(e);
+    }
+    if (desc->k_pool) {
+        c->k_pool = desc->k_pool;
+        c->v_pool = desc->v_pool;
+    } else {
+        c->owns_pools = true;
+        e = hipMalloc(&c->k_pool, each);
+        if (e == hipSuccess) e = hipMalloc(&c->v_pool, each);
+        if (e == hipSuccess) e = hipMemset(c->k_pool, 0, each);
+        if (e == hipSuccess) e = hipMemset(c->v_pool, 0, each);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        if (e != hipSuccess) {
+            if (c->k_pool) (void)hipFree(c->k_pool);
+            if (c->v_pool) (void)hipFree(c->v_pool);
+            (void)hipFree(c->faults);
+            delete c;
+            return hip_fail(e);
+        }
+    }
+    *out = c;
+    return SKV_OK;
+}
+
+skv_status_t skv_cache_free(skv_cache_t *c) {
+    if (!c) return SKV_OK;
+    skv_status_t st = SKV_OK;
+    if (c->owns_pools) {
+        hipError_t e1 = hipFree(c->k_pool), e2 = hipFree(c->v_pool);
+        if (e1 != hipSuccess) st = hip_fail(e1);
+        if (e2 != hipSuccess) st = hip_fail(e2);
+    }
+    hipError_t e = hipFree(c->faults);
+    if (e != hipSuccess) st = hip_fail(e);
+    delete c;
+    return st;
+}
+
+skv_status_t skv_cache_info(const skv_cache_t *c, int32_t *n_slots, void **k_pool, void **v_pool,
+                            size_t *pool_bytes_each) {
+    if (!c) return SKV_ERR_INVALID_ARG;
+    if (n_slots) *n_slots = c->n_slots;
+    if (k_pool) *k_pool = c->k_pool;
+    if (v_pool) *v_pool = c->v_pool;
+    if (pool_bytes_each) *pool_bytes_each = c->pool_bytes_each;
+    return SKV_OK;
+}
+
+skv_status_t skv_cache_slot_of_layer(const skv_cache_t *c, int32_t layer, int32_t *slot, int32_t *is_owner) {
+    if (!c || layer < 0 || layer >= c->d.n_layers) return SKV_ERR_INVALID_ARG;
+    if (slot) *slot = c->slot[layer];
+    if (is_owner) *is_owner = c->route[layer] == layer;
+    return SKV_OK;
+}
+
+skv_status_t skv_cache_set_block_table(skv_cache_t *c, const int32_t *table, int32_t max_blocks_per_seq) {
+    if (!c || !table || max_blocks_per_seq <= 0) return SKV_ERR_INVALID_ARG;
+    if (c->d.block_size == 0) return SKV_ERR_UNSUPPORTED;
+    c->block_table = table;
+    c->max_blocks_per_seq = max_blocks_per_seq;
+    return SKV_OK;
+}
+
+skv_status_t skv_cache_device_faults(skv_cache_t *c, uint32_t *faults) {
+    if (!c || !faults) return SKV_ERR_INVALID_ARG;
+    hipError_t e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipMemcpy(faults, c->faults, sizeof(uint32_t), hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemset(c->faults, 0, sizeof(uint32_t));
+    if (e != hipSuccess) return hip_fail(e);
+    return SKV_OK;
+}
+
+skv_status_t skv_kv_append(skv_cache_t *c, int32_t layer, const void *k_new, const void *v_new,
+                           const int32_t *start_pos, const int32_t *new_lens, int32_t max_new,
+                           void *stream) {
+    if (!c || !k_new || !v_new || !start_pos || !new_lens) return SKV_ERR_INVALID_ARG;
+    if (layer < 0 || layer >= c->d.n_layers || max_new < 0) return SKV_ERR_INVALID_ARG;
+    if (c->route[layer] != layer) return SKV_ERR_NOT_OWNER;
+    if (!paged_ready(c)) return SKV_ERR_INVALID_ARG;
+    if (max_new == 0) return SKV_OK;
+    hipError_t e = skv::launch_append(view_of(c, c->slot[layer]), c->d.dtype, k_new, v_new, start_pos,
+                                      new_lens, c->d.batch, max_new, (hipStream_t)stream);
+    return e == hipSuccess ? SKV_OK : hip_fail(e);
+}
+
+skv_status_t skv_decode_workspace_bytes(const skv_cache_t *c, int32_t max_kv_len, size_t *bytes) {
+    if (!c || !bytes || max_kv_len <= 0) return SKV_ERR_INVALID_ARG;
+    const int32_t kps = decode_keys_per_split(c, max_kv_len);
+    const size_t n_splits = (size_t)(max_kv_len + kps - 1) / kps;
+    *bytes = (size_t)c->d.batch * c->d.n_q_heads * n_splits * (c->d.head_dim + 2) * sizeof(float);
+    return SKV_OK;
+}
+
+skv_status_t skv_attn_decode(skv_cache_t *c, int32_t layer, const void *q, void *out,
+                             const int32_t *kv_lens, int32_t max_kv_len, float scale, void *workspace,
+                             size_t workspace_bytes, void *stream) {
+    if (!c || !q || !out || !kv_lens) return SKV_ERR_INVALID_ARG;
+    if (layer < 0 || layer >= c->d.n_layers || max_kv_len <= 0) return SKV_ERR_INVALID_ARG;
+    if (!paged_ready(c)) return SKV_ERR_INVALID_ARG;
+    const skv::SlotView view = view_of(c, c->slot[layer]);
+    if (max_kv_len > view.max_ctx) return SKV_ERR_CAPACITY;
+    size_t need = 0;
+    skv_decode_workspace_bytes(c, max_kv_len, &need);
+    if (!workspace || workspace_bytes < need) return SKV_ERR_INVALID_ARG;
+
+    skv::AttnArgs a;
+    a.cache = view;
+    a.q = q;
+    a.out = out;
+    a.q_lens = nullptr;
+    a.kv_lens = kv_lens;
+    a.batch = c->d.batch;
+    a.max_q = 1;
+    a.n_q_heads = c->d.n_q_heads;
+    a.max_kv_len = max_kv_len;
+    a.keys_per_split = decode_keys_per_split(c, max_kv_len);
+    a.n_splits = (max_kv_len + a.keys_per_split - 1) / a.keys_per_split;
+    a.scale_log2e = scale * 1.4426950408889634f;
+    a.part_o = (float *)workspace;
+    a.part_ml = a.part_o + (size_t)c->d.batch * c->d.n_q_heads * a.n_splits * c->d.head_dim;
+
+    const int g = c->d.n_q_heads / c->d.n_kv_heads;
+    hipError_t e;
+    if (skv::decode_mfma_supported(c->d.dtype, c->d.head_dim, g))
+        e = skv::launch_decode_mfma(a, c->d.dtype, c->d.head_dim, g, (hipStream_t)stream);
+    else
+        e = skv::launch_attn_valu(a, c->d.dtype, c->d.head_dim, g, (hipStream_t)stream);
+    if (e == hipSuccess && a.n_splits > 1) e = skv::launch_split_merge(a, c->d.dtype, (hipStream_t)stream);
+    return e == hipSuccess ? SKV_OK : hip_fail(e);
+}
+
+skv_status_t skv_attn_prefill(skv_cache_t *c, int32_t layer, const void *q, void *out,
+                              const int32_t *q_lens, const int32_t *kv_lens, int32_t max_q,
+                              int32_t max_kv_len, float scale, void *stream) {
+    if (!c || !q || !out || !q_lens || !kv_lens) return SKV_ERR_INVALID_ARG;
+    if (layer < 0 || layer >= c->d.n_layers || max_q <= 0 || max_kv_len <= 0) return SKV_ERR_INVALID_ARG;
+    if (!paged_ready(c)) return SKV_ERR_INVALID_ARG;
+    const skv::SlotView view = view_of(c, c->slot[layer]);
+    if (max_kv_len > view.max_ctx) return SKV_ERR_CAPACITY;
+
+    skv::AttnArgs a;
+    a.cache = view;
+    a.q = q;
+    a.out = out;
+    a.q_lens = q_lens;
+    a.kv_lens = kv_lens;
+    a.batch = c->d.batch;
+    a.max_q = max_q;
+    a.n_q_heads = c->d.n_q_heads;
+    a.max_kv_len = max_kv_len;
+    a.keys_per_split = max_kv_len; // a prefill row is never split along the key axis
+    a.n_splits = 1;
+    a.scale_log2e = scale * 1.4426950408889634f;
+    a.part_o = nullptr;
+    a.part_ml = nullptr;
+
+    const int g = c->d.n_q_heads / c->d.n_kv_heads;
+    hipError_t e;
+    if (skv::prefill_mfma_supported(c->d.dtype, c->d.head_dim, g))
+        e = skv::launch_prefill_mfma(a, c->d.dtype, c->d.head_dim, g, (hipStream_t)stream);
+    else
+        e = skv::launch_attn_valu(a, c->d.dtype, c->d.head_dim, g, (hipStream_t)stream);
+    return e == hipSuccess ? SKV_OK : hip_fail(e);
+}
+
+const char *skv_status_str(skv_status_t s) {
+    switch (s) {
+    case SKV_OK: return "SKV_OK";
+    case SKV_ERR_INVALID_ARG: return "SKV_ERR_INVALID_ARG";
+    case SKV_ERR_BAD_ROUTE: return "SKV_ERR_BAD_ROUTE";
+    case SKV_ERR_NOT_OWNER: return "SKV_ERR_NOT_OWNER";
+    case SKV_ERR_CAPACITY: return "SKV_ERR_CAPACITY";
+    case SKV_ERR_OOM: return "SKV_ERR_OOM";
+    case SKV_ERR_UNSUPPORTED: return "SKV_ERR_UNSUPPORTED";
+    case SKV_ERR_HIP: return "SKV_ERR_HIP";
+    }
+    return "SKV_ERR_UNKNOWN";
+}
+
+int32_t skv_last_hip_error(void) { return g_last_hip_error; }
+const char *skv_last_kernel_name(void) { return g_last_kernel; }
+
+} // extern "C"

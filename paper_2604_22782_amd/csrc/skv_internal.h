@@ -1,0 +1,68 @@
+// Internal declarations shared by the translation units of libskv (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "skv.h"
+
+namespace skv {
+
+// Where the rows of one cache slot live.  Passed by value to every kernel.
+struct SlotView {
+    const void *k;              // base of the slot inside the K pool
+    const void *v;              // base of the slot inside the V pool
+    const int32_t *block_table; // nullptr = contiguous
+    uint32_t *faults;           // device fault word of the cache
+    int32_t max_blocks_per_seq; // paged
+    int32_t block_shift;        // paged: log2(block_size)
+    int32_t n_blocks;           // paged
+    int32_t max_ctx;            // contiguous: rows per sequence; paged: max_blocks_per_seq << block_shift
+    int32_t n_kv_heads;
+    int32_t head_dim;
+};
+
+// Row number (in units of one [n_kv_heads][head_dim] row) of logical (b, pos) inside the slot,
+// or -1 if a paged lookup hits a block id outside the pool.  pos must be < max_ctx.
+__device__ __forceinline__ int64_t slot_row(const SlotView &c, int b, int pos) {
+    if (c.block_table == nullptr) return (int64_t)b * c.max_ctx + pos;
+    const int blk = c.block_table[(int64_t)b * c.max_blocks_per_seq + (pos >> c.block_shift)];
+    if ((unsigned)blk >= (unsigned)c.n_blocks) return -1;
+    return ((int64_t)blk << c.block_shift) + (pos & ((1 << c.block_shift) - 1));
+}
+
+struct AttnArgs {
+    SlotView cache;
+    const void *q;          // [rows][n_q_heads][head_dim]
+    void *out;              // same
+    const int32_t *q_lens;  // nullptr for decode (one row per sequence)
+    const int32_t *kv_lens; // [batch]
+    float *part_o;          // split partials [rows*n_q_heads][n_splits][head_dim]
+    float *part_ml;         // [rows*n_q_heads][n_splits][2]  (max, sum)
+    int32_t batch;
+    int32_t max_q;          // query rows per sequence in q/out (1 for decode)
+    int32_t n_q_heads;
+    int32_t max_kv_len;     // host bound on kv_lens
+    int32_t keys_per_split; // chunk of the key axis one work item covers
+    int32_t n_splits;       // ceil(max_kv_len / keys_per_split)
+    float scale_log2e;      // softmax scale * log2(e)
+};
+
+// Launchers (each returns the hipError_t of its launch).
+hipError_t launch_append(const SlotView &slot, int dtype, const void *k_new, const void *v_new,
+                         const int32_t *start_pos, const int32_t *new_lens, int batch, int max_new,
+                         hipStream_t stream);
+
+// Generic vector-ALU attention (any dtype; used for fp32 and for shapes the MFMA kernels do not cover).
+hipError_t launch_attn_valu(const AttnArgs &a, int dtype, int head_dim, int group, hipStream_t stream);
+hipError_t launch_split_merge(const AttnArgs &a, int dtype, hipStream_t stream);
+
+// 16-bit MFMA kernels.
+bool decode_mfma_supported(int dtype, int head_dim, int group);
+hipError_t launch_decode_mfma(const AttnArgs &a, int dtype, int head_dim, int group, hipStream_t stream);
+bool prefill_mfma_supported(int dtype, int head_dim, int group);
+hipError_t launch_prefill_mfma(const AttnArgs &a, int dtype, int head_dim, int group, hipStream_t stream);
+
+void set_last_kernel_name(const char *name);
+
+} // namespace skv

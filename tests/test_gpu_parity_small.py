@@ -1,0 +1,176 @@
+"""GPU parity, exhaustive on small workloads: every output element of the HIP path is compared
+with the float64 oracle, and the cache image is compared bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_22782_amd as skv
+from oracle import skv_oracle as O
+from tests import harness as H
+from workloads import configs, gen
+
+pytestmark = pytest.mark.gpu
+
+
+def _small(dtype, n_q_heads, n_kv_heads, head_dim, batch, lens, route, paged=False, seed=77):
+    lens = np.asarray(lens, dtype=np.int32)
+    w = configs.Workload(f"small_{dtype}", dtype, len(route), n_q_heads, n_kv_heads, head_dim, batch,
+                         list(route), lens, 1.0, 1.0 if dtype == "f32" else 0.5, seed=seed)
+    if paged:
+        rng = np.random.default_rng(seed)
+        table, n_blocks = configs._paged(lens, 16, rng)
+        w.block_size, w.block_table, w.n_blocks = 16, table, n_blocks
+        w.max_ctx = table.shape[1] * 16
+    return w
+
+
+def _check_cache_image(cache, w, oc, lens):
+    """Physical K/V pools == the oracle's logical image laid out as the header documents."""
+    k_pool, v_pool = H.pool_tensors(cache, w)
+    for pool, logical in ((k_pool, oc.bits_k), (v_pool, oc.bits_v)):
+        got = pool.numpy().view(logical.dtype)
+        if w.block_size:
+            want = O.paged_image(logical, w.block_table, w.block_size, w.n_blocks, lens)
+            want = want.reshape(got.shape)
+        else:
+            want = logical.reshape(got.shape)
+        assert np.array_equal(got, want)
+
+
+def test_config1_tiny_routed_gqa_f32_prefill_then_decode():
+    """4 layers, route [0,0,2,2]: causal prefill of 128 tokens on every layer (append on the two
+    owners only), then one decode step per layer (owners append position 128 first)."""
+    w = configs.tiny_f32()
+    cache, _ = H.alloc_cache(w)
+    assert skv.skv_cache_info(cache)[0] == 2
+    oc = O.Cache(w.route, w.batch, w.max_ctx, w.n_kv_heads, w.head_dim, np.uint32)
+    T = 128
+    lens_p = np.full(w.batch, T, dtype=np.int32)
+    d_lens_p = torch.from_numpy(lens_p).cuda()
+    zeros = torch.zeros(w.batch, dtype=torch.int32, device="cuda")
+    for layer in range(w.n_layers):
+        if layer in w.owner_layers:
+            k = w.kv_rows("k", layer, 0, w.batch, 0, T, "cuda")
+            v = w.kv_rows("v", layer, 0, w.batch, 0, T, "cuda")
+            skv.skv_kv_append(cache, layer, k, v, zeros, d_lens_p, T)
+            oc.append(layer, gen.to_f64(k), gen.to_f64(v), gen.to_bits(k), gen.to_bits(v), np.zeros(2, int), lens_p)
+        q = w.q_prefill(layer, 0, w.batch, 0, T, "cuda")
+        out = torch.empty_like(q)
+        skv.skv_attn_prefill(cache, layer, q, out, d_lens_p, d_lens_p, T, T, w.scale)
+        want = O.prefill(oc, layer, gen.to_f64(q), lens_p, lens_p, w.scale)
+        assert H.max_abs_err(out, want) <= H.TOL["f32"], layer
+    # one decode step
+    lens_d = np.full(w.batch, T + 1, dtype=np.int32)
+    d_lens_d = torch.from_numpy(lens_d).cuda()
+    ws = H.workspace_for(cache, T + 1)
+    ones = torch.ones(w.batch, dtype=torch.int32, device="cuda")
+    outs = []
+    for layer in range(w.n_layers):
+        if layer in w.owner_layers:
+            k = w.kv_rows("k", layer, 0, w.batch, T, T + 1, "cuda")
+            v = w.kv_rows("v", layer, 0, w.batch, T, T + 1, "cuda")
+            skv.skv_kv_append(cache, layer, k, v, d_lens_p, ones, 1)
+            oc.append(layer, gen.to_f64(k), gen.to_f64(v), gen.to_bits(k), gen.to_bits(v), lens_p, np.ones(2, int))
+        q = w.q_decode(layer, "cuda")
+        out = H.decode_layer(cache, w, layer, q, d_lens_d, T + 1, ws)
+        want = O.decode(oc, layer, gen.to_f64(q), lens_d, w.scale)
+        assert H.max_abs_err(out, want) <= H.TOL["f32"], layer
+        outs.append(out)
+    _check_cache_image(cache, w, oc, lens_d)
+    assert skv.skv_cache_device_faults(cache) == 0
+    # layers that share a slot give identical outputs for identical queries
+    q = w.q_decode(0, "cuda")
+    same = [H.decode_layer(cache, w, l, q, d_lens_d, T + 1, ws).clone() for l in range(4)]
+    assert torch.equal(same[0], same[1]) and torch.equal(same[2], same[3]) and not torch.equal(same[0], same[2])
+
+
+CASES = [
+    # dtype, Hq, Hkv, D, lens, route, paged
+    ("f32", 4, 2, 64, [1, 2, 65, 300], [0, 0, 2, 2], False),
+    ("f32", 8, 1, 128, [257, 33], [0, 1, 1], True),
+    ("f32", 2, 2, 256, [70, 5, 131], [0, 0], False),
+    ("bf16", 32, 8, 128, [1, 17, 640, 1500], [0, 0, 2, 0], False),
+    ("bf16", 8, 2, 128, [513, 31, 1100], [0, 1, 1, 1], True),
+    ("f16", 4, 4, 128, [1200, 64, 1], [0, 0, 0], False),
+    ("f16", 16, 2, 64, [100, 777], [0, 1], True),
+    ("bf16", 16, 1, 64, [2049, 3], [0, 0], False),
+    ("bf16", 4, 2, 256, [300, 45], [0, 0, 2], True),
+]
+
+
+@pytest.mark.parametrize("dtype,hq,hkv,d,lens,route,paged", CASES)
+def test_decode_matches_oracle_exhaustively(dtype, hq, hkv, d, lens, route, paged):
+    w = _small(dtype, hq, hkv, d, len(lens), lens, route, paged)
+    cache, _ = H.alloc_cache(w, caller_pools=True)
+    H.fill_by_append(cache, w, chunk_tokens=w.batch * 500)     # several append chunks
+    oc = H.oracle_cache(w)
+    _check_cache_image(cache, w, oc, w.kv_lens)
+    d_lens = torch.from_numpy(w.kv_lens).cuda()
+    max_len = int(w.kv_lens.max())
+    ws = H.workspace_for(cache, max_len)
+    for layer in range(w.n_layers):
+        q = w.q_decode(layer, "cuda")
+        out = H.decode_layer(cache, w, layer, q, d_lens, max_len, ws)
+        want = O.decode(oc, layer, gen.to_f64(q), w.kv_lens, w.scale)
+        err = H.max_abs_err(out, want)
+        assert err <= H.TOL[dtype], (layer, err)
+    # a single cached position returns its V row exactly
+    for b, n in enumerate(lens):
+        if n == 1:
+            src_slot = oc.slot[w.n_layers - 1]
+            want = np.repeat(oc.vals_v[src_slot, b, 0], w.group, axis=0)
+            assert np.array_equal(gen.to_f64(out[b]), want)
+    assert skv.skv_cache_device_faults(cache) == 0
+
+
+PREFILL_CASES = [
+    # dtype, Hq, Hkv, D, kv_lens, q_lens, route, paged
+    ("f32", 4, 2, 64, [200, 77, 5], [200, 30, 1], [0, 0, 2, 2], False),
+    ("f32", 2, 1, 128, [130, 64], [130, 0], [0, 1], True),
+    ("bf16", 8, 2, 128, [300, 129, 256, 7], [300, 129, 100, 7], [0, 0, 2], False),
+    ("bf16", 32, 8, 128, [260, 515], [260, 131], [0, 0], True),
+    ("f16", 4, 4, 128, [333, 128], [333, 1], [0, 1, 1], False),
+    ("bf16", 4, 1, 64, [400, 63], [400, 63], [0, 0], True),
+    ("f16", 16, 2, 64, [257], [200], [0], False),
+]
+
+
+@pytest.mark.parametrize("dtype,hq,hkv,d,kv_lens,q_lens,route,paged", PREFILL_CASES)
+def test_prefill_matches_oracle_exhaustively(dtype, hq, hkv, d, kv_lens, q_lens, route, paged):
+    w = _small(dtype, hq, hkv, d, len(kv_lens), kv_lens, route, paged, seed=99)
+    cache, _ = H.alloc_cache(w)
+    H.fill_by_append(cache, w)
+    oc = H.oracle_cache(w)
+    max_q, max_kv = max(max(q_lens), 1), int(max(kv_lens))
+    d_q = torch.tensor(q_lens, dtype=torch.int32, device="cuda")
+    d_kv = torch.from_numpy(w.kv_lens).cuda()
+    for layer in range(w.n_layers):
+        q = w.q_prefill(layer, 0, w.batch, 0, max_q, "cuda")
+        out = torch.full_like(q, 7.0)
+        skv.skv_attn_prefill(cache, layer, q, out, d_q, d_kv, max_q, max_kv, w.scale)
+        want = O.prefill(oc, layer, gen.to_f64(q), q_lens, kv_lens, w.scale)
+        got = gen.to_f64(out)
+        for b, nq in enumerate(q_lens):
+            err = float(np.max(np.abs(got[b, :nq] - want[b, :nq]))) if nq else 0.0
+            assert err <= H.TOL[dtype], (layer, b, err)
+            assert (got[b, nq:] == 7.0).all()           # padding rows are not written
+    assert skv.skv_cache_device_faults(cache) == 0
+
+
+def test_decode_equals_last_prefill_row_and_chunked_prefill():
+    w = _small("bf16", 8, 2, 128, 2, [384, 200], [0, 0])
+    cache, _ = H.alloc_cache(w)
+    H.fill_by_append(cache, w)
+    d_kv = torch.from_numpy(w.kv_lens).cuda()
+    q = w.q_prefill(1, 0, 2, 0, 200, "cuda")
+    full = torch.zeros_like(q)
+    d_q = torch.tensor([200, 200], dtype=torch.int32, device="cuda")
+    skv.skv_attn_prefill(cache, 1, q, full, d_q, d_kv, 200, 384, w.scale)
+    ws = H.workspace_for(cache, 384)
+    dec = H.decode_layer(cache, w, 1, q[:, -1].contiguous(), d_kv, 384, ws)
+    assert (dec.float() - full[:, -1].float()).abs().max().item() <= 2e-2
+    # second chunk alone: rows 100..199 are the last 100 positions
+    part = torch.zeros_like(q[:, 100:])
+    d_q2 = torch.tensor([100, 100], dtype=torch.int32, device="cuda")
+    skv.skv_attn_prefill(cache, 1, q[:, 100:].contiguous(), part, d_q2, d_kv, 100, 384, w.scale)
+    assert (part.float() - full[:, 100:].float()).abs().max().item() <= 2e-2
