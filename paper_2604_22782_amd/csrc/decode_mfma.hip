@@ -1,5 +1,306 @@
+// Sampling-phase routed attention for 16-bit caches (paper Eq. (3.1) with one query token per
+// sequence, Sec. 3.1.1 "Sampling"): a split-K flash-decoding kernel for gfx950.
+//
+// The kernel is bound by streaming K and V rows from HBM exactly once.  Work group = 4 waves =
+// one (sequence, kv head, key-axis split); the waves take 32-key tiles round-robin.  Per tile a
+// wave
+//   1. has the tile's K and V rows in registers from coalesced 128-bit global loads issued one
+//      tile ahead (16 lanes cover one 256-byte row, a wave-wide load covers 4 whole rows),
+//   2. parks them in its private LDS region and at once issues the loads of its next tile,
+//   3. S^T[key][head] = K . Q^T on the matrix cores (v_mfma_f32_16x16x32): the G <= 16 query heads
+//      of the GQA group are the 16 columns, so a K/V tile is read once for the whole group and
+//      16-bit data feeds the MFMA without unpacking,
+//   4. online softmax in registers: a lane holds one head (column) and 8 keys; the maximum over
+//      the 32 keys needs two cross-lane steps (lanes l, l^16, l^32, l^48 share a column),
+//   5. O^T[d][head] += V^T . P^T, with V^T read from LDS through the transposing read
+//      ds_read_b64_tr_b16.  The key order inside the contraction is permuted so that the
+//      accumulator layout of step 3 is directly the B-operand layout of this product: the
+//      weights never leave the registers.
+// The four waves merge through LDS; a split writes (max, sum, unnormalised out) in fp32 for the
+// merge launch, a single split writes the normalised output.
 #include "skv_internal.h"
+
 namespace skv {
-bool decode_mfma_supported(int, int, int) { return false; }
-hipError_t launch_decode_mfma(const AttnArgs &, int, int, int, hipStream_t) { return hipErrorNotSupported; }
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+
+struct MBF16 {
+    using vec8 = bf16x8;
+    __device__ static f32x4 mfma(vec8 a, vec8 b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+    __device__ static uint32_t pack2(float lo, float hi) { // round to nearest even
+        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+        bf16x2 v = {(__bf16)lo, (__bf16)hi};
+        return __builtin_bit_cast(uint32_t, v);
+    }
+};
+struct MF16 {
+    using vec8 = f16x8;
+    __device__ static f32x4 mfma(vec8 a, vec8 b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+    }
+    __device__ static uint32_t pack2(float lo, float hi) {
+        typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+        f16x2 v = {(_Float16)lo, (_Float16)hi};
+        return __builtin_bit_cast(uint32_t, v);
+    }
+};
+
+constexpr int kWaves = 4;
+constexpr int kTile = 32; // keys per wave tile
+
+template <int D> struct Geo {
+    static constexpr int LPR = D / 8;            // lanes per 16-bit row (16 bytes each)
+    static constexpr int RPL = 64 / LPR;         // rows per wave-wide load
+    static constexpr int NL = kTile / RPL;       // loads per tile and tensor
+    static constexpr int K_STRIDE = D * 2 + 16;  // LDS row strides in bytes: chosen so that the 16 rows
+    static constexpr int V_STRIDE = D * 2 + 32;  //   one MFMA operand read touches fall in distinct banks
+    static constexpr int K_BYTES = kTile * K_STRIDE;
+    static constexpr int V_BYTES = kTile * V_STRIDE;
+    static constexpr int WAVE_BYTES = K_BYTES + V_BYTES;
+};
+
+__device__ __forceinline__ s16x4 lds_read_tr16(const char *p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(p));
+}
+
+template <typename M, int D>
+__global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a, int G) {
+    using Ge = Geo<D>;
+    using vec8 = typename M::vec8;
+    constexpr int NL = Ge::NL, LPR = Ge::LPR, RPL = Ge::RPL;
+    __shared__ __attribute__((aligned(16))) char lds[kWaves * Ge::WAVE_BYTES];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int n = lane & 15; // MFMA column: query head of the group (B, C operands) / row (A operand)
+    const int g = lane >> 4; // MFMA k-group
+    const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    const int hkv = a.cache.n_kv_heads;
+    const int head0 = kvh * G;
+
+    const int kv_end = a.kv_lens[b];
+    if (kv_end < 1 || kv_end > a.max_kv_len) { // lengths the host promised not to pass
+        if (threadIdx.x == 0 && split == 0 && kvh == 0) atomicOr(a.cache.faults, (uint32_t)SKV_FAULT_KV_LEN);
+        if (split == 0)
+            for (int e = threadIdx.x; e < G * D; e += blockDim.x)
+                ((uint16_t *)a.out)[((int64_t)b * a.n_q_heads + head0) * D + e] = 0;
+        return;
+    }
+    const int k_begin = split * a.keys_per_split;
+    const int k_end = min(kv_end, k_begin + a.keys_per_split);
+    if (k_begin >= k_end) return; // uniform over the work group
+
+    // Q^T as B operand: lane (n, g), k-step s holds Q[head n][32 s + 8 g .. + 8); heads >= G are zero.
+    vec8 qB[D / 32];
+    {
+        const uint16_t *qp = (const uint16_t *)a.q + ((int64_t)b * a.n_q_heads + head0 + n) * D + 8 * g;
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s) {
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (n < G) raw = *(const uint4 *)(qp + 32 * s);
+            qB[s] = __builtin_bit_cast(vec8, raw);
+        }
+    }
+
+    char *ks = lds + wave * Ge::WAVE_BYTES;
+    char *vs = ks + Ge::K_BYTES;
+    const int lrow = lane / LPR;   // row inside one wave-wide load
+    const int lcol = lane % LPR;   // 16-byte piece inside the row
+    const uint16_t *kp = (const uint16_t *)a.cache.k + (int64_t)kvh * D + lcol * 8;
+    const uint16_t *vp = (const uint16_t *)a.cache.v + (int64_t)kvh * D + lcol * 8;
+    const int64_t row_elems = (int64_t)hkv * D;
+
+    // Row numbers of a tile's keys (-1 = key beyond the range, or a bad block id).
+    auto rows_of = [&](int j0, int32_t *rows) {
+#pragma unroll
+        for (int t = 0; t < NL; ++t) {
+            const int key = j0 + RPL * t + lrow;
+            int64_t r = -1;
+            if (key < k_end) {
+                r = slot_row(a.cache, b, key);
+                if (r < 0 && lcol == 0) atomicOr(a.cache.faults, (uint32_t)SKV_FAULT_BLOCK_ID);
+            }
+            rows[t] = (int32_t)r;
+        }
+    };
+    auto issue = [&](const int32_t *rows, uint4 *kr, uint4 *vr) {
+#pragma unroll
+        for (int t = 0; t < NL; ++t) {
+            kr[t] = make_uint4(0, 0, 0, 0);
+            vr[t] = make_uint4(0, 0, 0, 0);
+            if (rows[t] >= 0) {
+                kr[t] = *(const uint4 *)(kp + rows[t] * row_elems);
+                vr[t] = *(const uint4 *)(vp + rows[t] * row_elems);
+            }
+        }
+    };
+
+    float m_run = -INFINITY, l_part = 0.f;
+    f32x4 o[D / 16];
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    uint4 kr[NL], vr[NL];
+    int32_t rows[NL];
+    int j0 = k_begin + wave * kTile;
+    if (j0 < k_end) {
+        rows_of(j0, rows);
+        issue(rows, kr, vr);
+        if (j0 + kWaves * kTile < k_end) rows_of(j0 + kWaves * kTile, rows);
+    }
+
+    for (; j0 < k_end; j0 += kWaves * kTile) {
+        // park the tile in LDS: row-major, 16-byte pieces, padded row stride
+#pragma unroll
+        for (int t = 0; t < NL; ++t) {
+            *(uint4 *)(ks + (RPL * t + lrow) * Ge::K_STRIDE + lcol * 16) = kr[t];
+            *(uint4 *)(vs + (RPL * t + lrow) * Ge::V_STRIDE + lcol * 16) = vr[t];
+        }
+        // the tile is exchanged between the lanes of this wave only: order the LDS traffic for the
+        // compiler (the hardware runs one wave's LDS operations in order)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // loads of the next tile fly while this one is computed; row numbers run one tile further ahead
+        const int jn = j0 + kWaves * kTile;
+        if (jn < k_end) {
+            issue(rows, kr, vr);
+            if (jn + kWaves * kTile < k_end) rows_of(jn + kWaves * kTile, rows);
+        }
+
+        // S^T = K Q^T for keys [j0, j0+16) and [j0+16, j0+32)
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s) {
+            const vec8 a0 = __builtin_bit_cast(vec8, *(const uint4 *)(ks + n * Ge::K_STRIDE + (4 * s + g) * 16));
+            const vec8 a1 = __builtin_bit_cast(vec8, *(const uint4 *)(ks + (16 + n) * Ge::K_STRIDE + (4 * s + g) * 16));
+            s0 = M::mfma(a0, qB[s], s0);
+            s1 = M::mfma(a1, qB[s], s1);
+        }
+        // lane (head n, group g) holds keys j0 + 4g + r (s0) and j0 + 16 + 4g + r (s1); log2 units
+        float sc[8];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            sc[r] = s0[r] * a.scale_log2e;
+            sc[4 + r] = s1[r] * a.scale_log2e;
+        }
+        if (j0 + kTile > k_end) { // ragged tail
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if (j0 + 4 * g + r >= k_end) sc[r] = -INFINITY;
+                if (j0 + 16 + 4 * g + r >= k_end) sc[4 + r] = -INFINITY;
+            }
+        }
+        float mt = sc[0];
+#pragma unroll
+        for (int r = 1; r < 8; ++r) mt = fmaxf(mt, sc[r]);
+        mt = fmaxf(mt, __shfl_xor(mt, 16, 64));
+        mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+        const float m_new = fmaxf(m_run, mt); // finite: every tile holds at least one key
+        const float alpha = exp2f(m_run - m_new);
+        m_run = m_new;
+        float p[8], psum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            p[r] = exp2f(sc[r] - m_new);
+            psum += p[r];
+        }
+        l_part = l_part * alpha + psum;
+        if (__any(alpha != 1.f)) { // the running maximum settles quickly; skip the rescale when it did
+#pragma unroll
+            for (int i = 0; i < D / 16; ++i) o[i] *= alpha;
+        }
+        const uint4 praw = make_uint4(M::pack2(p[0], p[1]), M::pack2(p[2], p[3]), M::pack2(p[4], p[5]),
+                                      M::pack2(p[6], p[7]));
+        const vec8 pB = __builtin_bit_cast(vec8, praw);
+        // O^T[d][head] += V^T P^T; k-slot (g, j) is key 4g + j for j < 4 and 16 + 4g + (j - 4) otherwise
+        const char *v_lo = vs + (4 * g + (n >> 2)) * Ge::V_STRIDE + (n & 3) * 8;
+        const char *v_hi = v_lo + 16 * Ge::V_STRIDE;
+#pragma unroll
+        for (int i = 0; i < D / 16; ++i) {
+            const s16x4 lo = lds_read_tr16(v_lo + i * 32);
+            const s16x4 hi = lds_read_tr16(v_hi + i * 32);
+            const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            o[i] = M::mfma(__builtin_bit_cast(vec8, both), pB, o[i]);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); // reads of this tile before the next tile's writes
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    // ---- merge the four waves through LDS --------------------------------------------------
+    float l_tot = l_part + __shfl_xor(l_part, 16, 64);
+    l_tot += __shfl_xor(l_tot, 32, 64);
+    __syncthreads(); // every wave is done with its tile region
+    float *mo = (float *)lds;                 // [wave][G][D]
+    float *mml = mo + kWaves * 16 * D;        // [wave][16][2]
+    if (n < G) {
+#pragma unroll
+        for (int i = 0; i < D / 16; ++i)
+            *(f32x4 *)(mo + ((wave * G + n) * D + 16 * i + 4 * g)) = o[i];
+        if (g == 0) {
+            mml[(wave * 16 + n) * 2] = m_run;
+            mml[(wave * 16 + n) * 2 + 1] = l_tot;
+        }
+    }
+    __syncthreads();
+    for (int w = threadIdx.x; w < G * (D / 4); w += blockDim.x) {
+        const int h = w / (D / 4), d4 = (w % (D / 4)) * 4;
+        float m = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < kWaves; ++v) m = fmaxf(m, mml[(v * 16 + h) * 2]);
+        float l = 0.f;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int v = 0; v < kWaves; ++v) {
+            const float mv = mml[(v * 16 + h) * 2];
+            const float wv = mv == -INFINITY ? 0.f : exp2f(mv - m);
+            l += mml[(v * 16 + h) * 2 + 1] * wv;
+            acc += *(const f32x4 *)(mo + ((v * G + h) * D + d4)) * wv;
+        }
+        const int64_t rh = (int64_t)b * a.n_q_heads + head0 + h;
+        if (a.n_splits == 1) {
+            const float inv = 1.f / l;
+            *(uint2 *)((uint16_t *)a.out + rh * D + d4) =
+                make_uint2(M::pack2(acc[0] * inv, acc[1] * inv), M::pack2(acc[2] * inv, acc[3] * inv));
+        } else {
+            const int64_t pidx = rh * a.n_splits + split;
+            *(f32x4 *)(a.part_o + pidx * D + d4) = acc;
+            if (d4 == 0) {
+                a.part_ml[pidx * 2] = m;
+                a.part_ml[pidx * 2 + 1] = l;
+            }
+        }
+    }
+}
+
+template <typename M, int D>
+hipError_t launch_d(const AttnArgs &a, int group, hipStream_t stream) {
+    const dim3 grid((unsigned)a.n_splits, (unsigned)a.cache.n_kv_heads, (unsigned)a.batch);
+    decode_mfma_kernel<M, D><<<grid, 64 * kWaves, 0, stream>>>(a, group);
+    set_last_kernel_name("decode_mfma_kernel");
+    return hipGetLastError();
+}
+
+} // namespace
+
+bool decode_mfma_supported(int dtype, int head_dim, int group) {
+    return (dtype == SKV_BF16 || dtype == SKV_F16) && (head_dim == 64 || head_dim == 128) && group <= 16;
+}
+
+hipError_t launch_decode_mfma(const AttnArgs &a, int dtype, int head_dim, int group, hipStream_t stream) {
+    if (a.batch > 65535 || a.cache.n_kv_heads > 65535) return hipErrorInvalidValue;
+    if (dtype == SKV_BF16) {
+        return head_dim == 128 ? launch_d<MBF16, 128>(a, group, stream) : launch_d<MBF16, 64>(a, group, stream);
+    }
+    return head_dim == 128 ? launch_d<MF16, 128>(a, group, stream) : launch_d<MF16, 64>(a, group, stream);
+}
+
 } // namespace skv
