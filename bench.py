@@ -1,0 +1,230 @@
+#!/usr/bin/env python3
+"""Benchmark of the routed-attention hot path on one MI355X.
+
+A "step" is one decode token of the Llama-3-8B-shaped workload (BASELINE config 2): for each of
+the 32 layers, owner layers append the new token's K/V row to their slot (skv_kv_append), then
+every layer attends over the slot it is routed to (skv_attn_decode: split-K kernel + merge).
+`value` is the algorithmic HBM traffic of the step divided by its wall time.  The causal prefill
+workload (BASELINE config 3) is measured after it and reported in the "prefill" object of the
+same JSON line, because the metric names both.
+
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline_decode(w, seconds_budget=12.0):
+    """The float64 oracle, as it stands, on a bounded sample of the decode workload."""
+    import torch
+    from oracle import skv_oracle as O
+    from workloads import gen
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    n_seq = 2
+    lens = w.kv_lens[:n_seq]
+    n = int(lens.max())
+    layer = 1                                   # a routed (non-owner) layer
+    src = O.validate_route(w.route)[layer]
+    cache = O.Cache([0], n_seq, n, w.n_kv_heads, w.head_dim, np.uint16)
+    k = w.kv_rows("k", src, 0, n_seq, 0, n, "cpu")
+    v = w.kv_rows("v", src, 0, n_seq, 0, n, "cpu")
+    cache.append(0, gen.to_f64(k), gen.to_f64(v), gen.to_bits(k), gen.to_bits(v), np.zeros(n_seq, int), lens)
+    q = gen.to_f64(w.q_decode(layer, "cpu")[:n_seq])
+    O.decode(cache, 0, q, lens, w.scale)        # warm
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        O.decode(cache, 0, q, lens, w.scale)
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt > seconds_budget or reps >= 2000:
+            break
+    row = w.n_kv_heads * w.head_dim * w.elem_bytes
+    bytes_per_call = int(lens.sum()) * 2 * row + 2 * n_seq * w.n_q_heads * w.head_dim * w.elem_bytes
+    return {"value": round(bytes_per_call * reps / dt / 1e9, 4), "unit": "GB/s", "cores": int(cores),
+            "kind": "oracle",
+            "sample": f"oracle decode() of 1 routed layer over {n_seq} of {w.batch} sequences x {w.n_q_heads} "
+                      f"heads x {n} keys, repeated {reps}x ({dt:.1f} s); bytes counted as for the GPU (16-bit K/V)"}
+
+
+def run_decode(args, torch, skv, H, configs):
+    w = configs.llama3_decode()
+    log(f"[bench] workload {w.name}: B={w.batch} ctx={int(w.kv_lens[0])} layers={w.n_layers} slots={len(w.owner_layers)}")
+    cache, _ = H.alloc_cache(w)
+    t0 = time.perf_counter()
+    H.fill_by_append(cache, w, lens=w.kv_lens - 1)
+    log(f"[bench] cache of {skv.skv_cache_info(cache)[3] * 2 / 2**30:.1f} GiB filled through skv_kv_append in {time.perf_counter() - t0:.1f} s")
+    ctx = int(w.kv_lens.max())
+    d_lens = torch.from_numpy(w.kv_lens).cuda()
+    d_start = (d_lens - 1).to(torch.int32)
+    ones = torch.ones(w.batch, dtype=torch.int32, device="cuda")
+    ws = H.workspace_for(cache, ctx)
+    qs = [w.q_decode(l, "cuda") for l in range(w.n_layers)]
+    new_k = {l: w.kv_rows("k", l, 0, w.batch, ctx - 1, ctx, "cuda") for l in w.owner_layers}
+    new_v = {l: w.kv_rows("v", l, 0, w.batch, ctx - 1, ctx, "cuda") for l in w.owner_layers}
+    outs = [torch.empty_like(qs[0]) for _ in range(w.n_layers)]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(w.n_layers)]
+
+    def step(timed_events=False):
+        for l in range(w.n_layers):
+            if l in new_k:
+                skv.skv_kv_append(cache, l, new_k[l], new_v[l], d_start, ones, 1)
+            if timed_events:
+                ev[l][0].record()
+            skv.skv_attn_decode(cache, l, qs[l], outs[l], d_lens, ctx, w.scale, ws)
+            if timed_events:
+                ev[l][1].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kernel_name = skv.skv_last_kernel_name()
+    # dominant kernel: events around each layer's decode call (kernel + its small merge launch)
+    per_call = []
+    for _ in range(max(3, min(args.steps, 10))):
+        step(timed_events=True)
+        torch.cuda.synchronize()
+        per_call += [ev[l][0].elapsed_time(ev[l][1]) for l in range(w.n_layers)]
+    call_ms = float(np.mean(per_call))
+    assert skv.skv_cache_device_faults(cache) == 0
+    layer_bytes = w.decode_bytes_per_layer()
+    append_bytes = len(w.owner_layers) * 2 * 2 * w.batch * w.n_kv_heads * w.head_dim * w.elem_bytes
+    step_bytes = layer_bytes * w.n_layers + append_bytes
+    ms_per_step = dt / args.steps * 1e3
+    value = step_bytes / (dt / args.steps) / 1e9
+    achieved = layer_bytes / (call_ms * 1e-3) / 1e9
+    res = {
+        "value": round(value, 1), "ms_per_step": round(ms_per_step, 4),
+        "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "launch_us": round(call_ms * 1e3, 2), "algorithmic_bytes_per_launch": layer_bytes},
+        "workload": w,
+    }
+    cache.free()
+    del ws, qs, outs
+    torch.cuda.empty_cache()
+    return res
+
+
+def run_prefill(args, torch, skv, H, configs):
+    w = configs.llama3_prefill()
+    S = int(w.kv_lens.max())
+    log(f"[bench] workload {w.name}: B={w.batch} S={S} layers={w.n_layers} slots={len(w.owner_layers)}")
+    cache, _ = H.alloc_cache(w)
+    d_lens = torch.from_numpy(w.kv_lens).cuda()
+    zeros = torch.zeros(w.batch, dtype=torch.int32, device="cuda")
+    # two query/output buffers are rotated over the layers (a full set would be 16 GiB)
+    q = [w.q_prefill(l, 0, w.batch, 0, S, "cuda") for l in range(2)]
+    out = [torch.empty_like(q[0]) for _ in range(2)]
+    k_new = {l: w.kv_rows("k", l, 0, w.batch, 0, S, "cuda") for l in w.owner_layers[:2]}
+    v_new = {l: w.kv_rows("v", l, 0, w.batch, 0, S, "cuda") for l in w.owner_layers[:2]}
+    owner_src = w.owner_layers[:2]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(w.n_layers)]
+
+    def step(timed_events=False):
+        for l in range(w.n_layers):
+            if w.route[l] == l:   # owner: append its K/V rows of all prompt tokens
+                src = owner_src[(l // 4) % 2]
+                skv.skv_kv_append(cache, l, k_new[src], v_new[src], zeros, d_lens, S)
+            if timed_events:
+                ev[l][0].record()
+            skv.skv_attn_prefill(cache, l, q[l % 2], out[l % 2], d_lens, d_lens, S, S, w.scale)
+            if timed_events:
+                ev[l][1].record()
+
+    steps = max(1, args.steps // 10)
+    step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    step(timed_events=True)
+    torch.cuda.synchronize()
+    call_ms = float(np.mean([ev[l][0].elapsed_time(ev[l][1]) for l in range(w.n_layers)]))
+    assert skv.skv_cache_device_faults(cache) == 0
+    flops = w.prefill_flops_per_layer()
+    tflops_kernel = flops / (call_ms * 1e-3) / 1e12
+    tflops_step = flops * w.n_layers / dt / 1e12
+    res = {"workload": w.name, "config": {"batch": w.batch, "seq_len": S, "layers": w.n_layers,
+                                           "slots": len(w.owner_layers), "dtype": w.dtype},
+           "steps": steps, "ms_per_step": round(dt * 1e3, 3), "value": round(tflops_step, 1), "unit": "TFLOP/s",
+           "roofline": {"bound": "mfma", "kernel": skv.skv_last_kernel_name(), "achieved": round(tflops_kernel, 1),
+                        "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(tflops_kernel / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                        "launch_us": round(call_ms * 1e3, 1), "algorithmic_flops_per_launch": flops}}
+    cache.free()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--skip-prefill", action="store_true")
+    ap.add_argument("--skip-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1")
+        sys.exit(2)
+
+    import torch
+    import paper_2604_22782_amd as skv
+    from workloads import driver as H
+    from workloads import configs
+
+    if not torch.cuda.is_available():
+        log("bench.py needs a GPU: the hot path has no CPU fallback")
+        sys.exit(3)
+    skv.lib()
+
+    dec = run_decode(args, torch, skv, H, configs)
+    w = dec.pop("workload")
+    line = {
+        "metric": "routed decode attn HBM GB/s (% of peak) + prefill MFMA util %, 1 MI355X",
+        "value": dec["value"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dec["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "context": int(w.kv_lens.max()), "layers": w.n_layers,
+                   "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
+                   "route": "route[l]=l-(l%2)", "slots": len(w.owner_layers), "step": "append(owner)+decode per layer"},
+        "pct_of_hbm_peak": round(100 * dec["value"] / HBM_PEAK_GBS, 2),
+        "roofline": dec["roofline"],
+    }
+    if not args.skip_prefill:
+        line["prefill"] = run_prefill(args, torch, skv, H, configs)
+    if not args.skip_cpu_baseline:
+        log("[bench] timing the CPU oracle on a bounded sample ...")
+        line["cpu_baseline"] = cpu_baseline_decode(w)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()
