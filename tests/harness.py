@@ -32,8 +32,8 @@ def oracle_kv_rows(w, layer, b, kvh, n):
     """float64 K[n][D], V[n][D] that `layer` reads for sequence b, kv head kvh: the rows its
     source layer (per the oracle's routing) produced."""
     src = O.validate_route(w.route)[layer]
-    k = w.kv_rows("k", src, b, b + 1, 0, n, "cpu")[0, :, kvh]
-    v = w.kv_rows("v", src, b, b + 1, 0, n, "cpu")[0, :, kvh]
+    k = w.kv_rows("k", src, b, b + 1, 0, n, "cpu", kv_head=kvh)[0]
+    v = w.kv_rows("v", src, b, b + 1, 0, n, "cpu", kv_head=kvh)[0]
     return gen.to_f64(k), gen.to_f64(v)
 
 

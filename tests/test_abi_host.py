@@ -1,0 +1,118 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+and its routing / sizing / validation agree with the oracle and the paper's printed numbers.
+No compute call is made (there is no GPU here)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2604_22782_amd as skv
+from oracle import skv_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = os.path.join(ROOT, "tests", "golden")
+
+
+def _rows(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        return [l.split() for l in f if l.strip() and not l.startswith("#")]
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "skv.h")).read()
+    declared = set(re.findall(r"\b(skv_[a-z_]+)\s*\(", header))
+    assert len(declared) >= 16
+    lib = skv.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == {n for n in skv.__all__ if n.startswith("skv_")}   # binding uses the same names
+
+
+def test_status_strings():
+    for code, name in skv.STATUS.items():
+        assert skv.skv_status_str(code) == name
+
+
+def test_route_from_strategy_matches_eq_3_2_and_oracle():
+    assert skv.skv_route_from_strategy([0, 2], 5) == [0, 0, 2, 2, 2]          # Fig. 4, 0-based
+    rng = np.random.default_rng(1)
+    for _ in range(200):
+        L = int(rng.integers(1, 40))
+        S = [0] + [l for l in range(1, L) if rng.random() < 0.5]
+        rng.shuffle(S)
+        route = skv.skv_route_from_strategy(S, L)
+        assert route == O.mu(S, L)
+        slots, n = skv.skv_route_validate(route)
+        assert slots == O.slot_of_layer(route) and n == len(S)
+    for bad in ([1, 3], [0, 0], [0, 7]):
+        with pytest.raises(skv.SkvError) as e:
+            skv.skv_route_from_strategy(bad, 5)
+        assert e.value.status == 2
+
+
+def test_route_validate_accepts_non_monotone_and_rejects_bad():
+    assert skv.skv_route_validate([0, 1, 0, 1, 4]) == ([0, 1, 0, 1, 2], 3)
+    for bad in ([1], [0, 2], [0, 0, 1], [0, -1]):
+        with pytest.raises(skv.SkvError) as e:
+            skv.skv_route_validate(bad)
+        assert e.value.status == 2, bad
+
+
+def _desc(**kw):
+    d = dict(n_layers=4, n_q_heads=4, n_kv_heads=2, head_dim=64, batch=2, max_ctx=128, dtype=skv.SKV_F32,
+             route=[0, 0, 2, 2])
+    d.update(kw)
+    return d
+
+
+def test_cache_bytes_reproduces_the_papers_numbers():
+    for model, L, hkv, d, e, kb in _rows("kv_bytes_per_token.txt"):
+        L, hkv, d = int(L), int(hkv), int(d)
+        got = skv.skv_cache_bytes(n_layers=L, n_q_heads=hkv, n_kv_heads=hkv, head_dim=d, batch=1, max_ctx=1,
+                                  dtype=skv.SKV_F16, route=list(range(L)))
+        assert got == int(kb) * 1024, model
+    for T, g, mb in _rows("table4_kv_cache_mb.txt"):
+        T, g = int(T), int(g)
+        got = skv.skv_cache_bytes(n_layers=36, n_q_heads=32, n_kv_heads=8, head_dim=128, batch=1,
+                                  max_ctx=T + 128, dtype=skv.SKV_BF16, route=[l - l % g for l in range(36)])
+        assert abs(got / 2 ** 20 - int(mb)) <= 0.5 + 1e-9
+    for B, g, mb in _rows("table5_kv_cache_mb.txt"):
+        B, g = int(B), int(g)
+        got = skv.skv_cache_bytes(n_layers=36, n_q_heads=32, n_kv_heads=8, head_dim=128, batch=B,
+                                  max_ctx=8192 + 63, dtype=skv.SKV_BF16, route=[l - l % g for l in range(36)])
+        assert abs(got / 2 ** 20 - int(mb)) <= 0.5 + 1e-9
+    # config 1: two slots, 512 KiB; paged sizing counts blocks
+    assert skv.skv_cache_bytes(**_desc()) == 512 * 1024 == O.cache_bytes(2, 2, 128, 2, 64, 4)
+    assert skv.skv_cache_bytes(**_desc(block_size=16, n_blocks=10)) == 2 * 2 * 10 * 16 * 2 * 64 * 4
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(route=[0, 0, 1, 1]), 2), (dict(n_q_heads=5), 6), (dict(head_dim=80), 6), (dict(dtype=9), 6),
+    (dict(n_q_heads=6, n_kv_heads=2), 6), (dict(batch=0), 1), (dict(max_ctx=-1), 1),
+    (dict(block_size=12, n_blocks=4), 6), (dict(block_size=16, n_blocks=0), 1), (dict(route=None), 1),
+])
+def test_descriptor_validation(kw, status):
+    with pytest.raises(skv.SkvError) as e:
+        skv.skv_cache_bytes(**_desc(**kw))
+    assert e.value.status == status
+    with pytest.raises(skv.SkvError) as e:
+        skv.skv_cache_alloc(**_desc(**kw))
+    assert e.value.status == status
+
+
+def test_null_handles_and_no_device_behaviour():
+    lib = skv.lib()
+    assert lib.skv_cache_free(None) == 0
+    assert lib.skv_cache_info(None, None, None, None, None) == 1
+    assert lib.skv_kv_append(None, 0, None, None, None, None, 1, None) == 1
+    assert lib.skv_attn_decode(None, 0, None, None, None, 1, ctypes.c_float(1.0), None, 0, None) == 1
+    assert lib.skv_attn_prefill(None, 0, None, None, None, None, 1, 1, ctypes.c_float(1.0), None) == 1
+    assert lib.skv_cache_bytes(None, None) == 1
+    import torch
+    if not torch.cuda.is_available():
+        # without a device there is no compute path: allocation reports the HIP failure
+        with pytest.raises(skv.SkvError) as e:
+            skv.skv_cache_alloc(**_desc())
+        assert e.value.status == 7 and skv.skv_last_hip_error() != 0

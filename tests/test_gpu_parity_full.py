@@ -1,0 +1,108 @@
+"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py
+times.  The caches (16-64 GB) are generated on the device; the oracle recomputes, one by one, a
+seeded sample of (layer, sequence, head[, query row]) outputs from host-regenerated rows."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_22782_amd as skv
+from oracle import skv_oracle as O
+from tests import harness as H
+from workloads import configs, gen
+
+pytestmark = pytest.mark.gpu
+
+
+def _decode_sampled(w, seqs_per_layer, heads_per_seq, must_seqs=()):
+    print(f"\n{w.name}: B={w.batch} layers={w.n_layers} slots={len(w.owner_layers)} "
+          f"sum(len)={int(w.kv_lens.sum())}", flush=True)
+    cache, _ = H.alloc_cache(w)
+    H.fill_by_append(cache, w, lens=w.kv_lens - 1)
+    max_len = int(w.kv_lens.max())
+    d_lens = torch.from_numpy(w.kv_lens).cuda()
+    d_start = (d_lens - 1).to(torch.int32)
+    ones = torch.ones(w.batch, dtype=torch.int32, device="cuda")
+    ws = H.workspace_for(cache, max_len)
+    rng = np.random.default_rng(w.seed)
+    G = w.group
+    worst = 0.0
+    prev = {}
+    for layer in range(w.n_layers):
+        if layer in w.owner_layers:       # the decode step appends the newest position first
+            k = torch.cat([w.kv_rows("k", layer, b, b + 1, int(w.kv_lens[b]) - 1, int(w.kv_lens[b]), "cuda")
+                           for b in range(w.batch)])
+            v = torch.cat([w.kv_rows("v", layer, b, b + 1, int(w.kv_lens[b]) - 1, int(w.kv_lens[b]), "cuda")
+                           for b in range(w.batch)])
+            skv.skv_kv_append(cache, layer, k, v, d_start, ones, 1)
+        q = w.q_decode(layer, "cuda")
+        out = H.decode_layer(cache, w, layer, q, d_lens, max_len, ws)
+        qh, oh = gen.to_f64(q), gen.to_f64(out)
+        seqs = list(must_seqs) + rng.choice(w.batch, seqs_per_layer, replace=False).tolist()
+        for b in seqs:
+            n = int(w.kv_lens[b])
+            for h in rng.choice(w.n_q_heads, heads_per_seq, replace=False).tolist():
+                K, V = H.oracle_kv_rows(w, layer, b, h // G, n)
+                want = O.attn_one(qh[b, h], K, V, w.scale)
+                worst = max(worst, float(np.abs(oh[b, h] - want).max()))
+        # a layer that shares its slot with the previous layer gives, for the same query, the same bits
+        src = w.route[layer]
+        if src in prev:
+            again = H.decode_layer(cache, w, layer, prev[src][0], d_lens, max_len, ws)
+            assert torch.equal(again, prev[src][1]), layer
+        else:
+            prev[src] = (q, out)
+    assert skv.skv_cache_device_faults(cache) == 0
+    assert skv.skv_last_kernel_name() == "decode_mfma_kernel"
+    print(f"{w.name}: worst sampled |err| = {worst:.3e}", flush=True)
+    assert worst <= H.TOL[w.dtype]
+    cache.free()
+
+
+def test_config2_llama3_decode_bf16_full_size():
+    _decode_sampled(configs.llama3_decode(), seqs_per_layer=2, heads_per_seq=3)
+
+
+def test_config4_qwen3_paged_ragged_decode_full_size():
+    w = configs.qwen3_paged_decode()
+    shortest, longest = int(np.argmin(w.kv_lens)), int(np.argmax(w.kv_lens))
+    _decode_sampled(w, seqs_per_layer=1, heads_per_seq=2, must_seqs=(shortest, longest))
+
+
+def test_config5_llama2_mha_decode_f16_batch32():
+    _decode_sampled(configs.llama2_mha_decode(batch=32), seqs_per_layer=1, heads_per_seq=3)
+
+
+def test_config3_llama3_prefill_bf16_full_size():
+    w = configs.llama3_prefill()
+    S = int(w.kv_lens.max())
+    cache, _ = H.alloc_cache(w)
+    d_lens = torch.from_numpy(w.kv_lens).cuda()
+    zeros = torch.zeros(w.batch, dtype=torch.int32, device="cuda")
+    rng = np.random.default_rng(w.seed)
+    fixed_rows = [0, 1, 31, 32, 63, 64, 255, 256, 257, 4095, 4096, S - 257, S - 1]
+    worst = 0.0
+    for layer in range(w.n_layers):
+        if layer in w.owner_layers:      # only the 8 owner layers write K/V
+            k = w.kv_rows("k", layer, 0, w.batch, 0, S, "cuda")
+            v = w.kv_rows("v", layer, 0, w.batch, 0, S, "cuda")
+            skv.skv_kv_append(cache, layer, k, v, zeros, d_lens, S)
+            del k, v
+        q = w.q_prefill(layer, 0, w.batch, 0, S, "cuda")
+        out = torch.empty_like(q)
+        skv.skv_attn_prefill(cache, layer, q, out, d_lens, d_lens, S, S, w.scale)
+        if layer % 5 not in (0, 3):      # sample 13 of the 32 layers (owners and readers)
+            continue
+        b = int(rng.integers(w.batch))
+        for h in rng.choice(w.n_q_heads, 2, replace=False).tolist():
+            K, V = H.oracle_kv_rows(w, layer, b, h // w.group, S)
+            rows = fixed_rows + rng.integers(0, S, 8).tolist()
+            qh = gen.to_f64(q[b, rows, h])
+            oh = gen.to_f64(out[b, rows, h])
+            for i, r in enumerate(rows):
+                want = O.attn_one(qh[i], K[: r + 1], V[: r + 1], w.scale)
+                worst = max(worst, float(np.abs(oh[i] - want).max()))
+        print(f"layer {layer}: worst so far {worst:.3e}", flush=True)
+    assert skv.skv_cache_device_faults(cache) == 0
+    assert skv.skv_last_kernel_name() == "prefill_mfma_kernel"
+    assert worst <= H.TOL["bf16"]
+    cache.free()

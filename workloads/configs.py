@@ -78,17 +78,27 @@ class Workload:
         return 4 * self.n_q_heads * self.head_dim * pairs
 
     # ---- seeded tensors --------------------------------------------------------------------
-    def kv_rows(self, which: str, layer: int, b0: int, b1: int, p0: int, p1: int, device) -> torch.Tensor:
-        """K or V rows that layer `layer` produces for sequences [b0,b1), positions [p0,p1):
-        tensor [b1-b0][p1-p0][kv_heads][head_dim]."""
+    def kv_rows(self, which: str, layer: int, b0: int, b1: int, p0: int, p1: int, device,
+                kv_head: int | None = None, seqs=None) -> torch.Tensor:
+        """K or V rows that layer `layer` produces for sequences [b0,b1) (or the explicit list
+        `seqs`), positions [p0,p1): tensor [n_seq][p1-p0][kv_heads][head_dim], or
+        [n_seq][p1-p0][head_dim] for one kv head."""
         stream = STREAM_K if which == "k" else STREAM_V
         hd = self.n_kv_heads * self.head_dim
-        b = torch.arange(b0, b1, dtype=torch.int64, device=device)[:, None, None]
+        if seqs is None:
+            b = torch.arange(b0, b1, dtype=torch.int64, device=device)[:, None, None]
+        else:
+            b = torch.as_tensor(seqs, dtype=torch.int64, device=device)[:, None, None]
         p = torch.arange(p0, p1, dtype=torch.int64, device=device)[None, :, None]
-        r = torch.arange(hd, dtype=torch.int64, device=device)[None, None, :]
+        if kv_head is None:
+            r = torch.arange(hd, dtype=torch.int64, device=device)[None, None, :]
+        else:
+            r = kv_head * self.head_dim + torch.arange(self.head_dim, dtype=torch.int64, device=device)[None, None, :]
         idx = ((layer * self.batch + b) * self.max_ctx + p) * hd + r
         x = gen.normal(idx, self.seed, stream, self.sigma_kv, self.torch_dtype)
-        return x.view(b1 - b0, p1 - p0, self.n_kv_heads, self.head_dim)
+        if kv_head is not None:
+            return x
+        return x.view(b.shape[0], p1 - p0, self.n_kv_heads, self.head_dim)
 
     def q_decode(self, layer: int, device) -> torch.Tensor:
         """[batch][q_heads][head_dim] query of the newest token at layer `layer`."""

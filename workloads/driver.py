@@ -43,20 +43,30 @@ def pool_tensors(cache, w):
     return [o.view(view).view(shape) for o in outs]
 
 
-def fill_by_append(cache, w, lens=None, chunk_tokens=1 << 22, device="cuda"):
-    """Append positions [0, lens[b]) of every owner layer, generated on the device in chunks."""
+def fill_by_append(cache, w, lens=None, chunk_tokens=1 << 19, device="cuda"):
+    """Append positions [0, lens[b]) of every owner layer, generated on the device in chunks of
+    positions; sequences that already ended are neither generated nor appended."""
     lens = w.kv_lens if lens is None else np.asarray(lens, dtype=np.int32)
     max_len = int(lens.max())
     d_lens = torch.from_numpy(lens.astype(np.int32)).to(device)
     step = max(1, min(max_len, chunk_tokens // w.batch))
+    shape = (w.batch, step, w.n_kv_heads, w.head_dim)
+    kbuf = torch.zeros(shape, dtype=w.torch_dtype, device=device)
+    vbuf = torch.zeros(shape, dtype=w.torch_dtype, device=device)
     for layer in w.owner_layers:
         for p0 in range(0, max_len, step):
             p1 = min(max_len, p0 + step)
-            k = w.kv_rows("k", layer, 0, w.batch, p0, p1, device)
-            v = w.kv_rows("v", layer, 0, w.batch, p0, p1, device)
+            active = np.nonzero(lens > p0)[0]
+            if len(active) == w.batch:
+                kbuf[:, : p1 - p0] = w.kv_rows("k", layer, 0, w.batch, p0, p1, device)
+                vbuf[:, : p1 - p0] = w.kv_rows("v", layer, 0, w.batch, p0, p1, device)
+            else:
+                idx = torch.from_numpy(active).to(device)
+                kbuf[idx, : p1 - p0] = w.kv_rows("k", layer, 0, 0, p0, p1, device, seqs=active)
+                vbuf[idx, : p1 - p0] = w.kv_rows("v", layer, 0, 0, p0, p1, device, seqs=active)
             start = torch.full((w.batch,), p0, dtype=torch.int32, device=device)
             new = (d_lens - p0).clamp(0, p1 - p0).to(torch.int32)
-            skv.skv_kv_append(cache, layer, k, v, start, new, p1 - p0)
+            skv.skv_kv_append(cache, layer, kbuf, vbuf, start, new, step)
     torch.cuda.synchronize()
 
 
