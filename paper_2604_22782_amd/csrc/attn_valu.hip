@@ -203,7 +203,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void attn_valu_kernel(AttnArgs
     }
 
     if (grp != 0) return;
-    if (a.n_splits == 1) {
+    if ((kv_end + a.keys_per_split - 1) / a.keys_per_split == 1) { // the row fits one split: final result
 #pragma unroll
         for (int h = 0; h < G; ++h) {
             const float inv = 1.f / l[h];
@@ -242,6 +242,7 @@ __global__ __launch_bounds__(256) void split_merge_kernel(AttnArgs a, int D) {
     const int kv_end = a.kv_lens[b];
     if (kv_end < 1 || kv_end > a.max_kv_len) return; // the attention kernel wrote zeros
     const int ns = (kv_end + a.keys_per_split - 1) / a.keys_per_split;
+    if (ns == 1) return; // the attention kernel already wrote the final result
     const float *ml = a.part_ml + rh * a.n_splits * 2;
     float m = -INFINITY;
     for (int s = 0; s < ns; ++s) m = fmaxf(m, ml[2 * s]);

@@ -16,8 +16,13 @@
 //      ds_read_b64_tr_b16.  The key order inside the contraction is permuted so that the
 //      accumulator layout of step 3 is directly the B-operand layout of this product: the
 //      weights never leave the registers.
-// The four waves merge through LDS; a split writes (max, sum, unnormalised out) in fp32 for the
-// merge launch, a single split writes the normalised output.
+// The four waves merge through LDS.  A sequence that fits one split gets its normalised output
+// at once; otherwise every split writes (max, sum, unnormalised out) in fp32 for the merge launch.
+// (Merging in the same launch by the last work group to finish was measured and rejected: making
+// the partials visible across the per-XCD L2s costs each work group either an L2 write-back or
+// the round trip of write-through stores, which is more than the small merge launch.)
+#include <cstdlib>
+
 #include "skv_internal.h"
 
 namespace skv {
@@ -53,7 +58,6 @@ struct MF16 {
     }
 };
 
-constexpr int kWaves = 4;
 constexpr int kTile = 32; // keys per wave tile
 
 template <int D> struct Geo {
@@ -71,7 +75,7 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const char *p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(p));
 }
 
-template <typename M, int D>
+template <typename M, int D, int kWaves>
 __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a, int G) {
     using Ge = Geo<D>;
     using vec8 = typename M::vec8;
@@ -97,6 +101,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
     const int k_begin = split * a.keys_per_split;
     const int k_end = min(kv_end, k_begin + a.keys_per_split);
     if (k_begin >= k_end) return; // uniform over the work group
+    const int ns = (kv_end + a.keys_per_split - 1) / a.keys_per_split; // splits that hold keys of this sequence
 
     // Q^T as B operand: lane (n, g), k-step s holds Q[head n][32 s + 8 g .. + 8); heads >= G are zero.
     vec8 qB[D / 32];
@@ -148,16 +153,36 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
 #pragma unroll
     for (int i = 0; i < D / 16; ++i) o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    uint4 kr[NL], vr[NL];
-    int32_t rows[NL];
-    int j0 = k_begin + wave * kTile;
-    if (j0 < k_end) {
-        rows_of(j0, rows);
-        issue(rows, kr, vr);
-        if (j0 + kWaves * kTile < k_end) rows_of(j0 + kWaves * kTile, rows);
-    }
+    // Tiles of the split are dealt round-robin to the waves.  The walk starts at a tile that
+    // differs from work group to work group (softmax does not care about key order): work groups
+    // that run side by side then sit at unrelated offsets of their ranges instead of marching
+    // through the HBM channels in lockstep.
+    const int n_tiles = (k_end - k_begin + kTile - 1) / kTile;
+    const int start = (split * 7 + kvh * 3 + b * 5) % n_tiles;
+    auto tile_j0 = [&](int tt) {
+        int t2 = tt + start;
+        if (t2 >= n_tiles) t2 -= n_tiles;
+        return k_begin + t2 * kTile;
+    };
 
-    for (; j0 < k_end; j0 += kWaves * kTile) {
+    // Two tiles per wave are in flight from HBM (register sets A and B) while a third is computed
+    // from LDS; the row numbers (block-table lookups) run one more tile ahead.
+    int32_t rows[NL];
+    int tt_issue = wave; // next tile of this wave to request
+    auto issue_next = [&](uint4 *kr, uint4 *vr) {
+        if (tt_issue < n_tiles) {
+            issue(rows, kr, vr);
+            tt_issue += kWaves;
+            if (tt_issue < n_tiles) rows_of(tile_j0(tt_issue), rows);
+        }
+    };
+    uint4 krA[NL], vrA[NL], krB[NL], vrB[NL];
+    if (wave < n_tiles) rows_of(tile_j0(wave), rows);
+    issue_next(krA, vrA);
+    issue_next(krB, vrB);
+
+    auto process = [&](int tt, uint4 *kr, uint4 *vr) {
+        const int j0 = tile_j0(tt);
         // park the tile in LDS: row-major, 16-byte pieces, padded row stride
 #pragma unroll
         for (int t = 0; t < NL; ++t) {
@@ -169,12 +194,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        // loads of the next tile fly while this one is computed; row numbers run one tile further ahead
-        const int jn = j0 + kWaves * kTile;
-        if (jn < k_end) {
-            issue(rows, kr, vr);
-            if (jn + kWaves * kTile < k_end) rows_of(jn + kWaves * kTile, rows);
-        }
+        issue_next(kr, vr); // the freed register set requests the tile after the one in flight
 
         // S^T = K Q^T for keys [j0, j0+16) and [j0+16, j0+32)
         f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
@@ -233,6 +253,10 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); // reads of this tile before the next tile's writes
         __builtin_amdgcn_wave_barrier();
+    };
+    for (int tt = wave; tt < n_tiles; tt += 2 * kWaves) {
+        process(tt, krA, vrA);
+        if (tt + kWaves < n_tiles) process(tt + kWaves, krB, vrB);
     }
 
     // ---- merge the four waves through LDS --------------------------------------------------
@@ -266,7 +290,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
             acc += *(const f32x4 *)(mo + ((v * G + h) * D + d4)) * wv;
         }
         const int64_t rh = (int64_t)b * a.n_q_heads + head0 + h;
-        if (a.n_splits == 1) {
+        if (ns == 1) {
             const float inv = 1.f / l;
             *(uint2 *)((uint16_t *)a.out + rh * D + d4) =
                 make_uint2(M::pack2(acc[0] * inv, acc[1] * inv), M::pack2(acc[2] * inv, acc[3] * inv));
@@ -283,8 +307,15 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
 
 template <typename M, int D>
 hipError_t launch_d(const AttnArgs &a, int group, hipStream_t stream) {
+    static const int waves = [] { // tuning knob: SKV_DECODE_WAVES=2|4 waves per work group
+        const char *e = getenv("SKV_DECODE_WAVES");
+        return e && atoi(e) == 4 ? 4 : 2;
+    }();
     const dim3 grid((unsigned)a.n_splits, (unsigned)a.cache.n_kv_heads, (unsigned)a.batch);
-    decode_mfma_kernel<M, D><<<grid, 64 * kWaves, 0, stream>>>(a, group);
+    if (waves == 4)
+        decode_mfma_kernel<M, D, 4><<<grid, 256, 0, stream>>>(a, group);
+    else
+        decode_mfma_kernel<M, D, 2><<<grid, 128, 0, stream>>>(a, group);
     set_last_kernel_name("decode_mfma_kernel");
     return hipGetLastError();
 }
