@@ -31,6 +31,15 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def measured_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary (or None)."""
+    try:
+        t = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic.json")))[kernel]
+        return int(t["FETCH_SIZE"]["bytes"] + t["WRITE_SIZE"]["bytes"])
+    except Exception:
+        return None
+
+
 def cpu_baseline_decode(w, seconds_budget=12.0):
     """The float64 oracle, as it stands, on a bounded sample of the decode workload."""
     import torch
@@ -121,7 +130,7 @@ def run_decode(args, torch, skv, H, configs):
     res = {
         "value": round(value, 1), "ms_per_step": round(ms_per_step, 4),
         "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(kernel_name),
                      "launch_us": round(call_ms * 1e3, 2), "algorithmic_bytes_per_launch": layer_bytes},
         "workload": w,
     }
@@ -177,7 +186,8 @@ def run_prefill(args, torch, skv, H, configs):
            "steps": steps, "ms_per_step": round(dt * 1e3, 3), "value": round(tflops_step, 1), "unit": "TFLOP/s",
            "roofline": {"bound": "mfma", "kernel": skv.skv_last_kernel_name(), "achieved": round(tflops_kernel, 1),
                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                        "frac": round(tflops_kernel / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                        "frac": round(tflops_kernel / MFMA_BF16_PEAK_TFLOPS, 4),
+                        "traffic": measured_traffic("prefill_mfma_kernel"),
                         "launch_us": round(call_ms * 1e3, 1), "algorithmic_flops_per_launch": flops}}
     cache.free()
     return res
@@ -190,6 +200,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first run a plain 1 GiB device copy 5 times (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1")
@@ -204,6 +216,14 @@ def main():
         log("bench.py needs a GPU: the hot path has no CPU fallback")
         sys.exit(3)
     skv.lib()
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")    # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     dec = run_decode(args, torch, skv, H, configs)
     w = dec.pop("workload")
