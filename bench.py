@@ -199,6 +199,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--skip-prefill", action="store_true")
+    ap.add_argument("--only-prefill", action="store_true", help="profiling aid: measure only the prefill workload")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device copy 5 times (reference for HBM byte counters)")
@@ -225,6 +226,9 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
 
+    if args.only_prefill:
+        print(json.dumps({"prefill": run_prefill(args, torch, skv, H, configs)}), flush=True)
+        return
     dec = run_decode(args, torch, skv, H, configs)
     w = dec.pop("workload")
     line = {

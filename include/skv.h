@@ -142,7 +142,8 @@ skv_status_t skv_decode_workspace_bytes(const skv_cache_t *cache, int32_t max_kv
 /* Sampling-phase attention, Eq. (3.1) for one query token per sequence:
  *   out[b][h] = sum_j softmax_j(scale * <q[b][h], K[j]>) V[j],  j < kv_lens[b],
  * over the slot of route[layer].  q, out: device [batch][n_q_heads][head_dim], dtype of the
- * cache; fp32 accumulation; out rounded to nearest even.  kv_lens: device int32[batch], each in
+ * cache; fp32 accumulation; out rounded to nearest even.  scale must be > 0 (else
+ * SKV_ERR_INVALID_ARG; the same holds for skv_attn_prefill).  kv_lens: device int32[batch], each in
  * [1, max_kv_len]; max_kv_len (host) only sizes the launch and must be >= every kv_lens[b]
  * (positions beyond it are not read).  workspace: device, >= skv_decode_workspace_bytes. */
 skv_status_t skv_attn_decode(skv_cache_t *cache, int32_t layer, const void *q, void *out,

@@ -14,6 +14,8 @@
 // Row i of a sequence with n cached positions and q query rows sits at position n - q + i and
 // sees keys 0..that position; tiles entirely above a wave's diagonal are skipped, only tiles that
 // touch it are masked.
+#include <type_traits>
+
 #include "skv_internal.h"
 
 namespace skv {
@@ -196,83 +198,95 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_mfma_kernel(AttnArgs a
     }
     __syncthreads();
 
+    const float cs = a.scale_log2e; // > 0 (checked by the host): maxima can be taken on raw scores
+    const int sl = lane & 15;
+    const int v_lane_off = (4 * hh + (sl >> 2)) * Ge::V_STRIDE + ((lane >> 4) & 1) * 32 + (sl & 3) * 8;
+
+    // One 64-key tile for this wave.  `masked` is a compile-time tag: only tiles that touch the
+    // wave's diagonal pay for the causal mask.
+    auto compute_tile = [&](const char *ks, const char *vs, int j0, auto masked) {
+        // S^T = K Q^T: key blocks [j0, j0+32) and [j0+32, j0+64), two independent accumulator chains
+        f32x16 s0, s1;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s0[r] = s1[r] = 0.f;
+        const char *k0 = ks + c * Ge::K_STRIDE + hh * 16;
+        const char *k1 = k0 + 32 * Ge::K_STRIDE;
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) {
+            const vec8 a0 = __builtin_bit_cast(vec8, *(const uint4 *)(k0 + s * 32));
+            const vec8 a1 = __builtin_bit_cast(vec8, *(const uint4 *)(k1 + s * 32));
+            s0 = M::mfma(a0, qB[s], s0);
+            s1 = M::mfma(a1, qB[s], s1);
+        }
+        // element r of block kb is key j0 + 32 kb + 8 (r / 4) + 4 hh + (r % 4)
+        float sc[32];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            sc[r] = s0[r];
+            sc[16 + r] = s1[r];
+        }
+        if constexpr (decltype(masked)::value) {
+#pragma unroll
+            for (int r = 0; r < 32; ++r) {
+                const int key = j0 + 32 * (r >> 4) + 8 * ((r & 15) >> 2) + 4 * hh + (r & 3);
+                if (key > my_pos) sc[r] = -INFINITY;
+            }
+        }
+        float mt = sc[0];
+#pragma unroll
+        for (int r = 1; r < 32; ++r) mt = fmaxf(mt, sc[r]);
+        mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+        const float m_new = fmaxf(m_run, mt); // raw-score units; finite from the first tile on
+        if (__any(m_new > m_run)) {           // the running maximum settles after a few tiles
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * cs);
+            l_part *= alpha;
+#pragma unroll
+            for (int i = 0; i < D / 32; ++i) o[i] *= alpha;
+            m_run = m_new;
+        }
+        const float neg_mc = -m_run * cs;
+        float psum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 32; ++r) { // weights 2^(cs (s - m)); masked scores are -inf -> 0
+            sc[r] = __builtin_amdgcn_exp2f(fmaf(sc[r], cs, neg_mc));
+            psum += sc[r];
+        }
+        l_part += psum;
+        // P^T as B operands: MFMA step x = 2 kb + u takes accumulator elements 8u .. 8u+7 of block kb:
+        // k-slot (hh, j) = key 16 x + 4 hh + j (j < 4) or 16 x + 8 + 4 hh + (j - 4)
+        vec8 pB[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const uint4 raw = make_uint4(M::pack2(sc[8 * x], sc[8 * x + 1]), M::pack2(sc[8 * x + 2], sc[8 * x + 3]),
+                                         M::pack2(sc[8 * x + 4], sc[8 * x + 5]), M::pack2(sc[8 * x + 6], sc[8 * x + 7]));
+            pB[x] = __builtin_bit_cast(vec8, raw);
+        }
+        // O^T[d][row] += V^T P^T.  A 16-lane block reads 4 keys x 16 d transposed:
+        // lanes 0-15 / 16-31 are the low / high 16 d of the 32-d block, hh picks the key group.
+        const char *vbase = vs + v_lane_off;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const char *vx = vbase + 16 * x * Ge::V_STRIDE;
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db) {
+                const s16x4 lo = lds_read_tr16(vx + db * 64);
+                const s16x4 hi = lds_read_tr16(vx + 8 * Ge::V_STRIDE + db * 64);
+                const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                o[db] = M::mfma(__builtin_bit_cast(vec8, both), pB[x], o[db]);
+            }
+        }
+    };
+
     for (int t = 0; t < n_tiles; ++t) {
         const int j0 = t * kBN;
         const char *ks = lds + (t & 1) * Ge::STAGE_BYTES;
         const char *vs = ks + Ge::K_BYTES;
 
         if (wave_ok && j0 <= wave_last_pos) {
-            // S^T = K Q^T: key blocks [j0, j0+32) and [j0+32, j0+64)
-            f32x16 sacc[2];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
-#pragma unroll
-                for (int s = 0; s < D / 16; ++s) {
-                    const vec8 ak = __builtin_bit_cast(
-                        vec8, *(const uint4 *)(ks + (32 * kb + c) * Ge::K_STRIDE + (2 * s + hh) * 16));
-                    sacc[kb] = M::mfma(ak, qB[s], sacc[kb]);
-                }
-            }
-            // element r of block kb is key j0 + 32 kb + 8 (r / 4) + 4 hh + (r % 4); log2 units
-            float sc[32];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sc[16 * kb + r] = sacc[kb][r] * a.scale_log2e;
-            if (j0 + kBN - 1 > offset + r0) { // the tile touches the diagonal of this wave
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int key = j0 + 32 * kb + 8 * (r >> 2) + 4 * hh + (r & 3);
-                        if (key > my_pos) sc[16 * kb + r] = -INFINITY;
-                    }
-            }
-            float mt = sc[0];
-#pragma unroll
-            for (int r = 1; r < 32; ++r) mt = fmaxf(mt, sc[r]);
-            mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
-            // rows beyond q_lens are padding: keep them finite, they are never stored
-            const float m_new = row_ok ? fmaxf(m_run, mt) : 0.f;
-            const float alpha = exp2f(m_run - m_new);
-            m_run = m_new;
-            float psum = 0.f;
-#pragma unroll
-            for (int r = 0; r < 32; ++r) {
-                sc[r] = exp2f(sc[r] - m_new);
-                psum += sc[r];
-            }
-            l_part = l_part * alpha + psum;
-            if (__any(alpha != 1.f)) {
-#pragma unroll
-                for (int i = 0; i < D / 32; ++i) o[i] *= alpha;
-            }
-            // P^T as B operands: MFMA step (kb, u) takes accumulator elements 8u .. 8u+7 of block kb:
-            // k-slot (hh, j) = key 32 kb + 16 u + 4 hh + j (j < 4) or + 8 + 4 hh + (j - 4)
-            vec8 pB[4];
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const uint4 raw = make_uint4(M::pack2(sc[8 * x], sc[8 * x + 1]), M::pack2(sc[8 * x + 2], sc[8 * x + 3]),
-                                             M::pack2(sc[8 * x + 4], sc[8 * x + 5]), M::pack2(sc[8 * x + 6], sc[8 * x + 7]));
-                pB[x] = __builtin_bit_cast(vec8, raw);
-            }
-            // O^T[d][row] += V^T P^T.  A 16-lane block reads 4 keys x 16 d transposed:
-            // lanes 0-15 / 16-31 are the low / high 16 d of the 32-d block, hh picks the key group.
-            const int sl = lane & 15;
-            const char *vbase = vs + (4 * hh + (sl >> 2)) * Ge::V_STRIDE + ((lane >> 4) & 1) * 32 + (sl & 3) * 8;
-#pragma unroll
-            for (int x = 0; x < 4; ++x) { // x = 2 kb + u: keys j0 + 16 x ..
-                const char *vx = vbase + 16 * x * Ge::V_STRIDE;
-#pragma unroll
-                for (int db = 0; db < D / 32; ++db) {
-                    const s16x4 lo = lds_read_tr16(vx + db * 64);
-                    const s16x4 hi = lds_read_tr16(vx + 8 * Ge::V_STRIDE + db * 64);
-                    const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    o[db] = M::mfma(__builtin_bit_cast(vec8, both), pB[x], o[db]);
-                }
-            }
+            if (j0 + kBN - 1 > offset + r0) // the tile touches the diagonal of this wave
+                compute_tile(ks, vs, j0, std::true_type{});
+            else
+                compute_tile(ks, vs, j0, std::false_type{});
         }
 
         // stage the next tile (its loads were issued a tile ago), then fetch the one after

@@ -287,6 +287,7 @@ skv_status_t skv_attn_decode(skv_cache_t *c, int32_t layer, const void *q, void 
                              size_t workspace_bytes, void *stream) {
     if (!c || !q || !out || !kv_lens) return SKV_ERR_INVALID_ARG;
     if (layer < 0 || layer >= c->d.n_layers || max_kv_len <= 0) return SKV_ERR_INVALID_ARG;
+    if (!(scale > 0.f)) return SKV_ERR_INVALID_ARG;
     if (!paged_ready(c)) return SKV_ERR_INVALID_ARG;
     const skv::SlotView view = view_of(c, c->slot[layer]);
     if (max_kv_len > view.max_ctx) return SKV_ERR_CAPACITY;
@@ -325,6 +326,7 @@ skv_status_t skv_attn_prefill(skv_cache_t *c, int32_t layer, const void *q, void
                               int32_t max_kv_len, float scale, void *stream) {
     if (!c || !q || !out || !q_lens || !kv_lens) return SKV_ERR_INVALID_ARG;
     if (layer < 0 || layer >= c->d.n_layers || max_q <= 0 || max_kv_len <= 0) return SKV_ERR_INVALID_ARG;
+    if (!(scale > 0.f)) return SKV_ERR_INVALID_ARG;
     if (!paged_ready(c)) return SKV_ERR_INVALID_ARG;
     const skv::SlotView view = view_of(c, c->slot[layer]);
     if (max_kv_len > view.max_ctx) return SKV_ERR_CAPACITY;
