@@ -147,21 +147,18 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_mfma_kernel(AttnArgs a
     auto rows_of = [&](int j0, int32_t *rows) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            const int key = j0 + (tid + i * 64 * kWaves) / LPR;
-            int64_t r = -1;
-            if (key < n_keys) {
-                r = slot_row(a.cache, b, key);
-                if (r < 0 && (tid % LPR) == 0) atomicOr(a.cache.faults, (uint32_t)SKV_FAULT_BLOCK_ID);
-            }
+            // keys past the last needed one repeat it: they are masked anyway, and a real row keeps
+            // the V operand finite (0 x NaN from never-written cache memory would poison the sum)
+            const int key = min(j0 + (tid + i * 64 * kWaves) / LPR, n_keys - 1);
+            const int64_t r = slot_row(a.cache, b, key);
+            if (r < 0 && (tid % LPR) == 0) atomicOr(a.cache.faults, (uint32_t)SKV_FAULT_BLOCK_ID);
             rows[i] = (int32_t)r;
         }
     };
     auto issue = [&](const int32_t *rows, uint4 *kr, uint4 *vr) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            kr[i] = make_uint4(0, 0, 0, 0);
-            vr[i] = make_uint4(0, 0, 0, 0);
-            if (rows[i] >= 0) {
+            if (rows[i] >= 0) { // a bad block id keeps the previous (finite) piece
                 const int64_t off = rows[i] * row_elems + (tid % LPR) * 8;
                 kr[i] = *(const uint4 *)(kp + off);
                 vr[i] = *(const uint4 *)(vp + off);
@@ -187,6 +184,8 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_mfma_kernel(AttnArgs a
         for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
 
     uint4 kr[NL], vr[NL];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) kr[i] = vr[i] = make_uint4(0, 0, 0, 0);
     int32_t rows[NL];
     rows_of(0, rows);
     issue(rows, kr, vr);
@@ -237,7 +236,10 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_mfma_kernel(AttnArgs a
         for (int r = 1; r < 32; ++r) mt = fmaxf(mt, sc[r]);
         mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
         const float m_new = fmaxf(m_run, mt); // raw-score units; finite from the first tile on
-        if (__any(m_new > m_run)) {           // the running maximum settles after a few tiles
+        // Lazy reference: the accumulators are rescaled only when some row's maximum grew by more
+        // than 2^8 in weight; until then weights may reach 256 instead of 1, which fp32 sums and
+        // 16-bit weights hold without loss, and the final division by the row sum is unaffected.
+        if (__any((m_new - m_run) * cs > 8.f)) {
             const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * cs);
             l_part *= alpha;
 #pragma unroll
