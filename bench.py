@@ -77,7 +77,12 @@ def cpu_baseline_decode(w, seconds_budget=12.0):
 
 
 def run_decode(args, torch, skv, H, configs):
-    w = configs.llama3_decode()
+    if args.decode_workload == "qwen3_paged":
+        w = configs.qwen3_paged_decode()
+    elif args.decode_workload == "llama2_mha":
+        w = configs.llama2_mha_decode(batch=args.mha_batch)
+    else:
+        w = configs.llama3_decode()
     log(f"[bench] workload {w.name}: B={w.batch} ctx={int(w.kv_lens[0])} layers={w.n_layers} slots={len(w.owner_layers)}")
     cache, _ = H.alloc_cache(w)
     t0 = time.perf_counter()
@@ -89,8 +94,14 @@ def run_decode(args, torch, skv, H, configs):
     ones = torch.ones(w.batch, dtype=torch.int32, device="cuda")
     ws = H.workspace_for(cache, ctx)
     qs = [w.q_decode(l, "cuda") for l in range(w.n_layers)]
-    new_k = {l: w.kv_rows("k", l, 0, w.batch, ctx - 1, ctx, "cuda") for l in w.owner_layers}
-    new_v = {l: w.kv_rows("v", l, 0, w.batch, ctx - 1, ctx, "cuda") for l in w.owner_layers}
+
+    def newest_rows(which, l):   # the K/V row of each sequence's newest position
+        if int(w.kv_lens.min()) == ctx:
+            return w.kv_rows(which, l, 0, w.batch, ctx - 1, ctx, "cuda")
+        return torch.cat([w.kv_rows(which, l, b, b + 1, int(n) - 1, int(n), "cuda") for b, n in enumerate(w.kv_lens)])
+
+    new_k = {l: newest_rows("k", l) for l in w.owner_layers}
+    new_v = {l: newest_rows("v", l) for l in w.owner_layers}
     outs = [torch.empty_like(qs[0]) for _ in range(w.n_layers)]
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(w.n_layers)]
 
@@ -201,6 +212,9 @@ def main():
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--only-prefill", action="store_true", help="profiling aid: measure only the prefill workload")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--decode-workload", default="llama3_decode", choices=["llama3_decode", "qwen3_paged", "llama2_mha"],
+                    help="decode workload to time (default: the one the metric is quoted on)")
+    ap.add_argument("--mha-batch", type=int, default=32, help="batch of the llama2_mha workload")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device copy 5 times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -236,9 +250,10 @@ def main():
         "value": dec["value"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": dec["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": w.name, "batch": w.batch, "context": int(w.kv_lens.max()), "layers": w.n_layers,
+        "config": {"workload": w.name, "batch": w.batch, "max_context": int(w.kv_lens.max()), "layers": w.n_layers,
                    "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
-                   "route": "route[l]=l-(l%2)", "slots": len(w.owner_layers), "step": "append(owner)+decode per layer"},
+                   "slots": len(w.owner_layers), "sum_kv_len": int(w.kv_lens.sum()), "paged": bool(w.block_size),
+                   "step": "append(owner)+decode per layer"},
         "pct_of_hbm_peak": round(100 * dec["value"] / HBM_PEAK_GBS, 2),
         "roofline": dec["roofline"],
     }

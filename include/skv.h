@@ -14,7 +14,9 @@
  *     the memory lives.  Device pointers are ordinary HIP allocations (for example the storage
  *     of a PyTorch-ROCm tensor).  `stream` is a hipStream_t passed as void* (NULL = default).
  *   - Every compute call only ENQUEUES work on `stream`: no synchronisation, no allocation.
- *     Caller-owned buffers must stay alive until that work has run.
+ *     Caller-owned buffers must stay alive until that work has run.  Calls on ONE cache must not
+ *     overlap in time (enqueue them on one stream, or order the streams): the attention kernels
+ *     keep small work counters in the cache object.
  *   - Layers, heads, positions and slots are 0-based (the paper counts layers from 1).
  *   - Query head h reads kv head h / (n_q_heads / n_kv_heads).
  *   - The query at absolute position p sees cached positions 0..p.

@@ -76,20 +76,23 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const char *p) {
 }
 
 template <typename M, int D, int kWaves>
-__global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a, int G) {
+__global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a, int G, int persistent) {
     using Ge = Geo<D>;
     using vec8 = typename M::vec8;
     constexpr int NL = Ge::NL, LPR = Ge::LPR, RPL = Ge::RPL;
     __shared__ __attribute__((aligned(16))) char lds[kWaves * Ge::WAVE_BYTES];
+    __shared__ int s_item;
+    extern __shared__ int s_prefix[]; // persistent mode: batch + 1 running split counts
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform on purpose (scalar loads below)
     const int n = lane & 15; // MFMA column: query head of the group (B, C operands) / row (A operand)
     const int g = lane >> 4; // MFMA k-group
-    const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
     const int hkv = a.cache.n_kv_heads;
-    const int head0 = kvh * G;
 
+    // One work item = (sequence, kv head, key split).
+    auto process_item = [&](const int b, const int kvh, const int split) {
+    const int head0 = kvh * G;
     const int kv_end = a.kv_lens[b];
     if (kv_end < 1 || kv_end > a.max_kv_len) { // lengths the host promised not to pass
         if (threadIdx.x == 0 && split == 0 && kvh == 0) atomicOr(a.cache.faults, (uint32_t)SKV_FAULT_KV_LEN);
@@ -123,27 +126,41 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
     const uint16_t *vp = (const uint16_t *)a.cache.v + (int64_t)kvh * D + lcol * 8;
     const int64_t row_elems = (int64_t)hkv * D;
 
-    // Row numbers of a tile's keys (-1 = key beyond the range, or a bad block id).
-    auto rows_of = [&](int j0, int32_t *rows) {
+    // Paged caches: the (at most four) block ids a 32-key tile touches are fetched with SCALAR loads
+    // one tile ahead.  They have a counter of their own, so waiting for them never drains the
+    // vector loads of the K/V tiles that are still in flight.
+    const bool paged = a.cache.block_table != nullptr;
+    const int shift = a.cache.block_shift;
+    auto blocks_of = [&](int j0, int32_t *blk) {
+        if (paged) {
+            const int32_t *row = a.cache.block_table + (int64_t)b * a.cache.max_blocks_per_seq;
+            const int first = j0 >> shift;
 #pragma unroll
-        for (int t = 0; t < NL; ++t) {
-            const int key = j0 + RPL * t + lrow;
-            int64_t r = -1;
-            if (key < k_end) {
-                r = slot_row(a.cache, b, key);
-                if (r < 0 && lcol == 0) atomicOr(a.cache.faults, (uint32_t)SKV_FAULT_BLOCK_ID);
-            }
-            rows[t] = (int32_t)r;
+            for (int u = 0; u < 4; ++u) blk[u] = row[min(first + u, a.cache.max_blocks_per_seq - 1)];
         }
     };
-    auto issue = [&](const int32_t *rows, uint4 *kr, uint4 *vr) {
+    // Row number of this lane's key in load t of the tile at j0 (-1 = beyond the range / bad block id).
+    auto row_of = [&](int j0, const int32_t *blk, int t) -> int32_t {
+        const int key = j0 + RPL * t + lrow;
+        if (key >= k_end) return -1;
+        if (!paged) return b * a.cache.max_ctx + key;
+        const int u = (key - j0) >> shift; // 0..3 (0 when a block holds 32 keys or more)
+        const int32_t id = u == 0 ? blk[0] : u == 1 ? blk[1] : u == 2 ? blk[2] : blk[3];
+        if ((uint32_t)id >= (uint32_t)a.cache.n_blocks) {
+            if (lcol == 0) atomicOr(a.cache.faults, (uint32_t)SKV_FAULT_BLOCK_ID);
+            return -1;
+        }
+        return (id << shift) + (key & ((1 << shift) - 1));
+    };
+    auto issue = [&](int j0, const int32_t *blk, uint4 *kr, uint4 *vr) {
 #pragma unroll
         for (int t = 0; t < NL; ++t) {
             kr[t] = make_uint4(0, 0, 0, 0);
             vr[t] = make_uint4(0, 0, 0, 0);
-            if (rows[t] >= 0) {
-                kr[t] = *(const uint4 *)(kp + rows[t] * row_elems);
-                vr[t] = *(const uint4 *)(vp + rows[t] * row_elems);
+            const int32_t r = row_of(j0, blk, t);
+            if (r >= 0) {
+                kr[t] = *(const uint4 *)(kp + r * row_elems);
+                vr[t] = *(const uint4 *)(vp + r * row_elems);
             }
         }
     };
@@ -166,18 +183,18 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
     };
 
     // Two tiles per wave are in flight from HBM (register sets A and B) while a third is computed
-    // from LDS; the row numbers (block-table lookups) run one more tile ahead.
-    int32_t rows[NL];
+    // from LDS; the block ids run one more tile ahead.
+    int32_t blk[4] = {0, 0, 0, 0};
     int tt_issue = wave; // next tile of this wave to request
     auto issue_next = [&](uint4 *kr, uint4 *vr) {
         if (tt_issue < n_tiles) {
-            issue(rows, kr, vr);
+            issue(tile_j0(tt_issue), blk, kr, vr);
             tt_issue += kWaves;
-            if (tt_issue < n_tiles) rows_of(tile_j0(tt_issue), rows);
+            if (tt_issue < n_tiles) blocks_of(tile_j0(tt_issue), blk);
         }
     };
     uint4 krA[NL], vrA[NL], krB[NL], vrB[NL];
-    if (wave < n_tiles) rows_of(tile_j0(wave), rows);
+    if (wave < n_tiles) blocks_of(tile_j0(wave), blk);
     issue_next(krA, vrA);
     issue_next(krB, vrB);
 
@@ -303,19 +320,99 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
             }
         }
     }
+    }; // process_item
+
+    if (!persistent) {
+        process_item(blockIdx.z, blockIdx.y, blockIdx.x);
+        return;
+    }
+    // Persistent mode: when the sequences have very different lengths, a (split, head, sequence) grid
+    // is mostly work groups with nothing to do, each costing a slot and a memory round trip under
+    // load.  Instead a fixed number of work groups (two per compute unit) pull items from a counter.
+    // prefix[b] = number of splits of the sequences before b (a sequence with an impossible length
+    // counts one item, which zero-fills its output and raises the fault word).
+    if (wave == 0) {
+        const int per = (a.batch + 63) / 64;
+        int cnt = 0;
+        for (int i = 0; i < per; ++i) {
+            const int bb = lane * per + i;
+            if (bb < a.batch) {
+                const int len = a.kv_lens[bb];
+                cnt += (len < 1 || len > a.max_kv_len) ? 1 : (len + a.keys_per_split - 1) / a.keys_per_split;
+            }
+        }
+        int incl = cnt;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += up;
+        }
+        int run = incl - cnt;
+        if (lane == 0) s_prefix[0] = 0;
+        for (int i = 0; i < per; ++i) {
+            const int bb = lane * per + i;
+            if (bb < a.batch) {
+                const int len = a.kv_lens[bb];
+                run += (len < 1 || len > a.max_kv_len) ? 1 : (len + a.keys_per_split - 1) / a.keys_per_split;
+                s_prefix[bb + 1] = run;
+            }
+        }
+    }
+    __syncthreads();
+    const int total = s_prefix[a.batch] * hkv;
+    int32_t *counter = a.work_counters, *done = a.work_counters + 1;
+    int next = blockIdx.x; // the first item needs no ticket; tickets count on from the grid size
+    for (;;) {
+        if (threadIdx.x == 0) s_item = next;
+        __syncthreads();
+        const int item = s_item;
+        __syncthreads(); // every thread has read the item; also fences the previous item's LDS use
+        if (item >= total) break;
+        // take the next ticket now: its round trip hides behind this item's work
+        if (threadIdx.x == 0)
+            next = (int)gridDim.x + __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int kvh = item % hkv;
+        const int j = item / hkv;
+        int lo = 0, hi = a.batch; // largest b with prefix[b] <= j
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (s_prefix[mid] <= j) lo = mid;
+            else hi = mid;
+        }
+        // all lanes hold the same values; say so to the compiler (scalar registers, scalar loads)
+        process_item(__builtin_amdgcn_readfirstlane(lo), __builtin_amdgcn_readfirstlane(kvh),
+                     __builtin_amdgcn_readfirstlane(j - s_prefix[lo]));
+    }
+    // The last work group to leave puts the counters back to rest for the next launch.
+    if (threadIdx.x == 0) {
+        const int left = __hip_atomic_fetch_add(done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (left == (int)gridDim.x - 1) {
+            __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
 }
 
 template <typename M, int D>
 hipError_t launch_d(const AttnArgs &a, int group, hipStream_t stream) {
-    static const int waves = [] { // tuning knob: SKV_DECODE_WAVES=2|4 waves per work group
-        const char *e = getenv("SKV_DECODE_WAVES");
-        return e && atoi(e) == 4 ? 4 : 2;
+    static const int n_cu = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        return cus;
     }();
-    const dim3 grid((unsigned)a.n_splits, (unsigned)a.cache.n_kv_heads, (unsigned)a.batch);
-    if (waves == 4)
-        decode_mfma_kernel<M, D, 4><<<grid, 256, 0, stream>>>(a, group);
-    else
-        decode_mfma_kernel<M, D, 2><<<grid, 128, 0, stream>>>(a, group);
+    // Items are pulled from a counter by two resident work groups per compute unit when the grid
+    // could hold many empty splits (more than two splits per sequence); a batch too large for the
+    // split-count table in LDS, or a launch with few items, uses the plain grid.
+    const int64_t max_items = (int64_t)a.n_splits * a.cache.n_kv_heads * a.batch;
+    if (a.n_splits > 2 && a.batch <= 2048 && a.work_counters != nullptr && max_items > 2 * n_cu) {
+        const size_t dyn = sizeof(int) * (size_t)(a.batch + 1);
+        decode_mfma_kernel<M, D, 4><<<dim3(2 * n_cu), 256, dyn, stream>>>(a, group, 1);
+    } else {
+        const dim3 grid((unsigned)a.n_splits, (unsigned)a.cache.n_kv_heads, (unsigned)a.batch);
+        decode_mfma_kernel<M, D, 4><<<grid, 256, 0, stream>>>(a, group, 0);
+    }
     set_last_kernel_name("decode_mfma_kernel");
     return hipGetLastError();
 }

@@ -310,6 +310,7 @@ skv_status_t skv_attn_decode(skv_cache_t *c, int32_t layer, const void *q, void 
     a.scale_log2e = scale * 1.4426950408889634f;
     a.part_o = (float *)workspace;
     a.part_ml = a.part_o + (size_t)c->d.batch * c->d.n_q_heads * a.n_splits * c->d.head_dim;
+    a.work_counters = (int32_t *)c->faults + 16; // inside the cache's zero-initialised 256-byte device block
 
     const int g = c->d.n_q_heads / c->d.n_kv_heads;
     hipError_t e;
@@ -346,6 +347,7 @@ skv_status_t skv_attn_prefill(skv_cache_t *c, int32_t layer, const void *q, void
     a.scale_log2e = scale * 1.4426950408889634f;
     a.part_o = nullptr;
     a.part_ml = nullptr;
+    a.work_counters = nullptr;
 
     const int g = c->d.n_q_heads / c->d.n_kv_heads;
     hipError_t e;

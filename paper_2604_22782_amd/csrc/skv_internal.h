@@ -39,6 +39,7 @@ struct AttnArgs {
     const int32_t *kv_lens; // [batch]
     float *part_o;          // split partials [rows*n_q_heads][n_splits][head_dim]
     float *part_ml;         // [rows*n_q_heads][n_splits][2]  (max, sum)
+    int32_t *work_counters; // two device words, zero at rest: next work item, work groups that left
     int32_t batch;
     int32_t max_q;          // query rows per sequence in q/out (1 for decode)
     int32_t n_q_heads;
