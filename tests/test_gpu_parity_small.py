@@ -174,3 +174,53 @@ def test_decode_equals_last_prefill_row_and_chunked_prefill():
     d_q2 = torch.tensor([100, 100], dtype=torch.int32, device="cuda")
     skv.skv_attn_prefill(cache, 1, q[:, 100:].contiguous(), part, d_q2, d_kv, 100, 384, w.scale)
     assert (part.float() - full[:, 100:].float()).abs().max().item() <= 2e-2
+
+
+def test_decode_work_queue_mode_ragged_batch():
+    """A ragged batch with many splits per sequence runs the decode kernel in its persistent mode
+    (work groups pull (sequence, kv head, split) items from a counter).  Every output element is
+    checked, twice in a row (the counters must be back at rest after a launch), and a sequence with
+    an impossible length is contained."""
+    rng = np.random.default_rng(5)
+    lens = np.clip(np.rint(rng.lognormal(np.log(600), 1.0, size=24)), 1, 4000).astype(np.int32)
+    lens[3], lens[7] = 4000, 1
+    w = _small("bf16", 32, 8, 128, len(lens), lens, [0, 0], paged=True, seed=123)
+    cache, _ = H.alloc_cache(w)
+    H.fill_by_append(cache, w)
+    oc = H.oracle_cache(w)
+    d_lens = torch.from_numpy(w.kv_lens).cuda()
+    max_len = int(w.kv_lens.max())
+    ws = H.workspace_for(cache, max_len)
+    # 24 sequences x 8 kv heads x ceil(4000 / 256) splits: far more grid slots than items with keys
+    q = w.q_decode(1, "cuda")
+    want = O.decode(oc, 1, gen.to_f64(q), w.kv_lens, w.scale)
+    for _ in range(2):
+        out = H.decode_layer(cache, w, 1, q, d_lens, max_len, ws)
+        assert H.max_abs_err(out, want) <= H.TOL["bf16"]
+    assert skv.skv_cache_device_faults(cache) == 0
+    bad = w.kv_lens.copy()
+    bad[5] = 0
+    bad[9] = max_len + 1
+    out = H.decode_layer(cache, w, 1, q, torch.from_numpy(bad).cuda(), max_len, ws)
+    assert skv.skv_cache_device_faults(cache) & 4
+    got = gen.to_f64(out)
+    ok = [b for b in range(len(lens)) if b not in (5, 9)]
+    assert np.abs(got[ok] - want[ok]).max() <= H.TOL["bf16"]
+    assert not got[5].any() and not got[9].any()
+    out = H.decode_layer(cache, w, 1, q, d_lens, max_len, ws)      # and the queue still works afterwards
+    assert H.max_abs_err(out, want) <= H.TOL["bf16"]
+
+
+def test_scale_must_be_positive():
+    w = _small("bf16", 8, 2, 128, 2, [64, 64], [0])
+    cache, _ = H.alloc_cache(w)
+    q = w.q_decode(0, "cuda")
+    lens = torch.from_numpy(w.kv_lens).cuda()
+    ws = H.workspace_for(cache, 64)
+    for bad in (0.0, -1.0, float("nan")):
+        with pytest.raises(skv.SkvError) as e:
+            skv.skv_attn_decode(cache, 0, q, torch.empty_like(q), lens, 64, bad, ws)
+        assert e.value.status == 1
+        with pytest.raises(skv.SkvError) as e:
+            skv.skv_attn_prefill(cache, 0, q, torch.empty_like(q), lens, lens, 1, 64, bad)
+        assert e.value.status == 1
