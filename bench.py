@@ -198,7 +198,7 @@ def run_prefill(args, torch, skv, H, configs):
            "roofline": {"bound": "mfma", "kernel": skv.skv_last_kernel_name(), "achieved": round(tflops_kernel, 1),
                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                         "frac": round(tflops_kernel / MFMA_BF16_PEAK_TFLOPS, 4),
-                        "traffic": measured_traffic("prefill_mfma_kernel"),
+                        "traffic": measured_traffic(skv.skv_last_kernel_name()),
                         "launch_us": round(call_ms * 1e3, 1), "algorithmic_flops_per_launch": flops}}
     cache.free()
     return res

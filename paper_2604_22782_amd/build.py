@@ -16,7 +16,7 @@ LIB = os.path.join(PKG, "libskv.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-I" + os.path.join(ROOT, "include"),
-    "-I" + CSRC, "-Wall", "-Wno-unused-function",
+    "-I" + CSRC, "-I" + OBJ, "-Wall", "-Wno-unused-function",
     # keep the compiler from forming packed fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]
@@ -36,6 +36,9 @@ def _compile(src: str) -> str:
 
 def build_library(verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
+    # the instruction stream of the pipelined pre-fill kernel is written by a generator
+    subprocess.check_call([sys.executable, os.path.join(CSRC, "gen_prefill_pipe.py"),
+                           os.path.join(OBJ, "prefill_pipe_body.inc")])
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
     with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
         objs = list(ex.map(_compile, srcs))

@@ -1,0 +1,616 @@
+#!/usr/bin/env python3
+"""Writes the hand-scheduled gfx950 instruction stream of the pipelined pre-fill attention kernel
+(prefill_pipe.hip includes the generated header).
+
+Why a generated stream: the kernel keeps one wave per SIMD busy with 64 query rows, and its inner
+loop only reaches the matrix-core rate if every MFMA is followed by a handful of independent
+vector instructions (softmax of the previous 32 keys), LDS operand reads two operands ahead and
+the staging traffic of the tile three tiles ahead.  The order of ~450 instructions per 64-key
+tile and the ~400 registers per lane are fixed here.
+
+What is computed (paper Eq. (3.1), pre-fill phase of Sec. 3.1.1): for a wave's 64 query rows
+(two blocks of 32, "nq" = 0, 1) and the keys 0..position of each row,
+  S^T = K Q^T (v_mfma_f32_32x32x16), online softmax down the columns, O^T += V^T P^T.
+Keys are walked in half tiles of 32 ("u"); a half step runs, interleaved,
+  matrix cores:  S^T(u+1)  and  O^T += V^T(u-1) P^T(u-1)
+  vector ALU:    max / exp2 / row sums / 16-bit weights of S^T(u)
+so the three stages of three consecutive half tiles are in flight at once.
+
+Register map (per lane):
+  a[0:127]    O^T accumulators  [nq][d block of 32][16]
+  a[128:191]  Q^T as MFMA B operand [nq][k step of 16][4]
+  a[192:223]  K and V rows on their way from HBM to LDS (4 + 4 x 16 bytes)
+  v[32:63], v[64:95]    S^T of even / odd half tiles [nq][16]
+  v[96:111], v[112:127] P^T (16-bit pairs) of even / odd half tiles [nq][k step of 16 keys][4]
+  v[128:143], v[144:159] rings of 4 K / V^T operands read from LDS
+  v[160:...]  softmax state, lane constants, addresses
+  v[0:23], s[0:39] are left to the compiler for the operands of the asm statement.
+
+Hazards the hardware does not interlock (MFMA result read by the vector ALU, transcendental
+result read by the next instruction, lane-swap operands, dot-product results read by other
+opcodes) are kept apart by construction or by s_nop; see the comments at the emit sites.
+"""
+from __future__ import annotations
+
+import sys
+
+K_STRIDE = 272            # bytes per K row in LDS (256 + 16: 16 rows x 16 B hit distinct banks)
+V_STRIDE = 320            # bytes per V row in LDS
+K_BYTES = 64 * K_STRIDE
+V_BYTES = 64 * V_STRIDE
+STAGE = K_BYTES + V_BYTES  # one 64-key tile of K and V
+N_STAGE = 4
+LDS_BYTES = N_STAGE * STAGE
+
+# ---- register names ---------------------------------------------------------------------------
+SA, SB = 32, 64
+PA, PB = 96, 112
+KO, VO = 128, 144
+T_MAX = (160, 161)
+T_MAX2 = (162, 163)
+M_NEW = (164, 165)
+M_RUN = (166, 167)
+NEG_MC = (168, 169)
+L_SUM = (170, 171)
+ALPHA = (172, 173)
+LIM = (174, 175)
+DIFF = (176, 177)
+LANE, COL, HH = 178, 179, 180
+KL, VL = 181, 182              # lane parts of the K / V^T read addresses (LDS base included)
+KA_CUR, KA_NXT = 183, 184      # K read address of tile t / t+1
+VA_PRV, VA_CUR = 185, 186      # V^T read address of tile t-1 / t
+WK, WV = 187, 188              # lane parts of the staging write addresses
+WA_K, WA_V = 189, 190          # staging write addresses of the current target stage
+ROWB, PIECE = 191, 192         # tid / 16, (tid % 16) * 16
+VOFF = (193, 194, 195, 196)    # byte offsets of this lane's 4 rows of the tile being fetched
+NEG_INF = 197
+TMP = tuple(range(198, 214))   # scratch
+Q_OFF = (214, 215)
+O_OFF = (216, 217)
+ROW = (218, 219)
+STG = 220                      # scratch of the staging address arithmetic
+
+A_O, A_Q, A_LK, A_LV = 0, 128, 192, 208
+
+S_T, S_TMP, S_STW, S_J0, S_FLAG = 40, 41, 42, 43, 44
+S_CMP = 46                     # pair
+S_ST_NXT, S_ST_CUR = 48, 49
+S_ONES, S_NCS, S_C272, S_C320 = 50, 51, 52, 53
+S_EXEC = 54                    # pair
+S_NK1 = 56
+
+FIRST_V, FIRST_S, LAST_S = 24, 40, 59
+
+PD = 2  # operand groups fetched ahead of the MFMAs that use them
+
+
+class Asm:
+    def __init__(self, dt: str):
+        self.dt = dt              # "bf16" or "f16"
+        self.lines: list[str] = []
+        self.lds: list[object] = []   # LDS operations in program order (tags)
+        self.waited = -1              # index of the newest operation known to be complete
+        self.uid = 0
+
+    def e(self, s: str):
+        self.lines.append(s)
+
+    def c(self, s: str):
+        self.lines.append("// " + s)
+
+    def fresh(self) -> int:
+        self.uid += 1
+        return self.uid
+
+    # LDS operations complete in order; lgkmcnt(n) waits until at most n are outstanding.
+    def lds_op(self, text: str, tag):
+        self.e(text)
+        self.lds.append(tag)
+
+    def wait_lds(self, tag):
+        idx = max(i for i, t in enumerate(self.lds) if t == tag)
+        if idx <= self.waited:
+            return
+        n = len(self.lds) - 1 - idx
+        self.e(f"s_waitcnt lgkmcnt({min(n, 15)})")
+        self.waited = len(self.lds) - 1 - min(n, 15)
+
+    def reset_lds(self, pending):
+        self.lds = list(pending)
+        self.waited = -1
+
+
+def vr(b, n=1):
+    return f"v{b}" if n == 1 else f"v[{b}:{b + n - 1}]"
+
+
+def ar(b, n=1):
+    return f"a{b}" if n == 1 else f"a[{b}:{b + n - 1}]"
+
+
+def sr(b, n=1):
+    return f"s{b}" if n == 1 else f"s[{b}:{b + n - 1}]"
+
+
+# ---- softmax of one half tile (vector ALU stream) ------------------------------------------------
+def softmax_stream(A: Asm, s_cur: int, p_cur: int, masked: bool, tagid: str):
+    """Returns a list of instruction strings.  s_cur: 32 registers [nq][16], element r of a block is
+    key 8 (r / 4) + 4 hh + (r % 4) of the half tile.  p_cur: 16 registers [nq][2][4]."""
+    o = []
+    S = [[s_cur + 16 * q + r for r in range(16)] for q in range(2)]
+    if masked:
+        # key offset inside the half tile vs. (row position - first key of the half tile - 4 hh)
+        for r in range(16):
+            for q in range(2):
+                kk = 8 * (r // 4) + (r % 4)
+                o.append(f"v_cmp_lt_i32_e64 vcc, {vr(LIM[q])}, {kk}")
+                o.append(f"v_cndmask_b32_e32 {vr(S[q][r])}, {vr(S[q][r])}, {vr(NEG_INF)}, vcc")
+    for q in range(2):
+        o.append(f"v_max3_f32 {vr(T_MAX[q])}, {vr(S[q][0])}, {vr(S[q][1])}, {vr(S[q][2])}")
+    for k in range(6):
+        for q in range(2):
+            o.append(f"v_max3_f32 {vr(T_MAX[q])}, {vr(T_MAX[q])}, {vr(S[q][3 + 2 * k])}, {vr(S[q][4 + 2 * k])}")
+    for q in range(2):
+        o.append(f"v_max_f32_e32 {vr(T_MAX[q])}, {vr(T_MAX[q])}, {vr(S[q][15])}")
+    for q in range(2):
+        o.append(f"v_mov_b32_e32 {vr(T_MAX2[q])}, {vr(T_MAX[q])}")
+    # the lane swap must not follow a vector write of its operands within two issue slots
+    o.append("s_nop 1")
+    for q in range(2):
+        # lanes 32-63 of the first operand <-> lanes 0-31 of the second: afterwards the first holds
+        # the lower half's value in both halves, the second the upper half's
+        o.append(f"v_permlane32_swap_b32_e32 {vr(T_MAX[q])}, {vr(T_MAX2[q])}")
+    o.append("s_nop 1")
+    for q in range(2):
+        o.append(f"v_max3_f32 {vr(M_NEW[q])}, {vr(T_MAX[q])}, {vr(T_MAX2[q])}, {vr(M_RUN[q])}")
+    for q in range(2):
+        o.append(f"v_sub_f32_e32 {vr(DIFF[q])}, {vr(M_NEW[q])}, {vr(M_RUN[q])}")
+    # rescale only when some row's maximum grew by more than 2^8 in weight (threshold in raw scores)
+    o.append(f"v_cmp_lt_f32_e64 {sr(S_CMP, 2)}, %[thr], {vr(DIFF[0])}")
+    o.append(f"v_cmp_lt_f32_e32 vcc, %[thr], {vr(DIFF[1])}")
+    o.append(f"s_or_b64 vcc, vcc, {sr(S_CMP, 2)}")
+    o.append(f"s_cbranch_vccnz L_RESC_{tagid}_%=")
+    o.append(f"L_RET_{tagid}_%=:")
+    for r in range(16):
+        for q in range(2):
+            o.append(f"v_fma_f32 {vr(S[q][r])}, {vr(S[q][r])}, %[cs], {vr(NEG_MC[q])}")
+    for r in range(16):
+        for q in range(2):
+            o.append(f"v_exp_f32_e32 {vr(S[q][r])}, {vr(S[q][r])}")
+    # 16-bit weights: register j of block (q, x) packs elements 8x + 2j, 8x + 2j + 1
+    for j in range(8):
+        for q in range(2):
+            d = p_cur + 8 * q + j
+            if A.dt == "bf16":
+                o.append(f"v_cvt_pk_bf16_f32 {vr(d)}, {vr(S[q][2 * j])}, {vr(S[q][2 * j + 1])}")
+            else:
+                o.append(f"v_cvt_f16_f32_e32 {vr(S[q][2 * j])}, {vr(S[q][2 * j])}")
+                o.append(f"v_cvt_f16_f32_e32 {vr(S[q][2 * j + 1])}, {vr(S[q][2 * j + 1])}")
+                o.append(f"v_pack_b32_f16 {vr(d)}, {vr(S[q][2 * j])}, {vr(S[q][2 * j + 1])}")
+    # row sums of the rounded weights (the same values the second product uses)
+    for j in range(8):
+        for q in range(2):
+            d = p_cur + 8 * q + j
+            o.append(f"v_dot2_f32_{A.dt} {vr(L_SUM[q])}, {vr(d)}, {sr(S_ONES)}, {vr(L_SUM[q])}")
+    if masked:
+        for q in range(2):
+            o.append(f"v_subrev_u32_e32 {vr(LIM[q])}, 32, {vr(LIM[q])}")
+    return o
+
+
+def rescale_blocks(A: Asm, tagid: str):
+    """Out-of-line code of one half step: new running maximum, and the deferred O rescale."""
+    A.e(f"L_RESC_{tagid}_%=:")
+    for q in range(2):
+        A.e(f"v_sub_f32_e32 {vr(ALPHA[q])}, {vr(M_RUN[q])}, {vr(M_NEW[q])}")
+    for q in range(2):
+        A.e(f"v_mul_f32_e32 {vr(ALPHA[q])}, %[cs], {vr(ALPHA[q])}")
+    for q in range(2):
+        A.e(f"v_exp_f32_e32 {vr(ALPHA[q])}, {vr(ALPHA[q])}")
+    for q in range(2):
+        A.e(f"v_mov_b32_e32 {vr(M_RUN[q])}, {vr(M_NEW[q])}")
+    for q in range(2):
+        A.e(f"v_mul_f32_e32 {vr(NEG_MC[q])}, {sr(S_NCS)}, {vr(M_NEW[q])}")
+    for q in range(2):  # >= 4 instructions after the exponentials and far from the last dot product
+        A.e(f"v_mul_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}, {vr(ALPHA[q])}")
+    A.e(f"s_mov_b32 {sr(S_FLAG)}, 1")
+    A.e(f"s_branch L_RET_{tagid}_%=")
+
+    A.e(f"L_RESO_{tagid}_%=:")
+    # the accumulators were last written by MFMAs issued a few instructions ago: let them retire
+    for _ in range(3):
+        A.e("s_nop 7")
+    for q in range(2):
+        for i in range(0, 64, 8):
+            for k in range(8):
+                A.e(f"v_accvgpr_read_b32 {vr(TMP[k])}, {ar(A_O + 64 * q + i + k)}")
+            for k in range(8):
+                A.e(f"v_mul_f32_e32 {vr(TMP[k])}, {vr(TMP[k])}, {vr(ALPHA[q])}")
+            for k in range(8):
+                A.e(f"v_accvgpr_write_b32 {ar(A_O + 64 * q + i + k)}, {vr(TMP[k])}")
+    A.e("s_nop 7")
+    A.e(f"s_mov_b32 {sr(S_FLAG)}, 0")
+    A.e(f"s_branch L_RESO_RET_{tagid}_%=")
+
+
+# ---- operand reads -----------------------------------------------------------------------------
+def k_read(A: Asm, addr: int, kb: int, g: int, tag):
+    dst = KO + 4 * (g % 4)
+    A.lds_op(f"ds_read_b128 {vr(dst, 4)}, {vr(addr)} offset:{kb * 32 * K_STRIDE + g * 32}", tag)
+
+
+def v_read(A: Asm, addr: int, kb: int, g: int, tag_lo, tag_hi):
+    x, db = g // 4, g % 4
+    dst = VO + 4 * (g % 4)
+    off = (kb * 32 + 16 * x) * V_STRIDE + db * 64
+    A.lds_op(f"ds_read_b64_tr_b16 {vr(dst, 2)}, {vr(addr)} offset:{off}", tag_lo)
+    A.lds_op(f"ds_read_b64_tr_b16 {vr(dst + 2, 2)}, {vr(addr)} offset:{off + 8 * V_STRIDE}", tag_hi)
+
+
+def half_step(A: Asm, hs: int, qk, pv, sm, nxt, extra, tagid: str, cold=False):
+    """One half step.
+    qk  = (K address register, key block, S destination base) or None
+    pv  = (V address register, key block, P source base) or None
+    sm  = (S source base, P destination base, masked) or None
+    nxt = ((K address register, key block) or None, (V address register, key block) or None):
+          operands of the next half step's first PD groups, fetched at the end of this one
+    extra = instructions for the first four gaps (staging); entries are strings, or
+          ("lds", text, tag) for LDS writes.
+    hs  = serial number of the half step inside the emitted code (tags of its operand reads)."""
+    valu = softmax_stream(A, sm[0], sm[1], sm[2], tagid) if sm else []
+    gaps = [[] for _ in range(32)]
+    for i, ins in enumerate(extra):
+        gaps[min(3, i * 4 // max(1, len(extra)))].append(ins)
+    # the softmax starts after the first group of MFMAs: the last S^T MFMA of the previous half
+    # step is then >= 5 MFMAs old when the vector ALU first reads its result
+    first, n_gap = 4, 28
+    per = [len(valu) * (i + 1) // n_gap - len(valu) * i // n_gap for i in range(n_gap)]
+    pos = 0
+    for i in range(n_gap):
+        gaps[first + i].extend(valu[pos:pos + per[i]])
+        pos += per[i]
+    assert pos == len(valu)
+
+    def emit_gap(i):
+        for ins in gaps[i]:
+            if isinstance(ins, tuple):
+                A.lds_op(ins[1], ins[2])
+            else:
+                A.e(ins)
+
+    def fetch(hs_id, g, kcfg, vcfg):
+        if kcfg:
+            k_read(A, kcfg[0], kcfg[1], g, ("K", hs_id, g))
+        if vcfg:
+            v_read(A, vcfg[0], vcfg[1], g, ("Vl", hs_id, g), ("Vh", hs_id, g))
+
+    kcfg = (qk[0], qk[1]) if qk else None
+    vcfg = (pv[0], pv[1]) if pv else None
+    if cold:
+        for g in range(PD):
+            fetch(hs, g, kcfg, vcfg)
+    for g in range(8):
+        if g + PD < 8:
+            fetch(hs, g + PD, kcfg, vcfg)
+        elif nxt is not None:
+            fetch(hs + 1, g + PD - 8, nxt[0], nxt[1])
+        ko, vo = KO + 4 * (g % 4), VO + 4 * (g % 4)
+        for q in range(2):
+            if qk:
+                if q == 0:
+                    A.wait_lds(("K", hs, g))
+                s_dst = qk[2] + 16 * q
+                c_in = "0" if g == 0 else vr(s_dst, 16)
+                A.e(f"v_mfma_f32_32x32x16_{A.dt} {vr(s_dst, 16)}, {vr(ko, 4)}, {ar(A_Q + 32 * q + 4 * g, 4)}, {c_in}")
+            emit_gap(4 * g + 2 * q)
+            if pv:
+                if q == 0:
+                    A.wait_lds(("Vh", hs, g))
+                x, db = g // 4, g % 4
+                o_acc = A_O + 64 * q + 16 * db
+                p_src = pv[2] + 8 * q + 4 * x
+                A.e(f"v_mfma_f32_32x32x16_{A.dt} {ar(o_acc, 16)}, {vr(vo, 4)}, {vr(p_src, 4)}, {ar(o_acc, 16)}")
+            emit_gap(4 * g + 2 * q + 1)
+    if sm:
+        A.e(f"s_cmp_lg_u32 {sr(S_FLAG)}, 0")
+        A.e(f"s_cbranch_scc1 L_RESO_{tagid}_%=")
+        A.e(f"L_RESO_RET_{tagid}_%=:")
+
+
+def pending_reads(hs, with_k=True, with_v=True):
+    out = []
+    for g in range(PD):
+        if with_k:
+            out.append(("K", hs, g))
+        if with_v:
+            out += [("Vl", hs, g), ("Vh", hs, g)]
+    return out
+
+
+# ---- staging (HBM -> registers -> LDS) ------------------------------------------------------------
+def voffsets(j0_sreg: int):
+    o = []
+    for i in range(4):
+        # key = min(j0 + tid / 16 + 16 i, last needed key): rows past it repeat it (finite, masked)
+        o.append(f"v_add3_u32 {vr(STG)}, {sr(j0_sreg)}, {vr(ROWB)}, {16 * i}")
+        o.append(f"v_min_u32_e32 {vr(STG)}, {sr(S_NK1)}, {vr(STG)}")
+        o.append(f"v_mad_u32_u24 {vr(VOFF[i])}, {vr(STG)}, %[krb], {vr(PIECE)}")
+    return o
+
+
+def tile_loads():
+    o = []
+    for i in range(4):
+        o.append(f"buffer_load_dwordx4 {ar(A_LK + 4 * i, 4)}, {vr(VOFF[i])}, %[srdk], 0 offen")
+        o.append(f"buffer_load_dwordx4 {ar(A_LV + 4 * i, 4)}, {vr(VOFF[i])}, %[srdv], 0 offen")
+    return o
+
+
+def tile_writes(A: Asm):
+    o = []
+    for i in range(4):
+        o.append(("lds", f"ds_write_b128 {vr(WA_K)}, {ar(A_LK + 4 * i, 4)} offset:{16 * i * K_STRIDE}", ("W", A.fresh())))
+        o.append(("lds", f"ds_write_b128 {vr(WA_V)}, {ar(A_LV + 4 * i, 4)} offset:{16 * i * V_STRIDE}", ("W", A.fresh())))
+    return o
+
+
+def staging_ops(A: Asm):
+    """Tile t+2 (fetched a tile ago) goes to its LDS stage, then tile t+3 is requested."""
+    o = ["s_waitcnt vmcnt(0)",
+         f"s_add_u32 {sr(S_TMP)}, {sr(S_T)}, 2",
+         f"s_and_b32 {sr(S_TMP)}, {sr(S_TMP)}, 3",
+         f"s_mul_i32 {sr(S_STW)}, {sr(S_TMP)}, {STAGE}",
+         f"v_add_u32_e32 {vr(WA_K)}, {sr(S_STW)}, {vr(WK)}",
+         f"v_add_u32_e32 {vr(WA_V)}, {sr(S_STW)}, {vr(WV)}"]
+    o += tile_writes(A)
+    o += [f"s_lshl_b32 {sr(S_J0)}, {sr(S_T)}, 6",
+          f"s_add_u32 {sr(S_J0)}, {sr(S_J0)}, 192"]
+    o += voffsets(S_J0)
+    o += tile_loads()
+    return o
+
+
+def rotate_addresses(A: Asm):
+    A.e(f"v_mov_b32_e32 {vr(KA_CUR)}, {vr(KA_NXT)}")
+    A.e(f"v_mov_b32_e32 {vr(VA_PRV)}, {vr(VA_CUR)}")
+    A.e(f"s_add_u32 {sr(S_TMP)}, {sr(S_T)}, 1")
+    A.e(f"s_and_b32 {sr(S_TMP)}, {sr(S_TMP)}, 3")
+    A.e(f"s_mul_i32 {sr(S_ST_NXT)}, {sr(S_TMP)}, {STAGE}")
+    A.e(f"s_and_b32 {sr(S_TMP)}, {sr(S_T)}, 3")
+    A.e(f"s_mul_i32 {sr(S_ST_CUR)}, {sr(S_TMP)}, {STAGE}")
+    A.e(f"v_add_u32_e32 {vr(KA_NXT)}, {sr(S_ST_NXT)}, {vr(KL)}")
+    A.e(f"v_add_u32_e32 {vr(VA_CUR)}, {sr(S_ST_CUR)}, {vr(VL)}")
+
+
+def body(A: Asm, masked: bool, name: str):
+    """Tile t for a computing wave: half steps u = 2t and 2t + 1."""
+    A.reset_lds(pending_reads(0))
+    rotate_addresses(A)
+    half_step(A, 0, qk=(KA_CUR, 1, SB), pv=(VA_PRV, 1, PB), sm=(SA, PA, masked),
+              nxt=((KA_NXT, 0), (VA_CUR, 0)), extra=[], tagid=name + "0")
+    half_step(A, 1, qk=(KA_NXT, 0, SA), pv=(VA_CUR, 0, PA), sm=(SB, PB, masked),
+              nxt=((KA_NXT, 1), (VA_CUR, 1)), extra=staging_ops(A), tagid=name + "1")
+    # every staging write is older than the last operand read that was waited for
+    last_w = max(i for i, t in enumerate(A.lds) if t[0] == "W")
+    assert last_w <= A.waited, (last_w, A.waited)
+    assert A.lds[-3 * PD:] == pending_reads(2), A.lds[-6:]
+    A.e("s_barrier")
+
+
+def body_stage_only(A: Asm):
+    for ins in staging_ops(A):
+        if isinstance(ins, tuple):
+            A.e(ins[1])
+        else:
+            A.e(ins)
+    A.e("s_waitcnt lgkmcnt(0)")
+    A.e("s_barrier")
+
+
+# ---- the whole stream ---------------------------------------------------------------------------
+def generate(dt: str) -> list[str]:
+    A = Asm(dt)
+    e = A.e
+    ones = 0x3F803F80 if dt == "bf16" else 0x3C003C00
+
+    A.c("lane constants")
+    e(f"s_movk_i32 {sr(S_C272)}, {K_STRIDE}")
+    e(f"s_movk_i32 {sr(S_C320)}, {V_STRIDE}")
+    e(f"s_mov_b32 {sr(S_ONES)}, 0x{ones:08x}")
+    e(f"s_xor_b32 {sr(S_NCS)}, %[cs], 0x80000000")
+    e(f"s_mov_b32 {sr(S_NK1)}, %[nk1]")
+    e(f"v_and_b32_e32 {vr(LANE)}, 63, %[tid]")
+    e(f"v_and_b32_e32 {vr(COL)}, 31, {vr(LANE)}")
+    e(f"v_lshrrev_b32_e32 {vr(HH)}, 5, {vr(LANE)}")
+    # K operand: row c of the key block, bytes [16 hh, 16 hh + 16) of each 32-byte k step
+    e(f"v_lshlrev_b32_e32 {vr(TMP[0])}, 4, {vr(HH)}")
+    e(f"v_mad_u32_u24 {vr(KL)}, {vr(COL)}, {sr(S_C272)}, {vr(TMP[0])}")
+    e(f"v_add_u32_e32 {vr(KL)}, %[lds], {vr(KL)}")
+    # V^T operand through the transposing read: a 16-lane block covers 4 keys x 16 d
+    e(f"v_and_b32_e32 {vr(TMP[0])}, 15, {vr(LANE)}")
+    e(f"v_lshrrev_b32_e32 {vr(TMP[1])}, 2, {vr(TMP[0])}")
+    e(f"v_lshl_add_u32 {vr(TMP[1])}, {vr(HH)}, 2, {vr(TMP[1])}")
+    e(f"v_and_b32_e32 {vr(TMP[2])}, 3, {vr(TMP[0])}")
+    e(f"v_lshlrev_b32_e32 {vr(TMP[2])}, 3, {vr(TMP[2])}")
+    e(f"v_bfe_u32 {vr(TMP[3])}, {vr(LANE)}, 4, 1")
+    e(f"v_lshl_add_u32 {vr(TMP[2])}, {vr(TMP[3])}, 5, {vr(TMP[2])}")
+    e(f"v_mad_u32_u24 {vr(VL)}, {vr(TMP[1])}, {sr(S_C320)}, {vr(TMP[2])}")
+    e(f"s_add_u32 {sr(S_TMP)}, %[lds], {K_BYTES}")
+    e(f"v_add_u32_e32 {vr(VL)}, {sr(S_TMP)}, {vr(VL)}")
+    # staging: thread t moves 16-byte piece t % 16 of rows t / 16 + 16 i
+    e(f"v_lshrrev_b32_e32 {vr(ROWB)}, 4, %[tid]")
+    e(f"v_and_b32_e32 {vr(TMP[0])}, 15, %[tid]")
+    e(f"v_lshlrev_b32_e32 {vr(PIECE)}, 4, {vr(TMP[0])}")
+    e(f"v_mad_u32_u24 {vr(WK)}, {vr(ROWB)}, {sr(S_C272)}, {vr(PIECE)}")
+    e(f"v_add_u32_e32 {vr(WK)}, %[lds], {vr(WK)}")
+    e(f"v_mad_u32_u24 {vr(WV)}, {vr(ROWB)}, {sr(S_C320)}, {vr(PIECE)}")
+    e(f"v_add_u32_e32 {vr(WV)}, {sr(S_TMP)}, {vr(WV)}")
+
+    A.c("Q^T into AGPRs: lane (row c, k group hh) holds Q[row][16 s + 8 hh, +8); rows past the last valid one repeat it")
+    e(f"s_sub_u32 {sr(S_TMP)}, %[rv], 1")
+    e(f"v_lshlrev_b32_e32 {vr(TMP[2])}, 4, {vr(HH)}")
+    for q in range(2):
+        e(f"v_add_u32_e32 {vr(ROW[q])}, {32 * q}, {vr(COL)}")
+        e(f"v_min_u32_e32 {vr(TMP[0])}, {sr(S_TMP)}, {vr(ROW[q])}")
+        e(f"v_mad_u32_u24 {vr(Q_OFF[q])}, {vr(TMP[0])}, %[qrs], {vr(TMP[2])}")
+    for q in range(2):
+        for s in range(8):
+            e(f"global_load_dwordx4 {ar(A_Q + 32 * q + 4 * s, 4)}, {vr(Q_OFF[q])}, %[qp] offset:{32 * s}")
+    # output: element r of d block db is d = 32 db + 8 (r / 4) + 4 hh + (r % 4)
+    e(f"v_lshlrev_b32_e32 {vr(TMP[2])}, 3, {vr(HH)}")
+    for q in range(2):
+        e(f"v_mad_u32_u24 {vr(O_OFF[q])}, {vr(ROW[q])}, %[qrs], {vr(TMP[2])}")
+
+    A.c("state")
+    for i in range(128):
+        e(f"v_accvgpr_write_b32 {ar(A_O + i)}, 0")
+    for i in range(16):
+        e(f"v_mov_b32_e32 {vr(PB + i)}, 0")
+    e(f"v_mov_b32_e32 {vr(NEG_INF)}, 0xff800000")
+    for q in range(2):
+        e(f"v_mov_b32_e32 {vr(M_RUN[q])}, 0xff800000")
+        e(f"v_mov_b32_e32 {vr(L_SUM[q])}, 0")
+        e(f"v_mov_b32_e32 {vr(NEG_MC[q])}, 0")
+    e(f"s_mov_b32 {sr(S_FLAG)}, 0")
+    e(f"s_mov_b32 {sr(S_T)}, 0")
+
+    A.c("tiles 0 and 1 to LDS, tile 2 requested")
+    for x in range(3):
+        e(f"s_movk_i32 {sr(S_J0)}, {64 * x}")
+        for ins in voffsets(S_J0):
+            e(ins)
+        for ins in tile_loads():
+            e(ins)
+        if x < 2:
+            e("s_waitcnt vmcnt(0)")
+            e(f"v_add_u32_e32 {vr(WA_K)}, {x * STAGE}, {vr(WK)}")
+            e(f"v_add_u32_e32 {vr(WA_V)}, {x * STAGE}, {vr(WV)}")
+            for ins in tile_writes(A):
+                e(ins[1])
+    A.c("the first half step multiplies zero weights with the V part of stage 3: make it finite")
+    e(f"v_mul_u32_u24_e32 {vr(TMP[0])}, 80, %[tid]")
+    e(f"s_add_u32 {sr(S_TMP)}, %[lds], {3 * STAGE + K_BYTES}")
+    e(f"v_add_u32_e32 {vr(TMP[0])}, {sr(S_TMP)}, {vr(TMP[0])}")
+    for i in range(5):
+        e(f"ds_write_b128 {vr(TMP[0])}, {vr(PB, 4)} offset:{16 * i}")
+    e("s_waitcnt lgkmcnt(0)")
+    e("s_barrier")
+    e(f"v_mov_b32_e32 {vr(KA_NXT)}, {vr(KL)}")
+    e(f"v_add_u32_e32 {vr(VA_CUR)}, {3 * STAGE}, {vr(VL)}")
+
+    A.c("S^T of half tile 0")
+    A.reset_lds([])
+    half_step(A, -1, qk=(KA_NXT, 0, SA), pv=None, sm=None, nxt=((KA_NXT, 1), (VA_CUR, 1)), extra=[],
+              tagid="pro", cold=True)
+
+    A.c("tiles entirely below the wave's diagonal")
+    e("L_FULL_%=:")
+    e(f"s_cmp_ge_i32 {sr(S_T)}, %[tms]")
+    e("s_cbranch_scc1 L_FULL_END_%=")
+    body(A, False, "f")
+    e(f"s_add_u32 {sr(S_T)}, {sr(S_T)}, 1")
+    e("s_branch L_FULL_%=")
+    e("L_FULL_END_%=:")
+
+    A.c("tiles that touch the diagonal: lim = row position - first key of the half tile - 4 hh")
+    e(f"s_lshl_b32 {sr(S_TMP)}, {sr(S_T)}, 6")
+    e(f"s_sub_i32 {sr(S_TMP)}, %[p0], {sr(S_TMP)}")
+    e(f"v_lshlrev_b32_e32 {vr(TMP[0])}, 2, {vr(HH)}")
+    for q in range(2):
+        e(f"v_sub_u32_e32 {vr(LIM[q])}, {vr(ROW[q])}, {vr(TMP[0])}")
+        e(f"v_add_u32_e32 {vr(LIM[q])}, {sr(S_TMP)}, {vr(LIM[q])}")
+    e("L_MASK_%=:")
+    e(f"s_cmp_gt_i32 {sr(S_T)}, %[twl]")
+    e("s_cbranch_scc1 L_MASK_END_%=")
+    body(A, True, "m")
+    e(f"s_add_u32 {sr(S_T)}, {sr(S_T)}, 1")
+    e("s_branch L_MASK_%=")
+    e("L_MASK_END_%=:")
+
+    A.c("a wave without rows only helps with the staging")
+    e("s_cmp_lt_i32 %[twl], 0")
+    e("s_cbranch_scc1 L_STAGE_%=")
+
+    A.c("last O^T += V^T P^T")
+    A.reset_lds(pending_reads(0))
+    half_step(A, 0, qk=None, pv=(VA_CUR, 1, PB), sm=None, nxt=None, extra=[], tagid="dr")
+    for _ in range(3):  # the accumulators are read by the vector ALU next
+        e("s_nop 7")
+
+    A.c("row sums of both lane halves, normalise, store")
+    for q in range(2):
+        e(f"v_mov_b32_e32 {vr(T_MAX2[q])}, {vr(L_SUM[q])}")
+    e("s_nop 1")
+    for q in range(2):
+        e(f"v_permlane32_swap_b32_e32 {vr(L_SUM[q])}, {vr(T_MAX2[q])}")
+    e("s_nop 1")
+    for q in range(2):
+        e(f"v_add_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}, {vr(T_MAX2[q])}")
+    for q in range(2):
+        e(f"v_rcp_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}")
+    e("s_nop 1")
+    for q in range(2):
+        e(f"v_cmp_gt_i32_e32 vcc, %[rvs], {vr(ROW[q])}")
+        e(f"s_and_saveexec_b64 {sr(S_EXEC, 2)}, vcc")
+        n = 0
+        for db in range(4):
+            for g4 in range(4):
+                t = TMP[(n % 2) * 8:(n % 2) * 8 + 8]
+                n += 1
+                base = A_O + 64 * q + 16 * db + 4 * g4
+                for k in range(4):
+                    e(f"v_accvgpr_read_b32 {vr(t[k])}, {ar(base + k)}")
+                for k in range(4):
+                    e(f"v_mul_f32_e32 {vr(t[k])}, {vr(t[k])}, {vr(L_SUM[q])}")
+                if dt == "bf16":
+                    e(f"v_cvt_pk_bf16_f32 {vr(t[4])}, {vr(t[0])}, {vr(t[1])}")
+                    e(f"v_cvt_pk_bf16_f32 {vr(t[5])}, {vr(t[2])}, {vr(t[3])}")
+                else:
+                    for k in range(4):
+                        e(f"v_cvt_f16_f32_e32 {vr(t[k])}, {vr(t[k])}")
+                    e(f"v_pack_b32_f16 {vr(t[4])}, {vr(t[0])}, {vr(t[1])}")
+                    e(f"v_pack_b32_f16 {vr(t[5])}, {vr(t[2])}, {vr(t[3])}")
+                e(f"global_store_dwordx2 {vr(O_OFF[q])}, {vr(t[4], 2)}, %[op] offset:{64 * db + 16 * g4}")
+        e(f"s_mov_b64 exec, {sr(S_EXEC, 2)}")
+
+    A.c("remaining tiles of the work group: staging and barriers only")
+    e("L_STAGE_%=:")
+    e("s_waitcnt lgkmcnt(0)")
+    e("L_STAGE_LOOP_%=:")
+    e(f"s_cmp_ge_i32 {sr(S_T)}, %[nt]")
+    e("s_cbranch_scc1 L_END_%=")
+    body_stage_only(A)
+    e(f"s_add_u32 {sr(S_T)}, {sr(S_T)}, 1")
+    e("s_branch L_STAGE_LOOP_%=")
+
+    A.c("out-of-line: running maximum moved")
+    for name in ("f0", "f1", "m0", "m1"):
+        rescale_blocks(A, name)
+    e("L_END_%=:")
+    e("s_waitcnt vmcnt(0) lgkmcnt(0)")
+    return A.lines
+
+
+def clobbers() -> str:
+    regs = [f"v{i}" for i in range(FIRST_V, 256)] + [f"a{i}" for i in range(256)]
+    regs += [f"s{i}" for i in range(FIRST_S, LAST_S + 1)]
+    regs += ["vcc", "scc", "memory"]
+    return ", ".join(f'"{r}"' for r in regs)
+
+
+def main(out_path: str):
+    with open(out_path, "w") as f:
+        f.write("// Generated by gen_prefill_pipe.py -- do not edit.\n")
+        f.write(f"#define SKV_PIPE_LDS_BYTES {LDS_BYTES}\n")
+        for dt in ("bf16", "f16"):
+            f.write(f"#define SKV_PIPE_ASM_{dt.upper()} \\\n")
+            for line in generate(dt):
+                if line.startswith("//"):
+                    continue
+                f.write(f'    "{line}\\n" \\\n')
+            f.write('    ""\n')
+        f.write(f"#define SKV_PIPE_CLOBBERS {clobbers()}\n")
+
+
+if __name__ == "__main__":
+    main(sys.argv[1])

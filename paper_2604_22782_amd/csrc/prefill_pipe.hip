@@ -1,0 +1,152 @@
+// Pre-fill-phase routed attention (paper Sec. 3.1.1 "Pre-fill", Eq. (3.1)) for 16-bit contiguous
+// caches with head_dim 128: the software-pipelined kernel.
+//
+// Work group = 4 waves = 256 consecutive query rows of one (sequence, query head); wave w owns
+// rows 64w..64w+63 as two blocks of 32, so every K / V^T operand read from LDS feeds two MFMAs.
+// One wave per SIMD holds ~400 registers: O^T and Q^T in AGPRs, two S^T and two P^T buffers in
+// VGPRs.  K/V tiles of 64 keys travel HBM -> AGPRs -> a ring of four LDS stages, requested a full
+// tile before they are written and written a full tile before they are read.  The instruction
+// stream of the loop (which MFMA, which vector instruction, which LDS read goes where) is written
+// by gen_prefill_pipe.py and included below; this file only prepares its scalar operands.
+//
+// Buffer loads with a per-(slot, sequence, kv head) resource descriptor fetch K and V: the
+// hardware clamps any offset outside the sequence's region to a zero read, so even a wrong offset
+// cannot touch foreign memory.  Offsets are 32-bit, hence the 4 GiB limit in pipe_supported().
+#include "skv_internal.h"
+
+#include "prefill_pipe_body.inc"
+
+namespace skv {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int kRowsPerGroup = 256;
+constexpr int kD = 128;
+
+__device__ __forceinline__ uint32_t uni(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
+
+// Raw buffer descriptor: 48-bit base, stride 0, byte count, 32-bit untyped data.
+__device__ __forceinline__ u32x4 make_srd(const void *base, uint32_t bytes) {
+    const uint64_t p = (uint64_t)base;
+    u32x4 r;
+    r[0] = uni((uint32_t)p);
+    r[1] = uni((uint32_t)(p >> 32) & 0xffffu);
+    r[2] = uni(bytes);
+    r[3] = 0x00020000u;
+    return r;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256, 1) void prefill_pipe_kernel(AttnArgs a, int G, int n_qt, int xcd_map) {
+    __shared__ __attribute__((aligned(16))) char lds[SKV_PIPE_LDS_BYTES];
+
+    const int hkv = a.cache.n_kv_heads;
+    // block -> (query tile, head, sequence): heavy (late) query tiles first; with xcd_map the G
+    // heads of a kv head and neighbouring query tiles land on one XCD and share its L2
+    int qt, head, b;
+    {
+        const int id = blockIdx.x;
+        int pair, rem;
+        if (xcd_map) {
+            const int per_pair = G * n_qt;
+            const int k = id >> 3;
+            pair = (id & 7) + 8 * (k / per_pair);
+            rem = k % per_pair;
+        } else {
+            pair = id / (G * n_qt);
+            rem = id % (G * n_qt);
+        }
+        qt = n_qt - 1 - rem / G;
+        head = (pair % hkv) * G + rem % G;
+        b = pair / hkv;
+    }
+    const int kvh = head / G;
+
+    const int nq = a.q_lens[b];
+    const int n = a.kv_lens[b];
+    if (nq < 0 || nq > a.max_q || n < 1 || n > a.max_kv_len || nq > n) {
+        if (threadIdx.x == 0 && qt == 0 && head == 0) atomicOr(a.cache.faults, (uint32_t)SKV_FAULT_KV_LEN);
+        return; // nothing is written for a sequence with impossible lengths
+    }
+    const int q_begin = qt * kRowsPerGroup;
+    if (q_begin >= nq) return;
+    const int offset = n - nq;
+    const int q_last = min(q_begin + kRowsPerGroup, nq) - 1;
+    const int n_keys = offset + q_last + 1; // keys the work group needs
+    const int n_tiles = (n_keys + 63) >> 6;
+
+    const int wave = (int)uni(threadIdx.x >> 6);
+    const int r0 = q_begin + 64 * wave;
+    const int rows_valid = nq - r0;
+    const bool active = rows_valid > 0;
+    const int p0 = offset + r0;
+    const int p1 = offset + min(r0 + 63, nq - 1);
+    const int tw_last = active ? (p1 >> 6) : -1; // last tile this wave computes on
+    const int t_mask = active ? ((p0 + 1) >> 6) : 0; // first tile that touches its diagonal
+
+    const int64_t row_bytes = (int64_t)hkv * kD * 2;
+    const char *kbase = (const char *)a.cache.k + ((int64_t)b * a.cache.max_ctx * hkv + kvh) * (kD * 2);
+    const char *vbase = (const char *)a.cache.v + ((int64_t)b * a.cache.max_ctx * hkv + kvh) * (kD * 2);
+    const uint32_t span = (uint32_t)((int64_t)a.cache.max_ctx * row_bytes - (int64_t)kvh * (kD * 2));
+    const u32x4 srdk = make_srd(kbase, span);
+    const u32x4 srdv = make_srd(vbase, span);
+
+    const int q_row = active ? r0 : q_begin; // an idle wave still loads (and ignores) valid rows
+    const int64_t qo = (((int64_t)b * a.max_q + q_row) * a.n_q_heads + head) * kD * 2;
+    const char *qp = (const char *)a.q + qo;
+    char *op = (char *)a.out + qo;
+    const uint32_t q_row_stride = (uint32_t)a.n_q_heads * kD * 2;
+    const uint32_t rv_clamp = active ? (uint32_t)min(rows_valid, 64) : 1u;
+    const float cs = a.scale_log2e;
+    const float thr = 8.0f / cs;
+
+    const uint32_t lds_base = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)lds);
+    const uint32_t tid = threadIdx.x;
+
+#define SKV_PIPE_OPERANDS                                                                              \
+    [srdk] "s"(srdk), [srdv] "s"(srdv), [qp] "s"(qp), [op] "s"(op), [lds] "s"(uni(lds_base)),         \
+        [qrs] "s"(uni(q_row_stride)), [rv] "s"(uni(rv_clamp)), [rvs] "s"(uni((uint32_t)rows_valid)),   \
+        [krb] "s"(uni((uint32_t)row_bytes)), [nk1] "s"(uni((uint32_t)(n_keys - 1))),                   \
+        [nt] "s"(uni((uint32_t)n_tiles)), [tms] "s"(uni((uint32_t)t_mask)),                            \
+        [twl] "s"(uni((uint32_t)tw_last)), [p0] "s"(uni((uint32_t)p0)),                                \
+        [cs] "s"(uni(__builtin_bit_cast(uint32_t, cs))), [thr] "s"(uni(__builtin_bit_cast(uint32_t, thr))), \
+        [tid] "v"(tid)
+
+    if constexpr (BF16) {
+        asm volatile(SKV_PIPE_ASM_BF16 : : SKV_PIPE_OPERANDS : SKV_PIPE_CLOBBERS);
+    } else {
+        asm volatile(SKV_PIPE_ASM_F16 : : SKV_PIPE_OPERANDS : SKV_PIPE_CLOBBERS);
+    }
+#undef SKV_PIPE_OPERANDS
+}
+
+} // namespace
+
+bool prefill_pipe_supported(const AttnArgs &a, int dtype, int head_dim) {
+    if (!(dtype == SKV_BF16 || dtype == SKV_F16) || head_dim != kD) return false;
+    if (a.cache.block_table != nullptr) return false; // paged caches take the plain kernel
+    // 32-bit byte offsets inside one sequence's region of the slot, 24-bit multiplier operands
+    const int64_t row_bytes = (int64_t)a.cache.n_kv_heads * kD * 2;
+    if (row_bytes >= (1 << 24) || a.cache.max_ctx >= (1 << 24)) return false;
+    if ((int64_t)a.cache.max_ctx * row_bytes >= ((int64_t)1 << 32)) return false;
+    if ((int64_t)a.n_q_heads * kD * 2 >= (1 << 24)) return false;
+    return true;
+}
+
+hipError_t launch_prefill_pipe(const AttnArgs &a, int dtype, int group, hipStream_t stream) {
+    const int n_qt = (a.max_q + kRowsPerGroup - 1) / kRowsPerGroup;
+    const int pairs = a.batch * a.cache.n_kv_heads;
+    const int64_t blocks = (int64_t)pairs * group * n_qt;
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    const int xcd_map = (pairs % 8) == 0;
+    if (dtype == SKV_BF16)
+        prefill_pipe_kernel<true><<<dim3((unsigned)blocks), 256, 0, stream>>>(a, group, n_qt, xcd_map);
+    else
+        prefill_pipe_kernel<false><<<dim3((unsigned)blocks), 256, 0, stream>>>(a, group, n_qt, xcd_map);
+    set_last_kernel_name("prefill_pipe_kernel");
+    return hipGetLastError();
+}
+
+} // namespace skv

@@ -4,6 +4,7 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <cstring>
 #include <new>
 #include <vector>
 
@@ -351,7 +352,14 @@ skv_status_t skv_attn_prefill(skv_cache_t *c, int32_t layer, const void *q, void
 
     const int g = c->d.n_q_heads / c->d.n_kv_heads;
     hipError_t e;
-    if (skv::prefill_mfma_supported(c->d.dtype, c->d.head_dim, g))
+    // SKV_PREFILL_KERNEL=plain keeps the pipelined kernel out (for A/B timing and fault finding)
+    static const bool no_pipe = [] {
+        const char *v = getenv("SKV_PREFILL_KERNEL");
+        return v && strcmp(v, "plain") == 0;
+    }();
+    if (!no_pipe && skv::prefill_pipe_supported(a, c->d.dtype, c->d.head_dim))
+        e = skv::launch_prefill_pipe(a, c->d.dtype, g, (hipStream_t)stream);
+    else if (skv::prefill_mfma_supported(c->d.dtype, c->d.head_dim, g))
         e = skv::launch_prefill_mfma(a, c->d.dtype, c->d.head_dim, g, (hipStream_t)stream);
     else
         e = skv::launch_attn_valu(a, c->d.dtype, c->d.head_dim, g, (hipStream_t)stream);

@@ -64,6 +64,10 @@ hipError_t launch_decode_mfma(const AttnArgs &a, int dtype, int head_dim, int gr
 bool prefill_mfma_supported(int dtype, int head_dim, int group);
 hipError_t launch_prefill_mfma(const AttnArgs &a, int dtype, int head_dim, int group, hipStream_t stream);
 
+// Software-pipelined pre-fill kernel (16-bit, head_dim 128, contiguous caches below 4 GiB per sequence).
+bool prefill_pipe_supported(const AttnArgs &a, int dtype, int head_dim);
+hipError_t launch_prefill_pipe(const AttnArgs &a, int dtype, int group, hipStream_t stream);
+
 void set_last_kernel_name(const char *name);
 
 } // namespace skv

@@ -103,6 +103,6 @@ def test_config3_llama3_prefill_bf16_full_size():
                 worst = max(worst, float(np.abs(oh[i] - want).max()))
         print(f"layer {layer}: worst so far {worst:.3e}", flush=True)
     assert skv.skv_cache_device_faults(cache) == 0
-    assert skv.skv_last_kernel_name() == "prefill_mfma_kernel"
+    assert skv.skv_last_kernel_name() == "prefill_pipe_kernel"
     assert worst <= H.TOL["bf16"]
     cache.free()
