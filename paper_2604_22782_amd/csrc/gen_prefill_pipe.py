@@ -22,8 +22,7 @@ Register map (per lane):
   a[192:223]  K and V rows on their way from HBM to LDS (4 + 4 x 16 bytes)
   v[32:63], v[64:95]    S^T of even / odd half tiles [nq][16]
   v[96:111], v[112:127] P^T (16-bit pairs) of even / odd half tiles [nq][k step of 16 keys][4]
-  v[128:143], v[144:159] rings of 4 K / V^T operands read from LDS
-  v[160:...]  softmax state, lane constants, addresses
+  v[128:...]  rings of K / V^T operands read from LDS, then softmax state, lane constants, addresses
   v[0:23], s[0:39] are left to the compiler for the operands of the asm statement.
 
 Hazards the hardware does not interlock (MFMA result read by the vector ALU, transcendental
@@ -32,6 +31,7 @@ opcodes) are kept apart by construction or by s_nop; see the comments at the emi
 """
 from __future__ import annotations
 
+import os
 import sys
 
 K_STRIDE = 272            # bytes per K row in LDS (256 + 16: 16 rows x 16 B hit distinct banks)
@@ -43,32 +43,38 @@ N_STAGE = 4
 LDS_BYTES = N_STAGE * STAGE
 
 # ---- register names ---------------------------------------------------------------------------
+PD = int(os.environ.get("SKV_GEN_PD", "2"))      # operand groups fetched ahead of the MFMAs that use them
+RING = int(os.environ.get("SKV_GEN_RING", "4"))  # operand buffers per ring (> PD)
+
 SA, SB = 32, 64
 PA, PB = 96, 112
-KO, VO = 128, 144
-T_MAX = (160, 161)
-T_MAX2 = (162, 163)
-M_NEW = (164, 165)
-M_RUN = (166, 167)
-NEG_MC = (168, 169)
-L_SUM = (170, 171)
-ALPHA = (172, 173)
-LIM = (174, 175)
-DIFF = (176, 177)
-LANE, COL, HH = 178, 179, 180
-KL, VL = 181, 182              # lane parts of the K / V^T read addresses (LDS base included)
-KA_CUR, KA_NXT = 183, 184      # K read address of tile t / t+1
-VA_PRV, VA_CUR = 185, 186      # V^T read address of tile t-1 / t
-WK, WV = 187, 188              # lane parts of the staging write addresses
-WA_K, WA_V = 189, 190          # staging write addresses of the current target stage
-ROWB, PIECE = 191, 192         # tid / 16, (tid % 16) * 16
-VOFF = (193, 194, 195, 196)    # byte offsets of this lane's 4 rows of the tile being fetched
-NEG_INF = 197
-TMP = tuple(range(198, 214))   # scratch
-Q_OFF = (214, 215)
-O_OFF = (216, 217)
-ROW = (218, 219)
-STG = 220                      # scratch of the staging address arithmetic
+KO = 128
+VO = KO + 4 * RING
+_T = VO + 4 * RING
+T_MAX = (_T + 0, _T + 1)
+T_MAX2 = (_T + 2, _T + 3)
+M_NEW = (_T + 4, _T + 5)
+M_RUN = (_T + 6, _T + 7)
+NEG_MC = (_T + 8, _T + 9)
+L_SUM = (_T + 10, _T + 11)
+ALPHA = (_T + 12, _T + 13)
+LIM = (_T + 14, _T + 15)
+DIFF = (_T + 16, _T + 17)
+LANE, COL, HH = _T + 18, _T + 19, _T + 20
+KL, VL = _T + 21, _T + 22              # lane parts of the K / V^T read addresses (LDS base included)
+KA_CUR, KA_NXT = _T + 23, _T + 24      # K read address of tile t / t+1
+VA_PRV, VA_CUR = _T + 25, _T + 26      # V^T read address of tile t-1 / t
+WK, WV = _T + 27, _T + 28              # lane parts of the staging write addresses
+WA_K, WA_V = _T + 29, _T + 30          # staging write addresses of the current target stage
+ROWB, PIECE = _T + 31, _T + 32         # tid / 16, (tid % 16) * 16
+VOFF = (_T + 33, _T + 34, _T + 35, _T + 36)  # byte offsets of this lane's 4 rows of the tile being fetched
+NEG_INF = _T + 37
+TMP = tuple(range(_T + 38, _T + 54))   # scratch
+Q_OFF = (_T + 54, _T + 55)
+O_OFF = (_T + 56, _T + 57)
+ROW = (_T + 58, _T + 59)
+STG = _T + 60                          # scratch of the staging address arithmetic
+assert STG < 256 and PD < RING
 
 A_O, A_Q, A_LK, A_LV = 0, 128, 192, 208
 
@@ -81,8 +87,6 @@ S_NK1 = 56
 
 FIRST_V, FIRST_S, LAST_S = 24, 40, 59
 
-PD = 2  # operand groups fetched ahead of the MFMAs that use them
-
 
 class Asm:
     def __init__(self, dt: str):
@@ -93,7 +97,7 @@ class Asm:
         self.uid = 0
 
     def e(self, s: str):
-        self.lines.append(s)
+        self.lines.extend(s.split("\n"))
 
     def c(self, s: str):
         self.lines.append("// " + s)
@@ -169,29 +173,35 @@ def softmax_stream(A: Asm, s_cur: int, p_cur: int, masked: bool, tagid: str):
     o.append(f"v_cmp_lt_f32_e64 {sr(S_CMP, 2)}, %[thr], {vr(DIFF[0])}")
     o.append(f"v_cmp_lt_f32_e32 vcc, %[thr], {vr(DIFF[1])}")
     o.append(f"s_or_b64 vcc, vcc, {sr(S_CMP, 2)}")
-    o.append(f"s_cbranch_vccnz L_RESC_{tagid}_%=")
-    o.append(f"L_RET_{tagid}_%=:")
-    for r in range(16):
-        for q in range(2):
+    # one entry: nothing may be scheduled between the branch and the label its target returns to
+    o.append(f"s_cbranch_vccnz L_RESC_{tagid}_%=\nL_RET_{tagid}_%=:")
+    # weights 2^(cs s - cs m), their row sums and their 16-bit form, software-pipelined element by
+    # element so that the slow transcendental instructions are spread evenly between the MFMAs
+    # (a run of them would leave the matrix cores waiting for the in-order instruction stream).
+    # A v_exp result is first read two instructions later; v_dot2 would sum the rounded pairs in one
+    # instruction but runs on the matrix pipeline and does not overlap with MFMAs.
+    elems = [(i % 2, i // 2) for i in range(32)]  # (q, r), alternating row blocks
+
+    def pack(q, j):
+        d = p_cur + 8 * q + j
+        if A.dt == "bf16":
+            return [f"v_cvt_pk_bf16_f32 {vr(d)}, {vr(S[q][2 * j])}, {vr(S[q][2 * j + 1])}"]
+        return [f"v_cvt_f16_f32_e32 {vr(S[q][2 * j])}, {vr(S[q][2 * j])}",
+                f"v_cvt_f16_f32_e32 {vr(S[q][2 * j + 1])}, {vr(S[q][2 * j + 1])}",
+                f"v_pack_b32_f16 {vr(d)}, {vr(S[q][2 * j])}, {vr(S[q][2 * j + 1])}"]
+
+    for i in range(32 + 4):
+        if i < 32:
+            q, r = elems[i]
             o.append(f"v_fma_f32 {vr(S[q][r])}, {vr(S[q][r])}, %[cs], {vr(NEG_MC[q])}")
-    for r in range(16):
-        for q in range(2):
+        if 2 <= i < 34:
+            q, r = elems[i - 2]
             o.append(f"v_exp_f32_e32 {vr(S[q][r])}, {vr(S[q][r])}")
-    # 16-bit weights: register j of block (q, x) packs elements 8x + 2j, 8x + 2j + 1
-    for j in range(8):
-        for q in range(2):
-            d = p_cur + 8 * q + j
-            if A.dt == "bf16":
-                o.append(f"v_cvt_pk_bf16_f32 {vr(d)}, {vr(S[q][2 * j])}, {vr(S[q][2 * j + 1])}")
-            else:
-                o.append(f"v_cvt_f16_f32_e32 {vr(S[q][2 * j])}, {vr(S[q][2 * j])}")
-                o.append(f"v_cvt_f16_f32_e32 {vr(S[q][2 * j + 1])}, {vr(S[q][2 * j + 1])}")
-                o.append(f"v_pack_b32_f16 {vr(d)}, {vr(S[q][2 * j])}, {vr(S[q][2 * j + 1])}")
-    # row sums of the rounded weights (the same values the second product uses)
-    for j in range(8):
-        for q in range(2):
-            d = p_cur + 8 * q + j
-            o.append(f"v_dot2_f32_{A.dt} {vr(L_SUM[q])}, {vr(d)}, {sr(S_ONES)}, {vr(L_SUM[q])}")
+        if 4 <= i < 36:
+            q, r = elems[i - 4]
+            o.append(f"v_add_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}, {vr(S[q][r])}")
+            if r % 2 == 1:  # both elements of register pair (q, r / 2) are final
+                o += pack(q, r // 2)
     if masked:
         for q in range(2):
             o.append(f"v_subrev_u32_e32 {vr(LIM[q])}, 32, {vr(LIM[q])}")
@@ -235,13 +245,13 @@ def rescale_blocks(A: Asm, tagid: str):
 
 # ---- operand reads -----------------------------------------------------------------------------
 def k_read(A: Asm, addr: int, kb: int, g: int, tag):
-    dst = KO + 4 * (g % 4)
+    dst = KO + 4 * (g % RING)
     A.lds_op(f"ds_read_b128 {vr(dst, 4)}, {vr(addr)} offset:{kb * 32 * K_STRIDE + g * 32}", tag)
 
 
 def v_read(A: Asm, addr: int, kb: int, g: int, tag_lo, tag_hi):
     x, db = g // 4, g % 4
-    dst = VO + 4 * (g % 4)
+    dst = VO + 4 * (g % RING)
     off = (kb * 32 + 16 * x) * V_STRIDE + db * 64
     A.lds_op(f"ds_read_b64_tr_b16 {vr(dst, 2)}, {vr(addr)} offset:{off}", tag_lo)
     A.lds_op(f"ds_read_b64_tr_b16 {vr(dst + 2, 2)}, {vr(addr)} offset:{off + 8 * V_STRIDE}", tag_hi)
@@ -254,13 +264,13 @@ def half_step(A: Asm, hs: int, qk, pv, sm, nxt, extra, tagid: str, cold=False):
     sm  = (S source base, P destination base, masked) or None
     nxt = ((K address register, key block) or None, (V address register, key block) or None):
           operands of the next half step's first PD groups, fetched at the end of this one
-    extra = instructions for the first four gaps (staging); entries are strings, or
-          ("lds", text, tag) for LDS writes.
+    extra = {gap: [instructions]} (staging); entries are strings, or ("lds", text, tag) for LDS
+          writes.
     hs  = serial number of the half step inside the emitted code (tags of its operand reads)."""
     valu = softmax_stream(A, sm[0], sm[1], sm[2], tagid) if sm else []
     gaps = [[] for _ in range(32)]
-    for i, ins in enumerate(extra):
-        gaps[min(3, i * 4 // max(1, len(extra)))].append(ins)
+    for gi, lst in (extra or {}).items():
+        gaps[gi].extend(lst)
     # the softmax starts after the first group of MFMAs: the last S^T MFMA of the previous half
     # step is then >= 5 MFMAs old when the vector ALU first reads its result
     first, n_gap = 4, 28
@@ -294,7 +304,7 @@ def half_step(A: Asm, hs: int, qk, pv, sm, nxt, extra, tagid: str, cold=False):
             fetch(hs, g + PD, kcfg, vcfg)
         elif nxt is not None:
             fetch(hs + 1, g + PD - 8, nxt[0], nxt[1])
-        ko, vo = KO + 4 * (g % 4), VO + 4 * (g % 4)
+        ko, vo = KO + 4 * (g % RING), VO + 4 * (g % RING)
         for q in range(2):
             if qk:
                 if q == 0:
@@ -338,36 +348,39 @@ def voffsets(j0_sreg: int):
     return o
 
 
-def tile_loads():
-    o = []
-    for i in range(4):
-        o.append(f"buffer_load_dwordx4 {ar(A_LK + 4 * i, 4)}, {vr(VOFF[i])}, %[srdk], 0 offen")
-        o.append(f"buffer_load_dwordx4 {ar(A_LV + 4 * i, 4)}, {vr(VOFF[i])}, %[srdv], 0 offen")
-    return o
+def tile_loads(which: str):
+    base, srd = (A_LK, "%[srdk]") if which == "k" else (A_LV, "%[srdv]")
+    return [f"buffer_load_dwordx4 {ar(base + 4 * i, 4)}, {vr(VOFF[i])}, {srd}, 0 offen" for i in range(4)]
 
 
-def tile_writes(A: Asm):
-    o = []
-    for i in range(4):
-        o.append(("lds", f"ds_write_b128 {vr(WA_K)}, {ar(A_LK + 4 * i, 4)} offset:{16 * i * K_STRIDE}", ("W", A.fresh())))
-        o.append(("lds", f"ds_write_b128 {vr(WA_V)}, {ar(A_LV + 4 * i, 4)} offset:{16 * i * V_STRIDE}", ("W", A.fresh())))
-    return o
+def tile_writes(A: Asm, which: str):
+    base, addr, stride = (A_LK, WA_K, K_STRIDE) if which == "k" else (A_LV, WA_V, V_STRIDE)
+    return [("lds", f"ds_write_b128 {vr(addr)}, {ar(base + 4 * i, 4)} offset:{16 * i * stride}", ("W", A.fresh()))
+            for i in range(4)]
 
 
-def staging_ops(A: Asm):
-    """Tile t+2 (fetched a tile ago) goes to its LDS stage, then tile t+3 is requested."""
-    o = ["s_waitcnt vmcnt(0)",
-         f"s_add_u32 {sr(S_TMP)}, {sr(S_T)}, 2",
-         f"s_and_b32 {sr(S_TMP)}, {sr(S_TMP)}, 3",
-         f"s_mul_i32 {sr(S_STW)}, {sr(S_TMP)}, {STAGE}",
-         f"v_add_u32_e32 {vr(WA_K)}, {sr(S_STW)}, {vr(WK)}",
-         f"v_add_u32_e32 {vr(WA_V)}, {sr(S_STW)}, {vr(WV)}"]
-    o += tile_writes(A)
-    o += [f"s_lshl_b32 {sr(S_J0)}, {sr(S_T)}, 6",
-          f"s_add_u32 {sr(S_J0)}, {sr(S_J0)}, 192"]
-    o += voffsets(S_J0)
-    o += tile_loads()
-    return o
+def staging_ops(A: Asm, which: str):
+    """K (first half step) or V (second) rows of tile t+2, requested a tile ago, go to their LDS
+    stage; then the rows of tile t+3 are requested.  Returns {gap: [instructions]}: memory
+    instructions are kept four gaps apart, a burst of them would hold up the in-order stream and
+    starve the matrix cores.  The other tensor's four loads are still in flight: vmcnt(4)."""
+    g = {0: ["s_waitcnt vmcnt(4)"]}
+    if which == "k":
+        g[0] += [f"s_add_u32 {sr(S_TMP)}, {sr(S_T)}, 2",
+                 f"s_and_b32 {sr(S_TMP)}, {sr(S_TMP)}, 3",
+                 f"s_mul_i32 {sr(S_STW)}, {sr(S_TMP)}, {STAGE}",
+                 f"v_add_u32_e32 {vr(WA_K)}, {sr(S_STW)}, {vr(WK)}",
+                 f"v_add_u32_e32 {vr(WA_V)}, {sr(S_STW)}, {vr(WV)}"]
+    for i, w in enumerate(tile_writes(A, which)):
+        g[1 + 4 * i] = [w]
+    if which == "k":
+        g[15] = [f"s_lshl_b32 {sr(S_J0)}, {sr(S_T)}, 6", f"s_add_u32 {sr(S_J0)}, {sr(S_J0)}, 192"]
+        vo = voffsets(S_J0)
+        g[15] += vo[:6]
+        g[16] = vo[6:]
+    for i, l in enumerate(tile_loads(which)):
+        g[17 + 4 * i] = [l]
+    return g
 
 
 def rotate_addresses(A: Asm):
@@ -387,9 +400,9 @@ def body(A: Asm, masked: bool, name: str):
     A.reset_lds(pending_reads(0))
     rotate_addresses(A)
     half_step(A, 0, qk=(KA_CUR, 1, SB), pv=(VA_PRV, 1, PB), sm=(SA, PA, masked),
-              nxt=((KA_NXT, 0), (VA_CUR, 0)), extra=[], tagid=name + "0")
+              nxt=((KA_NXT, 0), (VA_CUR, 0)), extra=staging_ops(A, "k"), tagid=name + "0")
     half_step(A, 1, qk=(KA_NXT, 0, SA), pv=(VA_CUR, 0, PA), sm=(SB, PB, masked),
-              nxt=((KA_NXT, 1), (VA_CUR, 1)), extra=staging_ops(A), tagid=name + "1")
+              nxt=((KA_NXT, 1), (VA_CUR, 1)), extra=staging_ops(A, "v"), tagid=name + "1")
     # every staging write is older than the last operand read that was waited for
     last_w = max(i for i, t in enumerate(A.lds) if t[0] == "W")
     assert last_w <= A.waited, (last_w, A.waited)
@@ -398,11 +411,11 @@ def body(A: Asm, masked: bool, name: str):
 
 
 def body_stage_only(A: Asm):
-    for ins in staging_ops(A):
-        if isinstance(ins, tuple):
-            A.e(ins[1])
-        else:
-            A.e(ins)
+    for which in ("k", "v"):
+        ops = staging_ops(A, which)
+        for gi in sorted(ops):
+            for ins in ops[gi]:
+                A.e(ins[1] if isinstance(ins, tuple) else ins)
     A.e("s_waitcnt lgkmcnt(0)")
     A.e("s_barrier")
 
@@ -474,18 +487,18 @@ def generate(dt: str) -> list[str]:
     e(f"s_mov_b32 {sr(S_FLAG)}, 0")
     e(f"s_mov_b32 {sr(S_T)}, 0")
 
-    A.c("tiles 0 and 1 to LDS, tile 2 requested")
+    A.c("tiles 0 and 1 to LDS, tile 2 requested (K rows first, then V rows)")
     for x in range(3):
         e(f"s_movk_i32 {sr(S_J0)}, {64 * x}")
         for ins in voffsets(S_J0):
             e(ins)
-        for ins in tile_loads():
+        for ins in tile_loads("k") + tile_loads("v"):
             e(ins)
         if x < 2:
             e("s_waitcnt vmcnt(0)")
             e(f"v_add_u32_e32 {vr(WA_K)}, {x * STAGE}, {vr(WK)}")
             e(f"v_add_u32_e32 {vr(WA_V)}, {x * STAGE}, {vr(WV)}")
-            for ins in tile_writes(A):
+            for ins in tile_writes(A, "k") + tile_writes(A, "v"):
                 e(ins[1])
     A.c("the first half step multiplies zero weights with the V part of stage 3: make it finite")
     e(f"v_mul_u32_u24_e32 {vr(TMP[0])}, 80, %[tid]")
@@ -575,7 +588,7 @@ def generate(dt: str) -> list[str]:
 
     A.c("remaining tiles of the work group: staging and barriers only")
     e("L_STAGE_%=:")
-    e("s_waitcnt lgkmcnt(0)")
+    e("s_waitcnt vmcnt(0) lgkmcnt(0)")  # also the output stores: loads and stores may retire out of order
     e("L_STAGE_LOOP_%=:")
     e(f"s_cmp_ge_i32 {sr(S_T)}, %[nt]")
     e("s_cbranch_scc1 L_END_%=")
