@@ -5,8 +5,9 @@
 Why a generated stream: the kernel keeps one wave per SIMD busy with 64 query rows, and its inner
 loop only reaches the matrix-core rate if every MFMA is followed by a handful of independent
 vector instructions (softmax of the previous 32 keys), LDS operand reads two operands ahead and
-the staging traffic of the tile three tiles ahead.  The order of ~450 instructions per 64-key
-tile and the ~400 registers per lane are fixed here.
+now and then a memory instruction of the tile three tiles ahead.  A lone wave issues in order:
+a burst of slow instructions (transcendentals, memory) anywhere starves the matrix cores, so the
+order of the ~450 instructions per 64-key tile and the ~400 registers per lane are fixed here.
 
 What is computed (paper Eq. (3.1), pre-fill phase of Sec. 3.1.1): for a wave's 64 query rows
 (two blocks of 32, "nq" = 0, 1) and the keys 0..position of each row,
@@ -16,29 +17,36 @@ Keys are walked in half tiles of 32 ("u"); a half step runs, interleaved,
   vector ALU:    max / exp2 / row sums / 16-bit weights of S^T(u)
 so the three stages of three consecutive half tiles are in flight at once.
 
+K/V tiles (64 keys) go from HBM straight into LDS (buffer_load ... lds, no registers): lane L of
+such a load writes 16 bytes at M0 + 16 L, so one instruction fills a 1 KiB chunk = 4 rows.  Inside
+a chunk the 16-byte piece p of row r sits at 64 p + 16 r (piece-major), and chunks are 1088 bytes
+apart: both the 128-bit K operand reads (16 lanes = 16 consecutive rows, one piece) and the
+transposing 64-bit V reads (4 rows x 32 bytes per 16 lanes) then touch every bank exactly once.
+Four tile stages form a ring.  Tile t+3 is requested in the second half of tile t (its stage held
+tile t-1, last read in the first half); one barrier per tile, placed after every wave has waited
+for its own loads of tile t+1 and for its last reads of tile t-1, publishes the former and
+releases the latter.  A load is in flight for about 1.75 tiles before anybody waits for it.
+
 Register map (per lane):
   a[0:127]    O^T accumulators  [nq][d block of 32][16]
   a[128:191]  Q^T as MFMA B operand [nq][k step of 16][4]
-  a[192:223]  K and V rows on their way from HBM to LDS (4 + 4 x 16 bytes)
   v[32:63], v[64:95]    S^T of even / odd half tiles [nq][16]
   v[96:111], v[112:127] P^T (16-bit pairs) of even / odd half tiles [nq][k step of 16 keys][4]
   v[128:...]  rings of K / V^T operands read from LDS, then softmax state, lane constants, addresses
   v[0:23], s[0:39] are left to the compiler for the operands of the asm statement.
 
 Hazards the hardware does not interlock (MFMA result read by the vector ALU, transcendental
-result read by the next instruction, lane-swap operands, dot-product results read by other
-opcodes) are kept apart by construction or by s_nop; see the comments at the emit sites.
+result read by the next instruction, lane-swap operands, M0 written right before a load to LDS)
+are kept apart by construction or by s_nop; see the comments at the emit sites.
 """
 from __future__ import annotations
 
 import os
 import sys
 
-K_STRIDE = 272            # bytes per K row in LDS (256 + 16: 16 rows x 16 B hit distinct banks)
-V_STRIDE = 320            # bytes per V row in LDS
-K_BYTES = 64 * K_STRIDE
-V_BYTES = 64 * V_STRIDE
-STAGE = K_BYTES + V_BYTES  # one 64-key tile of K and V
+CHUNK = 1088              # 4 rows x 256 bytes + 64 bytes of padding
+T_BYTES = 16 * CHUNK      # one tensor (K or V) of a 64-key tile
+STAGE = 2 * T_BYTES       # K then V
 N_STAGE = 4
 LDS_BYTES = N_STAGE * STAGE
 
@@ -64,24 +72,35 @@ LANE, COL, HH = _T + 18, _T + 19, _T + 20
 KL, VL = _T + 21, _T + 22              # lane parts of the K / V^T read addresses (LDS base included)
 KA_CUR, KA_NXT = _T + 23, _T + 24      # K read address of tile t / t+1
 VA_PRV, VA_CUR = _T + 25, _T + 26      # V^T read address of tile t-1 / t
-WK, WV = _T + 27, _T + 28              # lane parts of the staging write addresses
-WA_K, WA_V = _T + 29, _T + 30          # staging write addresses of the current target stage
-ROWB, PIECE = _T + 31, _T + 32         # tid / 16, (tid % 16) * 16
-VOFF = (_T + 33, _T + 34, _T + 35, _T + 36)  # byte offsets of this lane's 4 rows of the tile being fetched
-NEG_INF = _T + 37
-TMP = tuple(range(_T + 38, _T + 54))   # scratch
-Q_OFF = (_T + 54, _T + 55)
-O_OFF = (_T + 56, _T + 57)
-ROW = (_T + 58, _T + 59)
-STG = _T + 60                          # scratch of the staging address arithmetic
-assert STG < 256 and PD < RING
+ROWB, PIECE = _T + 27, _T + 28         # staging: first row of this lane in a tile, byte offset of its piece
+VOFF = (_T + 29, _T + 30, _T + 31, _T + 32)  # byte offsets of this lane's 4 rows of the tile being fetched
+NEG_INF = _T + 33
+TMP = tuple(range(_T + 34, _T + 50))   # scratch (16, 8-aligned halves not required)
+Q_OFF = (_T + 50, _T + 51)
+O_OFF = (_T + 52, _T + 53)
+ROW = (_T + 54, _T + 55)
+STG = _T + 56                          # scratch of the staging address arithmetic
+ONES4 = _T + 58                        # 4 registers of 16-bit ones (A operand of the row-sum MFMA)
+assert ONES4 % 2 == 0 and ONES4 + 3 < 256 and PD < RING
+assert TMP[4] % 2 == 0 and TMP[12] % 2 == 0   # 64-bit store operands
 
-A_O, A_Q, A_LK, A_LV = 0, 128, 192, 208
+A_O, A_Q, A_L = 0, 128, 192
+# Row sums of the weights by one extra MFMA per 16 keys and row block (an all-ones A operand
+# makes every row of the product the column sum) instead of 32 vector additions per half step.
+SUM_BY_MFMA = os.environ.get("SKV_GEN_SUM_MFMA", "0") == "1"
+# softmax software pipeline: element i gets its fma at step i, its exponential EXP_LAG steps later,
+# and is first read (row sum, 16-bit packing) USE_LAG steps later
+EXP_LAG = int(os.environ.get("SKV_GEN_EXP_LAG", "2"))
+USE_LAG = int(os.environ.get("SKV_GEN_USE_LAG", "4"))
+assert 1 <= EXP_LAG < USE_LAG
+# first gap of a half step that takes softmax instructions.  The vector ALU may read an MFMA result
+# only 11 issued instructions after the MFMA (no hardware interlock); check_mfma_results() verifies it.
+FIRST_GAP = int(os.environ.get("SKV_GEN_FIRST_GAP", "0"))
 
 S_T, S_TMP, S_STW, S_J0, S_FLAG = 40, 41, 42, 43, 44
 S_CMP = 46                     # pair
 S_ST_NXT, S_ST_CUR = 48, 49
-S_ONES, S_NCS, S_C272, S_C320 = 50, 51, 52, 53
+S_ONES, S_NCS, S_WBASE = 50, 51, 52
 S_EXEC = 54                    # pair
 S_NK1 = 56
 
@@ -190,16 +209,17 @@ def softmax_stream(A: Asm, s_cur: int, p_cur: int, masked: bool, tagid: str):
                 f"v_cvt_f16_f32_e32 {vr(S[q][2 * j + 1])}, {vr(S[q][2 * j + 1])}",
                 f"v_pack_b32_f16 {vr(d)}, {vr(S[q][2 * j])}, {vr(S[q][2 * j + 1])}"]
 
-    for i in range(32 + 4):
+    for i in range(32 + USE_LAG):
         if i < 32:
             q, r = elems[i]
             o.append(f"v_fma_f32 {vr(S[q][r])}, {vr(S[q][r])}, %[cs], {vr(NEG_MC[q])}")
-        if 2 <= i < 34:
-            q, r = elems[i - 2]
+        if EXP_LAG <= i < 32 + EXP_LAG:
+            q, r = elems[i - EXP_LAG]
             o.append(f"v_exp_f32_e32 {vr(S[q][r])}, {vr(S[q][r])}")
-        if 4 <= i < 36:
-            q, r = elems[i - 4]
-            o.append(f"v_add_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}, {vr(S[q][r])}")
+        if USE_LAG <= i < 32 + USE_LAG:
+            q, r = elems[i - USE_LAG]
+            if not SUM_BY_MFMA:
+                o.append(f"v_add_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}, {vr(S[q][r])}")
             if r % 2 == 1:  # both elements of register pair (q, r / 2) are final
                 o += pack(q, r // 2)
     if masked:
@@ -221,8 +241,9 @@ def rescale_blocks(A: Asm, tagid: str):
         A.e(f"v_mov_b32_e32 {vr(M_RUN[q])}, {vr(M_NEW[q])}")
     for q in range(2):
         A.e(f"v_mul_f32_e32 {vr(NEG_MC[q])}, {sr(S_NCS)}, {vr(M_NEW[q])}")
-    for q in range(2):  # >= 4 instructions after the exponentials and far from the last dot product
-        A.e(f"v_mul_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}, {vr(ALPHA[q])}")
+    if not SUM_BY_MFMA:
+        for q in range(2):  # >= 4 instructions after the exponentials
+            A.e(f"v_mul_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}, {vr(ALPHA[q])}")
     A.e(f"s_mov_b32 {sr(S_FLAG)}, 1")
     A.e(f"s_branch L_RET_{tagid}_%=")
 
@@ -238,6 +259,13 @@ def rescale_blocks(A: Asm, tagid: str):
                 A.e(f"v_mul_f32_e32 {vr(TMP[k])}, {vr(TMP[k])}, {vr(ALPHA[q])}")
             for k in range(8):
                 A.e(f"v_accvgpr_write_b32 {ar(A_O + 64 * q + i + k)}, {vr(TMP[k])}")
+    if SUM_BY_MFMA:
+        for q in range(2):
+            A.e(f"v_accvgpr_read_b32 {vr(TMP[q])}, {ar(A_L + 16 * q)}")
+        for q in range(2):
+            A.e(f"v_mul_f32_e32 {vr(TMP[q])}, {vr(TMP[q])}, {vr(ALPHA[q])}")
+        for q in range(2):
+            A.e(f"v_accvgpr_write_b32 {ar(A_L + 16 * q)}, {vr(TMP[q])}")
     A.e("s_nop 7")
     A.e(f"s_mov_b32 {sr(S_FLAG)}, 0")
     A.e(f"s_branch L_RESO_RET_{tagid}_%=")
@@ -246,47 +274,57 @@ def rescale_blocks(A: Asm, tagid: str):
 # ---- operand reads -----------------------------------------------------------------------------
 def k_read(A: Asm, addr: int, kb: int, g: int, tag):
     dst = KO + 4 * (g % RING)
-    A.lds_op(f"ds_read_b128 {vr(dst, 4)}, {vr(addr)} offset:{kb * 32 * K_STRIDE + g * 32}", tag)
+    A.lds_op(f"ds_read_b128 {vr(dst, 4)}, {vr(addr)} offset:{kb * 8 * CHUNK + g * 128}", tag)
 
 
 def v_read(A: Asm, addr: int, kb: int, g: int, tag_lo, tag_hi):
     x, db = g // 4, g % 4
     dst = VO + 4 * (g % RING)
-    off = (kb * 32 + 16 * x) * V_STRIDE + db * 64
+    off = (kb * 8 + 4 * x) * CHUNK + db * 256
     A.lds_op(f"ds_read_b64_tr_b16 {vr(dst, 2)}, {vr(addr)} offset:{off}", tag_lo)
-    A.lds_op(f"ds_read_b64_tr_b16 {vr(dst + 2, 2)}, {vr(addr)} offset:{off + 8 * V_STRIDE}", tag_hi)
+    A.lds_op(f"ds_read_b64_tr_b16 {vr(dst + 2, 2)}, {vr(addr)} offset:{off + 2 * CHUNK}", tag_hi)
 
 
-def half_step(A: Asm, hs: int, qk, pv, sm, nxt, extra, tagid: str, cold=False):
+def half_step(A: Asm, hs: int, qk, pv, sm, nxt, extra, tagid: str, cold=False, publish=False):
     """One half step.
     qk  = (K address register, key block, S destination base) or None
     pv  = (V address register, key block, P source base) or None
     sm  = (S source base, P destination base, masked) or None
     nxt = ((K address register, key block) or None, (V address register, key block) or None):
           operands of the next half step's first PD groups, fetched at the end of this one
-    extra = {gap: [instructions]} (staging); entries are strings, or ("lds", text, tag) for LDS
-          writes.
+    extra = {gap: [instructions]} (staging)
+    publish: before it requests the first operands of the next half step (the first reads of the
+          newly published tile) the wave waits for its loads of that tile and for its own
+          outstanding operand reads, then meets the other waves at the barrier.
     hs  = serial number of the half step inside the emitted code (tags of its operand reads)."""
     valu = softmax_stream(A, sm[0], sm[1], sm[2], tagid) if sm else []
-    gaps = [[] for _ in range(32)]
-    for gi, lst in (extra or {}).items():
-        gaps[gi].extend(lst)
-    # the softmax starts after the first group of MFMAs: the last S^T MFMA of the previous half
-    # step is then >= 5 MFMAs old when the vector ALU first reads its result
-    first, n_gap = 4, 28
-    per = [len(valu) * (i + 1) // n_gap - len(valu) * i // n_gap for i in range(n_gap)]
-    pos = 0
-    for i in range(n_gap):
-        gaps[first + i].extend(valu[pos:pos + per[i]])
-        pos += per[i]
-    assert pos == len(valu)
-
-    def emit_gap(i):
-        for ins in gaps[i]:
-            if isinstance(ins, tuple):
-                A.lds_op(ins[1], ins[2])
-            else:
-                A.e(ins)
+    # MFMAs of the half step in issue order; a "gap" of other instructions follows each of them
+    slots = []
+    for g in range(8):
+        for q in range(2):
+            if qk:
+                slots.append(("qk", g, q))
+            if pv:
+                slots.append(("pv", g, q))
+                if SUM_BY_MFMA and g % 4 == 0:
+                    slots.append(("sum", g, q))
+    n = len(slots)
+    gaps = [[] for _ in range(n)]
+    for gi, lst in (extra or {}).items():   # positions given on a scale of 32
+        gaps[gi * n // 32].extend(lst)
+    # An in-order wave reaches the next MFMA only after issuing everything before it: time per
+    # MFMA is max(32 clocks of the matrix pipe, issue time of its gap).  Spread the vector stream
+    # by issue cost (a transcendental costs about three plain instructions).
+    def cost(ins):
+        return 0 if ins.endswith(":") else 3 if ins.startswith("v_exp") else 1
+    total = sum(cost(i) for i in valu)
+    ngap = n - FIRST_GAP
+    done, gi = 0, 0
+    for ins in valu:
+        while gi < ngap - 1 and done >= total * (gi + 1) / ngap:
+            gi += 1
+        gaps[FIRST_GAP + gi].append(ins)
+        done += cost(ins)
 
     def fetch(hs_id, g, kcfg, vcfg):
         if kcfg:
@@ -299,28 +337,35 @@ def half_step(A: Asm, hs: int, qk, pv, sm, nxt, extra, tagid: str, cold=False):
     if cold:
         for g in range(PD):
             fetch(hs, g, kcfg, vcfg)
-    for g in range(8):
-        if g + PD < 8:
-            fetch(hs, g + PD, kcfg, vcfg)
-        elif nxt is not None:
-            fetch(hs + 1, g + PD - 8, nxt[0], nxt[1])
+    cur_g = -1
+    for si, (kind, g, q) in enumerate(slots):
+        if g != cur_g:   # first MFMA of operand group g
+            cur_g = g
+            if publish and g + PD == 8:
+                # every operand of this half step has been requested: wait for the last one (reads
+                # return in order), for this wave's loads of the tile after next, then meet the others
+                A.wait_lds(("Vh", hs, 7))
+                A.e("s_waitcnt vmcnt(8)")  # all but the 8 newest loads (the tile requested last) landed
+                A.e("s_barrier")
+            if g + PD < 8:
+                fetch(hs, g + PD, kcfg, vcfg)
+            elif nxt is not None:
+                fetch(hs + 1, g + PD - 8, nxt[0], nxt[1])
+            # one wait per group: the V^T pair was requested after the K operand and returns after it
+            A.wait_lds(("Vh", hs, g) if pv else ("K", hs, g))
         ko, vo = KO + 4 * (g % RING), VO + 4 * (g % RING)
-        for q in range(2):
-            if qk:
-                if q == 0:
-                    A.wait_lds(("K", hs, g))
-                s_dst = qk[2] + 16 * q
-                c_in = "0" if g == 0 else vr(s_dst, 16)
-                A.e(f"v_mfma_f32_32x32x16_{A.dt} {vr(s_dst, 16)}, {vr(ko, 4)}, {ar(A_Q + 32 * q + 4 * g, 4)}, {c_in}")
-            emit_gap(4 * g + 2 * q)
-            if pv:
-                if q == 0:
-                    A.wait_lds(("Vh", hs, g))
-                x, db = g // 4, g % 4
-                o_acc = A_O + 64 * q + 16 * db
-                p_src = pv[2] + 8 * q + 4 * x
-                A.e(f"v_mfma_f32_32x32x16_{A.dt} {ar(o_acc, 16)}, {vr(vo, 4)}, {vr(p_src, 4)}, {ar(o_acc, 16)}")
-            emit_gap(4 * g + 2 * q + 1)
+        if kind == "qk":
+            s_dst = qk[2] + 16 * q
+            c_in = "0" if g == 0 else vr(s_dst, 16)
+            A.e(f"v_mfma_f32_32x32x16_{A.dt} {vr(s_dst, 16)}, {vr(ko, 4)}, {ar(A_Q + 32 * q + 4 * g, 4)}, {c_in}")
+        else:
+            x, db = g // 4, g % 4
+            p_src = pv[2] + 8 * q + 4 * x
+            acc = A_O + 64 * q + 16 * db if kind == "pv" else A_L + 16 * q
+            a_op = vr(vo, 4) if kind == "pv" else vr(ONES4, 4)
+            A.e(f"v_mfma_f32_32x32x16_{A.dt} {ar(acc, 16)}, {a_op}, {vr(p_src, 4)}, {ar(acc, 16)}")
+        for ins in gaps[si]:
+            A.e(ins)
     if sm:
         A.e(f"s_cmp_lg_u32 {sr(S_FLAG)}, 0")
         A.e(f"s_cbranch_scc1 L_RESO_{tagid}_%=")
@@ -337,49 +382,43 @@ def pending_reads(hs, with_k=True, with_v=True):
     return out
 
 
-# ---- staging (HBM -> registers -> LDS) ------------------------------------------------------------
+# ---- staging (HBM -> LDS) -------------------------------------------------------------------------
 def voffsets(j0_sreg: int):
     o = []
     for i in range(4):
-        # key = min(j0 + tid / 16 + 16 i, last needed key): rows past it repeat it (finite, masked)
-        o.append(f"v_add3_u32 {vr(STG)}, {sr(j0_sreg)}, {vr(ROWB)}, {16 * i}")
+        # key = min(j0 + first row of the lane + 4 i, last needed key): rows past it repeat it
+        # (finite, and masked wherever they are not the real key)
+        o.append(f"v_add3_u32 {vr(STG)}, {sr(j0_sreg)}, {vr(ROWB)}, {4 * i}")
         o.append(f"v_min_u32_e32 {vr(STG)}, {sr(S_NK1)}, {vr(STG)}")
         o.append(f"v_mad_u32_u24 {vr(VOFF[i])}, {vr(STG)}, %[krb], {vr(PIECE)}")
     return o
 
 
-def tile_loads(which: str):
-    base, srd = (A_LK, "%[srdk]") if which == "k" else (A_LV, "%[srdv]")
-    return [f"buffer_load_dwordx4 {ar(base + 4 * i, 4)}, {vr(VOFF[i])}, {srd}, 0 offen" for i in range(4)]
+def tile_load(which: str, i: int, base_sreg: int):
+    """Chunk 4 w + i of K or V: lane L fetches piece L / 4 of row 4 (4 w + i) + L % 4."""
+    srd, off = ("%[srdk]", 0) if which == "k" else ("%[srdv]", T_BYTES)
+    return [f"s_add_u32 m0, {sr(base_sreg)}, {off + i * CHUNK}",
+            "s_nop 0",  # M0 must not be written by the instruction right before the load
+            f"buffer_load_dwordx4 {vr(VOFF[i])}, {srd}, 0 offen lds"]
 
 
-def tile_writes(A: Asm, which: str):
-    base, addr, stride = (A_LK, WA_K, K_STRIDE) if which == "k" else (A_LV, WA_V, V_STRIDE)
-    return [("lds", f"ds_write_b128 {vr(addr)}, {ar(base + 4 * i, 4)} offset:{16 * i * stride}", ("W", A.fresh()))
-            for i in range(4)]
-
-
-def staging_ops(A: Asm, which: str):
-    """K (first half step) or V (second) rows of tile t+2, requested a tile ago, go to their LDS
-    stage; then the rows of tile t+3 are requested.  Returns {gap: [instructions]}: memory
-    instructions are kept four gaps apart, a burst of them would hold up the in-order stream and
-    starve the matrix cores.  The other tensor's four loads are still in flight: vmcnt(4)."""
-    g = {0: ["s_waitcnt vmcnt(4)"]}
-    if which == "k":
-        g[0] += [f"s_add_u32 {sr(S_TMP)}, {sr(S_T)}, 2",
-                 f"s_and_b32 {sr(S_TMP)}, {sr(S_TMP)}, 3",
-                 f"s_mul_i32 {sr(S_STW)}, {sr(S_TMP)}, {STAGE}",
-                 f"v_add_u32_e32 {vr(WA_K)}, {sr(S_STW)}, {vr(WK)}",
-                 f"v_add_u32_e32 {vr(WA_V)}, {sr(S_STW)}, {vr(WV)}"]
-    for i, w in enumerate(tile_writes(A, which)):
-        g[1 + 4 * i] = [w]
-    if which == "k":
-        g[15] = [f"s_lshl_b32 {sr(S_J0)}, {sr(S_T)}, 6", f"s_add_u32 {sr(S_J0)}, {sr(S_J0)}, 192"]
-        vo = voffsets(S_J0)
-        g[15] += vo[:6]
-        g[16] = vo[6:]
-    for i, l in enumerate(tile_loads(which)):
-        g[17 + 4 * i] = [l]
+def staging_ops():
+    """Requests tile t+3 (second half step of tile t).  Returns {gap: [instructions]}: the memory
+    instructions are kept three gaps apart, a burst of them would hold up the in-order stream."""
+    g = {0: [f"s_add_u32 {sr(S_TMP)}, {sr(S_T)}, 3",
+             f"s_and_b32 {sr(S_TMP)}, {sr(S_TMP)}, 3",
+             f"s_mul_i32 {sr(S_STW)}, {sr(S_TMP)}, {STAGE}",
+             f"s_add_u32 {sr(S_STW)}, {sr(S_STW)}, {sr(S_WBASE)}",
+             f"s_lshl_b32 {sr(S_J0)}, {sr(S_T)}, 6",
+             f"s_add_u32 {sr(S_J0)}, {sr(S_J0)}, 192"]}
+    vo = voffsets(S_J0)
+    g[0] += vo[:6]
+    g[1] = vo[6:]
+    n = 0
+    for i in range(4):
+        for which in ("k", "v"):
+            g[2 + 3 * n] = tile_load(which, i, S_STW)
+            n += 1
     return g
 
 
@@ -400,24 +439,49 @@ def body(A: Asm, masked: bool, name: str):
     A.reset_lds(pending_reads(0))
     rotate_addresses(A)
     half_step(A, 0, qk=(KA_CUR, 1, SB), pv=(VA_PRV, 1, PB), sm=(SA, PA, masked),
-              nxt=((KA_NXT, 0), (VA_CUR, 0)), extra=staging_ops(A, "k"), tagid=name + "0")
+              nxt=((KA_NXT, 0), (VA_CUR, 0)), extra=None, tagid=name + "0", publish=True)
     half_step(A, 1, qk=(KA_NXT, 0, SA), pv=(VA_CUR, 0, PA), sm=(SB, PB, masked),
-              nxt=((KA_NXT, 1), (VA_CUR, 1)), extra=staging_ops(A, "v"), tagid=name + "1")
-    # every staging write is older than the last operand read that was waited for
-    last_w = max(i for i, t in enumerate(A.lds) if t[0] == "W")
-    assert last_w <= A.waited, (last_w, A.waited)
+              nxt=((KA_NXT, 1), (VA_CUR, 1)), extra=staging_ops(), tagid=name + "1")
     assert A.lds[-3 * PD:] == pending_reads(2), A.lds[-6:]
-    A.e("s_barrier")
 
 
 def body_stage_only(A: Asm):
-    for which in ("k", "v"):
-        ops = staging_ops(A, which)
-        for gi in sorted(ops):
-            for ins in ops[gi]:
-                A.e(ins[1] if isinstance(ins, tuple) else ins)
-    A.e("s_waitcnt lgkmcnt(0)")
+    A.e("s_waitcnt vmcnt(8)")
     A.e("s_barrier")
+    ops = staging_ops()
+    for gi in sorted(ops):
+        for ins in ops[gi]:
+            A.e(ins)
+
+
+# ---- hazard check ---------------------------------------------------------------------------------
+import re
+
+_MFMA_V = re.compile(r"^v_mfma\w+ v\[(\d+):(\d+)\]")
+_VREG = re.compile(r"\bv(\d+)\b|\bv\[(\d+):(\d+)\]")
+
+
+def check_mfma_results(lines, need=11):
+    """No instruction other than an MFMA may touch a VGPR block within `need` issued instructions
+    after the MFMA that writes it (vector reads of matrix results are not interlocked)."""
+    recent = []  # (lo, hi, age)
+    for ln in lines:
+        if ln.endswith(":") or ln.startswith("//"):
+            continue
+        m = _MFMA_V.match(ln)
+        if not ln.startswith("v_mfma"):
+            regs = set()
+            for r in _VREG.finditer(ln):
+                if r.group(1):
+                    regs.add(int(r.group(1)))
+                else:
+                    regs.update(range(int(r.group(2)), int(r.group(3)) + 1))
+            for lo, hi, age in recent:
+                assert not any(lo <= x <= hi for x in regs), (ln, lo, hi, age)
+        step = int(ln.split()[1]) + 1 if ln.startswith("s_nop") else 1
+        recent = [(lo, hi, age + step) for lo, hi, age in recent if age + step < need]
+        if m:
+            recent.append((int(m.group(1)), int(m.group(2)), 0))
 
 
 # ---- the whole stream ---------------------------------------------------------------------------
@@ -427,37 +491,43 @@ def generate(dt: str) -> list[str]:
     ones = 0x3F803F80 if dt == "bf16" else 0x3C003C00
 
     A.c("lane constants")
-    e(f"s_movk_i32 {sr(S_C272)}, {K_STRIDE}")
-    e(f"s_movk_i32 {sr(S_C320)}, {V_STRIDE}")
     e(f"s_mov_b32 {sr(S_ONES)}, 0x{ones:08x}")
     e(f"s_xor_b32 {sr(S_NCS)}, %[cs], 0x80000000")
     e(f"s_mov_b32 {sr(S_NK1)}, %[nk1]")
     e(f"v_and_b32_e32 {vr(LANE)}, 63, %[tid]")
     e(f"v_and_b32_e32 {vr(COL)}, 31, {vr(LANE)}")
     e(f"v_lshrrev_b32_e32 {vr(HH)}, 5, {vr(LANE)}")
-    # K operand: row c of the key block, bytes [16 hh, 16 hh + 16) of each 32-byte k step
-    e(f"v_lshlrev_b32_e32 {vr(TMP[0])}, 4, {vr(HH)}")
-    e(f"v_mad_u32_u24 {vr(KL)}, {vr(COL)}, {sr(S_C272)}, {vr(TMP[0])}")
-    e(f"v_add_u32_e32 {vr(KL)}, %[lds], {vr(KL)}")
-    # V^T operand through the transposing read: a 16-lane block covers 4 keys x 16 d
+    # K operand: row c of the key block (chunk c / 4, row c % 4 of it), piece 2 s + hh of k step s
+    e(f"v_lshrrev_b32_e32 {vr(TMP[0])}, 2, {vr(COL)}")
+    e(f"v_mul_u32_u24_e32 {vr(TMP[0])}, {CHUNK}, {vr(TMP[0])}")
+    e(f"v_and_b32_e32 {vr(TMP[1])}, 3, {vr(COL)}")
+    e(f"v_lshlrev_b32_e32 {vr(TMP[1])}, 4, {vr(TMP[1])}")
+    e(f"v_lshl_add_u32 {vr(TMP[1])}, {vr(HH)}, 6, {vr(TMP[1])}")
+    e(f"v_add3_u32 {vr(KL)}, {vr(TMP[0])}, {vr(TMP[1])}, %[lds]")
+    # V^T operand through the transposing read: lane (sl = lane % 16, a = (lane / 16) % 2, hh) reads
+    # 8 bytes of key row 4 hh + sl / 4 (chunk hh, row sl / 4), d offset 16 a + 4 (sl % 4) of the d
+    # block: piece 2 a + (sl % 4) / 2, half sl % 2
     e(f"v_and_b32_e32 {vr(TMP[0])}, 15, {vr(LANE)}")
-    e(f"v_lshrrev_b32_e32 {vr(TMP[1])}, 2, {vr(TMP[0])}")
-    e(f"v_lshl_add_u32 {vr(TMP[1])}, {vr(HH)}, 2, {vr(TMP[1])}")
-    e(f"v_and_b32_e32 {vr(TMP[2])}, 3, {vr(TMP[0])}")
-    e(f"v_lshlrev_b32_e32 {vr(TMP[2])}, 3, {vr(TMP[2])}")
-    e(f"v_bfe_u32 {vr(TMP[3])}, {vr(LANE)}, 4, 1")
-    e(f"v_lshl_add_u32 {vr(TMP[2])}, {vr(TMP[3])}, 5, {vr(TMP[2])}")
-    e(f"v_mad_u32_u24 {vr(VL)}, {vr(TMP[1])}, {sr(S_C320)}, {vr(TMP[2])}")
-    e(f"s_add_u32 {sr(S_TMP)}, %[lds], {K_BYTES}")
-    e(f"v_add_u32_e32 {vr(VL)}, {sr(S_TMP)}, {vr(VL)}")
-    # staging: thread t moves 16-byte piece t % 16 of rows t / 16 + 16 i
-    e(f"v_lshrrev_b32_e32 {vr(ROWB)}, 4, %[tid]")
-    e(f"v_and_b32_e32 {vr(TMP[0])}, 15, %[tid]")
+    e(f"v_bfe_u32 {vr(TMP[1])}, {vr(LANE)}, 4, 1")
+    e(f"v_mul_u32_u24_e32 {vr(TMP[2])}, {CHUNK}, {vr(HH)}")
+    e(f"v_lshl_add_u32 {vr(TMP[2])}, {vr(TMP[1])}, 7, {vr(TMP[2])}")
+    e(f"v_bfe_u32 {vr(TMP[3])}, {vr(TMP[0])}, 1, 1")
+    e(f"v_lshl_add_u32 {vr(TMP[2])}, {vr(TMP[3])}, 6, {vr(TMP[2])}")
+    e(f"v_lshrrev_b32_e32 {vr(TMP[3])}, 2, {vr(TMP[0])}")
+    e(f"v_lshl_add_u32 {vr(TMP[2])}, {vr(TMP[3])}, 4, {vr(TMP[2])}")
+    e(f"v_and_b32_e32 {vr(TMP[3])}, 1, {vr(TMP[0])}")
+    e(f"v_lshl_add_u32 {vr(TMP[2])}, {vr(TMP[3])}, 3, {vr(TMP[2])}")
+    e(f"s_add_u32 {sr(S_TMP)}, %[lds], {T_BYTES}")
+    e(f"v_add_u32_e32 {vr(VL)}, {sr(S_TMP)}, {vr(TMP[2])}")
+    # staging: wave w fills chunks 4 w .. 4 w + 3 of each tensor; its lane L fetches piece L / 4 of
+    # row L % 4 of the chunk
+    e(f"s_lshl_b32 {sr(S_TMP)}, %[wv], 4")
+    e(f"v_and_b32_e32 {vr(TMP[0])}, 3, {vr(LANE)}")
+    e(f"v_add_u32_e32 {vr(ROWB)}, {sr(S_TMP)}, {vr(TMP[0])}")
+    e(f"v_lshrrev_b32_e32 {vr(TMP[0])}, 2, {vr(LANE)}")
     e(f"v_lshlrev_b32_e32 {vr(PIECE)}, 4, {vr(TMP[0])}")
-    e(f"v_mad_u32_u24 {vr(WK)}, {vr(ROWB)}, {sr(S_C272)}, {vr(PIECE)}")
-    e(f"v_add_u32_e32 {vr(WK)}, %[lds], {vr(WK)}")
-    e(f"v_mad_u32_u24 {vr(WV)}, {vr(ROWB)}, {sr(S_C320)}, {vr(PIECE)}")
-    e(f"v_add_u32_e32 {vr(WV)}, {sr(S_TMP)}, {vr(WV)}")
+    e(f"s_mul_i32 {sr(S_WBASE)}, %[wv], {4 * CHUNK}")
+    e(f"s_add_u32 {sr(S_WBASE)}, {sr(S_WBASE)}, %[lds]")
 
     A.c("Q^T into AGPRs: lane (row c, k group hh) holds Q[row][16 s + 8 hh, +8); rows past the last valid one repeat it")
     e(f"s_sub_u32 {sr(S_TMP)}, %[rv], 1")
@@ -477,6 +547,11 @@ def generate(dt: str) -> list[str]:
     A.c("state")
     for i in range(128):
         e(f"v_accvgpr_write_b32 {ar(A_O + i)}, 0")
+    if SUM_BY_MFMA:
+        for i in range(32):
+            e(f"v_accvgpr_write_b32 {ar(A_L + i)}, 0")
+        for i in range(4):
+            e(f"v_mov_b32_e32 {vr(ONES4 + i)}, 0x{ones:08x}")
     for i in range(16):
         e(f"v_mov_b32_e32 {vr(PB + i)}, 0")
     e(f"v_mov_b32_e32 {vr(NEG_INF)}, 0xff800000")
@@ -487,26 +562,27 @@ def generate(dt: str) -> list[str]:
     e(f"s_mov_b32 {sr(S_FLAG)}, 0")
     e(f"s_mov_b32 {sr(S_T)}, 0")
 
-    A.c("tiles 0 and 1 to LDS, tile 2 requested (K rows first, then V rows)")
+    A.c("tiles 0, 1, 2 requested")
     for x in range(3):
         e(f"s_movk_i32 {sr(S_J0)}, {64 * x}")
         for ins in voffsets(S_J0):
             e(ins)
-        for ins in tile_loads("k") + tile_loads("v"):
-            e(ins)
-        if x < 2:
-            e("s_waitcnt vmcnt(0)")
-            e(f"v_add_u32_e32 {vr(WA_K)}, {x * STAGE}, {vr(WK)}")
-            e(f"v_add_u32_e32 {vr(WA_V)}, {x * STAGE}, {vr(WV)}")
-            for ins in tile_writes(A, "k") + tile_writes(A, "v"):
-                e(ins[1])
+        e(f"s_add_u32 {sr(S_STW)}, {sr(S_WBASE)}, {x * STAGE}")
+        for i in range(4):
+            for which in ("k", "v"):
+                for ins in tile_load(which, i, S_STW):
+                    e(ins)
     A.c("the first half step multiplies zero weights with the V part of stage 3: make it finite")
-    e(f"v_mul_u32_u24_e32 {vr(TMP[0])}, 80, %[tid]")
-    e(f"s_add_u32 {sr(S_TMP)}, %[lds], {3 * STAGE + K_BYTES}")
+    e(f"v_lshlrev_b32_e32 {vr(TMP[0])}, 4, %[tid]")
+    e(f"v_min_u32_e32 {vr(TMP[1])}, {T_BYTES - 16 - 16384}, {vr(TMP[0])}")
+    e(f"s_add_u32 {sr(S_TMP)}, %[lds], {3 * STAGE + T_BYTES}")
     e(f"v_add_u32_e32 {vr(TMP[0])}, {sr(S_TMP)}, {vr(TMP[0])}")
-    for i in range(5):
-        e(f"ds_write_b128 {vr(TMP[0])}, {vr(PB, 4)} offset:{16 * i}")
-    e("s_waitcnt lgkmcnt(0)")
+    e(f"v_add_u32_e32 {vr(TMP[1])}, {sr(S_TMP)}, {vr(TMP[1])}")
+    for i in range(4):
+        e(f"ds_write_b128 {vr(TMP[0])}, {vr(PB, 4)} offset:{4096 * i}")
+    e(f"ds_write_b128 {vr(TMP[1])}, {vr(PB, 4)} offset:16384")
+    A.c("Q and tile 0 have landed once at most the 16 newest loads (tiles 1, 2) are outstanding")
+    e("s_waitcnt vmcnt(16) lgkmcnt(0)")
     e("s_barrier")
     e(f"v_mov_b32_e32 {vr(KA_NXT)}, {vr(KL)}")
     e(f"v_add_u32_e32 {vr(VA_CUR)}, {3 * STAGE}, {vr(VL)}")
@@ -520,7 +596,9 @@ def generate(dt: str) -> list[str]:
     e("L_FULL_%=:")
     e(f"s_cmp_ge_i32 {sr(S_T)}, %[tms]")
     e("s_cbranch_scc1 L_FULL_END_%=")
+    n0 = len(A.lines)
     body(A, False, "f")
+    check_mfma_results(A.lines[:n0] + A.lines[n0:] * 2)   # after the prologue, and around the loop
     e(f"s_add_u32 {sr(S_T)}, {sr(S_T)}, 1")
     e("s_branch L_FULL_%=")
     e("L_FULL_END_%=:")
@@ -535,7 +613,10 @@ def generate(dt: str) -> list[str]:
     e("L_MASK_%=:")
     e(f"s_cmp_gt_i32 {sr(S_T)}, %[twl]")
     e("s_cbranch_scc1 L_MASK_END_%=")
+    n1 = len(A.lines)
     body(A, True, "m")
+    check_mfma_results(A.lines[n0:n1] + A.lines[n1:] * 2)  # unmasked -> masked, masked -> masked
+    check_mfma_results(A.lines[:n0] + A.lines[n1:])        # prologue -> masked
     e(f"s_add_u32 {sr(S_T)}, {sr(S_T)}, 1")
     e("s_branch L_MASK_%=")
     e("L_MASK_END_%=:")
@@ -551,14 +632,18 @@ def generate(dt: str) -> list[str]:
         e("s_nop 7")
 
     A.c("row sums of both lane halves, normalise, store")
-    for q in range(2):
-        e(f"v_mov_b32_e32 {vr(T_MAX2[q])}, {vr(L_SUM[q])}")
-    e("s_nop 1")
-    for q in range(2):
-        e(f"v_permlane32_swap_b32_e32 {vr(L_SUM[q])}, {vr(T_MAX2[q])}")
-    e("s_nop 1")
-    for q in range(2):
-        e(f"v_add_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}, {vr(T_MAX2[q])}")
+    if SUM_BY_MFMA:
+        for q in range(2):  # every element of the accumulator block holds the full sum of its column
+            e(f"v_accvgpr_read_b32 {vr(L_SUM[q])}, {ar(A_L + 16 * q)}")
+    else:
+        for q in range(2):
+            e(f"v_mov_b32_e32 {vr(T_MAX2[q])}, {vr(L_SUM[q])}")
+        e("s_nop 1")
+        for q in range(2):
+            e(f"v_permlane32_swap_b32_e32 {vr(L_SUM[q])}, {vr(T_MAX2[q])}")
+        e("s_nop 1")
+        for q in range(2):
+            e(f"v_add_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}, {vr(T_MAX2[q])}")
     for q in range(2):
         e(f"v_rcp_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}")
     e("s_nop 1")
@@ -605,9 +690,9 @@ def generate(dt: str) -> list[str]:
 
 
 def clobbers() -> str:
-    regs = [f"v{i}" for i in range(FIRST_V, 256)] + [f"a{i}" for i in range(256)]
+    regs = [f"v{i}" for i in range(FIRST_V, 256)] + [f"a{i}" for i in range(224)]
     regs += [f"s{i}" for i in range(FIRST_S, LAST_S + 1)]
-    regs += ["vcc", "scc", "memory"]
+    regs += ["vcc", "scc", "memory"]  # m0 is written too; nothing follows the statement
     return ", ".join(f'"{r}"' for r in regs)
 
 

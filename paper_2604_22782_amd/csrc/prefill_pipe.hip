@@ -4,8 +4,8 @@
 // Work group = 4 waves = 256 consecutive query rows of one (sequence, query head); wave w owns
 // rows 64w..64w+63 as two blocks of 32, so every K / V^T operand read from LDS feeds two MFMAs.
 // One wave per SIMD holds ~400 registers: O^T and Q^T in AGPRs, two S^T and two P^T buffers in
-// VGPRs.  K/V tiles of 64 keys travel HBM -> AGPRs -> a ring of four LDS stages, requested a full
-// tile before they are written and written a full tile before they are read.  The instruction
+// VGPRs.  K/V tiles of 64 keys travel from HBM straight into a ring of four LDS stages
+// (buffer_load ... lds), requested almost two tiles before their first use.  The instruction
 // stream of the loop (which MFMA, which vector instruction, which LDS read goes where) is written
 // by gen_prefill_pipe.py and included below; this file only prepares its scalar operands.
 //
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(256, 1) void prefill_pipe_kernel(AttnArgs a, int G,
         [nt] "s"(uni((uint32_t)n_tiles)), [tms] "s"(uni((uint32_t)t_mask)),                            \
         [twl] "s"(uni((uint32_t)tw_last)), [p0] "s"(uni((uint32_t)p0)),                                \
         [cs] "s"(uni(__builtin_bit_cast(uint32_t, cs))), [thr] "s"(uni(__builtin_bit_cast(uint32_t, thr))), \
-        [tid] "v"(tid)
+        [wv] "s"(uni((uint32_t)wave)), [tid] "v"(tid)
 
     if constexpr (BF16) {
         asm volatile(SKV_PIPE_ASM_BF16 : : SKV_PIPE_OPERANDS : SKV_PIPE_CLOBBERS);

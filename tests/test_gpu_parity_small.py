@@ -132,6 +132,11 @@ PREFILL_CASES = [
     ("f16", 4, 4, 128, [333, 128], [333, 1], [0, 1, 1], False),
     ("bf16", 4, 1, 64, [400, 63], [400, 63], [0, 0], True),
     ("f16", 16, 2, 64, [257], [200], [0], False),
+    # several 256-row work groups, rows that end inside a 64-row wave block, chunk offsets
+    # (kv > q), an empty and a one-row sequence, MHA and 8-head groups: the pipelined kernel
+    ("bf16", 4, 1, 128, [700, 900, 64, 300], [700, 333, 0, 1], [0, 0, 2, 2], False),
+    ("f16", 2, 2, 128, [513, 1025], [513, 257], [0, 1], False),
+    ("bf16", 8, 1, 128, [320, 65], [129, 65], [0], False),
 ]
 
 
