@@ -100,7 +100,7 @@ __global__ __launch_bounds__(256, 1) void prefill_pipe_kernel(AttnArgs a, int G,
     const uint32_t q_row_stride = (uint32_t)a.n_q_heads * kD * 2;
     const uint32_t rv_clamp = active ? (uint32_t)min(rows_valid, 64) : 1u;
     const float cs = a.scale_log2e;
-    const float thr = 8.0f / cs;
+    const float thr = fminf(8.0f / cs, 3.0e38f); // finite: the first tile (maximum -inf so far) must pass it
 
     const uint32_t lds_base = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)lds);
     const uint32_t tid = threadIdx.x;

@@ -1,0 +1,82 @@
+"""Host-side checks of the generator that writes the instruction stream of the pipelined pre-fill
+kernel (no GPU): it runs for both dtypes, its own hazard check accepts the stream it emits and
+rejects a planted violation, and the LDS geometry it assumes is conflict-free by construction."""
+import importlib.util
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+_spec = importlib.util.spec_from_file_location(
+    "gen_prefill_pipe", os.path.join(ROOT, "paper_2604_22782_amd", "csrc", "gen_prefill_pipe.py"))
+G = importlib.util.module_from_spec(_spec)
+_spec.loader.exec_module(G)
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+def test_stream_is_generated_and_self_consistent(dt):
+    lines = [l for l in G.generate(dt) if not l.startswith("//")]
+    text = "\n".join(lines)
+    n_mfma = sum(l.startswith("v_mfma") for l in lines)
+    # prologue 16 + two loop bodies (unmasked, masked) of 64 + the last O update 16
+    assert n_mfma == 16 + 2 * 64 + 16
+    assert f"v_mfma_f32_32x32x16_{dt}" in text
+    # every branch target exists exactly once
+    labels = re.findall(r"^(L_\w+_%=):$", text, flags=re.M)
+    assert len(labels) == len(set(labels))
+    for tgt in re.findall(r"s_c?branch\w* (L_\w+_%=)", text):
+        assert tgt in labels, tgt
+    # one barrier in the prologue, one per loop body variant (two computing, one staging-only)
+    assert sum(l == "s_barrier" for l in lines) == 4
+    # every register the stream names lies in the ranges the asm statement declares as clobbered
+    for m in re.finditer(r"\bv(\d+)\b|\bv\[(\d+):(\d+)\]", text):
+        lo = int(m.group(1) or m.group(2))
+        hi = int(m.group(1) or m.group(3))
+        assert G.FIRST_V <= lo <= hi <= 255
+    for m in re.finditer(r"\ba(\d+)\b|\ba\[(\d+):(\d+)\]", text):
+        hi = int(m.group(1) or m.group(3))
+        assert hi < 224
+    for m in re.finditer(r"\bs(\d+)\b|\bs\[(\d+):(\d+)\]", text):
+        lo = int(m.group(1) or m.group(2))
+        hi = int(m.group(1) or m.group(3))
+        assert G.FIRST_S <= lo <= hi <= G.LAST_S
+
+
+def test_hazard_check_accepts_the_stream_and_rejects_a_planted_read():
+    lines = G.generate("bf16")
+    G.check_mfma_results(lines)                      # the real stream: fine
+    i = next(k for k, l in enumerate(lines) if l.startswith("v_mfma") and " v[" in l.split(",")[0])
+    dst = int(re.match(r"v_mfma\w+ v\[(\d+):", lines[i]).group(1))
+    planted = lines[:i + 1] + [f"v_add_f32_e32 v200, v200, v{dst}"] + lines[i + 1:]
+    with pytest.raises(AssertionError):
+        G.check_mfma_results(planted)
+    # eleven instructions later the same read is allowed
+    ok = lines[:i + 1] + ["s_nop 7", "s_nop 2", f"v_add_f32_e32 v200, v200, v{dst}"]
+    G.check_mfma_results(ok)
+
+
+def test_lds_layout_is_bank_conflict_free():
+    """64 banks x 4 bytes.  K operand: a pass of 16 lanes reads 16 bytes each of rows c = 0..15, same
+    piece; V operand: a pass of 16 lanes reads 8 bytes each (4 rows x 4 x 8 bytes).  Every pass must
+    touch each bank at most once."""
+    def banks(addr, nbytes):
+        return [((addr + b) // 4) % 64 for b in range(0, nbytes, 4)]
+    for hh in range(2):
+        for s in range(8):
+            for base_c in (0, 16):
+                used = []
+                for c in range(base_c, base_c + 16):
+                    a = (c >> 2) * G.CHUNK + 16 * (c & 3) + 64 * hh + 128 * s
+                    used += banks(a, 16)
+                assert len(used) == len(set(used)) == 64
+    for hh in range(2):
+        for a in range(2):
+            for db in range(4):
+                used = []
+                for sl in range(16):
+                    addr = hh * G.CHUNK + 128 * a + 64 * ((sl & 3) >> 1) + 16 * (sl >> 2) + 8 * (sl & 1) + 256 * db
+                    used += banks(addr, 8)
+                assert len(used) == len(set(used)) == 32
+    # the ring fits the 160 KiB of LDS of a compute unit
+    assert G.LDS_BYTES <= 160 * 1024
