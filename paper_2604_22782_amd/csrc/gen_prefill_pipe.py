@@ -81,7 +81,9 @@ O_OFF = (_T + 52, _T + 53)
 ROW = (_T + 54, _T + 55)
 STG = _T + 56                          # scratch of the staging address arithmetic
 ONES4 = _T + 58                        # 4 registers of 16-bit ones (A operand of the row-sum MFMA)
-assert ONES4 % 2 == 0 and ONES4 + 3 < 256 and PD < RING
+VBO = (_T + 62, _T + 63, _T + 64, _T + 65)   # byte offsets of the lane's 4 rows in tile 0 (constants)
+LIMV = _T + 66                         # byte offset of the lane's piece in the last needed row
+assert ONES4 % 2 == 0 and LIMV < 256 and PD < RING
 assert TMP[4] % 2 == 0 and TMP[12] % 2 == 0   # 64-bit store operands
 
 A_O, A_Q, A_L = 0, 128, 192
@@ -99,10 +101,12 @@ FIRST_GAP = int(os.environ.get("SKV_GEN_FIRST_GAP", "0"))
 
 S_T, S_TMP, S_STW, S_J0, S_FLAG = 40, 41, 42, 43, 44
 S_CMP = 46                     # pair
-S_ST_NXT, S_ST_CUR = 48, 49
+S_ST_NXT, S_ST_CUR = 48, 49    # LDS offsets of the stages of tiles t+1, t
 S_ONES, S_NCS, S_WBASE = 50, 51, 52
+S_ST_PRV = 53                  # ... of tile t-1 (the stage tile t+3 goes to)
 S_EXEC = 54                    # pair
 S_NK1 = 56
+S_SOFF, S_NKM63 = 57, 58       # scalar byte offset of the tile being requested; last needed key - 63
 
 FIRST_V, FIRST_S, LAST_S = 24, 40, 59
 
@@ -292,7 +296,7 @@ def half_step(A: Asm, hs: int, qk, pv, sm, nxt, extra, tagid: str, cold=False, p
     sm  = (S source base, P destination base, masked) or None
     nxt = ((K address register, key block) or None, (V address register, key block) or None):
           operands of the next half step's first PD groups, fetched at the end of this one
-    extra = {gap: [instructions]} (staging)
+    extra = ({gap: [instructions issued first]}, {gap: [instructions issued last]}) (staging)
     publish: before it requests the first operands of the next half step (the first reads of the
           newly published tile) the wave waits for its loads of that tile and for its own
           outstanding operand reads, then meets the other waves at the barrier.
@@ -310,7 +314,8 @@ def half_step(A: Asm, hs: int, qk, pv, sm, nxt, extra, tagid: str, cold=False, p
                     slots.append(("sum", g, q))
     n = len(slots)
     gaps = [[] for _ in range(n)]
-    for gi, lst in (extra or {}).items():   # positions given on a scale of 32
+    head, tail = extra or ({}, {})
+    for gi, lst in head.items():   # positions given on a scale of 32
         gaps[gi * n // 32].extend(lst)
     # An in-order wave reaches the next MFMA only after issuing everything before it: time per
     # MFMA is max(32 clocks of the matrix pipe, issue time of its gap).  Spread the vector stream
@@ -325,6 +330,9 @@ def half_step(A: Asm, hs: int, qk, pv, sm, nxt, extra, tagid: str, cold=False, p
             gi += 1
         gaps[FIRST_GAP + gi].append(ins)
         done += cost(ins)
+    for gi, lst in tail.items():
+        assert len(gaps[gi * n // 32]) >= 2   # something is issued between an M0 write and its load
+        gaps[gi * n // 32].extend(lst)
 
     def fetch(hs_id, g, kcfg, vcfg):
         if kcfg:
@@ -383,55 +391,62 @@ def pending_reads(hs, with_k=True, with_v=True):
 
 
 # ---- staging (HBM -> LDS) -------------------------------------------------------------------------
-def voffsets(j0_sreg: int):
+def clamped_offsets():
+    """Byte offsets of the lane's four rows of the tile whose first row is at byte S_SOFF, rows
+    past the last needed key repeating it (finite, and masked wherever they are not the real
+    key); the scalar offset then is zero."""
     o = []
     for i in range(4):
-        # key = min(j0 + first row of the lane + 4 i, last needed key): rows past it repeat it
-        # (finite, and masked wherever they are not the real key)
-        o.append(f"v_add3_u32 {vr(STG)}, {sr(j0_sreg)}, {vr(ROWB)}, {4 * i}")
-        o.append(f"v_min_u32_e32 {vr(STG)}, {sr(S_NK1)}, {vr(STG)}")
-        o.append(f"v_mad_u32_u24 {vr(VOFF[i])}, {vr(STG)}, %[krb], {vr(PIECE)}")
+        o.append(f"v_add_u32_e32 {vr(VOFF[i])}, {sr(S_SOFF)}, {vr(VBO[i])}")
+        o.append(f"v_min_u32_e32 {vr(VOFF[i])}, {vr(LIMV)}, {vr(VOFF[i])}")
+    o.append(f"s_mov_b32 {sr(S_SOFF)}, 0")
     return o
 
 
 def tile_load(which: str, i: int, base_sreg: int):
-    """Chunk 4 w + i of K or V: lane L fetches piece L / 4 of row 4 (4 w + i) + L % 4."""
+    """Chunk 4 w + i of K or V: lane L fetches piece L / 4 of row 4 (4 w + i) + L % 4.  Returns
+    (M0 write, load): another instruction must be issued between the two."""
     srd, off = ("%[srdk]", 0) if which == "k" else ("%[srdv]", T_BYTES)
-    return [f"s_add_u32 m0, {sr(base_sreg)}, {off + i * CHUNK}",
-            "s_nop 0",  # M0 must not be written by the instruction right before the load
-            f"buffer_load_dwordx4 {vr(VOFF[i])}, {srd}, 0 offen lds"]
+    return (f"s_add_u32 m0, {sr(base_sreg)}, {off + i * CHUNK}",
+            f"buffer_load_dwordx4 {vr(VOFF[i])}, {srd}, {sr(S_SOFF)} offen lds")
 
 
-def staging_ops():
-    """Requests tile t+3 (second half step of tile t).  Returns {gap: [instructions]}: the memory
-    instructions are kept three gaps apart, a burst of them would hold up the in-order stream."""
-    g = {0: [f"s_add_u32 {sr(S_TMP)}, {sr(S_T)}, 3",
-             f"s_and_b32 {sr(S_TMP)}, {sr(S_TMP)}, 3",
-             f"s_mul_i32 {sr(S_STW)}, {sr(S_TMP)}, {STAGE}",
-             f"s_add_u32 {sr(S_STW)}, {sr(S_STW)}, {sr(S_WBASE)}",
-             f"s_lshl_b32 {sr(S_J0)}, {sr(S_T)}, 6",
-             f"s_add_u32 {sr(S_J0)}, {sr(S_J0)}, 192"]}
-    vo = voffsets(S_J0)
-    g[0] += vo[:6]
-    g[1] = vo[6:]
+def staging_ops(tagid: str):
+    """Requests tile t+3 (second half step of tile t) into the stage tile t-1 just left.  Returns
+    ({gap: [instructions issued first in the gap]}, {gap: [instructions issued last]}).  While
+    the whole tile lies before the last needed key its row offsets are the constants of tile 0
+    plus a scalar offset; only the tail tiles pay for the clamp.  The memory instructions are kept
+    three gaps apart: a burst of them would hold up the in-order stream."""
+    head = {0: [f"s_add_u32 {sr(S_STW)}, {sr(S_ST_PRV)}, {sr(S_WBASE)}",
+                f"s_lshl_b32 {sr(S_J0)}, {sr(S_T)}, 6",
+                f"s_add_u32 {sr(S_J0)}, {sr(S_J0)}, 192",
+                f"s_mul_i32 {sr(S_SOFF)}, {sr(S_J0)}, %[krb]",
+                f"s_cmp_le_i32 {sr(S_J0)}, {sr(S_NKM63)}",
+                "\n".join([f"s_cbranch_scc1 L_INRANGE_{tagid}_%="] + clamped_offsets() + [f"L_INRANGE_{tagid}_%=:"])]}
+    tail = {}
     n = 0
     for i in range(4):
         for which in ("k", "v"):
-            g[2 + 3 * n] = tile_load(which, i, S_STW)
+            m0w, ld = tile_load(which, i, S_STW)
+            head[2 + 3 * n] = [m0w]
+            tail[2 + 3 * n] = [ld]
             n += 1
-    return g
+    return head, tail
 
 
-def rotate_addresses(A: Asm):
-    A.e(f"v_mov_b32_e32 {vr(KA_CUR)}, {vr(KA_NXT)}")
-    A.e(f"v_mov_b32_e32 {vr(VA_PRV)}, {vr(VA_CUR)}")
-    A.e(f"s_add_u32 {sr(S_TMP)}, {sr(S_T)}, 1")
-    A.e(f"s_and_b32 {sr(S_TMP)}, {sr(S_TMP)}, 3")
-    A.e(f"s_mul_i32 {sr(S_ST_NXT)}, {sr(S_TMP)}, {STAGE}")
-    A.e(f"s_and_b32 {sr(S_TMP)}, {sr(S_T)}, 3")
-    A.e(f"s_mul_i32 {sr(S_ST_CUR)}, {sr(S_TMP)}, {STAGE}")
-    A.e(f"v_add_u32_e32 {vr(KA_NXT)}, {sr(S_ST_NXT)}, {vr(KL)}")
-    A.e(f"v_add_u32_e32 {vr(VA_CUR)}, {sr(S_ST_CUR)}, {vr(VL)}")
+def rotate_addresses(A: Asm, vector=True):
+    """Top of tile t: stage offsets and operand addresses move on by one tile."""
+    if vector:
+        A.e(f"v_mov_b32_e32 {vr(KA_CUR)}, {vr(KA_NXT)}")
+        A.e(f"v_mov_b32_e32 {vr(VA_PRV)}, {vr(VA_CUR)}")
+    A.e(f"s_mov_b32 {sr(S_ST_PRV)}, {sr(S_ST_CUR)}")
+    A.e(f"s_mov_b32 {sr(S_ST_CUR)}, {sr(S_ST_NXT)}")
+    A.e(f"s_add_u32 {sr(S_ST_NXT)}, {sr(S_ST_NXT)}, {STAGE}")
+    A.e(f"s_cmp_lt_u32 {sr(S_ST_NXT)}, {N_STAGE * STAGE}")
+    A.e(f"s_cselect_b32 {sr(S_ST_NXT)}, {sr(S_ST_NXT)}, 0")
+    if vector:
+        A.e(f"v_add_u32_e32 {vr(KA_NXT)}, {sr(S_ST_NXT)}, {vr(KL)}")
+        A.e(f"v_add_u32_e32 {vr(VA_CUR)}, {sr(S_ST_CUR)}, {vr(VL)}")
 
 
 def body(A: Asm, masked: bool, name: str):
@@ -441,30 +456,35 @@ def body(A: Asm, masked: bool, name: str):
     half_step(A, 0, qk=(KA_CUR, 1, SB), pv=(VA_PRV, 1, PB), sm=(SA, PA, masked),
               nxt=((KA_NXT, 0), (VA_CUR, 0)), extra=None, tagid=name + "0", publish=True)
     half_step(A, 1, qk=(KA_NXT, 0, SA), pv=(VA_CUR, 0, PA), sm=(SB, PB, masked),
-              nxt=((KA_NXT, 1), (VA_CUR, 1)), extra=staging_ops(), tagid=name + "1")
+              nxt=((KA_NXT, 1), (VA_CUR, 1)), extra=staging_ops(name), tagid=name + "1")
     assert A.lds[-3 * PD:] == pending_reads(2), A.lds[-6:]
 
 
 def body_stage_only(A: Asm):
+    rotate_addresses(A, vector=False)
     A.e("s_waitcnt vmcnt(8)")
     A.e("s_barrier")
-    ops = staging_ops()
-    for gi in sorted(ops):
-        for ins in ops[gi]:
+    head, tail = staging_ops("s")
+    for gi in sorted(head):
+        for ins in head[gi]:
             A.e(ins)
+        if gi in tail:
+            A.e("s_nop 0")  # M0 must not be written by the instruction right before the load
+            for ins in tail[gi]:
+                A.e(ins)
 
 
 # ---- hazard check ---------------------------------------------------------------------------------
 import re
 
-_MFMA_V = re.compile(r"^v_mfma\w+ v\[(\d+):(\d+)\]")
-_VREG = re.compile(r"\bv(\d+)\b|\bv\[(\d+):(\d+)\]")
+_MFMA_V = re.compile(r"^v_mfma\w+ ([va])\[(\d+):(\d+)\]")
+_VREG = re.compile(r"\b([va])(\d+)\b|\b([va])\[(\d+):(\d+)\]")
 
 
 def check_mfma_results(lines, need=11):
     """No instruction other than an MFMA may touch a VGPR block within `need` issued instructions
     after the MFMA that writes it (vector reads of matrix results are not interlocked)."""
-    recent = []  # (lo, hi, age)
+    recent = []  # (file, lo, hi, age)
     for ln in lines:
         if ln.endswith(":") or ln.startswith("//"):
             continue
@@ -473,15 +493,15 @@ def check_mfma_results(lines, need=11):
             regs = set()
             for r in _VREG.finditer(ln):
                 if r.group(1):
-                    regs.add(int(r.group(1)))
+                    regs.add((r.group(1), int(r.group(2))))
                 else:
-                    regs.update(range(int(r.group(2)), int(r.group(3)) + 1))
-            for lo, hi, age in recent:
-                assert not any(lo <= x <= hi for x in regs), (ln, lo, hi, age)
+                    regs.update((r.group(3), x) for x in range(int(r.group(4)), int(r.group(5)) + 1))
+            for f, lo, hi, age in recent:
+                assert not any(rf == f and lo <= x <= hi for rf, x in regs), (ln, f, lo, hi, age)
         step = int(ln.split()[1]) + 1 if ln.startswith("s_nop") else 1
-        recent = [(lo, hi, age + step) for lo, hi, age in recent if age + step < need]
+        recent = [(f, lo, hi, age + step) for f, lo, hi, age in recent if age + step < need]
         if m:
-            recent.append((int(m.group(1)), int(m.group(2)), 0))
+            recent.append((m.group(1), int(m.group(2)), int(m.group(3)), 0))
 
 
 # ---- the whole stream ---------------------------------------------------------------------------
@@ -528,6 +548,12 @@ def generate(dt: str) -> list[str]:
     e(f"v_lshlrev_b32_e32 {vr(PIECE)}, 4, {vr(TMP[0])}")
     e(f"s_mul_i32 {sr(S_WBASE)}, %[wv], {4 * CHUNK}")
     e(f"s_add_u32 {sr(S_WBASE)}, {sr(S_WBASE)}, %[lds]")
+    for i in range(4):
+        e(f"v_add_u32_e32 {vr(TMP[0])}, {4 * i}, {vr(ROWB)}")
+        e(f"v_mad_u32_u24 {vr(VBO[i])}, {vr(TMP[0])}, %[krb], {vr(PIECE)}")
+    e(f"v_mov_b32_e32 {vr(TMP[0])}, {sr(S_NK1)}")
+    e(f"v_mad_u32_u24 {vr(LIMV)}, {vr(TMP[0])}, %[krb], {vr(PIECE)}")
+    e(f"s_sub_i32 {sr(S_NKM63)}, {sr(S_NK1)}, 63")
 
     A.c("Q^T into AGPRs: lane (row c, k group hh) holds Q[row][16 s + 8 hh, +8); rows past the last valid one repeat it")
     e(f"s_sub_u32 {sr(S_TMP)}, %[rv], 1")
@@ -564,14 +590,21 @@ def generate(dt: str) -> list[str]:
 
     A.c("tiles 0, 1, 2 requested")
     for x in range(3):
-        e(f"s_movk_i32 {sr(S_J0)}, {64 * x}")
-        for ins in voffsets(S_J0):
+        e(f"s_mul_i32 {sr(S_SOFF)}, %[krb], {64 * x}")
+        for ins in clamped_offsets():
             e(ins)
         e(f"s_add_u32 {sr(S_STW)}, {sr(S_WBASE)}, {x * STAGE}")
         for i in range(4):
             for which in ("k", "v"):
-                for ins in tile_load(which, i, S_STW):
-                    e(ins)
+                m0w, ld = tile_load(which, i, S_STW)
+                e(m0w)
+                e("s_nop 0")
+                e(ld)
+    for i in range(4):   # the loop adds a scalar offset to these as long as whole tiles are in range
+        e(f"v_mov_b32_e32 {vr(VOFF[i])}, {vr(VBO[i])}")
+    A.c("stage offsets before the first rotation: tile -1 in stage 3, tile 0 in stage 0")
+    e(f"s_mov_b32 {sr(S_ST_CUR)}, {3 * STAGE}")
+    e(f"s_mov_b32 {sr(S_ST_NXT)}, 0")
     A.c("the first half step multiplies zero weights with the V part of stage 3: make it finite")
     e(f"v_lshlrev_b32_e32 {vr(TMP[0])}, 4, %[tid]")
     e(f"v_min_u32_e32 {vr(TMP[1])}, {T_BYTES - 16 - 16384}, {vr(TMP[0])}")
