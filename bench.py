@@ -76,6 +76,50 @@ def cpu_baseline_decode(w, seconds_budget=12.0):
                       f"heads x {n} keys, repeated {reps}x ({dt:.1f} s); bytes counted as for the GPU (16-bit K/V)"}
 
 
+def cross_layer_reuse_sweep(args, torch, skv, w, cache, qs, outs, new_k, new_v, d_lens, d_start, ones, ctx,
+                            step_bytes):
+    """The layers of one sharing group read the same slot.  Walk them group by group and, inside a
+    group, chunk by chunk over the sequences (all layers of the group on chunk 0, then on chunk 1,
+    ...): once a chunk's slice of the slot fits the on-chip caches, only the first layer of the group
+    reads it from HBM.  Same work and same algorithmic bytes as the plain step; chunk = batch is the
+    plain layer-by-layer order."""
+    groups = {}
+    for l in range(w.n_layers):
+        groups.setdefault(int(w.route[l]), []).append(l)
+    row = w.n_kv_heads * w.head_dim * w.elem_bytes
+    points = []
+    steps = max(3, min(args.steps, 10))
+    for chunk in (w.batch, 32, 16, 8, 4):
+        if chunk > w.batch or w.batch % chunk:
+            continue
+        n = skv.skv_decode_range_workspace_bytes(cache, chunk, ctx)
+        wsr = torch.empty(n // 4 + 1, dtype=torch.float32, device="cuda")
+
+        def step():
+            for owner, layers in groups.items():
+                skv.skv_kv_append(cache, owner, new_k[owner], new_v[owner], d_start, ones, 1)
+                for b0 in range(0, w.batch, chunk):
+                    for l in layers:
+                        skv.skv_attn_decode_range(cache, l, b0, chunk, qs[l][b0:], outs[l][b0:], d_lens[b0:],
+                                                  ctx, w.scale, wsr)
+        for _ in range(2):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        points.append({"chunk_seqs": chunk, "slot_slice_MiB": round(chunk * ctx * row * 2 / 2**20, 1),
+                       "ms_per_step": round(dt * 1e3, 3), "GB/s": round(step_bytes / dt / 1e9, 1)})
+        del wsr
+    assert skv.skv_cache_device_faults(cache) == 0
+    return {"schedule": "per sharing group: for each chunk of sequences, every layer of the group "
+                        "(skv_attn_decode_range)", "layers_per_group": w.n_layers // len(groups),
+            "unit_note": "GB/s = algorithmic bytes of the step / time; above the HBM peak means reuse on chip",
+            "points": points}
+
+
 def run_decode(args, torch, skv, H, configs):
     if args.decode_workload == "qwen3_paged":
         w = configs.qwen3_paged_decode()
@@ -138,8 +182,12 @@ def run_decode(args, torch, skv, H, configs):
     ms_per_step = dt / args.steps * 1e3
     value = step_bytes / (dt / args.steps) / 1e9
     achieved = layer_bytes / (call_ms * 1e-3) / 1e9
+    reuse = None
+    if args.reuse_sweep and not w.block_size:
+        reuse = cross_layer_reuse_sweep(args, torch, skv, w, cache, qs, outs, new_k, new_v, d_lens, d_start,
+                                        ones, ctx, step_bytes)
     res = {
-        "value": round(value, 1), "ms_per_step": round(ms_per_step, 4),
+        "value": round(value, 1), "ms_per_step": round(ms_per_step, 4), "cross_layer_reuse": reuse,
         "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(kernel_name),
                      "launch_us": round(call_ms * 1e3, 2), "algorithmic_bytes_per_launch": layer_bytes},
@@ -210,6 +258,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--skip-prefill", action="store_true")
+    ap.add_argument("--reuse-sweep", action="store_true",
+                    help="also time the group-by-group, chunk-by-chunk decode schedule (skv_attn_decode_range) "
+                         "that lets the later layers of a sharing group find their slot slice in the on-chip caches")
     ap.add_argument("--only-prefill", action="store_true", help="profiling aid: measure only the prefill workload")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--decode-workload", default="llama3_decode", choices=["llama3_decode", "qwen3_paged", "llama2_mha"],
@@ -257,6 +308,8 @@ def main():
         "pct_of_hbm_peak": round(100 * dec["value"] / HBM_PEAK_GBS, 2),
         "roofline": dec["roofline"],
     }
+    if dec.get("cross_layer_reuse"):
+        line["cross_layer_reuse"] = dec["cross_layer_reuse"]
     if not args.skip_prefill:
         line["prefill"] = run_prefill(args, torch, skv, H, configs)
     if not args.skip_cpu_baseline:

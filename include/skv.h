@@ -152,6 +152,22 @@ skv_status_t skv_attn_decode(skv_cache_t *cache, int32_t layer, const void *q, v
                              const int32_t *kv_lens, int32_t max_kv_len, float scale,
                              void *workspace, size_t workspace_bytes, void *stream);
 
+/* Sampling-phase attention for the sequences [seq_begin, seq_begin + seq_count) of the cache only.
+ * q, out and kv_lens describe just those sequences (q, out: device [seq_count][n_q_heads][head_dim];
+ * kv_lens: device int32[seq_count]); everything else is as in skv_attn_decode, which is the range
+ * [0, batch).  The workspace must hold skv_decode_range_workspace_bytes(cache, seq_count, max_kv_len).
+ * Purpose: the layers of one sharing group read the same slot, and the paper's closing remark on
+ * inference efficiency (Sec. 4.3, last paragraph) is that a backend could keep the shared K,V
+ * on chip across consecutive layers.  A caller that runs the group's layers back to back on one
+ * chunk of sequences whose slice of the slot fits the on-chip caches (256 MiB of Infinity Cache on
+ * MI355X), chunk by chunk, reads the slot from HBM once per group instead of once per layer.
+ * SKV_ERR_INVALID_ARG if the range is empty or leaves [0, batch). */
+skv_status_t skv_decode_range_workspace_bytes(const skv_cache_t *cache, int32_t seq_count,
+                                              int32_t max_kv_len, size_t *bytes);
+skv_status_t skv_attn_decode_range(skv_cache_t *cache, int32_t layer, int32_t seq_begin, int32_t seq_count,
+                                   const void *q, void *out, const int32_t *kv_lens, int32_t max_kv_len,
+                                   float scale, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Pre-fill-phase attention: q_lens[b] query rows per sequence; row i sits at absolute position
  * kv_lens[b] - q_lens[b] + i and sees cached positions 0..that position of the routed slot.
  * q, out: device [batch][max_q][n_q_heads][head_dim]; rows i >= q_lens[b] are neither read nor

@@ -10,7 +10,7 @@ __all__ = [
     "skv_route_from_strategy", "skv_route_validate", "skv_cache_bytes", "skv_cache_alloc",
     "skv_cache_free", "skv_cache_info", "skv_cache_slot_of_layer", "skv_cache_set_block_table",
     "skv_cache_device_faults", "skv_kv_append", "skv_decode_workspace_bytes", "skv_attn_decode",
-    "skv_attn_prefill", "skv_status_str", "skv_last_hip_error", "skv_last_kernel_name",
+    "skv_decode_range_workspace_bytes", "skv_attn_decode_range", "skv_attn_prefill", "skv_status_str", "skv_last_hip_error", "skv_last_kernel_name",
 ]
 
 SKV_F32, SKV_F16, SKV_BF16 = 0, 1, 2
@@ -193,6 +193,22 @@ def skv_attn_decode(cache: Cache, layer: int, q, out, kv_lens, max_kv_len: int, 
     _check(lib().skv_attn_decode(cache.handle, layer, _ptr(q), _ptr(out), _ptr(kv_lens), max_kv_len,
                                  ctypes.c_float(scale), _ptr(workspace), ctypes.c_size_t(wb),
                                  _stream(stream)), "skv_attn_decode")
+
+
+def skv_decode_range_workspace_bytes(cache: Cache, seq_count: int, max_kv_len: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().skv_decode_range_workspace_bytes(cache.handle, seq_count, max_kv_len, ctypes.byref(out)),
+           "skv_decode_range_workspace_bytes")
+    return out.value
+
+
+def skv_attn_decode_range(cache: Cache, layer: int, seq_begin: int, seq_count: int, q, out, kv_lens,
+                          max_kv_len: int, scale: float, workspace, stream=None):
+    """q, out, kv_lens: tensors (views) that start at the first sequence of the range."""
+    wb = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().skv_attn_decode_range(cache.handle, layer, seq_begin, seq_count, _ptr(q), _ptr(out),
+                                       _ptr(kv_lens), max_kv_len, ctypes.c_float(scale), _ptr(workspace),
+                                       ctypes.c_size_t(wb), _stream(stream)), "skv_attn_decode_range")
 
 
 def skv_attn_prefill(cache: Cache, layer: int, q, out, q_lens, kv_lens, max_q: int, max_kv_len: int,

@@ -94,7 +94,7 @@ skv::SlotView view_of(const skv_cache *c, int slot) {
 
 // Key-axis chunk covered by one work item of the decode kernels.  Deterministic in
 // (batch, n_kv_heads, max_kv_len) so that the workspace size and the launch agree.
-int32_t decode_keys_per_split(const skv_cache *c, int32_t max_kv_len) {
+int32_t decode_keys_per_split(const skv_cache *c, int32_t n_seqs, int32_t max_kv_len) {
     static const int forced = [] { // tuning knob: SKV_DECODE_KEYS_PER_SPLIT=<multiple of 128>
         const char *e = getenv("SKV_DECODE_KEYS_PER_SPLIT");
         const int v = e ? atoi(e) : 0;
@@ -105,7 +105,7 @@ int32_t decode_keys_per_split(const skv_cache *c, int32_t max_kv_len) {
     // within 256..2048 keys.  Measured on the Llama-3-8B decode shape: with two tiles per wave in
     // flight the kernel gains from long splits (fewer pipeline fills and partial results), and
     // four equal work groups per CU still balance.
-    const int64_t units = (int64_t)c->d.batch * c->d.n_kv_heads;
+    const int64_t units = (int64_t)n_seqs * c->d.n_kv_heads;
     int64_t kps = (int64_t)max_kv_len * units / 1024;
     kps = ((kps + 255) / 256) * 256;
     return (int32_t)std::min<int64_t>(2048, std::max<int64_t>(256, kps));
@@ -275,26 +275,42 @@ skv_status_t skv_kv_append(skv_cache_t *c, int32_t layer, const void *k_new, con
     return e == hipSuccess ? SKV_OK : hip_fail(e);
 }
 
-skv_status_t skv_decode_workspace_bytes(const skv_cache_t *c, int32_t max_kv_len, size_t *bytes) {
-    if (!c || !bytes || max_kv_len <= 0) return SKV_ERR_INVALID_ARG;
-    const int32_t kps = decode_keys_per_split(c, max_kv_len);
+skv_status_t skv_decode_range_workspace_bytes(const skv_cache_t *c, int32_t seq_count, int32_t max_kv_len,
+                                              size_t *bytes) {
+    if (!c || !bytes || max_kv_len <= 0 || seq_count <= 0 || seq_count > c->d.batch) return SKV_ERR_INVALID_ARG;
+    const int32_t kps = decode_keys_per_split(c, seq_count, max_kv_len);
     const size_t n_splits = (size_t)(max_kv_len + kps - 1) / kps;
-    *bytes = (size_t)c->d.batch * c->d.n_q_heads * n_splits * (c->d.head_dim + 2) * sizeof(float);
+    *bytes = (size_t)seq_count * c->d.n_q_heads * n_splits * (c->d.head_dim + 2) * sizeof(float);
     return SKV_OK;
 }
 
-skv_status_t skv_attn_decode(skv_cache_t *c, int32_t layer, const void *q, void *out,
-                             const int32_t *kv_lens, int32_t max_kv_len, float scale, void *workspace,
-                             size_t workspace_bytes, void *stream) {
+skv_status_t skv_decode_workspace_bytes(const skv_cache_t *c, int32_t max_kv_len, size_t *bytes) {
+    if (!c) return SKV_ERR_INVALID_ARG;
+    return skv_decode_range_workspace_bytes(c, c->d.batch, max_kv_len, bytes);
+}
+
+skv_status_t skv_attn_decode_range(skv_cache_t *c, int32_t layer, int32_t seq_begin, int32_t seq_count,
+                                   const void *q, void *out, const int32_t *kv_lens, int32_t max_kv_len,
+                                   float scale, void *workspace, size_t workspace_bytes, void *stream) {
     if (!c || !q || !out || !kv_lens) return SKV_ERR_INVALID_ARG;
     if (layer < 0 || layer >= c->d.n_layers || max_kv_len <= 0) return SKV_ERR_INVALID_ARG;
+    if (seq_begin < 0 || seq_count <= 0 || seq_begin > c->d.batch - seq_count) return SKV_ERR_INVALID_ARG;
     if (!(scale > 0.f)) return SKV_ERR_INVALID_ARG;
     if (!paged_ready(c)) return SKV_ERR_INVALID_ARG;
-    const skv::SlotView view = view_of(c, c->slot[layer]);
+    skv::SlotView view = view_of(c, c->slot[layer]);
     if (max_kv_len > view.max_ctx) return SKV_ERR_CAPACITY;
     size_t need = 0;
-    skv_decode_workspace_bytes(c, max_kv_len, &need);
+    skv_decode_range_workspace_bytes(c, seq_count, max_kv_len, &need);
     if (!workspace || workspace_bytes < need) return SKV_ERR_INVALID_ARG;
+
+    // The kernels number sequences from 0: move the view to the first sequence of the range.
+    if (view.block_table != nullptr) {
+        view.block_table += (size_t)seq_begin * view.max_blocks_per_seq;
+    } else {
+        const size_t seq_bytes = (size_t)view.max_ctx * c->d.n_kv_heads * c->d.head_dim * elem_bytes(c->d.dtype);
+        view.k = (const char *)view.k + (size_t)seq_begin * seq_bytes;
+        view.v = (const char *)view.v + (size_t)seq_begin * seq_bytes;
+    }
 
     skv::AttnArgs a;
     a.cache = view;
@@ -302,15 +318,15 @@ skv_status_t skv_attn_decode(skv_cache_t *c, int32_t layer, const void *q, void 
     a.out = out;
     a.q_lens = nullptr;
     a.kv_lens = kv_lens;
-    a.batch = c->d.batch;
+    a.batch = seq_count;
     a.max_q = 1;
     a.n_q_heads = c->d.n_q_heads;
     a.max_kv_len = max_kv_len;
-    a.keys_per_split = decode_keys_per_split(c, max_kv_len);
+    a.keys_per_split = decode_keys_per_split(c, seq_count, max_kv_len);
     a.n_splits = (max_kv_len + a.keys_per_split - 1) / a.keys_per_split;
     a.scale_log2e = scale * 1.4426950408889634f;
     a.part_o = (float *)workspace;
-    a.part_ml = a.part_o + (size_t)c->d.batch * c->d.n_q_heads * a.n_splits * c->d.head_dim;
+    a.part_ml = a.part_o + (size_t)seq_count * c->d.n_q_heads * a.n_splits * c->d.head_dim;
     a.work_counters = (int32_t *)c->faults + 16; // inside the cache's zero-initialised 256-byte device block
 
     const int g = c->d.n_q_heads / c->d.n_kv_heads;
@@ -321,6 +337,14 @@ skv_status_t skv_attn_decode(skv_cache_t *c, int32_t layer, const void *q, void 
         e = skv::launch_attn_valu(a, c->d.dtype, c->d.head_dim, g, (hipStream_t)stream);
     if (e == hipSuccess && a.n_splits > 1) e = skv::launch_split_merge(a, c->d.dtype, (hipStream_t)stream);
     return e == hipSuccess ? SKV_OK : hip_fail(e);
+}
+
+skv_status_t skv_attn_decode(skv_cache_t *c, int32_t layer, const void *q, void *out,
+                             const int32_t *kv_lens, int32_t max_kv_len, float scale, void *workspace,
+                             size_t workspace_bytes, void *stream) {
+    if (!c) return SKV_ERR_INVALID_ARG;
+    return skv_attn_decode_range(c, layer, 0, c->d.batch, q, out, kv_lens, max_kv_len, scale, workspace,
+                                 workspace_bytes, stream);
 }
 
 skv_status_t skv_attn_prefill(skv_cache_t *c, int32_t layer, const void *q, void *out,

@@ -108,6 +108,9 @@ def test_null_handles_and_no_device_behaviour():
     assert lib.skv_cache_info(None, None, None, None, None) == 1
     assert lib.skv_kv_append(None, 0, None, None, None, None, 1, None) == 1
     assert lib.skv_attn_decode(None, 0, None, None, None, 1, ctypes.c_float(1.0), None, 0, None) == 1
+    assert lib.skv_attn_decode_range(None, 0, 0, 1, None, None, None, 1, ctypes.c_float(1.0), None, 0, None) == 1
+    n = ctypes.c_size_t(0)
+    assert lib.skv_decode_range_workspace_bytes(None, 1, 1, ctypes.byref(n)) == 1
     assert lib.skv_attn_prefill(None, 0, None, None, None, None, 1, 1, ctypes.c_float(1.0), None) == 1
     assert lib.skv_cache_bytes(None, None) == 1
     import torch
