@@ -189,7 +189,9 @@ def run_decode(args, torch, skv, H, configs):
     res = {
         "value": round(value, 1), "ms_per_step": round(ms_per_step, 4), "cross_layer_reuse": reuse,
         "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(kernel_name),
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     # the committed counter summary was taken on the default workload only
+                     "traffic": measured_traffic(kernel_name) if args.decode_workload == "llama3_decode" else None,
                      "launch_us": round(call_ms * 1e3, 2), "algorithmic_bytes_per_launch": layer_bytes},
         "workload": w,
     }
