@@ -229,3 +229,37 @@ def test_scale_must_be_positive():
         with pytest.raises(skv.SkvError) as e:
             skv.skv_attn_prefill(cache, 0, q, torch.empty_like(q), lens, lens, 1, 64, bad)
         assert e.value.status == 1
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_prefill_with_growing_scores_rescales_often(dtype):
+    """Keys whose norm grows with the position: the running row maximum keeps jumping by far more
+    than the lazy-rescale threshold, so the rescale path of the prefill kernels (new maximum,
+    deferred O and row-sum rescale) runs on most tiles instead of once."""
+    tdt = {"bf16": torch.bfloat16, "f16": torch.float16}[dtype]
+    B, S, Hq, Hkv, D = 2, 700, 2, 1, 128
+    route = [0, 0]
+    w = _small(dtype, Hq, Hkv, D, B, [S, 450], route, False, seed=123)
+    g = torch.Generator().manual_seed(7)
+    grow = (0.1 + 0.012 * torch.arange(S, dtype=torch.float32)).view(1, S, 1, 1)
+    k = (torch.randn(B, S, Hkv, D, generator=g) * grow).to(tdt)
+    v = torch.randn(B, S, Hkv, D, generator=g).to(tdt)
+    q = torch.randn(B, S, Hq, D, generator=g).to(tdt)
+    lens = np.array([S, 450], dtype=np.int32)
+    cache, _ = H.alloc_cache(w)
+    d_lens = torch.from_numpy(lens).cuda()
+    zeros = torch.zeros(B, dtype=torch.int32, device="cuda")
+    skv.skv_kv_append(cache, 0, k.cuda(), v.cuda(), zeros, d_lens, S)
+    oc = O.Cache(route, B, w.max_ctx, Hkv, D, np.uint16)
+    oc.append(0, gen.to_f64(k), gen.to_f64(v), gen.to_bits(k), gen.to_bits(v), np.zeros(B, dtype=np.int64), lens)
+    for layer in (0, 1):
+        out = torch.full_like(q, 7.0, device="cuda")
+        skv.skv_attn_prefill(cache, layer, q.cuda(), out, d_lens, d_lens, S, S, w.scale)
+        want = O.prefill(oc, layer, gen.to_f64(q), lens, lens, w.scale)
+        got = gen.to_f64(out)
+        for b in range(B):
+            err = float(np.abs(got[b, : lens[b]] - want[b, : lens[b]]).max())
+            assert err <= H.TOL[dtype], (layer, b, err)
+    assert skv.skv_cache_device_faults(cache) == 0
+    cache.free()
