@@ -130,7 +130,7 @@ def run_decode(args, torch, skv, H, configs):
     log(f"[bench] workload {w.name}: B={w.batch} ctx={int(w.kv_lens[0])} layers={w.n_layers} slots={len(w.owner_layers)}")
     cache, _ = H.alloc_cache(w)
     t0 = time.perf_counter()
-    H.fill_by_append(cache, w, lens=w.kv_lens - 1)
+    H.fill_by_append(cache, w, lens=w.kv_lens - 1, chunk_tokens=args.fill_chunk_tokens)
     log(f"[bench] cache of {skv.skv_cache_info(cache)[3] * 2 / 2**30:.1f} GiB filled through skv_kv_append in {time.perf_counter() - t0:.1f} s")
     ctx = int(w.kv_lens.max())
     d_lens = torch.from_numpy(w.kv_lens).cuda()
@@ -268,6 +268,8 @@ def main():
     ap.add_argument("--decode-workload", default="llama3_decode", choices=["llama3_decode", "qwen3_paged", "llama2_mha"],
                     help="decode workload to time (default: the one the metric is quoted on)")
     ap.add_argument("--mha-batch", type=int, default=32, help="batch of the llama2_mha workload")
+    ap.add_argument("--fill-chunk-tokens", type=int, default=1 << 19,
+                    help="tokens generated per append call while the cache is filled (bounds the temporaries)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device copy 5 times (reference for HBM byte counters)")
     args = ap.parse_args()

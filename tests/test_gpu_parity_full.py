@@ -13,11 +13,17 @@ from workloads import configs, gen
 pytestmark = pytest.mark.gpu
 
 
-def _decode_sampled(w, seqs_per_layer, heads_per_seq, must_seqs=()):
+def _decode_sampled(w, seqs_per_layer, heads_per_seq, must_seqs=(), fill_chunk_tokens=1 << 19, skip_if_oom=False):
     print(f"\n{w.name}: B={w.batch} layers={w.n_layers} slots={len(w.owner_layers)} "
           f"sum(len)={int(w.kv_lens.sum())}", flush=True)
-    cache, _ = H.alloc_cache(w)
-    H.fill_by_append(cache, w, lens=w.kv_lens - 1)
+    torch.cuda.empty_cache()   # hand cached blocks of earlier tests back to the driver
+    try:
+        cache, _ = H.alloc_cache(w)
+    except skv.SkvError as e:
+        if skip_if_oom and e.status == 5:     # SKV_ERR_OOM: this device has less free memory than 288 GB
+            pytest.skip("not enough free device memory for the largest batch")
+        raise
+    H.fill_by_append(cache, w, lens=w.kv_lens - 1, chunk_tokens=fill_chunk_tokens)
     max_len = int(w.kv_lens.max())
     d_lens = torch.from_numpy(w.kv_lens).cuda()
     d_start = (d_lens - 1).to(torch.int32)
@@ -70,6 +76,13 @@ def test_config4_qwen3_paged_ragged_decode_full_size():
 
 def test_config5_llama2_mha_decode_f16_batch32():
     _decode_sampled(configs.llama2_mha_decode(batch=32), seqs_per_layer=1, heads_per_seq=3)
+
+
+def test_config5_llama2_mha_decode_f16_largest_batch_that_fits():
+    """One slot per 8 layers: 1 GiB of cache per sequence instead of 8, so 256 sequences of 16384
+    tokens (256 GiB) fit the 288 GB of one MI355X."""
+    _decode_sampled(configs.llama2_mha_decode(batch=256), seqs_per_layer=1, heads_per_seq=2,
+                    fill_chunk_tokens=1 << 15, skip_if_oom=True)
 
 
 def test_config3_llama3_prefill_bf16_full_size():
