@@ -201,6 +201,32 @@ def run_decode(args, torch, skv, H, configs):
     return res
 
 
+def mfma_only_rate(torch, skv):
+    """TFLOP/s of back-to-back v_mfma_f32_32x32x16_bf16 and nothing else, one wave per SIMD on all
+    256 compute units, with all-zero operands and with Gaussian ones (a different operand pair for
+    every instruction, as in attention).  The second figure is what the power limit of the device
+    leaves of the first."""
+    blocks, iters = 256, 6000                      # about 3 ms per launch
+    sink = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
+    gen_ = torch.Generator(device="cpu").manual_seed(1234)
+    ops = {"zeros": torch.zeros(8192, dtype=torch.bfloat16, device="cuda"),
+           "gaussian": torch.randn(8192, generator=gen_).to(torch.bfloat16).cuda()}
+    flops = blocks * 4 * iters * 32 * 32768
+    out = {}
+    for name, t in ops.items():
+        best = float("inf")
+        for rep in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            skv.skv_calib_mfma_bf16(t, sink, blocks, iters)
+            e1.record()
+            torch.cuda.synchronize()
+            if rep >= 2:
+                best = min(best, e0.elapsed_time(e1))
+        out[name] = round(flops / (best * 1e-3) / 1e12, 1)
+    return out
+
+
 def run_prefill(args, torch, skv, H, configs):
     w = configs.llama3_prefill()
     S = int(w.kv_lens.max())
@@ -251,6 +277,9 @@ def run_prefill(args, torch, skv, H, configs):
                         "traffic": measured_traffic(skv.skv_last_kernel_name()),
                         "launch_us": round(call_ms * 1e3, 1), "algorithmic_flops_per_launch": flops}}
     cache.free()
+    # the published peak is what "frac" is quoted on; the rates an MFMA-only kernel reaches on this
+    # device, measured in the same run, say how much of it any kernel can get
+    res["roofline"]["mfma_only_tflops"] = mfma_only_rate(torch, skv)
     return res
 
 

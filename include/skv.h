@@ -185,6 +185,18 @@ int32_t skv_last_hip_error(void);
  * for profiling scripts that have to find it in a trace. */
 const char *skv_last_kernel_name(void);
 
+
+/* ---- measurement aid (no part of the attention path) --------------------------------------- */
+/* Runs iters x 32 back-to-back v_mfma_f32_32x32x16_bf16 (32768 flop each) on every one of the
+ * 4 * blocks waves of the launch (work groups of 256 threads, one wave per SIMD) and nothing else:
+ * the rate the matrix cores of this device reach with the given operand values, the yardstick for
+ * the pre-fill kernel's MFMA utilisation.  operands: device, 16 KiB = 16 blocks of 64 lanes x
+ * 8 bf16 (A and B operand of 8 steps; every instruction takes a different pair).  sink: device
+ * float[blocks * 256], receives one value per lane so that the work cannot be dropped.
+ * Asynchronous on `stream`; the caller times it.  1 <= iters <= 2^20, else SKV_ERR_INVALID_ARG. */
+skv_status_t skv_calib_mfma_bf16(const void *operands, float *sink, int32_t blocks, int32_t iters,
+                                 void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -11,6 +11,7 @@ __all__ = [
     "skv_cache_free", "skv_cache_info", "skv_cache_slot_of_layer", "skv_cache_set_block_table",
     "skv_cache_device_faults", "skv_kv_append", "skv_decode_workspace_bytes", "skv_attn_decode",
     "skv_decode_range_workspace_bytes", "skv_attn_decode_range", "skv_attn_prefill", "skv_status_str", "skv_last_hip_error", "skv_last_kernel_name",
+    "skv_calib_mfma_bf16",
 ]
 
 SKV_F32, SKV_F16, SKV_BF16 = 0, 1, 2
@@ -216,6 +217,14 @@ def skv_attn_prefill(cache: Cache, layer: int, q, out, q_lens, kv_lens, max_q: i
     _check(lib().skv_attn_prefill(cache.handle, layer, _ptr(q), _ptr(out), _ptr(q_lens), _ptr(kv_lens),
                                   max_q, max_kv_len, ctypes.c_float(scale), _stream(stream)),
            "skv_attn_prefill")
+
+
+def skv_calib_mfma_bf16(operands, sink, blocks: int, iters: int, stream=None):
+    """operands: 16 KiB device tensor; sink: float32 device tensor of blocks * 256 elements."""
+    if operands.numel() * operands.element_size() < 16384 or sink.numel() < blocks * 256 or sink.dtype != torch.float32:
+        raise ValueError("skv_calib_mfma_bf16: operands need 16 KiB, sink blocks * 256 floats")
+    _check(lib().skv_calib_mfma_bf16(_ptr(operands), _ptr(sink), blocks, iters, _stream(stream)),
+           "skv_calib_mfma_bf16")
 
 
 def skv_status_str(status: int) -> str:

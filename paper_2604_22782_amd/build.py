@@ -36,9 +36,11 @@ def _compile(src: str) -> str:
 
 def build_library(verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    # the instruction stream of the pipelined pre-fill kernel is written by a generator
-    subprocess.check_call([sys.executable, os.path.join(CSRC, "gen_prefill_pipe.py"),
-                           os.path.join(OBJ, "prefill_pipe_body.inc")])
+    # the instruction streams of the pipelined pre-fill kernel (one per wave shape) are written by a generator
+    for nq in (1, 2):
+        subprocess.check_call([sys.executable, os.path.join(CSRC, "gen_prefill_pipe.py"),
+                               os.path.join(OBJ, f"prefill_pipe_body_nq{nq}.inc")],
+                              env={**os.environ, "SKV_GEN_NQ": str(nq)})
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
     with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
         objs = list(ex.map(_compile, srcs))

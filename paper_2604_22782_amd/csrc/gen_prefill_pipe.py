@@ -50,43 +50,54 @@ STAGE = 2 * T_BYTES       # K then V
 N_STAGE = 4
 LDS_BYTES = N_STAGE * STAGE
 
+# ---- shape ------------------------------------------------------------------------------------------
+# NQ = row blocks of 32 per wave.  NQ = 2: 4 waves per work group, one per SIMD, ~400 registers per
+# lane, every LDS operand feeds two MFMAs.  NQ = 1: 8 waves per work group, two per SIMD, < 256
+# registers per lane, so the second wave can issue while the first waits.
+NQ = int(os.environ.get("SKV_GEN_NQ", "2"))
+assert NQ in (1, 2)
+WAVES = 8 // NQ                       # waves per work group (256 query rows)
+THREADS = 64 * WAVES
+CPW = 16 // WAVES                     # 1 KiB chunks per wave, tile and tensor
+NEL = 16 * NQ                         # scores per lane and half tile
+
 # ---- register names ---------------------------------------------------------------------------
 PD = int(os.environ.get("SKV_GEN_PD", "2"))      # operand groups fetched ahead of the MFMAs that use them
 RING = int(os.environ.get("SKV_GEN_RING", "4"))  # operand buffers per ring (> PD)
 
-SA, SB = 32, 64
-PA, PB = 96, 112
-KO = 128
-VO = KO + 4 * RING
-_T = VO + 4 * RING
-T_MAX = (_T + 0, _T + 1)
-T_MAX2 = (_T + 2, _T + 3)
-M_NEW = (_T + 4, _T + 5)
-M_RUN = (_T + 6, _T + 7)
-NEG_MC = (_T + 8, _T + 9)
-L_SUM = (_T + 10, _T + 11)
-ALPHA = (_T + 12, _T + 13)
-LIM = (_T + 14, _T + 15)
-DIFF = (_T + 16, _T + 17)
-LANE, COL, HH = _T + 18, _T + 19, _T + 20
-KL, VL = _T + 21, _T + 22              # lane parts of the K / V^T read addresses (LDS base included)
-KA_CUR, KA_NXT = _T + 23, _T + 24      # K read address of tile t / t+1
-VA_PRV, VA_CUR = _T + 25, _T + 26      # V^T read address of tile t-1 / t
-ROWB, PIECE = _T + 27, _T + 28         # staging: first row of this lane in a tile, byte offset of its piece
-VOFF = (_T + 29, _T + 30, _T + 31, _T + 32)  # byte offsets of this lane's 4 rows of the tile being fetched
-NEG_INF = _T + 33
-TMP = tuple(range(_T + 34, _T + 50))   # scratch (16, 8-aligned halves not required)
-Q_OFF = (_T + 50, _T + 51)
-O_OFF = (_T + 52, _T + 53)
-ROW = (_T + 54, _T + 55)
-STG = _T + 56                          # scratch of the staging address arithmetic
-ONES4 = _T + 58                        # 4 registers of 16-bit ones (A operand of the row-sum MFMA)
-VBO = (_T + 62, _T + 63, _T + 64, _T + 65)   # byte offsets of the lane's 4 rows in tile 0 (constants)
-LIMV = _T + 66                         # byte offset of the lane's piece in the last needed row
-assert ONES4 % 2 == 0 and LIMV < 256 and PD < RING
-assert TMP[4] % 2 == 0 and TMP[12] % 2 == 0   # 64-bit store operands
+FIRST_V = 24 if NQ == 2 else 8        # v[0:FIRST_V) are left to the compiler
+_next = [32 if NQ == 2 else 8]
 
-A_O, A_Q, A_L = 0, 128, 192
+
+def _alloc(n=1, align=1):
+    base = (_next[0] + align - 1) // align * align
+    _next[0] = base + n
+    return base
+
+
+SA, SB = _alloc(16 * NQ, 4), _alloc(16 * NQ, 4)      # S^T of even / odd half tiles [nq][16]
+PA, PB = _alloc(8 * NQ, 4), _alloc(8 * NQ, 4)        # P^T of even / odd half tiles [nq][2][4]
+KO = _alloc(4 * RING, 4)
+VO = _alloc(4 * RING, 4)
+_per_q = lambda: tuple(_alloc() for _ in range(NQ))
+T_MAX, T_MAX2, M_NEW, M_RUN, NEG_MC, L_SUM, ALPHA, LIM, DIFF = (_per_q() for _ in range(9))
+LANE, COL, HH = _alloc(), _alloc(), _alloc()
+KL, VL = _alloc(), _alloc()            # lane parts of the K / V^T read addresses (LDS base included)
+KA_CUR, KA_NXT = _alloc(), _alloc()    # K read address of tile t / t+1
+VA_PRV, VA_CUR = _alloc(), _alloc()    # V^T read address of tile t-1 / t
+ROWB, PIECE = _alloc(), _alloc()       # staging: first row of this lane in a tile, byte offset of its piece
+VOFF = tuple(_alloc() for _ in range(CPW))   # byte offsets of this lane's rows of the tile being fetched
+VBO = tuple(_alloc() for _ in range(CPW))    # ... in tile 0 (constants)
+LIMV = _alloc()                        # byte offset of the lane's piece in the last needed row
+NEG_INF = _alloc()
+STG = _alloc()
+Q_OFF, O_OFF, ROW = _per_q(), _per_q(), _per_q()
+TMP = tuple(range(_alloc(16, 2), _next[0]))   # scratch; TMP[4:6] and TMP[12:14] are 64-bit store operands
+ONES4 = _alloc(4, 2)                   # 4 registers of 16-bit ones (A operand of the row-sum MFMA)
+LAST_V = (_next[0] + 7) // 8 * 8 - 1
+assert LAST_V < 256 and PD < RING and TMP[4] % 2 == 0 and TMP[12] % 2 == 0
+
+A_O, A_Q, A_L = 0, 64 * NQ, 96 * NQ
 # Row sums of the weights by one extra MFMA per 16 keys and row block (an all-ones A operand
 # makes every row of the product the column sum) instead of 32 vector additions per half step.
 SUM_BY_MFMA = os.environ.get("SKV_GEN_SUM_MFMA", "0") == "1"
@@ -108,7 +119,7 @@ S_EXEC = 54                    # pair
 S_NK1 = 56
 S_SOFF, S_NKM63 = 57, 58       # scalar byte offset of the tile being requested; last needed key - 63
 
-FIRST_V, FIRST_S, LAST_S = 24, 40, 59
+FIRST_S, LAST_S = 40, 59
 
 
 class Asm:
@@ -164,38 +175,41 @@ def softmax_stream(A: Asm, s_cur: int, p_cur: int, masked: bool, tagid: str):
     """Returns a list of instruction strings.  s_cur: 32 registers [nq][16], element r of a block is
     key 8 (r / 4) + 4 hh + (r % 4) of the half tile.  p_cur: 16 registers [nq][2][4]."""
     o = []
-    S = [[s_cur + 16 * q + r for r in range(16)] for q in range(2)]
+    S = [[s_cur + 16 * q + r for r in range(16)] for q in range(NQ)]
     if masked:
         # key offset inside the half tile vs. (row position - first key of the half tile - 4 hh)
         for r in range(16):
-            for q in range(2):
+            for q in range(NQ):
                 kk = 8 * (r // 4) + (r % 4)
                 o.append(f"v_cmp_lt_i32_e64 vcc, {vr(LIM[q])}, {kk}")
                 o.append(f"v_cndmask_b32_e32 {vr(S[q][r])}, {vr(S[q][r])}, {vr(NEG_INF)}, vcc")
-    for q in range(2):
+    for q in range(NQ):
         o.append(f"v_max3_f32 {vr(T_MAX[q])}, {vr(S[q][0])}, {vr(S[q][1])}, {vr(S[q][2])}")
     for k in range(6):
-        for q in range(2):
+        for q in range(NQ):
             o.append(f"v_max3_f32 {vr(T_MAX[q])}, {vr(T_MAX[q])}, {vr(S[q][3 + 2 * k])}, {vr(S[q][4 + 2 * k])}")
-    for q in range(2):
+    for q in range(NQ):
         o.append(f"v_max_f32_e32 {vr(T_MAX[q])}, {vr(T_MAX[q])}, {vr(S[q][15])}")
-    for q in range(2):
+    for q in range(NQ):
         o.append(f"v_mov_b32_e32 {vr(T_MAX2[q])}, {vr(T_MAX[q])}")
     # the lane swap must not follow a vector write of its operands within two issue slots
     o.append("s_nop 1")
-    for q in range(2):
+    for q in range(NQ):
         # lanes 32-63 of the first operand <-> lanes 0-31 of the second: afterwards the first holds
         # the lower half's value in both halves, the second the upper half's
         o.append(f"v_permlane32_swap_b32_e32 {vr(T_MAX[q])}, {vr(T_MAX2[q])}")
     o.append("s_nop 1")
-    for q in range(2):
+    for q in range(NQ):
         o.append(f"v_max3_f32 {vr(M_NEW[q])}, {vr(T_MAX[q])}, {vr(T_MAX2[q])}, {vr(M_RUN[q])}")
-    for q in range(2):
+    for q in range(NQ):
         o.append(f"v_sub_f32_e32 {vr(DIFF[q])}, {vr(M_NEW[q])}, {vr(M_RUN[q])}")
     # rescale only when some row's maximum grew by more than 2^8 in weight (threshold in raw scores)
-    o.append(f"v_cmp_lt_f32_e64 {sr(S_CMP, 2)}, %[thr], {vr(DIFF[0])}")
-    o.append(f"v_cmp_lt_f32_e32 vcc, %[thr], {vr(DIFF[1])}")
-    o.append(f"s_or_b64 vcc, vcc, {sr(S_CMP, 2)}")
+    if NQ == 2:
+        o.append(f"v_cmp_lt_f32_e64 {sr(S_CMP, 2)}, %[thr], {vr(DIFF[0])}")
+        o.append(f"v_cmp_lt_f32_e32 vcc, %[thr], {vr(DIFF[1])}")
+        o.append(f"s_or_b64 vcc, vcc, {sr(S_CMP, 2)}")
+    else:
+        o.append(f"v_cmp_lt_f32_e32 vcc, %[thr], {vr(DIFF[0])}")
     # one entry: nothing may be scheduled between the branch and the label its target returns to
     o.append(f"s_cbranch_vccnz L_RESC_{tagid}_%=\nL_RET_{tagid}_%=:")
     # weights 2^(cs s - cs m), their row sums and their 16-bit form, software-pipelined element by
@@ -203,7 +217,7 @@ def softmax_stream(A: Asm, s_cur: int, p_cur: int, masked: bool, tagid: str):
     # (a run of them would leave the matrix cores waiting for the in-order instruction stream).
     # A v_exp result is first read two instructions later; v_dot2 would sum the rounded pairs in one
     # instruction but runs on the matrix pipeline and does not overlap with MFMAs.
-    elems = [(i % 2, i // 2) for i in range(32)]  # (q, r), alternating row blocks
+    elems = [(i % NQ, i // NQ) for i in range(NEL)]  # (q, r), alternating row blocks
 
     def pack(q, j):
         d = p_cur + 8 * q + j
@@ -213,21 +227,21 @@ def softmax_stream(A: Asm, s_cur: int, p_cur: int, masked: bool, tagid: str):
                 f"v_cvt_f16_f32_e32 {vr(S[q][2 * j + 1])}, {vr(S[q][2 * j + 1])}",
                 f"v_pack_b32_f16 {vr(d)}, {vr(S[q][2 * j])}, {vr(S[q][2 * j + 1])}"]
 
-    for i in range(32 + USE_LAG):
-        if i < 32:
+    for i in range(NEL + USE_LAG):
+        if i < NEL:
             q, r = elems[i]
             o.append(f"v_fma_f32 {vr(S[q][r])}, {vr(S[q][r])}, %[cs], {vr(NEG_MC[q])}")
-        if EXP_LAG <= i < 32 + EXP_LAG:
+        if EXP_LAG <= i < NEL + EXP_LAG:
             q, r = elems[i - EXP_LAG]
             o.append(f"v_exp_f32_e32 {vr(S[q][r])}, {vr(S[q][r])}")
-        if USE_LAG <= i < 32 + USE_LAG:
+        if USE_LAG <= i < NEL + USE_LAG:
             q, r = elems[i - USE_LAG]
             if not SUM_BY_MFMA:
                 o.append(f"v_add_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}, {vr(S[q][r])}")
             if r % 2 == 1:  # both elements of register pair (q, r / 2) are final
                 o += pack(q, r // 2)
     if masked:
-        for q in range(2):
+        for q in range(NQ):
             o.append(f"v_subrev_u32_e32 {vr(LIM[q])}, 32, {vr(LIM[q])}")
     return o
 
@@ -235,18 +249,18 @@ def softmax_stream(A: Asm, s_cur: int, p_cur: int, masked: bool, tagid: str):
 def rescale_blocks(A: Asm, tagid: str):
     """Out-of-line code of one half step: new running maximum, and the deferred O rescale."""
     A.e(f"L_RESC_{tagid}_%=:")
-    for q in range(2):
+    for q in range(NQ):
         A.e(f"v_sub_f32_e32 {vr(ALPHA[q])}, {vr(M_RUN[q])}, {vr(M_NEW[q])}")
-    for q in range(2):
+    for q in range(NQ):
         A.e(f"v_mul_f32_e32 {vr(ALPHA[q])}, %[cs], {vr(ALPHA[q])}")
-    for q in range(2):
+    for q in range(NQ):
         A.e(f"v_exp_f32_e32 {vr(ALPHA[q])}, {vr(ALPHA[q])}")
-    for q in range(2):
+    for q in range(NQ):
         A.e(f"v_mov_b32_e32 {vr(M_RUN[q])}, {vr(M_NEW[q])}")
-    for q in range(2):
+    for q in range(NQ):
         A.e(f"v_mul_f32_e32 {vr(NEG_MC[q])}, {sr(S_NCS)}, {vr(M_NEW[q])}")
     if not SUM_BY_MFMA:
-        for q in range(2):  # >= 4 instructions after the exponentials
+        for q in range(NQ):  # >= 4 instructions after the exponentials
             A.e(f"v_mul_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}, {vr(ALPHA[q])}")
     A.e(f"s_mov_b32 {sr(S_FLAG)}, 1")
     A.e(f"s_branch L_RET_{tagid}_%=")
@@ -255,7 +269,7 @@ def rescale_blocks(A: Asm, tagid: str):
     # the accumulators were last written by MFMAs issued a few instructions ago: let them retire
     for _ in range(3):
         A.e("s_nop 7")
-    for q in range(2):
+    for q in range(NQ):
         for i in range(0, 64, 8):
             for k in range(8):
                 A.e(f"v_accvgpr_read_b32 {vr(TMP[k])}, {ar(A_O + 64 * q + i + k)}")
@@ -264,11 +278,11 @@ def rescale_blocks(A: Asm, tagid: str):
             for k in range(8):
                 A.e(f"v_accvgpr_write_b32 {ar(A_O + 64 * q + i + k)}, {vr(TMP[k])}")
     if SUM_BY_MFMA:
-        for q in range(2):
+        for q in range(NQ):
             A.e(f"v_accvgpr_read_b32 {vr(TMP[q])}, {ar(A_L + 16 * q)}")
-        for q in range(2):
+        for q in range(NQ):
             A.e(f"v_mul_f32_e32 {vr(TMP[q])}, {vr(TMP[q])}, {vr(ALPHA[q])}")
-        for q in range(2):
+        for q in range(NQ):
             A.e(f"v_accvgpr_write_b32 {ar(A_L + 16 * q)}, {vr(TMP[q])}")
     A.e("s_nop 7")
     A.e(f"s_mov_b32 {sr(S_FLAG)}, 0")
@@ -305,7 +319,7 @@ def half_step(A: Asm, hs: int, qk, pv, sm, nxt, extra, tagid: str, cold=False, p
     # MFMAs of the half step in issue order; a "gap" of other instructions follows each of them
     slots = []
     for g in range(8):
-        for q in range(2):
+        for q in range(NQ):
             if qk:
                 slots.append(("qk", g, q))
             if pv:
@@ -353,7 +367,7 @@ def half_step(A: Asm, hs: int, qk, pv, sm, nxt, extra, tagid: str, cold=False, p
                 # every operand of this half step has been requested: wait for the last one (reads
                 # return in order), for this wave's loads of the tile after next, then meet the others
                 A.wait_lds(("Vh", hs, 7))
-                A.e("s_waitcnt vmcnt(8)")  # all but the 8 newest loads (the tile requested last) landed
+                A.e(f"s_waitcnt vmcnt({2 * CPW})")  # all but the newest loads (the tile requested last) landed
                 A.e("s_barrier")
             if g + PD < 8:
                 fetch(hs, g + PD, kcfg, vcfg)
@@ -396,7 +410,7 @@ def clamped_offsets():
     past the last needed key repeating it (finite, and masked wherever they are not the real
     key); the scalar offset then is zero."""
     o = []
-    for i in range(4):
+    for i in range(CPW):
         o.append(f"v_add_u32_e32 {vr(VOFF[i])}, {sr(S_SOFF)}, {vr(VBO[i])}")
         o.append(f"v_min_u32_e32 {vr(VOFF[i])}, {vr(LIMV)}, {vr(VOFF[i])}")
     o.append(f"s_mov_b32 {sr(S_SOFF)}, 0")
@@ -425,11 +439,11 @@ def staging_ops(tagid: str):
                 "\n".join([f"s_cbranch_scc1 L_INRANGE_{tagid}_%="] + clamped_offsets() + [f"L_INRANGE_{tagid}_%=:"])]}
     tail = {}
     n = 0
-    for i in range(4):
+    for i in range(CPW):
         for which in ("k", "v"):
             m0w, ld = tile_load(which, i, S_STW)
-            head[2 + 3 * n] = [m0w]
-            tail[2 + 3 * n] = [ld]
+            head[2 + (12 // CPW) * n] = [m0w]
+            tail[2 + (12 // CPW) * n] = [ld]
             n += 1
     return head, tail
 
@@ -462,7 +476,7 @@ def body(A: Asm, masked: bool, name: str):
 
 def body_stage_only(A: Asm):
     rotate_addresses(A, vector=False)
-    A.e("s_waitcnt vmcnt(8)")
+    A.e(f"s_waitcnt vmcnt({2 * CPW})")
     A.e("s_barrier")
     head, tail = staging_ops("s")
     for gi in sorted(head):
@@ -541,14 +555,14 @@ def generate(dt: str) -> list[str]:
     e(f"v_add_u32_e32 {vr(VL)}, {sr(S_TMP)}, {vr(TMP[2])}")
     # staging: wave w fills chunks 4 w .. 4 w + 3 of each tensor; its lane L fetches piece L / 4 of
     # row L % 4 of the chunk
-    e(f"s_lshl_b32 {sr(S_TMP)}, %[wv], 4")
+    e(f"s_lshl_b32 {sr(S_TMP)}, %[wv], {2 + CPW.bit_length() - 1}")
     e(f"v_and_b32_e32 {vr(TMP[0])}, 3, {vr(LANE)}")
     e(f"v_add_u32_e32 {vr(ROWB)}, {sr(S_TMP)}, {vr(TMP[0])}")
     e(f"v_lshrrev_b32_e32 {vr(TMP[0])}, 2, {vr(LANE)}")
     e(f"v_lshlrev_b32_e32 {vr(PIECE)}, 4, {vr(TMP[0])}")
-    e(f"s_mul_i32 {sr(S_WBASE)}, %[wv], {4 * CHUNK}")
+    e(f"s_mul_i32 {sr(S_WBASE)}, %[wv], {CPW * CHUNK}")
     e(f"s_add_u32 {sr(S_WBASE)}, {sr(S_WBASE)}, %[lds]")
-    for i in range(4):
+    for i in range(CPW):
         e(f"v_add_u32_e32 {vr(TMP[0])}, {4 * i}, {vr(ROWB)}")
         e(f"v_mad_u32_u24 {vr(VBO[i])}, {vr(TMP[0])}, %[krb], {vr(PIECE)}")
     e(f"v_mov_b32_e32 {vr(TMP[0])}, {sr(S_NK1)}")
@@ -558,30 +572,30 @@ def generate(dt: str) -> list[str]:
     A.c("Q^T into AGPRs: lane (row c, k group hh) holds Q[row][16 s + 8 hh, +8); rows past the last valid one repeat it")
     e(f"s_sub_u32 {sr(S_TMP)}, %[rv], 1")
     e(f"v_lshlrev_b32_e32 {vr(TMP[2])}, 4, {vr(HH)}")
-    for q in range(2):
+    for q in range(NQ):
         e(f"v_add_u32_e32 {vr(ROW[q])}, {32 * q}, {vr(COL)}")
         e(f"v_min_u32_e32 {vr(TMP[0])}, {sr(S_TMP)}, {vr(ROW[q])}")
         e(f"v_mad_u32_u24 {vr(Q_OFF[q])}, {vr(TMP[0])}, %[qrs], {vr(TMP[2])}")
-    for q in range(2):
+    for q in range(NQ):
         for s in range(8):
             e(f"global_load_dwordx4 {ar(A_Q + 32 * q + 4 * s, 4)}, {vr(Q_OFF[q])}, %[qp] offset:{32 * s}")
     # output: element r of d block db is d = 32 db + 8 (r / 4) + 4 hh + (r % 4)
     e(f"v_lshlrev_b32_e32 {vr(TMP[2])}, 3, {vr(HH)}")
-    for q in range(2):
+    for q in range(NQ):
         e(f"v_mad_u32_u24 {vr(O_OFF[q])}, {vr(ROW[q])}, %[qrs], {vr(TMP[2])}")
 
     A.c("state")
-    for i in range(128):
+    for i in range(64 * NQ):
         e(f"v_accvgpr_write_b32 {ar(A_O + i)}, 0")
     if SUM_BY_MFMA:
-        for i in range(32):
+        for i in range(16 * NQ):
             e(f"v_accvgpr_write_b32 {ar(A_L + i)}, 0")
         for i in range(4):
             e(f"v_mov_b32_e32 {vr(ONES4 + i)}, 0x{ones:08x}")
-    for i in range(16):
+    for i in range(8 * NQ):
         e(f"v_mov_b32_e32 {vr(PB + i)}, 0")
     e(f"v_mov_b32_e32 {vr(NEG_INF)}, 0xff800000")
-    for q in range(2):
+    for q in range(NQ):
         e(f"v_mov_b32_e32 {vr(M_RUN[q])}, 0xff800000")
         e(f"v_mov_b32_e32 {vr(L_SUM[q])}, 0")
         e(f"v_mov_b32_e32 {vr(NEG_MC[q])}, 0")
@@ -594,28 +608,30 @@ def generate(dt: str) -> list[str]:
         for ins in clamped_offsets():
             e(ins)
         e(f"s_add_u32 {sr(S_STW)}, {sr(S_WBASE)}, {x * STAGE}")
-        for i in range(4):
+        for i in range(CPW):
             for which in ("k", "v"):
                 m0w, ld = tile_load(which, i, S_STW)
                 e(m0w)
                 e("s_nop 0")
                 e(ld)
-    for i in range(4):   # the loop adds a scalar offset to these as long as whole tiles are in range
+    for i in range(CPW):   # the loop adds a scalar offset to these as long as whole tiles are in range
         e(f"v_mov_b32_e32 {vr(VOFF[i])}, {vr(VBO[i])}")
     A.c("stage offsets before the first rotation: tile -1 in stage 3, tile 0 in stage 0")
     e(f"s_mov_b32 {sr(S_ST_CUR)}, {3 * STAGE}")
     e(f"s_mov_b32 {sr(S_ST_NXT)}, 0")
     A.c("the first half step multiplies zero weights with the V part of stage 3: make it finite")
+    full = T_BYTES // (16 * THREADS)          # passes in which every thread writes 16 bytes
+    rest = T_BYTES - full * 16 * THREADS      # bytes left for the last, partial pass
     e(f"v_lshlrev_b32_e32 {vr(TMP[0])}, 4, %[tid]")
-    e(f"v_min_u32_e32 {vr(TMP[1])}, {T_BYTES - 16 - 16384}, {vr(TMP[0])}")
+    e(f"v_min_u32_e32 {vr(TMP[1])}, {rest - 16}, {vr(TMP[0])}")
     e(f"s_add_u32 {sr(S_TMP)}, %[lds], {3 * STAGE + T_BYTES}")
     e(f"v_add_u32_e32 {vr(TMP[0])}, {sr(S_TMP)}, {vr(TMP[0])}")
     e(f"v_add_u32_e32 {vr(TMP[1])}, {sr(S_TMP)}, {vr(TMP[1])}")
-    for i in range(4):
-        e(f"ds_write_b128 {vr(TMP[0])}, {vr(PB, 4)} offset:{4096 * i}")
-    e(f"ds_write_b128 {vr(TMP[1])}, {vr(PB, 4)} offset:16384")
-    A.c("Q and tile 0 have landed once at most the 16 newest loads (tiles 1, 2) are outstanding")
-    e("s_waitcnt vmcnt(16) lgkmcnt(0)")
+    for i in range(full):
+        e(f"ds_write_b128 {vr(TMP[0])}, {vr(PB, 4)} offset:{16 * THREADS * i}")
+    e(f"ds_write_b128 {vr(TMP[1])}, {vr(PB, 4)} offset:{16 * THREADS * full}")
+    A.c("Q and tile 0 have landed once at most the newest loads (tiles 1, 2) are outstanding")
+    e(f"s_waitcnt vmcnt({4 * CPW}) lgkmcnt(0)")
     e("s_barrier")
     e(f"v_mov_b32_e32 {vr(KA_NXT)}, {vr(KL)}")
     e(f"v_add_u32_e32 {vr(VA_CUR)}, {3 * STAGE}, {vr(VL)}")
@@ -640,7 +656,7 @@ def generate(dt: str) -> list[str]:
     e(f"s_lshl_b32 {sr(S_TMP)}, {sr(S_T)}, 6")
     e(f"s_sub_i32 {sr(S_TMP)}, %[p0], {sr(S_TMP)}")
     e(f"v_lshlrev_b32_e32 {vr(TMP[0])}, 2, {vr(HH)}")
-    for q in range(2):
+    for q in range(NQ):
         e(f"v_sub_u32_e32 {vr(LIM[q])}, {vr(ROW[q])}, {vr(TMP[0])}")
         e(f"v_add_u32_e32 {vr(LIM[q])}, {sr(S_TMP)}, {vr(LIM[q])}")
     e("L_MASK_%=:")
@@ -666,21 +682,21 @@ def generate(dt: str) -> list[str]:
 
     A.c("row sums of both lane halves, normalise, store")
     if SUM_BY_MFMA:
-        for q in range(2):  # every element of the accumulator block holds the full sum of its column
+        for q in range(NQ):  # every element of the accumulator block holds the full sum of its column
             e(f"v_accvgpr_read_b32 {vr(L_SUM[q])}, {ar(A_L + 16 * q)}")
     else:
-        for q in range(2):
+        for q in range(NQ):
             e(f"v_mov_b32_e32 {vr(T_MAX2[q])}, {vr(L_SUM[q])}")
         e("s_nop 1")
-        for q in range(2):
+        for q in range(NQ):
             e(f"v_permlane32_swap_b32_e32 {vr(L_SUM[q])}, {vr(T_MAX2[q])}")
         e("s_nop 1")
-        for q in range(2):
+        for q in range(NQ):
             e(f"v_add_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}, {vr(T_MAX2[q])}")
-    for q in range(2):
+    for q in range(NQ):
         e(f"v_rcp_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}")
     e("s_nop 1")
-    for q in range(2):
+    for q in range(NQ):
         e(f"v_cmp_gt_i32_e32 vcc, %[rvs], {vr(ROW[q])}")
         e(f"s_and_saveexec_b64 {sr(S_EXEC, 2)}, vcc")
         n = 0
@@ -723,7 +739,8 @@ def generate(dt: str) -> list[str]:
 
 
 def clobbers() -> str:
-    regs = [f"v{i}" for i in range(FIRST_V, 256)] + [f"a{i}" for i in range(224)]
+    n_acc = 96 * NQ + (16 * NQ if SUM_BY_MFMA else 0)
+    regs = [f"v{i}" for i in range(FIRST_V, LAST_V + 1)] + [f"a{i}" for i in range(n_acc)]
     regs += [f"s{i}" for i in range(FIRST_S, LAST_S + 1)]
     regs += ["vcc", "scc", "memory"]  # m0 is written too; nothing follows the statement
     return ", ".join(f'"{r}"' for r in regs)
@@ -732,15 +749,16 @@ def clobbers() -> str:
 def main(out_path: str):
     with open(out_path, "w") as f:
         f.write("// Generated by gen_prefill_pipe.py -- do not edit.\n")
-        f.write(f"#define SKV_PIPE_LDS_BYTES {LDS_BYTES}\n")
+        f.write(f"#define SKV_PIPE{NQ}_LDS_BYTES {LDS_BYTES}\n")
+        f.write(f"#define SKV_PIPE{NQ}_THREADS {THREADS}\n")
         for dt in ("bf16", "f16"):
-            f.write(f"#define SKV_PIPE_ASM_{dt.upper()} \\\n")
+            f.write(f"#define SKV_PIPE{NQ}_ASM_{dt.upper()} \\\n")
             for line in generate(dt):
                 if line.startswith("//"):
                     continue
                 f.write(f'    "{line}\\n" \\\n')
             f.write('    ""\n')
-        f.write(f"#define SKV_PIPE_CLOBBERS {clobbers()}\n")
+        f.write(f"#define SKV_PIPE{NQ}_CLOBBERS {clobbers()}\n")
 
 
 if __name__ == "__main__":

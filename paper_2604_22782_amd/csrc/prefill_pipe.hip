@@ -14,7 +14,11 @@
 // cannot touch foreign memory.  Offsets are 32-bit, hence the 4 GiB limit in pipe_supported().
 #include "skv_internal.h"
 
-#include "prefill_pipe_body.inc"
+#include <cstdlib>
+#include <cstring>
+
+#include "prefill_pipe_body_nq1.inc"
+#include "prefill_pipe_body_nq2.inc"
 
 namespace skv {
 
@@ -38,9 +42,11 @@ __device__ __forceinline__ u32x4 make_srd(const void *base, uint32_t bytes) {
     return r;
 }
 
-template <bool BF16>
-__global__ __launch_bounds__(256, 1) void prefill_pipe_kernel(AttnArgs a, int G, int n_qt, int xcd_map) {
-    __shared__ __attribute__((aligned(16))) char lds[SKV_PIPE_LDS_BYTES];
+template <bool BF16, int NQ>
+__global__ __launch_bounds__(512 / NQ, 1) void prefill_pipe_kernel(AttnArgs a, int G, int n_qt, int xcd_map) {
+    static_assert(SKV_PIPE1_LDS_BYTES == SKV_PIPE2_LDS_BYTES && SKV_PIPE1_THREADS == 512 && SKV_PIPE2_THREADS == 256);
+    __shared__ __attribute__((aligned(16))) char lds[SKV_PIPE2_LDS_BYTES];
+    constexpr int kRowsPerWave = 32 * NQ;
 
     const int hkv = a.cache.n_kv_heads;
     // block -> (query tile, head, sequence): heavy (late) query tiles first; with xcd_map the G
@@ -78,11 +84,11 @@ __global__ __launch_bounds__(256, 1) void prefill_pipe_kernel(AttnArgs a, int G,
     const int n_tiles = (n_keys + 63) >> 6;
 
     const int wave = (int)uni(threadIdx.x >> 6);
-    const int r0 = q_begin + 64 * wave;
+    const int r0 = q_begin + kRowsPerWave * wave;
     const int rows_valid = nq - r0;
     const bool active = rows_valid > 0;
     const int p0 = offset + r0;
-    const int p1 = offset + min(r0 + 63, nq - 1);
+    const int p1 = offset + min(r0 + kRowsPerWave - 1, nq - 1);
     const int tw_last = active ? (p1 >> 6) : -1; // last tile this wave computes on
     const int t_mask = active ? ((p0 + 1) >> 6) : 0; // first tile that touches its diagonal
 
@@ -98,7 +104,7 @@ __global__ __launch_bounds__(256, 1) void prefill_pipe_kernel(AttnArgs a, int G,
     const char *qp = (const char *)a.q + qo;
     char *op = (char *)a.out + qo;
     const uint32_t q_row_stride = (uint32_t)a.n_q_heads * kD * 2;
-    const uint32_t rv_clamp = active ? (uint32_t)min(rows_valid, 64) : 1u;
+    const uint32_t rv_clamp = active ? (uint32_t)min(rows_valid, kRowsPerWave) : 1u;
     const float cs = a.scale_log2e;
     const float thr = fminf(8.0f / cs, 3.0e38f); // finite: the first tile (maximum -inf so far) must pass it
 
@@ -114,10 +120,24 @@ __global__ __launch_bounds__(256, 1) void prefill_pipe_kernel(AttnArgs a, int G,
         [cs] "s"(uni(__builtin_bit_cast(uint32_t, cs))), [thr] "s"(uni(__builtin_bit_cast(uint32_t, thr))), \
         [wv] "s"(uni((uint32_t)wave)), [tid] "v"(tid)
 
-    if constexpr (BF16) {
-        asm volatile(SKV_PIPE_ASM_BF16 : : SKV_PIPE_OPERANDS : SKV_PIPE_CLOBBERS);
+    if constexpr (NQ == 2) {
+        if constexpr (BF16) {
+            asm volatile(SKV_PIPE2_ASM_BF16 : : SKV_PIPE_OPERANDS : SKV_PIPE2_CLOBBERS);
+        } else {
+            asm volatile(SKV_PIPE2_ASM_F16 : : SKV_PIPE_OPERANDS : SKV_PIPE2_CLOBBERS);
+        }
     } else {
-        asm volatile(SKV_PIPE_ASM_F16 : : SKV_PIPE_OPERANDS : SKV_PIPE_CLOBBERS);
+        // 512 threads: the compiler keeps to v0..v127 itself (it halves the 256 registers of a wave
+        // between the two files) and says that clobbers above that do nothing for it; they do set the
+        // kernel's register count, which is what they are listed for
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+        if constexpr (BF16) {
+            asm volatile(SKV_PIPE1_ASM_BF16 : : SKV_PIPE_OPERANDS : SKV_PIPE1_CLOBBERS);
+        } else {
+            asm volatile(SKV_PIPE1_ASM_F16 : : SKV_PIPE_OPERANDS : SKV_PIPE1_CLOBBERS);
+        }
+#pragma clang diagnostic pop
     }
 #undef SKV_PIPE_OPERANDS
 }
@@ -141,10 +161,22 @@ hipError_t launch_prefill_pipe(const AttnArgs &a, int dtype, int group, hipStrea
     const int64_t blocks = (int64_t)pairs * group * n_qt;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     const int xcd_map = (pairs % 8) == 0;
-    if (dtype == SKV_BF16)
-        prefill_pipe_kernel<true><<<dim3((unsigned)blocks), 256, 0, stream>>>(a, group, n_qt, xcd_map);
-    else
-        prefill_pipe_kernel<false><<<dim3((unsigned)blocks), 256, 0, stream>>>(a, group, n_qt, xcd_map);
+    // SKV_PREFILL_WAVES=8 picks the shape with 8 waves of 32 rows (two waves per SIMD); read at every
+    // launch so that one process can time and test both shapes
+    const char *shape = getenv("SKV_PREFILL_WAVES");
+    const bool eight = shape != nullptr && strcmp(shape, "8") == 0;
+    const dim3 grid((unsigned)blocks);
+    if (eight) {
+        if (dtype == SKV_BF16)
+            prefill_pipe_kernel<true, 1><<<grid, 512, 0, stream>>>(a, group, n_qt, xcd_map);
+        else
+            prefill_pipe_kernel<false, 1><<<grid, 512, 0, stream>>>(a, group, n_qt, xcd_map);
+    } else {
+        if (dtype == SKV_BF16)
+            prefill_pipe_kernel<true, 2><<<grid, 256, 0, stream>>>(a, group, n_qt, xcd_map);
+        else
+            prefill_pipe_kernel<false, 2><<<grid, 256, 0, stream>>>(a, group, n_qt, xcd_map);
+    }
     set_last_kernel_name("prefill_pipe_kernel");
     return hipGetLastError();
 }

@@ -411,6 +411,12 @@ const char *skv_status_str(skv_status_t s) {
     return "SKV_ERR_UNKNOWN";
 }
 
+skv_status_t skv_calib_mfma_bf16(const void *operands, float *sink, int32_t blocks, int32_t iters, void *stream) {
+    if (!operands || !sink || blocks < 1 || iters < 1 || iters > (1 << 20)) return SKV_ERR_INVALID_ARG;
+    const hipError_t e = skv::launch_calib_mfma(operands, sink, blocks, iters, (hipStream_t)stream);
+    return e == hipSuccess ? SKV_OK : hip_fail(e);
+}
+
 int32_t skv_last_hip_error(void) { return g_last_hip_error; }
 const char *skv_last_kernel_name(void) { return g_last_kernel; }
 

@@ -68,6 +68,9 @@ hipError_t launch_prefill_mfma(const AttnArgs &a, int dtype, int head_dim, int g
 bool prefill_pipe_supported(const AttnArgs &a, int dtype, int head_dim);
 hipError_t launch_prefill_pipe(const AttnArgs &a, int dtype, int group, hipStream_t stream);
 
+// Measurement aid: back-to-back MFMAs on caller-given operands (16 blocks of 64 lanes x 16 bytes).
+hipError_t launch_calib_mfma(const void *operands, float *sink, int blocks, int iters, hipStream_t stream);
+
 void set_last_kernel_name(const char *name);
 
 } // namespace skv

@@ -22,7 +22,7 @@ def _rows(name):
 
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "skv.h")).read()
-    declared = set(re.findall(r"\b(skv_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(skv_[a-z0-9_]+)\s*\(", header))
     assert len(declared) >= 16
     lib = skv.lib()
     for name in declared:
@@ -113,6 +113,7 @@ def test_null_handles_and_no_device_behaviour():
     assert lib.skv_decode_range_workspace_bytes(None, 1, 1, ctypes.byref(n)) == 1
     assert lib.skv_attn_prefill(None, 0, None, None, None, None, 1, 1, ctypes.c_float(1.0), None) == 1
     assert lib.skv_cache_bytes(None, None) == 1
+    assert lib.skv_calib_mfma_bf16(None, None, 1, 1, None) == 1
     import torch
     if not torch.cuda.is_available():
         # without a device there is no compute path: allocation reports the HIP failure

@@ -8,19 +8,39 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-_spec = importlib.util.spec_from_file_location(
-    "gen_prefill_pipe", os.path.join(ROOT, "paper_2604_22782_amd", "csrc", "gen_prefill_pipe.py"))
-G = importlib.util.module_from_spec(_spec)
-_spec.loader.exec_module(G)
 
 
+def _load(nq):
+    """The generator fixes the wave shape (row blocks of 32 per wave) when it is imported."""
+    spec = importlib.util.spec_from_file_location(
+        f"gen_prefill_pipe_nq{nq}", os.path.join(ROOT, "paper_2604_22782_amd", "csrc", "gen_prefill_pipe.py"))
+    mod = importlib.util.module_from_spec(spec)
+    old = os.environ.get("SKV_GEN_NQ")
+    os.environ["SKV_GEN_NQ"] = str(nq)
+    try:
+        spec.loader.exec_module(mod)
+    finally:
+        if old is None:
+            del os.environ["SKV_GEN_NQ"]
+        else:
+            os.environ["SKV_GEN_NQ"] = old
+    return mod
+
+
+GEN = {1: _load(1), 2: _load(2)}
+G = GEN[2]
+
+
+@pytest.mark.parametrize("nq", [1, 2])
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
-def test_stream_is_generated_and_self_consistent(dt):
+def test_stream_is_generated_and_self_consistent(dt, nq):
+    G = GEN[nq]
+    assert (G.NQ, G.WAVES * G.NQ, G.THREADS) == (nq, 8, 512 // nq)
     lines = [l for l in G.generate(dt) if not l.startswith("//")]
     text = "\n".join(lines)
     n_mfma = sum(l.startswith("v_mfma") for l in lines)
-    # prologue 16 + two loop bodies (unmasked, masked) of 64 + the last O update 16
-    assert n_mfma == 16 + 2 * 64 + 16
+    # per row block: prologue 8 + two loop bodies (unmasked, masked) of 32 + the last O update 8
+    assert n_mfma == nq * (8 + 2 * 32 + 8)
     assert f"v_mfma_f32_32x32x16_{dt}" in text
     # every branch target exists exactly once
     labels = re.findall(r"^(L_\w+_%=):$", text, flags=re.M)
@@ -33,17 +53,21 @@ def test_stream_is_generated_and_self_consistent(dt):
     for m in re.finditer(r"\bv(\d+)\b|\bv\[(\d+):(\d+)\]", text):
         lo = int(m.group(1) or m.group(2))
         hi = int(m.group(1) or m.group(3))
-        assert G.FIRST_V <= lo <= hi <= 255
+        assert G.FIRST_V <= lo <= hi <= G.LAST_V
     for m in re.finditer(r"\ba(\d+)\b|\ba\[(\d+):(\d+)\]", text):
         hi = int(m.group(1) or m.group(3))
-        assert hi < 224
+        assert hi < 112 * nq
+    # two waves per SIMD (8 waves of 32 rows) share the 512 registers of a SIMD lane
+    assert G.LAST_V + 1 + 112 * nq <= 512 // (2 // nq)
     for m in re.finditer(r"\bs(\d+)\b|\bs\[(\d+):(\d+)\]", text):
         lo = int(m.group(1) or m.group(2))
         hi = int(m.group(1) or m.group(3))
         assert G.FIRST_S <= lo <= hi <= G.LAST_S
 
 
-def test_hazard_check_accepts_the_stream_and_rejects_a_planted_read():
+@pytest.mark.parametrize("nq", [1, 2])
+def test_hazard_check_accepts_the_stream_and_rejects_a_planted_read(nq):
+    G = GEN[nq]
     lines = G.generate("bf16")
     G.check_mfma_results(lines)                      # the real stream: fine
     i = next(k for k, l in enumerate(lines) if l.startswith("v_mfma") and " v[" in l.split(",")[0])
