@@ -186,6 +186,60 @@ int32_t skv_last_hip_error(void);
 const char *skv_last_kernel_name(void);
 
 
+/* ---- training-time routed attention (Sec. 3.2, Sec. 4.2.3) ---------------------------------- */
+/* During training every layer computes its own K, V and attends, in each forward pass, either to
+ * them or to those of an earlier layer.  The library draws the per-pass source layers and runs
+ * the attention over whole sequences with its gradient; the caller owns the activations. */
+
+typedef enum {
+    SKV_TRAIN_RCLA = 0,    /* Sec. 3.2: d ~ Bernoulli(p); d = 1 self, d = 0 a uniformly drawn earlier layer */
+    SKV_TRAIN_CLA_K = 1,   /* Sec. 4.2.3 CLA@k: groups of k layers attend to the group's first layer */
+    SKV_TRAIN_RDCLA_K = 2  /* Sec. 4.2.3 RD-CLA@k: per layer and pass a coin, d ~ Bernoulli(p);
+                              d = 1 the layer's own K, V, d = 0 the fixed layer of CLA@k */
+} skv_train_scheme_t;
+
+/* Source layers of one forward pass (host only): route[l] = layer whose K, V layer l attends to,
+ * 0-based, route[l] <= l, route[0] = 0.  Counter-based, so a pass can be replayed (backward,
+ * recomputation, another rank): r(layer, which) = mix(mix(mix(seed) ^ step) ^ (256 layer + which))
+ * with mix the SplitMix64 output function; the decision is d = 1 iff (r(l, 0) >> 11) 2^-53 < p,
+ * the R-CLA source is ((r(l, 1) >> 32) * l) >> 32.  k is used by the two @k schemes only (k >= 1),
+ * p by the two random ones (0 <= p <= 1).  SKV_ERR_INVALID_ARG otherwise. */
+skv_status_t skv_train_sample_route(int32_t scheme, int32_t n_layers, int32_t k, double p,
+                                    uint64_t seed, uint64_t step, int32_t *route);
+
+/* Forward, Eq. (3.1) over whole sequences with a causal mask: row i of sequence b attends to
+ * rows 0..i of k, v (the activations of the source layer), i < seq_lens[b].
+ * q, out: device [batch][seq][n_q_heads][head_dim]; k, v: device [batch][seq][n_kv_heads][head_dim];
+ * dtype SKV_BF16 or SKV_F16, head_dim 64 or 128 (else SKV_ERR_UNSUPPORTED); fp32 accumulation.
+ * lse: device float [batch][n_q_heads][seq], receives log sum_j exp(scale <q_i, k_j>) (natural
+ * log), which the backward needs.  seq_lens: device int32[batch], each in [1, seq]; rows at or
+ * beyond a sequence's length are neither read nor written.  Asynchronous on `stream`. */
+skv_status_t skv_train_attn_fwd(const void *q, const void *k, const void *v, void *out, float *lse,
+                                const int32_t *seq_lens, int32_t batch, int32_t seq,
+                                int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                int32_t dtype, float scale, void *stream);
+
+/* Scratch bytes of skv_train_attn_bwd (one float per query row and head). */
+skv_status_t skv_train_bwd_workspace_bytes(int32_t batch, int32_t seq, int32_t n_q_heads, size_t *bytes);
+
+/* Backward of skv_train_attn_fwd for the loss whose gradient with respect to out is d_out
+ * (device, layout and dtype of out); q, k, v, out, lse as in / from the forward.
+ * dq: device, layout and dtype of q, written (rows beyond a sequence's length untouched).
+ * dk_accum, dv_accum: device FLOAT [batch][seq][n_kv_heads][head_dim]; the gradients with
+ * respect to k and v are ADDED to them: a layer read by several layers in one pass (and by the
+ * heads of a group) collects all of them in one fp32 buffer, which the caller zeroes before the
+ * pass and rounds afterwards.  Calls that add into the same buffers must be ordered on one
+ * stream.  Deterministic (no atomics).  Asynchronous on `stream`. */
+skv_status_t skv_train_attn_bwd(const void *q, const void *k, const void *v, const void *out,
+                                const float *lse, const void *d_out, void *dq, float *dk_accum,
+                                float *dv_accum, const int32_t *seq_lens, int32_t batch, int32_t seq,
+                                int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t dtype,
+                                float scale, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Reads and clears the fault word of the training calls (a sequence length outside [1, seq] sets
+ * SKV_FAULT_KV_LEN and nothing is computed for that sequence).  Synchronises the device. */
+skv_status_t skv_train_device_faults(uint32_t *faults);
+
 /* ---- measurement aid (no part of the attention path) --------------------------------------- */
 /* Runs iters x 32 back-to-back v_mfma_f32_32x32x16_bf16 (32768 flop each) on every one of the
  * 4 * blocks waves of the launch (work groups of 256 threads, one wave per SIMD) and nothing else:

@@ -11,10 +11,12 @@ __all__ = [
     "skv_cache_free", "skv_cache_info", "skv_cache_slot_of_layer", "skv_cache_set_block_table",
     "skv_cache_device_faults", "skv_kv_append", "skv_decode_workspace_bytes", "skv_attn_decode",
     "skv_decode_range_workspace_bytes", "skv_attn_decode_range", "skv_attn_prefill", "skv_status_str", "skv_last_hip_error", "skv_last_kernel_name",
-    "skv_calib_mfma_bf16",
+    "skv_calib_mfma_bf16", "skv_train_sample_route", "skv_train_attn_fwd", "skv_train_bwd_workspace_bytes",
+    "skv_train_attn_bwd", "skv_train_device_faults", "SKV_TRAIN_RCLA", "SKV_TRAIN_CLA_K", "SKV_TRAIN_RDCLA_K",
 ]
 
 SKV_F32, SKV_F16, SKV_BF16 = 0, 1, 2
+SKV_TRAIN_RCLA, SKV_TRAIN_CLA_K, SKV_TRAIN_RDCLA_K = 0, 1, 2
 STATUS = {0: "SKV_OK", 1: "SKV_ERR_INVALID_ARG", 2: "SKV_ERR_BAD_ROUTE", 3: "SKV_ERR_NOT_OWNER",
           4: "SKV_ERR_CAPACITY", 5: "SKV_ERR_OOM", 6: "SKV_ERR_UNSUPPORTED", 7: "SKV_ERR_HIP"}
 
@@ -217,6 +219,55 @@ def skv_attn_prefill(cache: Cache, layer: int, q, out, q_lens, kv_lens, max_q: i
     _check(lib().skv_attn_prefill(cache.handle, layer, _ptr(q), _ptr(out), _ptr(q_lens), _ptr(kv_lens),
                                   max_q, max_kv_len, ctypes.c_float(scale), _stream(stream)),
            "skv_attn_prefill")
+
+
+def skv_train_sample_route(scheme: int, n_layers: int, k: int, p: float, seed: int, step: int) -> list:
+    route = (ctypes.c_int32 * max(n_layers, 1))()
+    _check(lib().skv_train_sample_route(scheme, n_layers, k, ctypes.c_double(p), ctypes.c_uint64(seed),
+                                        ctypes.c_uint64(step), route), "skv_train_sample_route")
+    return list(route)[:n_layers]
+
+
+def _train_shapes(q, k):
+    batch, seq, hq, d = q.shape
+    if k.shape[0] != batch or k.shape[1] != seq or k.shape[3] != d:
+        raise ValueError("q is [batch][seq][n_q_heads][head_dim], k and v [batch][seq][n_kv_heads][head_dim]")
+    return batch, seq, hq, k.shape[2], d
+
+
+def skv_train_attn_fwd(q, k, v, out, lse, seq_lens, scale: float, stream=None):
+    """q, out: [batch][seq][n_q_heads][head_dim]; k, v: [batch][seq][n_kv_heads][head_dim];
+    lse: float32 [batch][n_q_heads][seq]; seq_lens: int32 [batch] (all device tensors)."""
+    batch, seq, hq, hkv, d = _train_shapes(q, k)
+    _check(lib().skv_train_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(seq_lens), batch, seq,
+                                    hq, hkv, d, dtype_code(q.dtype), ctypes.c_float(scale), _stream(stream)),
+           "skv_train_attn_fwd")
+
+
+def skv_train_bwd_workspace_bytes(batch: int, seq: int, n_q_heads: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().skv_train_bwd_workspace_bytes(batch, seq, n_q_heads, ctypes.byref(out)),
+           "skv_train_bwd_workspace_bytes")
+    return out.value
+
+
+def skv_train_attn_bwd(q, k, v, out, lse, d_out, dq, dk_accum, dv_accum, seq_lens, scale: float, workspace,
+                       stream=None):
+    """dk_accum, dv_accum: float32 tensors of the shape of k; the gradients are ADDED to them."""
+    batch, seq, hq, hkv, d = _train_shapes(q, k)
+    if dk_accum.dtype != torch.float32 or dv_accum.dtype != torch.float32 or lse.dtype != torch.float32:
+        raise ValueError("lse, dk_accum and dv_accum are float32")
+    wb = workspace.numel() * workspace.element_size()
+    _check(lib().skv_train_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(d_out), _ptr(dq),
+                                    _ptr(dk_accum), _ptr(dv_accum), _ptr(seq_lens), batch, seq, hq, hkv, d,
+                                    dtype_code(q.dtype), ctypes.c_float(scale), _ptr(workspace),
+                                    ctypes.c_size_t(wb), _stream(stream)), "skv_train_attn_bwd")
+
+
+def skv_train_device_faults() -> int:
+    out = ctypes.c_uint32(0)
+    _check(lib().skv_train_device_faults(ctypes.byref(out)), "skv_train_device_faults")
+    return out.value
 
 
 def skv_calib_mfma_bf16(operands, sink, blocks: int, iters: int, stream=None):

@@ -693,6 +693,24 @@ def generate(dt: str) -> list[str]:
         e("s_nop 1")
         for q in range(NQ):
             e(f"v_add_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}, {vr(T_MAX2[q])}")
+    A.c("optional log-sum-exp of the scaled scores (natural log): ln 2 (log2 l + cs m), one float per row")
+    e("s_cmp_eq_u64 %[lsep], 0")
+    e("s_cbranch_scc1 L_NOLSE_%=")
+    for q in range(NQ):
+        e(f"v_log_f32_e32 {vr(M_NEW[q])}, {vr(L_SUM[q])}")
+    e(f"v_cmp_eq_u32_e64 {sr(S_CMP, 2)}, 0, {vr(HH)}")     # both lane halves hold the row: the low one stores
+    for q in range(NQ):
+        e(f"v_sub_f32_e32 {vr(M_NEW[q])}, {vr(M_NEW[q])}, {vr(NEG_MC[q])}")
+    for q in range(NQ):
+        e(f"v_mul_f32_e32 {vr(M_NEW[q])}, 0x3f317218, {vr(M_NEW[q])}")
+    for q in range(NQ):
+        e(f"v_cmp_gt_i32_e32 vcc, %[rvs], {vr(ROW[q])}")
+        e(f"s_and_b64 vcc, vcc, {sr(S_CMP, 2)}")
+        e(f"s_and_saveexec_b64 {sr(S_EXEC, 2)}, vcc")
+        e(f"v_lshlrev_b32_e32 {vr(TMP[0])}, 2, {vr(ROW[q])}")
+        e(f"global_store_dword {vr(TMP[0])}, {vr(M_NEW[q])}, %[lsep]")
+        e(f"s_mov_b64 exec, {sr(S_EXEC, 2)}")
+    e("L_NOLSE_%=:")
     for q in range(NQ):
         e(f"v_rcp_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}")
     e("s_nop 1")

@@ -303,6 +303,9 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_mfma_kernel(AttnArgs a
     if (!row_ok) return;
     const float l_tot = l_part + __shfl_xor(l_part, 32, 64);
     const float inv = 1.f / l_tot;
+    if (a.lse != nullptr && hh == 0) // natural log of sum_j exp(scale s_j) = ln 2 (cs m + log2 l)
+        a.lse[((int64_t)b * a.n_q_heads + head) * a.max_q + my_row] =
+            0.6931471805599453f * (m_run * cs + __builtin_amdgcn_logf(l_tot));
     // O^T accumulators: lane owns row my_row; element r of block db is d = 32 db + 8 (r/4) + 4 hh + (r%4)
     uint16_t *op = (uint16_t *)a.out + (((int64_t)b * a.max_q + my_row) * a.n_q_heads + head) * D + 4 * hh;
 #pragma unroll

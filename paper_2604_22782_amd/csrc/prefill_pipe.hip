@@ -103,6 +103,7 @@ __global__ __launch_bounds__(512 / NQ, 1) void prefill_pipe_kernel(AttnArgs a, i
     const int64_t qo = (((int64_t)b * a.max_q + q_row) * a.n_q_heads + head) * kD * 2;
     const char *qp = (const char *)a.q + qo;
     char *op = (char *)a.out + qo;
+    const float *lsep = a.lse != nullptr ? a.lse + ((int64_t)b * a.n_q_heads + head) * a.max_q + q_row : nullptr;
     const uint32_t q_row_stride = (uint32_t)a.n_q_heads * kD * 2;
     const uint32_t rv_clamp = active ? (uint32_t)min(rows_valid, kRowsPerWave) : 1u;
     const float cs = a.scale_log2e;
@@ -112,7 +113,7 @@ __global__ __launch_bounds__(512 / NQ, 1) void prefill_pipe_kernel(AttnArgs a, i
     const uint32_t tid = threadIdx.x;
 
 #define SKV_PIPE_OPERANDS                                                                              \
-    [srdk] "s"(srdk), [srdv] "s"(srdv), [qp] "s"(qp), [op] "s"(op), [lds] "s"(uni(lds_base)),         \
+    [srdk] "s"(srdk), [srdv] "s"(srdv), [qp] "s"(qp), [op] "s"(op), [lsep] "s"(lsep), [lds] "s"(uni(lds_base)),         \
         [qrs] "s"(uni(q_row_stride)), [rv] "s"(uni(rv_clamp)), [rvs] "s"(uni((uint32_t)rows_valid)),   \
         [krb] "s"(uni((uint32_t)row_bytes)), [nk1] "s"(uni((uint32_t)(n_keys - 1))),                   \
         [nt] "s"(uni((uint32_t)n_tiles)), [tms] "s"(uni((uint32_t)t_mask)),                            \

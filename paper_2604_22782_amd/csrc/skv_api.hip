@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -34,6 +35,23 @@ skv_status_t hip_fail(hipError_t e) {
     g_last_hip_error = (int32_t)e;
     (void)hipGetLastError(); // clear the sticky per-thread error
     return e == hipErrorOutOfMemory ? SKV_ERR_OOM : SKV_ERR_HIP;
+}
+
+// Pre-fill kernel choice: pipelined -> plain MFMA -> vector ALU.
+skv_status_t launch_prefill(const skv::AttnArgs &a, int dtype, int head_dim, int g, hipStream_t stream) {
+    hipError_t e;
+    // SKV_PREFILL_KERNEL=plain keeps the pipelined kernel out (for A/B timing and fault finding)
+    static const bool no_pipe = [] {
+        const char *v = getenv("SKV_PREFILL_KERNEL");
+        return v && strcmp(v, "plain") == 0;
+    }();
+    if (!no_pipe && skv::prefill_pipe_supported(a, dtype, head_dim))
+        e = skv::launch_prefill_pipe(a, dtype, g, stream);
+    else if (skv::prefill_mfma_supported(dtype, head_dim, g))
+        e = skv::launch_prefill_mfma(a, dtype, head_dim, g, stream);
+    else
+        e = skv::launch_attn_valu(a, dtype, head_dim, g, stream);
+    return e == hipSuccess ? SKV_OK : hip_fail(e);
 }
 
 int elem_bytes(int dtype) { return dtype == SKV_F32 ? 4 : 2; }
@@ -320,6 +338,7 @@ skv_status_t skv_attn_decode_range(skv_cache_t *c, int32_t layer, int32_t seq_be
     }
 
     skv::AttnArgs a;
+    a.lse = nullptr;
     a.cache = view;
     a.q = q;
     a.out = out;
@@ -365,6 +384,7 @@ skv_status_t skv_attn_prefill(skv_cache_t *c, int32_t layer, const void *q, void
     if (max_kv_len > view.max_ctx) return SKV_ERR_CAPACITY;
 
     skv::AttnArgs a;
+    a.lse = nullptr;
     a.cache = view;
     a.q = q;
     a.out = out;
@@ -381,20 +401,150 @@ skv_status_t skv_attn_prefill(skv_cache_t *c, int32_t layer, const void *q, void
     a.part_ml = nullptr;
     a.work_counters = nullptr;
 
-    const int g = c->d.n_q_heads / c->d.n_kv_heads;
-    hipError_t e;
-    // SKV_PREFILL_KERNEL=plain keeps the pipelined kernel out (for A/B timing and fault finding)
-    static const bool no_pipe = [] {
-        const char *v = getenv("SKV_PREFILL_KERNEL");
-        return v && strcmp(v, "plain") == 0;
-    }();
-    if (!no_pipe && skv::prefill_pipe_supported(a, c->d.dtype, c->d.head_dim))
-        e = skv::launch_prefill_pipe(a, c->d.dtype, g, (hipStream_t)stream);
-    else if (skv::prefill_mfma_supported(c->d.dtype, c->d.head_dim, g))
-        e = skv::launch_prefill_mfma(a, c->d.dtype, c->d.head_dim, g, (hipStream_t)stream);
-    else
-        e = skv::launch_attn_valu(a, c->d.dtype, c->d.head_dim, g, (hipStream_t)stream);
+    return launch_prefill(a, c->d.dtype, c->d.head_dim, c->d.n_q_heads / c->d.n_kv_heads, (hipStream_t)stream);
+}
+
+/* ---- training-time routed attention ------------------------------------------------------- */
+
+skv_status_t skv_train_sample_route(int32_t scheme, int32_t n_layers, int32_t k, double p, uint64_t seed,
+                                    uint64_t step, int32_t *route) {
+    if (!route || n_layers < 1) return SKV_ERR_INVALID_ARG;
+    const bool random = scheme == SKV_TRAIN_RCLA || scheme == SKV_TRAIN_RDCLA_K;
+    const bool grouped = scheme == SKV_TRAIN_CLA_K || scheme == SKV_TRAIN_RDCLA_K;
+    if (!random && !grouped) return SKV_ERR_INVALID_ARG;
+    if (grouped && k < 1) return SKV_ERR_INVALID_ARG;
+    if (random && !(p >= 0.0 && p <= 1.0)) return SKV_ERR_INVALID_ARG;
+    // SplitMix64 output function: the value a generator whose state is x returns on its next step
+    auto mix = [](uint64_t x) {
+        x += 0x9E3779B97F4A7C15ull;
+        x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+        x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+        return x ^ (x >> 31);
+    };
+    const uint64_t pass = mix(mix(seed) ^ step);
+    auto draw = [&](int32_t layer, int which) { return mix(pass ^ (uint64_t)(256 * (int64_t)layer + which)); };
+    auto decide = [&](int32_t layer) { return (double)(draw(layer, 0) >> 11) * 0x1.0p-53 < p; };
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const int32_t fixed = grouped ? k * (l / k) : l;
+        if (scheme == SKV_TRAIN_CLA_K)
+            route[l] = fixed;
+        else if (scheme == SKV_TRAIN_RDCLA_K)
+            route[l] = decide(l) ? l : fixed;
+        else if (l == 0 || decide(l))
+            route[l] = l;
+        else
+            route[l] = (int32_t)(((draw(l, 1) >> 32) * (uint64_t)l) >> 32);
+    }
+    return SKV_OK;
+}
+
+namespace {
+// Device fault word of the training calls: allocated on first use, kept until the process ends.
+skv_status_t train_fault_word(uint32_t **out) {
+    static std::mutex mu;
+    static uint32_t *word = nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (word == nullptr) {
+        hipError_t e = hipMalloc((void **)&word, 256);
+        if (e != hipSuccess) { word = nullptr; return hip_fail(e); }
+        e = hipMemset(word, 0, 256);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    *out = word;
+    return SKV_OK;
+}
+
+bool train_shape_ok(int32_t batch, int32_t seq, int32_t hq, int32_t hkv) {
+    return batch >= 1 && seq >= 1 && hq >= 1 && hkv >= 1 && hq % hkv == 0;
+}
+} // namespace
+
+skv_status_t skv_train_attn_fwd(const void *q, const void *k, const void *v, void *out, float *lse,
+                                const int32_t *seq_lens, int32_t batch, int32_t seq, int32_t n_q_heads,
+                                int32_t n_kv_heads, int32_t head_dim, int32_t dtype, float scale, void *stream) {
+    if (!q || !k || !v || !out || !lse || !seq_lens) return SKV_ERR_INVALID_ARG;
+    if (!train_shape_ok(batch, seq, n_q_heads, n_kv_heads) || !(scale > 0.f)) return SKV_ERR_INVALID_ARG;
+    if (!(dtype == SKV_BF16 || dtype == SKV_F16) || !(head_dim == 64 || head_dim == 128)) return SKV_ERR_UNSUPPORTED;
+    uint32_t *faults = nullptr;
+    if (skv_status_t st = train_fault_word(&faults); st != SKV_OK) return st;
+    // the source layer's activations are laid out exactly like one contiguous cache slot of
+    // capacity seq, so the pre-fill kernels run on them unchanged
+    skv::AttnArgs a;
+    a.cache.k = k;
+    a.cache.v = v;
+    a.cache.block_table = nullptr;
+    a.cache.faults = faults;
+    a.cache.max_blocks_per_seq = 0;
+    a.cache.block_shift = 0;
+    a.cache.n_blocks = 0;
+    a.cache.max_ctx = seq;
+    a.cache.n_kv_heads = n_kv_heads;
+    a.cache.head_dim = head_dim;
+    a.q = q;
+    a.out = out;
+    a.q_lens = seq_lens;
+    a.kv_lens = seq_lens;
+    a.part_o = nullptr;
+    a.part_ml = nullptr;
+    a.work_counters = nullptr;
+    a.batch = batch;
+    a.max_q = seq;
+    a.n_q_heads = n_q_heads;
+    a.max_kv_len = seq;
+    a.keys_per_split = seq;
+    a.n_splits = 1;
+    a.scale_log2e = scale * 1.4426950408889634f;
+    a.lse = lse;
+    return launch_prefill(a, dtype, head_dim, n_q_heads / n_kv_heads, (hipStream_t)stream);
+}
+
+skv_status_t skv_train_bwd_workspace_bytes(int32_t batch, int32_t seq, int32_t n_q_heads, size_t *bytes) {
+    if (!bytes || batch < 1 || seq < 1 || n_q_heads < 1) return SKV_ERR_INVALID_ARG;
+    *bytes = (size_t)batch * (size_t)seq * (size_t)n_q_heads * sizeof(float);
+    return SKV_OK;
+}
+
+skv_status_t skv_train_attn_bwd(const void *q, const void *k, const void *v, const void *out, const float *lse,
+                                const void *d_out, void *dq, float *dk_accum, float *dv_accum,
+                                const int32_t *seq_lens, int32_t batch, int32_t seq, int32_t n_q_heads,
+                                int32_t n_kv_heads, int32_t head_dim, int32_t dtype, float scale, void *workspace,
+                                size_t workspace_bytes, void *stream) {
+    if (!q || !k || !v || !out || !lse || !d_out || !dq || !dk_accum || !dv_accum || !seq_lens || !workspace)
+        return SKV_ERR_INVALID_ARG;
+    if (!train_shape_ok(batch, seq, n_q_heads, n_kv_heads) || !(scale > 0.f)) return SKV_ERR_INVALID_ARG;
+    if (!(dtype == SKV_BF16 || dtype == SKV_F16) || !(head_dim == 64 || head_dim == 128)) return SKV_ERR_UNSUPPORTED;
+    size_t need = 0;
+    skv_train_bwd_workspace_bytes(batch, seq, n_q_heads, &need);
+    if (workspace_bytes < need) return SKV_ERR_INVALID_ARG;
+    uint32_t *faults = nullptr;
+    if (skv_status_t st = train_fault_word(&faults); st != SKV_OK) return st;
+    skv::TrainBwdArgs a;
+    a.q = q; a.k = k; a.v = v; a.out = out; a.d_out = d_out;
+    a.lse = lse;
+    a.dq = dq;
+    a.dk_accum = dk_accum; a.dv_accum = dv_accum;
+    a.delta = (float *)workspace;
+    a.seq_lens = seq_lens;
+    a.faults = faults;
+    a.batch = batch; a.seq = seq; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads;
+    a.scale = scale;
+    const hipError_t e = skv::launch_train_bwd(a, dtype, head_dim, (hipStream_t)stream);
     return e == hipSuccess ? SKV_OK : hip_fail(e);
+}
+
+skv_status_t skv_train_device_faults(uint32_t *faults) {
+    if (!faults) return SKV_ERR_INVALID_ARG;
+    uint32_t *word = nullptr;
+    if (skv_status_t st = train_fault_word(&word); st != SKV_OK) return st;
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipMemcpy(faults, word, sizeof(uint32_t), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(e);
+    if (*faults != 0) {
+        e = hipMemset(word, 0, sizeof(uint32_t));
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return SKV_OK;
 }
 
 const char *skv_status_str(skv_status_t s) {

@@ -47,6 +47,7 @@ struct AttnArgs {
     int32_t keys_per_split; // chunk of the key axis one work item covers
     int32_t n_splits;       // ceil(max_kv_len / keys_per_split)
     float scale_log2e;      // softmax scale * log2(e)
+    float *lse;             // pre-fill only, may be nullptr: [batch][n_q_heads][max_q] log-sum-exp of the scaled scores
 };
 
 // Launchers (each returns the hipError_t of its launch).
@@ -67,6 +68,19 @@ hipError_t launch_prefill_mfma(const AttnArgs &a, int dtype, int head_dim, int g
 // Software-pipelined pre-fill kernel (16-bit, head_dim 128, contiguous caches below 4 GiB per sequence).
 bool prefill_pipe_supported(const AttnArgs &a, int dtype, int head_dim);
 hipError_t launch_prefill_pipe(const AttnArgs &a, int dtype, int group, hipStream_t stream);
+
+// Training backward (16-bit, head_dim 64 or 128).  delta: [batch][n_q_heads][seq] scratch.
+struct TrainBwdArgs {
+    const void *q, *k, *v, *out, *d_out;
+    const float *lse;
+    void *dq;
+    float *dk_accum, *dv_accum, *delta;
+    const int32_t *seq_lens;
+    uint32_t *faults;
+    int32_t batch, seq, n_q_heads, n_kv_heads;
+    float scale;
+};
+hipError_t launch_train_bwd(const TrainBwdArgs &a, int dtype, int head_dim, hipStream_t stream);
 
 // Measurement aid: back-to-back MFMAs on caller-given operands (16 blocks of 64 lanes x 16 bytes).
 hipError_t launch_calib_mfma(const void *operands, float *sink, int blocks, int iters, hipStream_t stream);

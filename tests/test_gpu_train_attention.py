@@ -1,0 +1,134 @@
+"""GPU parity of the training-time routed attention (forward with log-sum-exp, backward) against
+the fp64 oracle, element by element, on shapes that span several tiles, ragged tails, grouped
+heads and both head sizes; and a whole sampled pass over a stack of layers (Sec. 3.2)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_22782_amd as skv
+from oracle import rcla_train_oracle as T
+from tests import harness as H
+from workloads import gen
+
+pytestmark = pytest.mark.gpu
+
+TDT = {"bf16": torch.bfloat16, "f16": torch.float16}
+
+
+def _inputs(dtype, B, S, Hq, Hkv, D, seed, n_layers=1):
+    g = torch.Generator().manual_seed(seed)
+    mk = lambda *shape: torch.randn(*shape, generator=g).to(TDT[dtype])
+    return ([mk(B, S, Hq, D) for _ in range(n_layers)], [mk(B, S, Hkv, D) for _ in range(n_layers)],
+            [mk(B, S, Hkv, D) for _ in range(n_layers)], [mk(B, S, Hq, D) for _ in range(n_layers)])
+
+
+def _grad_tol(dtype, want):
+    """16-bit weights and products carry a relative rounding error of 2^-9 (bf16) / 2^-11 (f16) per
+    term; the bar of the inference path (2e-2 on values of order one) scaled to the gradient's size."""
+    return H.TOL[dtype] * max(1.0, float(np.abs(want).max()))
+
+
+def _run_fwd(q, k, v, lens, scale):
+    B, S, Hq, _ = q.shape
+    out = torch.full_like(q, 7.0, device="cuda")
+    lse = torch.full((B, Hq, S), 7.0, dtype=torch.float32, device="cuda")
+    skv.skv_train_attn_fwd(q.cuda(), k.cuda(), v.cuda(), out, lse, lens, scale)
+    return out, lse
+
+
+CASES = [
+    # dtype, B, S, Hq, Hkv, D, seq_lens
+    ("bf16", 2, 300, 4, 2, 128, [300, 129]),
+    ("f16", 1, 257, 2, 2, 128, [257]),
+    ("bf16", 2, 200, 4, 1, 64, [200, 1]),
+    ("f16", 3, 130, 8, 2, 64, [64, 130, 97]),
+    ("bf16", 1, 515, 2, 1, 128, [515]),
+]
+
+
+@pytest.mark.parametrize("dtype,B,S,Hq,Hkv,D,lens", CASES)
+def test_forward_and_backward_match_oracle(dtype, B, S, Hq, Hkv, D, lens):
+    print(f"\ntrain attention {dtype} B={B} S={S} Hq={Hq} Hkv={Hkv} D={D} lens={lens}", flush=True)
+    qs, ks, vs, dos = _inputs(dtype, B, S, Hq, Hkv, D, seed=5)
+    q, k, v, do = qs[0], ks[0], vs[0], dos[0]
+    scale = 1.0 / np.sqrt(D)
+    d_lens = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    out, lse = _run_fwd(q, k, v, d_lens, scale)
+    want_o, want_l = T.attn_fwd(gen.to_f64(q), gen.to_f64(k), gen.to_f64(v), scale, lens)
+    got_o, got_l = gen.to_f64(out), lse.cpu().double().numpy()
+    for b, n in enumerate(lens):
+        assert np.abs(got_o[b, :n] - want_o[b, :n]).max() <= H.TOL[dtype], b
+        assert np.abs(got_l[b, :, :n] - want_l[b, :, :n]).max() <= 2e-3, b
+        assert (got_o[b, n:] == 7.0).all() and (got_l[b, :, n:] == 7.0).all()   # padding rows untouched
+
+    dq = torch.full_like(q, 7.0, device="cuda")
+    dk = torch.zeros(B, S, Hkv, D, dtype=torch.float32, device="cuda")
+    dv = torch.zeros_like(dk)
+    ws = torch.empty(skv.skv_train_bwd_workspace_bytes(B, S, Hq) // 4, dtype=torch.float32, device="cuda")
+    args = (q.cuda(), k.cuda(), v.cuda(), out, lse, do.cuda(), dq, dk, dv, d_lens, scale, ws)
+    skv.skv_train_attn_bwd(*args)
+    want_dq, want_dk, want_dv = T.attn_bwd(gen.to_f64(q), gen.to_f64(k), gen.to_f64(v), gen.to_f64(do), scale, lens)
+    got_dq, got_dk, got_dv = gen.to_f64(dq), dk.cpu().double().numpy(), dv.cpu().double().numpy()
+    for b, n in enumerate(lens):
+        for name, got, want in (("dq", got_dq, want_dq), ("dk", got_dk, want_dk), ("dv", got_dv, want_dv)):
+            err = float(np.abs(got[b, :n] - want[b, :n]).max())
+            assert err <= _grad_tol(dtype, want[b, :n]), (name, b, err)
+        assert (got_dq[b, n:] == 7.0).all()                   # rows beyond the length: untouched
+        assert not got_dk[b, n:].any() and not got_dv[b, n:].any()
+    # the key/value gradients are added: a second call doubles them, bit for bit
+    once_k, once_v = dk.clone(), dv.clone()
+    skv.skv_train_attn_bwd(*args)
+    assert torch.equal(dk, 2 * once_k) and torch.equal(dv, 2 * once_v)
+    assert skv.skv_train_device_faults() == 0
+
+
+def test_sampled_pass_over_a_layer_stack():
+    """One R-CLA pass: the library draws the route, every layer attends to its source layer's K, V,
+    and in the backward every source layer collects the gradients of all its readers."""
+    L, B, S, Hq, Hkv, D = 6, 1, 160, 4, 2, 128
+    dtype = "bf16"
+    scale = 1.0 / np.sqrt(D)
+    qs, ks, vs, dos = _inputs(dtype, B, S, Hq, Hkv, D, seed=11, n_layers=L)
+    route = skv.skv_train_sample_route(skv.SKV_TRAIN_RCLA, L, 0, 0.4, seed=3, step=17)
+    assert route == T.sample_route(T.RCLA, L, 0, 0.4, 3, 17) and any(r != l for l, r in enumerate(route))
+    print(f"\nsampled route {route}", flush=True)
+    d_lens = torch.full((B,), S, dtype=torch.int32, device="cuda")
+    dks = [torch.zeros(B, S, Hkv, D, dtype=torch.float32, device="cuda") for _ in range(L)]
+    dvs = [torch.zeros_like(dks[0]) for _ in range(L)]
+    ws = torch.empty(skv.skv_train_bwd_workspace_bytes(B, S, Hq) // 4, dtype=torch.float32, device="cuda")
+    outs, lses, dqs = [], [], []
+    for l in range(L):
+        o, e = _run_fwd(qs[l], ks[route[l]], vs[route[l]], d_lens, scale)
+        outs.append(o)
+        lses.append(e)
+    for l in reversed(range(L)):
+        dq = torch.empty_like(outs[l])
+        src = route[l]
+        skv.skv_train_attn_bwd(qs[l].cuda(), ks[src].cuda(), vs[src].cuda(), outs[l], lses[l], dos[l].cuda(), dq,
+                               dks[src], dvs[src], d_lens, scale, ws)
+        dqs.append(dq)
+    dqs.reverse()
+    f = gen.to_f64
+    w_out, w_dq, w_dk, w_dv = T.layer_stack_fwd_bwd([f(x) for x in qs], [f(x) for x in ks], [f(x) for x in vs],
+                                                    [f(x) for x in dos], route, scale)
+    for l in range(L):
+        assert np.abs(f(outs[l]) - w_out[l]).max() <= H.TOL[dtype]
+        assert np.abs(f(dqs[l]) - w_dq[l]).max() <= _grad_tol(dtype, w_dq[l])
+        got_k, got_v = dks[l].cpu().double().numpy(), dvs[l].cpu().double().numpy()
+        assert np.abs(got_k - w_dk[l]).max() <= _grad_tol(dtype, w_dk[l]), l
+        assert np.abs(got_v - w_dv[l]).max() <= _grad_tol(dtype, w_dv[l]), l
+        if l not in route:
+            assert not got_k.any() and not got_v.any()       # read by nobody: no gradient
+    assert skv.skv_train_device_faults() == 0
+
+
+def test_impossible_length_is_contained_and_reported():
+    B, S, Hq, Hkv, D = 2, 64, 2, 1, 128
+    qs, ks, vs, dos = _inputs("bf16", B, S, Hq, Hkv, D, seed=2)
+    d_lens = torch.tensor([S + 5, 40], dtype=torch.int32, device="cuda")
+    out, lse = _run_fwd(qs[0], ks[0], vs[0], d_lens, 0.1)
+    assert skv.skv_train_device_faults() == 4                  # SKV_FAULT_KV_LEN
+    assert (gen.to_f64(out)[0] == 7.0).all()                   # nothing written for that sequence
+    want, _ = T.attn_fwd(gen.to_f64(qs[0])[1:], gen.to_f64(ks[0])[1:], gen.to_f64(vs[0])[1:], 0.1, [40])
+    assert np.abs(gen.to_f64(out)[1, :40] - want[0, :40]).max() <= H.TOL["bf16"]
+    assert skv.skv_train_device_faults() == 0                  # reading cleared it
