@@ -283,6 +283,71 @@ def run_prefill(args, torch, skv, H, configs):
     return res
 
 
+def run_train(args, torch, skv, configs):
+    """One R-CLA training pass (Sec. 3.2) over the attention of a Llama-3.1-8B-shaped stack at the
+    paper's fine-tuning length: sampled route, forward of every layer against its source layer's
+    K, V, then the backward in reverse order with the K/V gradients of a source layer collected
+    from all its readers.  Activations are synthetic; four layers' worth of buffers are rotated."""
+    w = configs.llama3_prefill()
+    B, S, Hq, Hkv, D, L = w.batch, int(w.kv_lens.max()), w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_layers
+    route = skv.skv_train_sample_route(skv.SKV_TRAIN_RCLA, L, 0, 0.5, 2604, 0)
+    log(f"[bench] training pass: B={B} S={S} layers={L} p=0.5 route={route}")
+    R = 4
+    g = torch.Generator(device="cuda").manual_seed(22782)
+    mk = lambda h: torch.randn(B, S, h, D, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    q, k, v, do = [mk(Hq) for _ in range(R)], [mk(Hkv) for _ in range(R)], [mk(Hkv) for _ in range(R)], [mk(Hq) for _ in range(R)]
+    out = [torch.empty_like(q[0]) for _ in range(R)]
+    dq = [torch.empty_like(q[0]) for _ in range(R)]
+    lse = [torch.empty(B, Hq, S, dtype=torch.float32, device="cuda") for _ in range(R)]
+    dk = [torch.zeros(B, S, Hkv, D, dtype=torch.float32, device="cuda") for _ in range(R)]
+    dv = [torch.zeros_like(dk[0]) for _ in range(R)]
+    lens = torch.full((B,), S, dtype=torch.int32, device="cuda")
+    ws = torch.empty(skv.skv_train_bwd_workspace_bytes(B, S, Hq) // 4, dtype=torch.float32, device="cuda")
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(L)]
+
+    def one_pass(timed=False):
+        for l in range(L):
+            src = route[l] % R
+            if timed:
+                ev[l][0].record()
+            skv.skv_train_attn_fwd(q[l % R], k[src], v[src], out[l % R], lse[l % R], lens, w.scale)
+            if timed:
+                ev[l][1].record()
+        for l in reversed(range(L)):
+            src = route[l] % R
+            skv.skv_train_attn_bwd(q[l % R], k[src], v[src], out[l % R], lse[l % R], do[l % R], dq[l % R],
+                                   dk[src], dv[src], lens, w.scale, ws)
+            if timed:
+                ev[l][2].record()
+
+    one_pass()
+    torch.cuda.synchronize()
+    steps = max(1, args.steps // 10)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        one_pass()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    one_pass(timed=True)
+    torch.cuda.synchronize()
+    fwd_ms = float(np.mean([ev[l][0].elapsed_time(ev[l][1]) for l in range(L)]))
+    # backward calls run back to back in reverse layer order: the gap between the end markers of
+    # consecutive calls is one call
+    bwd_ms = float(np.mean([ev[l + 1][2].elapsed_time(ev[l][2]) for l in range(L - 1)]))
+    assert skv.skv_train_device_faults() == 0
+    f_fwd = w.prefill_flops_per_layer()          # two causal products
+    f_bwd = f_fwd * 5 // 2                       # five: dV, dP, dQ, dK and the recomputed scores
+    return {"workload": "llama3_8b_rcla_train_attention_bf16",
+            "config": {"batch": B, "seq_len": S, "layers": L, "p": 0.5, "dtype": "bf16", "route": route},
+            "steps": steps, "ms_per_step": round(dt * 1e3, 3),
+            "value": round((f_fwd + f_bwd) * L / dt / 1e12, 1), "unit": "TFLOP/s",
+            "fwd": {"launch_us": round(fwd_ms * 1e3, 1), "achieved": round(f_fwd / (fwd_ms * 1e-3) / 1e12, 1)},
+            "roofline": {"bound": "mfma", "kernel": "dkdv_kernel + dq_kernel", "achieved": round(f_bwd / (bwd_ms * 1e-3) / 1e12, 1),
+                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": round(f_bwd / (bwd_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                         "launch_us": round(bwd_ms * 1e3, 1), "algorithmic_flops_per_launch": f_bwd}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -293,6 +358,8 @@ def main():
                     help="also time the group-by-group, chunk-by-chunk decode schedule (skv_attn_decode_range) "
                          "that lets the later layers of a sharing group find their slot slice in the on-chip caches")
     ap.add_argument("--only-prefill", action="store_true", help="profiling aid: measure only the prefill workload")
+    ap.add_argument("--only-train", action="store_true", help="profiling aid: measure only the training pass")
+    ap.add_argument("--skip-train", action="store_true")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--decode-workload", default="llama3_decode", choices=["llama3_decode", "qwen3_paged", "llama2_mha"],
                     help="decode workload to time (default: the one the metric is quoted on)")
@@ -327,6 +394,9 @@ def main():
     if args.only_prefill:
         print(json.dumps({"prefill": run_prefill(args, torch, skv, H, configs)}), flush=True)
         return
+    if args.only_train:
+        print(json.dumps({"train": run_train(args, torch, skv, configs)}), flush=True)
+        return
     dec = run_decode(args, torch, skv, H, configs)
     w = dec.pop("workload")
     line = {
@@ -345,6 +415,8 @@ def main():
         line["cross_layer_reuse"] = dec["cross_layer_reuse"]
     if not args.skip_prefill:
         line["prefill"] = run_prefill(args, torch, skv, H, configs)
+    if not args.skip_train:
+        line["train"] = run_train(args, torch, skv, configs)
     if not args.skip_cpu_baseline:
         log("[bench] timing the CPU oracle on a bounded sample ...")
         line["cpu_baseline"] = cpu_baseline_decode(w)

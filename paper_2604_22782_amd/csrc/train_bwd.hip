@@ -326,11 +326,17 @@ __global__ __launch_bounds__(kThreads, 1) void dkdv_kernel(TrainBwdArgs a, int n
 }
 
 // ---- dQ ------------------------------------------------------------------------------------------
-template <typename M, int D>
-__global__ __launch_bounds__(kThreads, 1) void dq_kernel(TrainBwdArgs a, int n_rt) {
+// W waves of 32 rows per work group.  W = 8 keeps the wave below 256 registers (the 64 keys of a
+// tile are processed as two blocks of 32), so two waves share a SIMD and cover each other's waits.
+template <typename M, int D, int W>
+__global__ __launch_bounds__(64 * W, 1) void dq_kernel(TrainBwdArgs a, int n_rt) {
     using Ge = Geo<D>;
     using vec8 = typename M::vec8;
-    constexpr int NL = Ge::NL, LPR = Ge::LPR;
+    constexpr int LPR = Ge::LPR;
+    constexpr int NT = 64 * W;                 // threads
+    constexpr int NL = kTile * LPR / NT;       // loads per thread, tile and tensor
+    static_assert(NL >= 1, "tile too small for the work group");
+    constexpr int kRows = 32 * W;              // rows a work group owns
     // per stage: K row-wise, K transposed view, V row-wise
     constexpr int kStage = 2 * Ge::R_BYTES + Ge::T_BYTES;
     __shared__ __attribute__((aligned(16))) char lds[2 * kStage];
@@ -351,9 +357,9 @@ __global__ __launch_bounds__(kThreads, 1) void dq_kernel(TrainBwdArgs a, int n_r
     const int kvh = head / G;
     const int n = a.seq_lens[b];
     if (n < 1 || n > a.seq) return; // reported by dkdv_kernel
-    const int q_begin = rt * kOwned;
+    const int q_begin = rt * kRows;
     if (q_begin >= n) return;
-    const int n_keys = min(q_begin + kOwned, n); // keys the work group needs: 0 .. its last row
+    const int n_keys = min(q_begin + kRows, n); // keys the work group needs: 0 .. its last row
     const int n_tiles = (n_keys + kTile - 1) / kTile;
 
     const int r0 = q_begin + 32 * wave;
@@ -388,7 +394,7 @@ __global__ __launch_bounds__(kThreads, 1) void dq_kernel(TrainBwdArgs a, int n_r
     auto issue = [&](int t) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            const int piece = tid + i * kThreads;
+            const int piece = tid + i * NT;
             const int key = t * kTile + piece / LPR;
             kr[i] = vr[i] = make_uint4(0, 0, 0, 0);
             if (key < n_keys) {
@@ -404,7 +410,7 @@ __global__ __launch_bounds__(kThreads, 1) void dq_kernel(TrainBwdArgs a, int n_r
         char *vs = ktv + Ge::T_BYTES;
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            const int piece = tid + i * kThreads;
+            const int piece = tid + i * NT;
             const int r = piece / LPR, p = (piece % LPR) * 16;
             *(uint4 *)(ks + r * Ge::R_STRIDE + p) = kr[i];
             *(uint4 *)(ktv + r * Ge::T_STRIDE + p) = kr[i];
@@ -422,44 +428,41 @@ __global__ __launch_bounds__(kThreads, 1) void dq_kernel(TrainBwdArgs a, int n_r
     const int sl = lane & 15;
     const int t_lane_off = (4 * hh + (sl >> 2)) * Ge::T_STRIDE + ((lane >> 4) & 1) * 32 + (sl & 3) * 8;
 
-    auto compute_tile = [&](const char *stage, int j0, auto masked) {
+    // one block of 32 keys (kb = 0, 1 of the staged tile) against this wave's 32 rows
+    auto compute_block = [&](const char *stage, int j0, int kb, auto masked) {
         const char *ks = stage;
         const char *ktv = ks + Ge::R_BYTES;
         const char *vs = ktv + Ge::T_BYTES;
-        // S^T = K Q^T and dP^T = V dO^T: keys x rows, lane = row column; two key blocks of 32
-        f32x16 s0, s1, p0, p1;
+        // S^T = K Q^T and dP^T = V dO^T: keys x rows, lane = row column
+        f32x16 s, dp;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s0[r] = s1[r] = p0[r] = p1[r] = 0.f;
-        const char *ka = ks + c * Ge::R_STRIDE + hh * 16;
-        const char *va = vs + c * Ge::R_STRIDE + hh * 16;
+        for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
+        const char *ka = ks + (32 * kb + c) * Ge::R_STRIDE + hh * 16;
+        const char *va = vs + (32 * kb + c) * Ge::R_STRIDE + hh * 16;
 #pragma unroll
         for (int st = 0; st < D / 16; ++st) {
-            s0 = M::mfma(__builtin_bit_cast(vec8, *(const uint4 *)(ka + st * 32)), qB[st], s0);
-            s1 = M::mfma(__builtin_bit_cast(vec8, *(const uint4 *)(ka + 32 * Ge::R_STRIDE + st * 32)), qB[st], s1);
-            p0 = M::mfma(__builtin_bit_cast(vec8, *(const uint4 *)(va + st * 32)), gB[st], p0);
-            p1 = M::mfma(__builtin_bit_cast(vec8, *(const uint4 *)(va + 32 * Ge::R_STRIDE + st * 32)), gB[st], p1);
+            s = M::mfma(__builtin_bit_cast(vec8, *(const uint4 *)(ka + st * 32)), qB[st], s);
+            dp = M::mfma(__builtin_bit_cast(vec8, *(const uint4 *)(va + st * 32)), gB[st], dp);
         }
-        // element r of block kb is key j0 + 32 kb + 8 (r/4) + 4 hh + r%4
-        float ds[32];
+        // element r is key j0 + 32 kb + 8 (r/4) + 4 hh + r%4
+        float ds[16];
 #pragma unroll
-        for (int r = 0; r < 32; ++r) {
-            const float sv = r < 16 ? s0[r & 15] : s1[r & 15];
-            const float pv = r < 16 ? p0[r & 15] : p1[r & 15];
-            float w = __builtin_amdgcn_exp2f(fmaf(sv, cs, -lse2));
+        for (int r = 0; r < 16; ++r) {
+            float w = __builtin_amdgcn_exp2f(fmaf(s[r], cs, -lse2));
             if constexpr (decltype(masked)::value) {
-                const int key = j0 + 32 * (r >> 4) + 8 * ((r & 15) >> 2) + 4 * hh + (r & 3);
+                const int key = j0 + 32 * kb + 8 * (r >> 2) + 4 * hh + (r & 3);
                 if (key > my_row) w = 0.f;
             }
-            ds[r] = w * (pv - delta);
+            ds[r] = w * (dp[r] - delta);
         }
-        // dQ^T += K^T dS^T: feature x rows, contraction over the 64 keys
-        const char *kb = ktv + t_lane_off;
+        // dQ^T += K^T dS^T: feature x rows, contraction over the 32 keys
+        const char *kt_ = ktv + 32 * kb * Ge::T_STRIDE + t_lane_off;
 #pragma unroll
-        for (int x = 0; x < 4; ++x) {
+        for (int x = 0; x < 2; ++x) {
             const vec8 dsB = pack_step<M>(ds + 8 * x);
 #pragma unroll
             for (int db = 0; db < D / 32; ++db)
-                dq[db] = M::mfma(read_transposed<M, Ge::T_STRIDE>(kb, x, db), dsB, dq[db]);
+                dq[db] = M::mfma(read_transposed<M, Ge::T_STRIDE>(kt_, x, db), dsB, dq[db]);
         }
     };
 
@@ -470,11 +473,14 @@ __global__ __launch_bounds__(kThreads, 1) void dq_kernel(TrainBwdArgs a, int n_r
     for (int t = 0; t < n_tiles; ++t) {
         const int j0 = t * kTile;
         const char *stage = lds + (t & 1) * kStage;
-        if (wave_ok && j0 <= wave_last) {
-            if (j0 + kTile - 1 > r0)
-                compute_tile(stage, j0, std::true_type{});
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            const int jb = j0 + 32 * kb;
+            if (!wave_ok || jb > wave_last) continue;
+            if (jb + 31 > r0)
+                compute_block(stage, j0, kb, std::true_type{});
             else
-                compute_tile(stage, j0, std::false_type{});
+                compute_block(stage, j0, kb, std::false_type{});
         }
         if (t + 1 < n_tiles) park((t + 1) & 1);
         __syncthreads();
@@ -494,12 +500,15 @@ __global__ __launch_bounds__(kThreads, 1) void dq_kernel(TrainBwdArgs a, int n_r
         }
 }
 
+constexpr int kDqWaves = 8;
+
 template <typename M, int D> hipError_t launch_b(const TrainBwdArgs &a, hipStream_t stream) {
     const int64_t n_rh = (int64_t)a.batch * a.seq * a.n_q_heads;
     const int64_t delta_blocks = (n_rh * (D / 8) + 255) / 256;
     const int n_kt = (a.seq + kOwned - 1) / kOwned;
     const int64_t kv_blocks = (int64_t)a.batch * a.n_kv_heads * n_kt;
-    const int64_t q_blocks = (int64_t)a.batch * a.n_q_heads * n_kt;
+    const int n_rt = (a.seq + 32 * kDqWaves - 1) / (32 * kDqWaves);
+    const int64_t q_blocks = (int64_t)a.batch * a.n_q_heads * n_rt;
     if (delta_blocks > 0x7fffffff || kv_blocks > 0x7fffffff || q_blocks > 0x7fffffff) return hipErrorInvalidValue;
     delta_kernel<M, D><<<dim3((unsigned)delta_blocks), 256, 0, stream>>>(a);
     hipError_t e = hipGetLastError();
@@ -507,7 +516,7 @@ template <typename M, int D> hipError_t launch_b(const TrainBwdArgs &a, hipStrea
     dkdv_kernel<M, D><<<dim3((unsigned)kv_blocks), kThreads, 0, stream>>>(a, n_kt);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    dq_kernel<M, D><<<dim3((unsigned)q_blocks), kThreads, 0, stream>>>(a, n_kt);
+    dq_kernel<M, D, kDqWaves><<<dim3((unsigned)q_blocks), 64 * kDqWaves, 0, stream>>>(a, n_rt);
     set_last_kernel_name("dkdv_kernel");
     return hipGetLastError();
 }
