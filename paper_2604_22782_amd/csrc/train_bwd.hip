@@ -5,15 +5,16 @@
 // P is recomputed from the forward's log-sum-exp, tile by tile, on the matrix cores
 // (v_mfma_f32_32x32x16); nothing of size seq x seq is ever stored.  Three launches, no atomics:
 //   delta_kernel   one float per (row, head);
-//   dkdv_kernel    a wave owns 32 keys of one kv head (K^T, V^T and the dK^T, dV^T accumulators
-//                  stay in its registers) and walks over the query heads of the group and the
-//                  query rows at or below its keys; the owner ADDS its result to the fp32 buffers
-//                  of the source layer, which several reader layers share;
+//   dkdv_kernel    a work group owns 128 keys of one kv head (their K, V rows stay in LDS, the
+//                  dK^T, dV^T accumulators in registers) and walks over the query heads of the
+//                  group and the query rows at or below its keys; it ADDS its result to the fp32
+//                  buffers of the source layer, which several reader layers share;
 //   dq_kernel      a wave owns 32 query rows (Q^T, dO^T, dQ^T in registers) and walks over the
 //                  keys at or before them, like the forward.
-// Tiles of the streamed operand (Q and dO rows, or K and V rows) are staged in LDS twice where both
-// a row-wise (A operand of S / dP) and a transposed (A operand of the d x row products, through
-// ds_read_b64_tr_b16) view is needed, each with the row stride that keeps its reads conflict-free.
+// Both run 8 waves per work group, two per SIMD, below 256 registers per lane: the instruction
+// order is the compiler's, and the second wave is what covers its waits.
+// The streamed tiles (Q and dO rows, or K and V rows) are read from LDS both row-wise (A operand
+// of S / dP) and transposed (A operand of the feature x row products, ds_read_b64_tr_b16).
 // As in the forward, the order of the contraction index inside a 16-wide MFMA step is permuted so
 // that exponentiated accumulators, rounded to 16 bits, are directly the next product's B operand.
 #include <type_traits>
@@ -55,33 +56,38 @@ struct TF16 {
     __device__ static float widen(uint16_t x) { return (float)__builtin_bit_cast(_Float16, x); }
 };
 
-constexpr int kWaves = 4;
-constexpr int kThreads = 64 * kWaves;
 constexpr int kTile = 64;            // rows of the streamed operand per LDS stage
-constexpr int kOwned = 32 * kWaves;  // rows (dq) / keys (dk, dv) a work group owns
 constexpr float kLog2e = 1.4426950408889634f;
-
-template <int D> struct Geo {
-    static constexpr int LPR = D / 8;                 // 16-byte pieces per row
-    static constexpr int NL = kTile * LPR / kThreads; // loads per thread, tile and tensor
-    static constexpr int R_STRIDE = D * 2 + 16;       // row-wise view: 16 rows x 16 bytes hit 16 bank groups
-    static constexpr int T_STRIDE = D * 2 + 64;       // transposed view: 4 rows x 64 bytes hit all banks
-    static constexpr int R_BYTES = kTile * R_STRIDE;
-    static constexpr int T_BYTES = kTile * T_STRIDE;
-    static_assert(NL >= 1, "tile too small for the work group");
-};
 
 __device__ __forceinline__ s16x4 lds_read_tr16(const char *p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(p));
 }
 
-// A operand (32 x 16, rows = the feature index d of block db, contraction = rows 16 x .. 16 x + 15
-// of the staged tile in the permuted order of the packed accumulators) through transposing reads.
-template <typename M, int T_STRIDE>
-__device__ __forceinline__ typename M::vec8 read_transposed(const char *lane_base, int x, int db) {
-    const char *p = lane_base + 16 * x * T_STRIDE + db * 64;
+// LDS layout of every tile (resident K, V block, staged Q, dO, K, V tiles): chunks of 4 rows
+// (4 x 2D bytes + 64 bytes of padding); inside a chunk the 16-byte piece p of row r sits at
+// 64 p + 16 r.  Row-wise operand reads (16 lanes = 16 consecutive rows, one piece) and transposing
+// reads (16 lanes = 4 rows x 32 bytes) both touch every bank exactly once, so one copy serves both.
+template <int D> struct Chunked {
+    static constexpr int CH = 8 * D + 64;
+    static constexpr int BLOCK32 = 8 * CH;  // 32 rows
+    static constexpr int TILE = 16 * CH;    // 64 rows
+    __device__ static int piece(int r, int p) { return (r >> 2) * CH + 64 * p + 16 * (r & 3); }
+    // lane part of a row-wise read of row c of a 32-row block: pieces 2 s + hh (+ 128 s per step)
+    __device__ static int row_lane(int c, int hh) { return (c >> 2) * CH + 16 * (c & 3) + 64 * hh; }
+    // lane part of a transposing read: rows 4 hh + sl / 4 of a 16-row step (+ 4 CH per step, + 2 CH
+    // for its second half), 8 bytes at byte 32 a + 8 (sl % 4) of the 64-byte feature block (+ 256 per block)
+    __device__ static int tr_lane(int lane) {
+        const int sl = lane & 15, a = (lane >> 4) & 1, hh = lane >> 5;
+        return hh * CH + 128 * a + 64 * ((sl & 3) >> 1) + 16 * (sl >> 2) + 8 * (sl & 1);
+    }
+};
+
+template <typename M, int D>
+__device__ __forceinline__ typename M::vec8 read_transposed_chunked(const char *lane_base, int x, int db) {
+    using C = Chunked<D>;
+    const char *p = lane_base + x * 4 * C::CH + db * 256;
     const s16x4 lo = lds_read_tr16(p);
-    const s16x4 hi = lds_read_tr16(p + 8 * T_STRIDE);
+    const s16x4 hi = lds_read_tr16(p + 2 * C::CH);
     const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     return __builtin_bit_cast(typename M::vec8, both);
 }
@@ -125,18 +131,32 @@ __global__ __launch_bounds__(256) void delta_kernel(TrainBwdArgs a) {
 }
 
 // ---- dK, dV --------------------------------------------------------------------------------------
+constexpr int kKvWaves = 8;             // 4 key blocks of 32 x the 2 row blocks of a 64-row tile
+constexpr int kKvThreads = 64 * kKvWaves;
+constexpr int kKvKeys = 128;            // keys a work group owns
+
+// A work group owns 128 keys of one kv head; their K and V rows stay in LDS (B operands of S and
+// dP).  Wave (kblk, rb) handles key block kblk against row block rb of every staged 64-row tile of
+// Q and dO, so two waves per SIMD cover each other's waits; the two waves of a key block add their
+// accumulators through LDS at the end.
 template <typename M, int D>
-__global__ __launch_bounds__(kThreads, 1) void dkdv_kernel(TrainBwdArgs a, int n_kt) {
-    using Ge = Geo<D>;
+__global__ __launch_bounds__(kKvThreads, 1) void dkdv_kernel(TrainBwdArgs a, int n_kt) {
+    using C = Chunked<D>;
     using vec8 = typename M::vec8;
-    constexpr int NL = Ge::NL, LPR = Ge::LPR;
-    // per stage: Q row-wise, Q transposed view, dO row-wise, dO transposed view, lse (log2), delta
-    constexpr int kStage = 2 * Ge::R_BYTES + 2 * Ge::T_BYTES + 2 * kTile * 4;
-    __shared__ __attribute__((aligned(16))) char lds[2 * kStage];
+    constexpr int LPR = D / 8;
+    constexpr int NL = kTile * LPR / kKvThreads;          // staged pieces per thread, tile and tensor
+    constexpr int NKV = kKvKeys * LPR / kKvThreads;       // resident pieces per thread and tensor
+    static_assert(NL >= 1 && NKV >= 1, "work group too large for the tile");
+    constexpr int kResident = 2 * 4 * C::BLOCK32;         // K then V of the 128 keys
+    constexpr int kStage = 2 * C::TILE + 2 * kTile * 4;   // Q, dO, lse (log2 units), delta
+    constexpr int kReduce = 4 * (D / 32) * 16 * 64 * 4;   // one tensor's accumulators of four waves
+    constexpr int kLds = kResident + 2 * kStage > kReduce ? kResident + 2 * kStage : kReduce;
+    __shared__ __attribute__((aligned(16))) char lds[kLds];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
+    const int kblk = wave & 3, rb = wave >> 2;
     const int c = lane & 31;
     const int hh = lane >> 5;
     const int hkv = a.n_kv_heads, hq = a.n_q_heads;
@@ -152,24 +172,25 @@ __global__ __launch_bounds__(kThreads, 1) void dkdv_kernel(TrainBwdArgs a, int n
         if (tid == 0 && kt == 0 && kvh == 0) atomicOr(a.faults, (uint32_t)SKV_FAULT_KV_LEN);
         return;
     }
-    const int k0 = kt * kOwned;
+    const int k0 = kt * kKvKeys;
     if (k0 >= n) return;
-    const int kb0 = k0 + 32 * wave; // first key of this wave
+    const int kb0 = k0 + 32 * kblk; // first key of this wave
     const int my_key = kb0 + c;
 
-    // K^T, V^T as B operands: lane (key c, k-group hh), step s holds K[key][16 s + 8 hh .. + 8)
-    vec8 kB[D / 16], vB[D / 16];
-    {
-        const int64_t off = (((int64_t)b * a.seq + my_key) * hkv + kvh) * D + 8 * hh;
+    char *k_res = lds, *v_res = lds + 4 * C::BLOCK32;
+    {   // resident K, V rows; keys beyond the length are zero
 #pragma unroll
-        for (int s = 0; s < D / 16; ++s) {
+        for (int i = 0; i < NKV; ++i) {
+            const int piece = tid + i * kKvThreads;
+            const int r = piece / LPR, p = piece % LPR;
             uint4 rk = make_uint4(0, 0, 0, 0), rv = rk;
-            if (my_key < n) {
-                rk = *(const uint4 *)((const uint16_t *)a.k + off + 16 * s);
-                rv = *(const uint4 *)((const uint16_t *)a.v + off + 16 * s);
+            if (k0 + r < n) {
+                const int64_t off = (((int64_t)b * a.seq + k0 + r) * hkv + kvh) * D + p * 8;
+                rk = *(const uint4 *)((const uint16_t *)a.k + off);
+                rv = *(const uint4 *)((const uint16_t *)a.v + off);
             }
-            kB[s] = __builtin_bit_cast(vec8, rk);
-            vB[s] = __builtin_bit_cast(vec8, rv);
+            *(uint4 *)(k_res + C::piece(r, p)) = rk;
+            *(uint4 *)(v_res + C::piece(r, p)) = rv;
         }
     }
 
@@ -177,7 +198,7 @@ __global__ __launch_bounds__(kThreads, 1) void dkdv_kernel(TrainBwdArgs a, int n
     const int n_qt = (n - 1) / kTile - qt0 + 1;    // row tiles per head
     const int n_it = G * n_qt;
 
-    // staging: thread t moves pieces t, t + 256, ... of the Q and dO tiles; rows beyond n are zero
+    // staging: thread t moves pieces t, t + 512, ... of the Q and dO tiles; rows beyond n are zero
     uint4 qr[NL], gr[NL];
     float aux = 0.f; // threads 0..63: lse of row tid (in log2 units), 64..127: delta of row tid - 64
     auto issue = [&](int it) {
@@ -185,7 +206,7 @@ __global__ __launch_bounds__(kThreads, 1) void dkdv_kernel(TrainBwdArgs a, int n
         const int r_first = (qt0 + it % n_qt) * kTile;
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            const int piece = tid + i * kThreads;
+            const int piece = tid + i * kKvThreads;
             const int row = r_first + piece / LPR;
             qr[i] = gr[i] = make_uint4(0, 0, 0, 0);
             if (row < n) {
@@ -204,19 +225,15 @@ __global__ __launch_bounds__(kThreads, 1) void dkdv_kernel(TrainBwdArgs a, int n
         }
     };
     auto park = [&](int stage) {
-        char *qs = lds + stage * kStage;
-        char *qt_ = qs + Ge::R_BYTES;
-        char *gs = qt_ + Ge::T_BYTES;
-        char *gt = gs + Ge::R_BYTES;
-        float *ax = (float *)(gt + Ge::T_BYTES);
+        char *qs = lds + kResident + stage * kStage;
+        char *gs = qs + C::TILE;
+        float *ax = (float *)(gs + C::TILE);
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            const int piece = tid + i * kThreads;
-            const int r = piece / LPR, p = (piece % LPR) * 16;
-            *(uint4 *)(qs + r * Ge::R_STRIDE + p) = qr[i];
-            *(uint4 *)(qt_ + r * Ge::T_STRIDE + p) = qr[i];
-            *(uint4 *)(gs + r * Ge::R_STRIDE + p) = gr[i];
-            *(uint4 *)(gt + r * Ge::T_STRIDE + p) = gr[i];
+            const int piece = tid + i * kKvThreads;
+            const int off = C::piece(piece / LPR, piece % LPR);
+            *(uint4 *)(qs + off) = qr[i];
+            *(uint4 *)(gs + off) = gr[i];
         }
         if (tid < 2 * kTile) ax[tid] = aux;
     };
@@ -228,26 +245,31 @@ __global__ __launch_bounds__(kThreads, 1) void dkdv_kernel(TrainBwdArgs a, int n
         for (int r = 0; r < 16; ++r) dk[i][r] = dv[i][r] = 0.f;
 
     const float cs = a.scale * kLog2e;
-    const int sl = lane & 15;
-    const int t_lane_off = (4 * hh + (sl >> 2)) * Ge::T_STRIDE + ((lane >> 4) & 1) * 32 + (sl & 3) * 8;
+    const int row_lane = C::row_lane(c, hh);
+    const int tr_lane = C::tr_lane(lane);
+    const char *kb_ = k_res + kblk * C::BLOCK32 + row_lane; // B operands: this wave's keys
+    const char *vb_ = v_res + kblk * C::BLOCK32 + row_lane;
 
-    // one block of 32 rows against this wave's 32 keys
-    auto compute_block = [&](const char *stage, int rb, int r0, auto masked) {
-        const char *qs = stage;
-        const char *qt_ = qs + Ge::R_BYTES;
-        const char *gs = qt_ + Ge::T_BYTES;
-        const char *gt = gs + Ge::R_BYTES;
-        const float *ax = (const float *)(gt + Ge::T_BYTES);
+    // this wave's block of 32 rows against its 32 keys
+    auto compute_block = [&](const char *stage, int r0, auto masked) {
+        const char *qs = stage + rb * C::BLOCK32;
+        const char *gs = qs + C::TILE;
+        const float *ax = (const float *)(stage + 2 * C::TILE);
         f32x16 s, dp;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
-        // S = Q K^T and dP = dO V^T: rows x keys, lane = key column, element r = row 8 (r/4) + 4 hh + r%4
-        const char *qa = qs + (32 * rb + c) * Ge::R_STRIDE + hh * 16;
-        const char *ga = gs + (32 * rb + c) * Ge::R_STRIDE + hh * 16;
+        // S = Q K^T and dP = dO V^T: rows x keys, lane = key column, element r = row 8 (r/4) + 4 hh + r%4.
+        // Four steps' operands at a time: fetching all eight at once does not fit the register budget.
 #pragma unroll
-        for (int st = 0; st < D / 16; ++st) {
-            s = M::mfma(__builtin_bit_cast(vec8, *(const uint4 *)(qa + st * 32)), kB[st], s);
-            dp = M::mfma(__builtin_bit_cast(vec8, *(const uint4 *)(ga + st * 32)), vB[st], dp);
+        for (int half = 0; half < D / 64; ++half) {
+#pragma unroll
+            for (int st = 4 * half; st < 4 * half + 4; ++st) {
+                s = M::mfma(__builtin_bit_cast(vec8, *(const uint4 *)(qs + row_lane + st * 128)),
+                            __builtin_bit_cast(vec8, *(const uint4 *)(kb_ + st * 128)), s);
+                dp = M::mfma(__builtin_bit_cast(vec8, *(const uint4 *)(gs + row_lane + st * 128)),
+                             __builtin_bit_cast(vec8, *(const uint4 *)(vb_ + st * 128)), dp);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
         float p[16], ds[16];
 #pragma unroll
@@ -267,17 +289,16 @@ __global__ __launch_bounds__(kThreads, 1) void dkdv_kernel(TrainBwdArgs a, int n
             }
         }
         // dV^T += dO^T P and dK^T += Q^T dS: feature x keys, contraction over the 32 rows
-        const char *gtb = gt + 32 * rb * Ge::T_STRIDE + t_lane_off;
-        const char *qtb = qt_ + 32 * rb * Ge::T_STRIDE + t_lane_off;
 #pragma unroll
         for (int x = 0; x < 2; ++x) {
             const vec8 pB = pack_step<M>(p + 8 * x);
             const vec8 dsB = pack_step<M>(ds + 8 * x);
 #pragma unroll
             for (int db = 0; db < D / 32; ++db) {
-                dv[db] = M::mfma(read_transposed<M, Ge::T_STRIDE>(gtb, x, db), pB, dv[db]);
-                dk[db] = M::mfma(read_transposed<M, Ge::T_STRIDE>(qtb, x, db), dsB, dk[db]);
+                dv[db] = M::mfma(read_transposed_chunked<M, D>(gs + tr_lane, x, db), pB, dv[db]);
+                dk[db] = M::mfma(read_transposed_chunked<M, D>(qs + tr_lane, x, db), dsB, dk[db]);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
@@ -286,43 +307,52 @@ __global__ __launch_bounds__(kThreads, 1) void dkdv_kernel(TrainBwdArgs a, int n
     if (n_it > 1) issue(1);
     __syncthreads();
     for (int it = 0; it < n_it; ++it) {
-        const char *stage = lds + (it & 1) * kStage;
-        const int r_first = (qt0 + it % n_qt) * kTile;
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-            const int r0 = r_first + 32 * rb;
-            if (r0 + 31 < kb0 || r0 >= n || kb0 >= n) continue; // rows before the keys, or nothing valid
+        const char *stage = lds + kResident + (it & 1) * kStage;
+        const int r0 = (qt0 + it % n_qt) * kTile + 32 * rb;
+        if (!(r0 + 31 < kb0 || r0 >= n || kb0 >= n)) { // else: rows before the keys, or nothing valid
             if (r0 < kb0 + 31)
-                compute_block(stage, rb, r0, std::true_type{});
+                compute_block(stage, r0, std::true_type{});
             else
-                compute_block(stage, rb, r0, std::false_type{});
+                compute_block(stage, r0, std::false_type{});
         }
         if (it + 1 < n_it) park((it + 1) & 1);
         __syncthreads();
         if (it + 2 < n_it) issue(it + 2);
     }
 
-    if (my_key >= n) return;
+    // The waves of the second row block hand their sums to their partners through LDS (all tiles
+    // are done: the staging area is free), one tensor at a time; the partners add and write out.
     // lane owns key my_key; element r of block db is feature 32 db + 8 (r/4) + 4 hh + r%4
+    float *red = (float *)lds + (size_t)kblk * (D / 32) * 16 * 64 + lane;
     const int64_t off = (((int64_t)b * a.seq + my_key) * hkv + kvh) * D + 4 * hh;
 #pragma unroll
-    for (int db = 0; db < D / 32; ++db)
+    for (int which = 0; which < 2; ++which) {
+        __syncthreads();
+        if (rb == 1) {
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            float4 *pk = (float4 *)(a.dk_accum + off + 32 * db + 8 * q4);
-            float4 *pv = (float4 *)(a.dv_accum + off + 32 * db + 8 * q4);
-            float4 ak = *pk, av = *pv;
-            ak.x += a.scale * dk[db][4 * q4];
-            ak.y += a.scale * dk[db][4 * q4 + 1];
-            ak.z += a.scale * dk[db][4 * q4 + 2];
-            ak.w += a.scale * dk[db][4 * q4 + 3];
-            av.x += dv[db][4 * q4];
-            av.y += dv[db][4 * q4 + 1];
-            av.z += dv[db][4 * q4 + 2];
-            av.w += dv[db][4 * q4 + 3];
-            *pk = ak;
-            *pv = av;
+            for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) red[(db * 16 + r) * 64] = which == 0 ? dk[db][r] : dv[db][r];
         }
+        __syncthreads();
+        if (rb == 0 && my_key < n) {
+            float *dst = (which == 0 ? a.dk_accum : a.dv_accum) + off;
+            const float f = which == 0 ? a.scale : 1.f;
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    float4 *pd = (float4 *)(dst + 32 * db + 8 * q4);
+                    float4 acc = *pd;
+                    const f32x16 &mine = which == 0 ? dk[db] : dv[db];
+                    acc.x += f * (mine[4 * q4] + red[(db * 16 + 4 * q4) * 64]);
+                    acc.y += f * (mine[4 * q4 + 1] + red[(db * 16 + 4 * q4 + 1) * 64]);
+                    acc.z += f * (mine[4 * q4 + 2] + red[(db * 16 + 4 * q4 + 2) * 64]);
+                    acc.w += f * (mine[4 * q4 + 3] + red[(db * 16 + 4 * q4 + 3) * 64]);
+                    *pd = acc;
+                }
+        }
+    }
 }
 
 // ---- dQ ------------------------------------------------------------------------------------------
@@ -330,15 +360,14 @@ __global__ __launch_bounds__(kThreads, 1) void dkdv_kernel(TrainBwdArgs a, int n
 // tile are processed as two blocks of 32), so two waves share a SIMD and cover each other's waits.
 template <typename M, int D, int W>
 __global__ __launch_bounds__(64 * W, 1) void dq_kernel(TrainBwdArgs a, int n_rt) {
-    using Ge = Geo<D>;
+    using C = Chunked<D>;
     using vec8 = typename M::vec8;
-    constexpr int LPR = Ge::LPR;
+    constexpr int LPR = D / 8;
     constexpr int NT = 64 * W;                 // threads
     constexpr int NL = kTile * LPR / NT;       // loads per thread, tile and tensor
     static_assert(NL >= 1, "tile too small for the work group");
     constexpr int kRows = 32 * W;              // rows a work group owns
-    // per stage: K row-wise, K transposed view, V row-wise
-    constexpr int kStage = 2 * Ge::R_BYTES + Ge::T_BYTES;
+    constexpr int kStage = 2 * C::TILE;        // K, V
     __shared__ __attribute__((aligned(16))) char lds[2 * kStage];
 
     const int tid = threadIdx.x;
@@ -406,15 +435,13 @@ __global__ __launch_bounds__(64 * W, 1) void dq_kernel(TrainBwdArgs a, int n_rt)
     };
     auto park = [&](int stage) {
         char *ks = lds + stage * kStage;
-        char *ktv = ks + Ge::R_BYTES;
-        char *vs = ktv + Ge::T_BYTES;
+        char *vs = ks + C::TILE;
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int piece = tid + i * NT;
-            const int r = piece / LPR, p = (piece % LPR) * 16;
-            *(uint4 *)(ks + r * Ge::R_STRIDE + p) = kr[i];
-            *(uint4 *)(ktv + r * Ge::T_STRIDE + p) = kr[i];
-            *(uint4 *)(vs + r * Ge::R_STRIDE + p) = vr[i];
+            const int off = C::piece(piece / LPR, piece % LPR);
+            *(uint4 *)(ks + off) = kr[i];
+            *(uint4 *)(vs + off) = vr[i];
         }
     };
 
@@ -425,24 +452,26 @@ __global__ __launch_bounds__(64 * W, 1) void dq_kernel(TrainBwdArgs a, int n_rt)
         for (int r = 0; r < 16; ++r) dq[i][r] = 0.f;
 
     const float cs = a.scale * kLog2e;
-    const int sl = lane & 15;
-    const int t_lane_off = (4 * hh + (sl >> 2)) * Ge::T_STRIDE + ((lane >> 4) & 1) * 32 + (sl & 3) * 8;
+    const int row_lane = C::row_lane(c, hh);
+    const int tr_lane = C::tr_lane(lane);
 
     // one block of 32 keys (kb = 0, 1 of the staged tile) against this wave's 32 rows
     auto compute_block = [&](const char *stage, int j0, int kb, auto masked) {
-        const char *ks = stage;
-        const char *ktv = ks + Ge::R_BYTES;
-        const char *vs = ktv + Ge::T_BYTES;
+        const char *ks = stage + kb * C::BLOCK32;
+        const char *vs = ks + C::TILE;
         // S^T = K Q^T and dP^T = V dO^T: keys x rows, lane = row column
         f32x16 s, dp;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
-        const char *ka = ks + (32 * kb + c) * Ge::R_STRIDE + hh * 16;
-        const char *va = vs + (32 * kb + c) * Ge::R_STRIDE + hh * 16;
+        // four steps' operands at a time: fetching all eight at once does not fit the register budget
 #pragma unroll
-        for (int st = 0; st < D / 16; ++st) {
-            s = M::mfma(__builtin_bit_cast(vec8, *(const uint4 *)(ka + st * 32)), qB[st], s);
-            dp = M::mfma(__builtin_bit_cast(vec8, *(const uint4 *)(va + st * 32)), gB[st], dp);
+        for (int half = 0; half < D / 64; ++half) {
+#pragma unroll
+            for (int st = 4 * half; st < 4 * half + 4; ++st) {
+                s = M::mfma(__builtin_bit_cast(vec8, *(const uint4 *)(ks + row_lane + st * 128)), qB[st], s);
+                dp = M::mfma(__builtin_bit_cast(vec8, *(const uint4 *)(vs + row_lane + st * 128)), gB[st], dp);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
         // element r is key j0 + 32 kb + 8 (r/4) + 4 hh + r%4
         float ds[16];
@@ -456,13 +485,12 @@ __global__ __launch_bounds__(64 * W, 1) void dq_kernel(TrainBwdArgs a, int n_rt)
             ds[r] = w * (dp[r] - delta);
         }
         // dQ^T += K^T dS^T: feature x rows, contraction over the 32 keys
-        const char *kt_ = ktv + 32 * kb * Ge::T_STRIDE + t_lane_off;
 #pragma unroll
         for (int x = 0; x < 2; ++x) {
             const vec8 dsB = pack_step<M>(ds + 8 * x);
 #pragma unroll
             for (int db = 0; db < D / 32; ++db)
-                dq[db] = M::mfma(read_transposed<M, Ge::T_STRIDE>(kt_, x, db), dsB, dq[db]);
+                dq[db] = M::mfma(read_transposed_chunked<M, D>(ks + tr_lane, x, db), dsB, dq[db]);
         }
     };
 
@@ -505,7 +533,7 @@ constexpr int kDqWaves = 8;
 template <typename M, int D> hipError_t launch_b(const TrainBwdArgs &a, hipStream_t stream) {
     const int64_t n_rh = (int64_t)a.batch * a.seq * a.n_q_heads;
     const int64_t delta_blocks = (n_rh * (D / 8) + 255) / 256;
-    const int n_kt = (a.seq + kOwned - 1) / kOwned;
+    const int n_kt = (a.seq + kKvKeys - 1) / kKvKeys;
     const int64_t kv_blocks = (int64_t)a.batch * a.n_kv_heads * n_kt;
     const int n_rt = (a.seq + 32 * kDqWaves - 1) / (32 * kDqWaves);
     const int64_t q_blocks = (int64_t)a.batch * a.n_q_heads * n_rt;
@@ -513,7 +541,7 @@ template <typename M, int D> hipError_t launch_b(const TrainBwdArgs &a, hipStrea
     delta_kernel<M, D><<<dim3((unsigned)delta_blocks), 256, 0, stream>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    dkdv_kernel<M, D><<<dim3((unsigned)kv_blocks), kThreads, 0, stream>>>(a, n_kt);
+    dkdv_kernel<M, D><<<dim3((unsigned)kv_blocks), kKvThreads, 0, stream>>>(a, n_kt);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     dq_kernel<M, D, kDqWaves><<<dim3((unsigned)q_blocks), 64 * kDqWaves, 0, stream>>>(a, n_rt);
