@@ -6,7 +6,9 @@ the 32 layers, owner layers append the new token's K/V row to their slot (skv_kv
 every layer attends over the slot it is routed to (skv_attn_decode: split-K kernel + merge).
 `value` is the algorithmic HBM traffic of the step divided by its wall time.  The causal prefill
 workload (BASELINE config 3) is measured after it and reported in the "prefill" object of the
-same JSON line, because the metric names both.
+same JSON line, because the metric names both.  A third object, "train", times one R-CLA
+training pass (Sec. 3.2: sampled route, forward and backward of the attention of every layer) on
+the same shape; it is a widening of the path and no part of `value`.
 
 Prints ONE JSON line on stdout; progress goes to stderr.
 """
@@ -335,6 +337,8 @@ def run_train(args, torch, skv, configs):
     # consecutive calls is one call
     bwd_ms = float(np.mean([ev[l + 1][2].elapsed_time(ev[l][2]) for l in range(L - 1)]))
     assert skv.skv_train_device_faults() == 0
+    parts = [measured_traffic(kn) for kn in ("delta_kernel", "dkdv_kernel", "dq_kernel")]
+    bwd_traffic = sum(parts) if all(p is not None for p in parts) else None
     f_fwd = w.prefill_flops_per_layer()          # two causal products
     f_bwd = f_fwd * 5 // 2                       # five: dV, dP, dQ, dK and the recomputed scores
     return {"workload": "llama3_8b_rcla_train_attention_bf16",
@@ -342,9 +346,9 @@ def run_train(args, torch, skv, configs):
             "steps": steps, "ms_per_step": round(dt * 1e3, 3),
             "value": round((f_fwd + f_bwd) * L / dt / 1e12, 1), "unit": "TFLOP/s",
             "fwd": {"launch_us": round(fwd_ms * 1e3, 1), "achieved": round(f_fwd / (fwd_ms * 1e-3) / 1e12, 1)},
-            "roofline": {"bound": "mfma", "kernel": "dkdv_kernel + dq_kernel", "achieved": round(f_bwd / (bwd_ms * 1e-3) / 1e12, 1),
+            "roofline": {"bound": "mfma", "kernel": "delta_kernel + dkdv_kernel + dq_kernel", "achieved": round(f_bwd / (bwd_ms * 1e-3) / 1e12, 1),
                          "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": round(f_bwd / (bwd_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                         "frac": round(f_bwd / (bwd_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": bwd_traffic,
                          "launch_us": round(bwd_ms * 1e3, 1), "algorithmic_flops_per_launch": f_bwd}}
 
 
