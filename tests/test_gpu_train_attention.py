@@ -132,3 +132,42 @@ def test_impossible_length_is_contained_and_reported():
     want, _ = T.attn_fwd(gen.to_f64(qs[0])[1:], gen.to_f64(ks[0])[1:], gen.to_f64(vs[0])[1:], 0.1, [40])
     assert np.abs(gen.to_f64(out)[1, :40] - want[0, :40]).max() <= H.TOL["bf16"]
     assert skv.skv_train_device_faults() == 0                  # reading cleared it
+
+
+def test_full_size_pass_layer_on_a_sampled_slice():
+    """The shape bench.py times (Llama-3.1-8B heads, 4 sequences of 8192 tokens, bf16): forward and
+    backward of one layer at full size; the oracle recomputes one (sequence, kv head) slice whole,
+    i.e. out, log-sum-exp and dQ of its four query heads and dK, dV of all its 8192 keys."""
+    B, S, Hq, Hkv, D = 4, 8192, 32, 8, 128
+    scale = 1.0 / np.sqrt(D)
+    g = torch.Generator(device="cuda").manual_seed(31)
+    mk = lambda h: torch.randn(B, S, h, D, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    q, k, v, do = mk(Hq), mk(Hkv), mk(Hkv), mk(Hq)
+    lens = torch.tensor([S, S - 77, S, 5000], dtype=torch.int32, device="cuda")
+    out = torch.empty_like(q)
+    lse = torch.empty(B, Hq, S, dtype=torch.float32, device="cuda")
+    dq = torch.empty_like(q)
+    dk = torch.zeros(B, S, Hkv, D, dtype=torch.float32, device="cuda")
+    dv = torch.zeros_like(dk)
+    ws = torch.empty(skv.skv_train_bwd_workspace_bytes(B, S, Hq) // 4, dtype=torch.float32, device="cuda")
+    skv.skv_train_attn_fwd(q, k, v, out, lse, lens, scale)
+    assert skv.skv_last_kernel_name() == "prefill_pipe_kernel"
+    skv.skv_train_attn_bwd(q, k, v, out, lse, do, dq, dk, dv, lens, scale, ws)
+    assert skv.skv_train_device_faults() == 0
+    for b, kvh in ((1, 5),):
+        n = int(lens[b])
+        hs = slice(4 * kvh, 4 * kvh + 4)
+        f = gen.to_f64
+        q1, k1, v1, do1 = f(q[b:b + 1, :, hs]), f(k[b:b + 1, :, kvh:kvh + 1]), f(v[b:b + 1, :, kvh:kvh + 1]), f(do[b:b + 1, :, hs])
+        print(f"\noracle on sequence {b} (length {n}), kv head {kvh} ...", flush=True)
+        w_out, w_lse = T.attn_fwd(q1, k1, v1, scale, [n])
+        w_dq, w_dk, w_dv = T.attn_bwd(q1, k1, v1, do1, scale, [n])
+        assert np.abs(f(out[b, :n, hs]) - w_out[0, :n]).max() <= H.TOL["bf16"]
+        assert np.abs(lse[b, hs, :n].cpu().double().numpy() - w_lse[0, :, :n]).max() <= 2e-3
+        for name, got, want in (("dq", f(dq[b, :n, hs]), w_dq[0, :n]),
+                                ("dk", dk[b, :n, kvh].cpu().double().numpy(), w_dk[0, :n, 0]),
+                                ("dv", dv[b, :n, kvh].cpu().double().numpy(), w_dv[0, :n, 0])):
+            err = float(np.abs(got - want).max())
+            print(f"{name}: max |err| {err:.3e}, max |want| {np.abs(want).max():.3e}", flush=True)
+            assert err <= _grad_tol("bf16", want), name
+        assert not dk[b, n:].any() and not dv[b, n:].any()
