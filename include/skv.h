@@ -138,6 +138,24 @@ skv_status_t skv_kv_append(skv_cache_t *cache, int32_t layer, const void *k_new,
                            const int32_t *start_pos, const int32_t *new_lens, int32_t max_new,
                            void *stream);
 
+/* The same update with the projection in front of it (Sec. 4.3: the leader layer of a sharing
+ * group computes and stores K, V; every other layer skips its K/V projections, which is where the
+ * paper's throughput gain comes from): K = x w_k^T, V = x w_v^T with fp32 accumulation, K
+ * optionally rotated by position, rounded once to the cache dtype and written to the slot as
+ * skv_kv_append would; the projected rows never exist in memory outside the cache.
+ * x: device [batch][max_new][hidden], cache dtype; w_k, w_v: device
+ * [n_kv_heads * head_dim][hidden] (one row per output feature).  rope_cos, rope_sin: device float
+ * [rope_positions][head_dim / 2], or both NULL for no rotation; feature i < head_dim / 2 of a head
+ * pairs with i + head_dim / 2:  k'_i = k_i cos - k_(i+d/2) sin,  k'_(i+d/2) = k_(i+d/2) cos +
+ * k_i sin, with the table row of the token's position start_pos[b] + i (a position beyond the
+ * table drops the row and sets SKV_FAULT_APPEND_RANGE).  V is never rotated.
+ * SKV_ERR_NOT_OWNER for a layer without a slot (nothing is computed: that is the saving);
+ * SKV_ERR_UNSUPPORTED unless the cache is 16-bit, head_dim 64 or 128 and hidden a multiple of 64. */
+skv_status_t skv_kv_project_append(skv_cache_t *cache, int32_t layer, const void *x, const void *w_k,
+                                   const void *w_v, const float *rope_cos, const float *rope_sin,
+                                   int32_t rope_positions, const int32_t *start_pos,
+                                   const int32_t *new_lens, int32_t max_new, int32_t hidden, void *stream);
+
 /* Scratch bytes skv_attn_decode needs for sequences of up to max_kv_len positions. */
 skv_status_t skv_decode_workspace_bytes(const skv_cache_t *cache, int32_t max_kv_len, size_t *bytes);
 

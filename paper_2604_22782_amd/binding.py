@@ -9,7 +9,7 @@ __all__ = [
     "SkvError", "Cache", "lib", "SKV_F32", "SKV_F16", "SKV_BF16", "STATUS", "dtype_code",
     "skv_route_from_strategy", "skv_route_validate", "skv_cache_bytes", "skv_cache_alloc",
     "skv_cache_free", "skv_cache_info", "skv_cache_slot_of_layer", "skv_cache_set_block_table",
-    "skv_cache_device_faults", "skv_kv_append", "skv_decode_workspace_bytes", "skv_attn_decode",
+    "skv_cache_device_faults", "skv_kv_append", "skv_kv_project_append", "skv_decode_workspace_bytes", "skv_attn_decode",
     "skv_decode_range_workspace_bytes", "skv_attn_decode_range", "skv_attn_prefill", "skv_status_str", "skv_last_hip_error", "skv_last_kernel_name",
     "skv_calib_mfma_bf16", "skv_train_sample_route", "skv_train_attn_fwd", "skv_train_bwd_workspace_bytes",
     "skv_train_attn_bwd", "skv_train_device_faults", "SKV_TRAIN_RCLA", "SKV_TRAIN_CLA_K", "SKV_TRAIN_RDCLA_K",
@@ -181,6 +181,23 @@ def skv_cache_device_faults(cache: Cache) -> int:
 def skv_kv_append(cache: Cache, layer: int, k_new, v_new, start_pos, new_lens, max_new: int, stream=None):
     _check(lib().skv_kv_append(cache.handle, layer, _ptr(k_new), _ptr(v_new), _ptr(start_pos),
                                _ptr(new_lens), max_new, _stream(stream)), "skv_kv_append")
+
+
+def skv_kv_project_append(cache: Cache, layer: int, x, w_k, w_v, rope_cos, rope_sin, start_pos, new_lens,
+                          max_new: int, stream=None):
+    """x: [batch][max_new][hidden]; w_k, w_v: [n_kv_heads * head_dim][hidden]; rope_cos, rope_sin:
+    float32 [positions][head_dim / 2] or None."""
+    hidden = x.shape[-1]
+    if w_k.shape[-1] != hidden or w_v.shape[-1] != hidden or w_k.dtype != x.dtype or w_v.dtype != x.dtype:
+        raise ValueError("w_k and w_v are [n_kv_heads * head_dim][hidden] in the dtype of x")
+    n_pos = 0
+    if rope_cos is not None:
+        if rope_cos.dtype != torch.float32 or rope_sin.dtype != torch.float32 or rope_cos.shape != rope_sin.shape:
+            raise ValueError("rope tables are float32 [positions][head_dim / 2]")
+        n_pos = rope_cos.shape[0]
+    _check(lib().skv_kv_project_append(cache.handle, layer, _ptr(x), _ptr(w_k), _ptr(w_v), _ptr(rope_cos),
+                                       _ptr(rope_sin), n_pos, _ptr(start_pos), _ptr(new_lens), max_new, hidden,
+                                       _stream(stream)), "skv_kv_project_append")
 
 
 def skv_decode_workspace_bytes(cache: Cache, max_kv_len: int) -> int:

@@ -309,6 +309,35 @@ skv_status_t skv_decode_range_workspace_bytes(const skv_cache_t *c, int32_t seq_
     return SKV_OK;
 }
 
+skv_status_t skv_kv_project_append(skv_cache_t *c, int32_t layer, const void *x, const void *w_k, const void *w_v,
+                                   const float *rope_cos, const float *rope_sin, int32_t rope_positions,
+                                   const int32_t *start_pos, const int32_t *new_lens, int32_t max_new,
+                                   int32_t hidden, void *stream) {
+    if (!c || !x || !w_k || !w_v || !start_pos || !new_lens) return SKV_ERR_INVALID_ARG;
+    if (layer < 0 || layer >= c->d.n_layers || max_new < 0 || hidden < 1) return SKV_ERR_INVALID_ARG;
+    if ((rope_cos == nullptr) != (rope_sin == nullptr)) return SKV_ERR_INVALID_ARG;
+    if (rope_cos != nullptr && rope_positions < 1) return SKV_ERR_INVALID_ARG;
+    if (c->route[layer] != layer) return SKV_ERR_NOT_OWNER;
+    if (!paged_ready(c)) return SKV_ERR_INVALID_ARG;
+    if (!skv::project_append_supported(c->d.dtype, c->d.head_dim, hidden)) return SKV_ERR_UNSUPPORTED;
+    if (max_new == 0) return SKV_OK;
+    skv::ProjArgs a;
+    a.slot = view_of(c, c->slot[layer]);
+    a.x = x;
+    a.w_k = w_k;
+    a.w_v = w_v;
+    a.rope_cos = rope_cos;
+    a.rope_sin = rope_sin;
+    a.start_pos = start_pos;
+    a.new_lens = new_lens;
+    a.batch = c->d.batch;
+    a.max_new = max_new;
+    a.hidden = hidden;
+    a.rope_positions = rope_positions;
+    const hipError_t e = skv::launch_project_append(a, c->d.dtype, c->d.head_dim, (hipStream_t)stream);
+    return e == hipSuccess ? SKV_OK : hip_fail(e);
+}
+
 skv_status_t skv_decode_workspace_bytes(const skv_cache_t *c, int32_t max_kv_len, size_t *bytes) {
     if (!c) return SKV_ERR_INVALID_ARG;
     return skv_decode_range_workspace_bytes(c, c->d.batch, max_kv_len, bytes);

@@ -69,6 +69,17 @@ hipError_t launch_prefill_mfma(const AttnArgs &a, int dtype, int head_dim, int g
 bool prefill_pipe_supported(const AttnArgs &a, int dtype, int head_dim);
 hipError_t launch_prefill_pipe(const AttnArgs &a, int dtype, int group, hipStream_t stream);
 
+// Owner-layer K/V projection fused with the append (16-bit, head_dim 64 or 128, hidden % 64 == 0).
+struct ProjArgs {
+    SlotView slot;
+    const void *x, *w_k, *w_v;
+    const float *rope_cos, *rope_sin; // both nullptr: no rotation
+    const int32_t *start_pos, *new_lens;
+    int32_t batch, max_new, hidden, rope_positions;
+};
+bool project_append_supported(int dtype, int head_dim, int hidden);
+hipError_t launch_project_append(const ProjArgs &a, int dtype, int head_dim, hipStream_t stream);
+
 // Training backward (16-bit, head_dim 64 or 128).  delta: [batch][n_q_heads][seq] scratch.
 struct TrainBwdArgs {
     const void *q, *k, *v, *out, *d_out;
