@@ -285,6 +285,59 @@ def run_prefill(args, torch, skv, H, configs):
     return res
 
 
+def run_project(args, torch, skv, H, configs):
+    """The owner layers' K/V projection fused with the cache update (Sec. 4.3), timed in the two
+    regimes of the path: the prompt of the prefill workload (compute bound) and one decode token
+    of the decode workload (bound by reading the weights).  Hidden size 4096 as in Llama-3-8B."""
+    hidden = 4096
+    out = {}
+    for regime, w, new in (("prefill", configs.llama3_prefill(), None), ("decode", configs.llama3_decode(n_layers=2), 1)):
+        S = int(w.kv_lens.max())
+        new = S if new is None else new
+        cache, _ = H.alloc_cache(w)
+        g = torch.Generator(device="cuda").manual_seed(7)
+        x = torch.randn(w.batch, new, hidden, generator=g, device="cuda").to(torch.bfloat16)
+        F = w.n_kv_heads * w.head_dim
+        wk = (torch.randn(F, hidden, generator=g, device="cuda") / hidden ** 0.5).to(torch.bfloat16)
+        wv = (torch.randn(F, hidden, generator=g, device="cuda") / hidden ** 0.5).to(torch.bfloat16)
+        inv = 10000.0 ** (-torch.arange(w.head_dim // 2, device="cuda", dtype=torch.float64) * 2.0 / w.head_dim)
+        ang = torch.arange(S, device="cuda", dtype=torch.float64)[:, None] * inv[None, :]
+        cos, sin = torch.cos(ang).float().contiguous(), torch.sin(ang).float().contiguous()
+        start = torch.full((w.batch,), S - new, dtype=torch.int32, device="cuda")
+        lens = torch.full((w.batch,), new, dtype=torch.int32, device="cuda")
+        layer = w.owner_layers[0]
+        reps = 20 if regime == "prefill" else 200
+        ws = torch.empty(max(skv.skv_kv_project_workspace_bytes(cache, new, hidden), 4) // 4, dtype=torch.float32, device="cuda")
+        for _ in range(3):
+            skv.skv_kv_project_append(cache, layer, x, wk, wv, cos, sin, start, lens, new, ws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            skv.skv_kv_project_append(cache, layer, x, wk, wv, cos, sin, start, lens, new, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        assert skv.skv_cache_device_faults(cache) == 0
+        us = e0.elapsed_time(e1) / reps * 1e3
+        tokens = w.batch * new
+        flops = 2 * tokens * hidden * 2 * F
+        nbytes = 2 * (2 * F * hidden + tokens * hidden + 2 * tokens * F)     # weights + x read, K/V rows written
+        r = {"tokens": tokens, "hidden": hidden, "launch_us": round(us, 1),
+             "tflops": round(flops / (us * 1e-6) / 1e12, 1), "gbs": round(nbytes / (us * 1e-6) / 1e9, 1)}
+        if regime == "prefill":
+            r["roofline"] = {"bound": "mfma", "kernel": "project_append_kernel", "achieved": r["tflops"],
+                             "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                             "frac": round(r["tflops"] / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                             "algorithmic_flops_per_launch": flops}
+        else:
+            r["roofline"] = {"bound": "hbm", "kernel": "project_append_kernel", "achieved": r["gbs"],
+                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(r["gbs"] / HBM_PEAK_GBS, 4),
+                             "traffic": None, "algorithmic_bytes_per_launch": nbytes}
+        out[regime] = r
+        cache.free()
+        torch.cuda.empty_cache()
+    return out
+
+
 def run_train(args, torch, skv, configs):
     """One R-CLA training pass (Sec. 3.2) over the attention of a Llama-3.1-8B-shaped stack at the
     paper's fine-tuning length: sampled route, forward of every layer against its source layer's
@@ -364,6 +417,8 @@ def main():
     ap.add_argument("--only-prefill", action="store_true", help="profiling aid: measure only the prefill workload")
     ap.add_argument("--only-train", action="store_true", help="profiling aid: measure only the training pass")
     ap.add_argument("--skip-train", action="store_true")
+    ap.add_argument("--only-project", action="store_true", help="profiling aid: measure only the fused K/V projection")
+    ap.add_argument("--skip-project", action="store_true")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--decode-workload", default="llama3_decode", choices=["llama3_decode", "qwen3_paged", "llama2_mha"],
                     help="decode workload to time (default: the one the metric is quoted on)")
@@ -398,6 +453,9 @@ def main():
     if args.only_prefill:
         print(json.dumps({"prefill": run_prefill(args, torch, skv, H, configs)}), flush=True)
         return
+    if args.only_project:
+        print(json.dumps({"project_append": run_project(args, torch, skv, H, configs)}), flush=True)
+        return
     if args.only_train:
         print(json.dumps({"train": run_train(args, torch, skv, configs)}), flush=True)
         return
@@ -419,6 +477,8 @@ def main():
         line["cross_layer_reuse"] = dec["cross_layer_reuse"]
     if not args.skip_prefill:
         line["prefill"] = run_prefill(args, torch, skv, H, configs)
+    if not args.skip_project:
+        line["project_append"] = run_project(args, torch, skv, H, configs)
     if not args.skip_train:
         line["train"] = run_train(args, torch, skv, configs)
     if not args.skip_cpu_baseline:

@@ -9,7 +9,7 @@ __all__ = [
     "SkvError", "Cache", "lib", "SKV_F32", "SKV_F16", "SKV_BF16", "STATUS", "dtype_code",
     "skv_route_from_strategy", "skv_route_validate", "skv_cache_bytes", "skv_cache_alloc",
     "skv_cache_free", "skv_cache_info", "skv_cache_slot_of_layer", "skv_cache_set_block_table",
-    "skv_cache_device_faults", "skv_kv_append", "skv_kv_project_append", "skv_decode_workspace_bytes", "skv_attn_decode",
+    "skv_cache_device_faults", "skv_kv_append", "skv_kv_project_append", "skv_kv_project_workspace_bytes", "skv_decode_workspace_bytes", "skv_attn_decode",
     "skv_decode_range_workspace_bytes", "skv_attn_decode_range", "skv_attn_prefill", "skv_status_str", "skv_last_hip_error", "skv_last_kernel_name",
     "skv_calib_mfma_bf16", "skv_train_sample_route", "skv_train_attn_fwd", "skv_train_bwd_workspace_bytes",
     "skv_train_attn_bwd", "skv_train_device_faults", "SKV_TRAIN_RCLA", "SKV_TRAIN_CLA_K", "SKV_TRAIN_RDCLA_K",
@@ -183,8 +183,15 @@ def skv_kv_append(cache: Cache, layer: int, k_new, v_new, start_pos, new_lens, m
                                _ptr(new_lens), max_new, _stream(stream)), "skv_kv_append")
 
 
+def skv_kv_project_workspace_bytes(cache: Cache, max_new: int, hidden: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().skv_kv_project_workspace_bytes(cache.handle, max_new, hidden, ctypes.byref(out)),
+           "skv_kv_project_workspace_bytes")
+    return out.value
+
+
 def skv_kv_project_append(cache: Cache, layer: int, x, w_k, w_v, rope_cos, rope_sin, start_pos, new_lens,
-                          max_new: int, stream=None):
+                          max_new: int, workspace=None, stream=None):
     """x: [batch][max_new][hidden]; w_k, w_v: [n_kv_heads * head_dim][hidden]; rope_cos, rope_sin:
     float32 [positions][head_dim / 2] or None."""
     hidden = x.shape[-1]
@@ -195,9 +202,10 @@ def skv_kv_project_append(cache: Cache, layer: int, x, w_k, w_v, rope_cos, rope_
         if rope_cos.dtype != torch.float32 or rope_sin.dtype != torch.float32 or rope_cos.shape != rope_sin.shape:
             raise ValueError("rope tables are float32 [positions][head_dim / 2]")
         n_pos = rope_cos.shape[0]
+    wb = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib().skv_kv_project_append(cache.handle, layer, _ptr(x), _ptr(w_k), _ptr(w_v), _ptr(rope_cos),
                                        _ptr(rope_sin), n_pos, _ptr(start_pos), _ptr(new_lens), max_new, hidden,
-                                       _stream(stream)), "skv_kv_project_append")
+                                       _ptr(workspace), ctypes.c_size_t(wb), _stream(stream)), "skv_kv_project_append")
 
 
 def skv_decode_workspace_bytes(cache: Cache, max_kv_len: int) -> int:

@@ -49,88 +49,13 @@ constexpr int kTokens = 32 * kWaves; // tokens per work group
 constexpr int kKT = 64;              // hidden elements per staged tile
 constexpr int kStride = kKT * 2 + 16; // LDS row stride: 16 consecutive rows x 16 bytes hit 16 bank groups
 
+// Rotation, rounding and the store of one lane's share of a token row: acc[nb][r] is feature
+// 32 nb + 8 (r/4) + 4 hh + r%4 of head `head` of K (or V) for the token at row m of x.
 template <typename M, int D>
-__global__ __launch_bounds__(kThreads, 1) void project_append_kernel(ProjArgs a) {
-    using vec8 = typename M::vec8;
-    constexpr int NB = D / 32;                           // feature blocks of the head
-    constexpr int NX = kTokens * (kKT / 8) / kThreads;   // x pieces per thread and tile (4)
-    constexpr int NW = D * (kKT / 8) / kThreads;         // weight pieces per thread and tile (2 or 1)
-    constexpr int kStage = (kTokens + D) * kStride;
-    __shared__ __attribute__((aligned(16))) char lds[2 * kStage];
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int c = lane & 31;
-    const int hh = lane >> 5;
+__device__ __forceinline__ void finish_token(const ProjArgs &a, f32x16 (&acc)[D / 32], int64_t m, int head, bool is_v,
+                                             int hh) {
+    constexpr int NB = D / 32;
     const int hkv = a.slot.n_kv_heads;
-    const bool is_v = (int)blockIdx.x >= hkv;
-    const int head = blockIdx.x % hkv;
-    const int64_t n_tok = (int64_t)a.batch * a.max_new;
-    const int64_t tok0 = (int64_t)blockIdx.y * kTokens;
-
-    const uint16_t *w = (const uint16_t *)(is_v ? a.w_v : a.w_k) + (int64_t)head * D * a.hidden;
-    const uint16_t *x = (const uint16_t *)a.x;
-
-    uint4 xr[NX], wr[NW];
-    auto issue = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < NX; ++i) {
-            const int piece = tid + i * kThreads;
-            const int64_t row = tok0 + piece / (kKT / 8);
-            xr[i] = make_uint4(0, 0, 0, 0);
-            if (row < n_tok) xr[i] = *(const uint4 *)(x + row * a.hidden + kt * kKT + (piece % (kKT / 8)) * 8);
-        }
-#pragma unroll
-        for (int i = 0; i < NW; ++i) {
-            const int piece = tid + i * kThreads;
-            wr[i] = *(const uint4 *)(w + (int64_t)(piece / (kKT / 8)) * a.hidden + kt * kKT + (piece % (kKT / 8)) * 8);
-        }
-    };
-    auto park = [&](int stage) {
-        char *xs = lds + stage * kStage;
-        char *ws = xs + kTokens * kStride;
-#pragma unroll
-        for (int i = 0; i < NX; ++i) {
-            const int piece = tid + i * kThreads;
-            *(uint4 *)(xs + (piece / (kKT / 8)) * kStride + (piece % (kKT / 8)) * 16) = xr[i];
-        }
-#pragma unroll
-        for (int i = 0; i < NW; ++i) {
-            const int piece = tid + i * kThreads;
-            *(uint4 *)(ws + (piece / (kKT / 8)) * kStride + (piece % (kKT / 8)) * 16) = wr[i];
-        }
-    };
-
-    f32x16 acc[NB];
-#pragma unroll
-    for (int i = 0; i < NB; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-
-    const int n_kt = a.hidden / kKT;
-    issue(0);
-    park(0);
-    if (n_kt > 1) issue(1);
-    __syncthreads();
-    for (int kt = 0; kt < n_kt; ++kt) {
-        const char *xs = lds + (kt & 1) * kStage + (32 * wave + c) * kStride + hh * 16;
-        const char *ws = lds + (kt & 1) * kStage + kTokens * kStride + c * kStride + hh * 16;
-#pragma unroll
-        for (int st = 0; st < kKT / 16; ++st) {
-            const vec8 b = __builtin_bit_cast(vec8, *(const uint4 *)(xs + st * 32));
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                acc[nb] = M::mfma(__builtin_bit_cast(vec8, *(const uint4 *)(ws + nb * 32 * kStride + st * 32)), b, acc[nb]);
-        }
-        if (kt + 1 < n_kt) park((kt + 1) & 1);
-        __syncthreads();
-        if (kt + 2 < n_kt) issue(kt + 2);
-    }
-
-    // lane owns token tok0 + 32 wave + c; element r of block nb is feature 32 nb + 8 (r/4) + 4 hh + r%4
-    const int64_t m = tok0 + 32 * wave + c;
-    if (m >= n_tok) return;
     const int b = (int)(m / a.max_new);
     const int i = (int)(m - (int64_t)b * a.max_new);
     if (i >= a.new_lens[b]) return;
@@ -172,11 +97,188 @@ __global__ __launch_bounds__(kThreads, 1) void project_append_kernel(ProjArgs a)
                                                             M::pack2(acc[nb][4 * g4 + 2], acc[nb][4 * g4 + 3]));
 }
 
-template <typename M, int D> hipError_t launch_j(const ProjArgs &a, hipStream_t stream) {
+// grid = (2 n_kv_heads, token tiles, splits of the hidden axis).  With one split the work group
+// finishes its rows itself; with more (few tokens: the launch would not fill the chip, and the
+// weights have to stream from HBM at full rate) it stores its fp32 partial sums,
+// partial[split][token][K or V][head][feature], and finish_kernel adds them up.
+template <typename M, int D>
+__global__ __launch_bounds__(kThreads, 1) void project_append_kernel(ProjArgs a) {
+    using vec8 = typename M::vec8;
+    constexpr int NB = D / 32;                           // feature blocks of the head
+    constexpr int NX = kTokens * (kKT / 8) / kThreads;   // x pieces per thread and tile (4)
+    constexpr int NW = D * (kKT / 8) / kThreads;         // weight pieces per thread and tile (2 or 1)
+    constexpr int kStage = (kTokens + D) * kStride;
+    __shared__ __attribute__((aligned(16))) char lds[2 * kStage];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int c = lane & 31;
+    const int hh = lane >> 5;
+    const int hkv = a.slot.n_kv_heads;
+    const bool is_v = (int)blockIdx.x >= hkv;
+    const int head = blockIdx.x % hkv;
+    const int64_t n_tok = (int64_t)a.batch * a.max_new;
+    const int64_t tok0 = (int64_t)blockIdx.y * kTokens;
+
+    const uint16_t *w = (const uint16_t *)(is_v ? a.w_v : a.w_k) + (int64_t)head * D * a.hidden;
+    const uint16_t *x = (const uint16_t *)a.x;
+
+    // Loads run kDepth tiles ahead of the MFMAs, in a ring of register sets (one tile of MFMAs is far
+    // shorter than a trip to HBM); the LDS stage of a tile is filled one tile ahead.
+    constexpr int kDepth = 4;
+    struct Slot {
+        uint4 x[NX], w[NW];
+    };
+    Slot s0, s1, s2, s3;
+    auto issue = [&](int kt, Slot &q) {
+        uint4 *xq = q.x, *wq = q.w;
+#pragma unroll
+        for (int i = 0; i < NX; ++i) {
+            const int piece = tid + i * kThreads;
+            const int64_t row = tok0 + piece / (kKT / 8);
+            xq[i] = make_uint4(0, 0, 0, 0);
+            if (row < n_tok) xq[i] = *(const uint4 *)(x + row * a.hidden + kt * kKT + (piece % (kKT / 8)) * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            const int piece = tid + i * kThreads;
+            wq[i] = *(const uint4 *)(w + (int64_t)(piece / (kKT / 8)) * a.hidden + kt * kKT + (piece % (kKT / 8)) * 8);
+        }
+    };
+    auto park = [&](int stage, const Slot &q) {
+        const uint4 *xq = q.x, *wq = q.w;
+        char *xs = lds + stage * kStage;
+        char *ws = xs + kTokens * kStride;
+#pragma unroll
+        for (int i = 0; i < NX; ++i) {
+            const int piece = tid + i * kThreads;
+            *(uint4 *)(xs + (piece / (kKT / 8)) * kStride + (piece % (kKT / 8)) * 16) = xq[i];
+        }
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            const int piece = tid + i * kThreads;
+            *(uint4 *)(ws + (piece / (kKT / 8)) * kStride + (piece % (kKT / 8)) * 16) = wq[i];
+        }
+    };
+
+    f32x16 acc[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+
+    const int n_kt = a.hidden / kKT / (int)gridDim.z;   // tiles of this split
+    const int kt0 = (int)blockIdx.z * n_kt;
+    static_assert(kDepth == 4, "the ring is spelled out below");
+    issue(kt0, s0);
+    if (1 < n_kt) issue(kt0 + 1, s1);
+    if (2 < n_kt) issue(kt0 + 2, s2);
+    if (3 < n_kt) issue(kt0 + 3, s3);
+    park(0, s0);
+    __syncthreads();
+    auto step = [&](int kt, Slot &mine, const Slot &next) {
+        const char *xs = lds + (kt & 1) * kStage + (32 * wave + c) * kStride + hh * 16;
+        const char *ws = lds + (kt & 1) * kStage + kTokens * kStride + c * kStride + hh * 16;
+#pragma unroll
+        for (int st = 0; st < kKT / 16; ++st) {
+            const vec8 b = __builtin_bit_cast(vec8, *(const uint4 *)(xs + st * 32));
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                acc[nb] = M::mfma(__builtin_bit_cast(vec8, *(const uint4 *)(ws + nb * 32 * kStride + st * 32)), b, acc[nb]);
+        }
+        if (kt + 1 < n_kt) park((kt + 1) & 1, next);         // the next tile's registers landed long ago
+        __syncthreads();
+        if (kt + kDepth < n_kt) issue(kt0 + kt + kDepth, mine); // this tile's registers are free again
+    };
+    for (int base = 0; base < n_kt; base += kDepth) { // ring slots named explicitly: fixed registers
+        step(base, s0, s1);
+        if (base + 1 < n_kt) step(base + 1, s1, s2);
+        if (base + 2 < n_kt) step(base + 2, s2, s3);
+        if (base + 3 < n_kt) step(base + 3, s3, s0);
+    }
+
+    // lane owns token tok0 + 32 wave + c; element r of block nb is feature 32 nb + 8 (r/4) + 4 hh + r%4
+    const int64_t m = tok0 + 32 * wave + c;
+    if (m >= n_tok) return;
+    if (gridDim.z == 1) {
+        finish_token<M, D>(a, acc, m, head, is_v, hh);
+        return;
+    }
+    float *part = a.partial + (((int64_t)blockIdx.z * n_tok + m) * 2 * hkv + blockIdx.x) * D + 4 * hh;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4)
+            *(float4 *)(part + 32 * nb + 8 * g4) =
+                make_float4(acc[nb][4 * g4], acc[nb][4 * g4 + 1], acc[nb][4 * g4 + 2], acc[nb][4 * g4 + 3]);
+}
+
+// Adds up the partial sums of the splits.  One thread per (token, K or V head, half hh, feature
+// block nb < NB/2, group g4): the four features 32 nb + 8 g4 + 4 hh .. + 3 of the head and their
+// rotary partners d/2 further on, i.e. what finish_token needs together.
+template <typename M, int D>
+__global__ __launch_bounds__(256) void project_finish_kernel(ProjArgs a, int n_splits) {
+    constexpr int NB = D / 32;
+    const int hkv = a.slot.n_kv_heads;
+    const int64_t n_tok = (int64_t)a.batch * a.max_new;
+    int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int g4 = (int)(t & 3);
+    t >>= 2;
+    const int nb = (int)(t % (NB / 2));
+    t /= NB / 2;
+    const int hh = (int)(t & 1);
+    t >>= 1;
+    const int kh = (int)(t % (2 * hkv));
+    const int64_t m = t / (2 * hkv);
+    if (m >= n_tok) return;
+    const int f_lo = 32 * nb + 8 * g4 + 4 * hh, f_hi = f_lo + D / 2;
+    float4 lo = make_float4(0.f, 0.f, 0.f, 0.f), hi = lo;
+    for (int s = 0; s < n_splits; ++s) {
+        const float *part = a.partial + (((int64_t)s * n_tok + m) * 2 * hkv + kh) * D;
+        const float4 u = *(const float4 *)(part + f_lo), v = *(const float4 *)(part + f_hi);
+        lo.x += u.x; lo.y += u.y; lo.z += u.z; lo.w += u.w;
+        hi.x += v.x; hi.y += v.y; hi.z += v.z; hi.w += v.w;
+    }
+    const int head = kh % hkv;
+    const bool is_v = kh >= hkv;
+    const int b = (int)(m / a.max_new);
+    const int i = (int)(m - (int64_t)b * a.max_new);
+    if (i >= a.new_lens[b]) return;
+    const int64_t pos = (int64_t)a.start_pos[b] + i;
+    const bool rotate = !is_v && a.rope_cos != nullptr;
+    const bool first = hh == 0 && nb == 0 && g4 == 0;
+    if (pos < 0 || pos >= a.slot.max_ctx || (rotate && pos >= a.rope_positions)) {
+        if (first) atomicOr(a.slot.faults, (uint32_t)SKV_FAULT_APPEND_RANGE);
+        return;
+    }
+    const int64_t dst_row = slot_row(a.slot, b, (int)pos);
+    if (dst_row < 0) {
+        if (first) atomicOr(a.slot.faults, (uint32_t)SKV_FAULT_BLOCK_ID);
+        return;
+    }
+    if (rotate) {
+        const float4 cv = *(const float4 *)(a.rope_cos + pos * (D / 2) + f_lo);
+        const float4 sv = *(const float4 *)(a.rope_sin + pos * (D / 2) + f_lo);
+        const float4 l = lo, h = hi;
+        lo = make_float4(l.x * cv.x - h.x * sv.x, l.y * cv.y - h.y * sv.y, l.z * cv.z - h.z * sv.z, l.w * cv.w - h.w * sv.w);
+        hi = make_float4(h.x * cv.x + l.x * sv.x, h.y * cv.y + l.y * sv.y, h.z * cv.z + l.z * sv.z, h.w * cv.w + l.w * sv.w);
+    }
+    uint16_t *dst = (uint16_t *)(is_v ? a.slot.v : a.slot.k) + (dst_row * hkv + head) * D;
+    *(uint2 *)(dst + f_lo) = make_uint2(M::pack2(lo.x, lo.y), M::pack2(lo.z, lo.w));
+    *(uint2 *)(dst + f_hi) = make_uint2(M::pack2(hi.x, hi.y), M::pack2(hi.z, hi.w));
+}
+
+template <typename M, int D> hipError_t launch_j(const ProjArgs &a, int n_splits, hipStream_t stream) {
     const int64_t n_tok = (int64_t)a.batch * a.max_new;
     const int64_t tiles = (n_tok + kTokens - 1) / kTokens;
     if (tiles > 65535 || 2 * a.slot.n_kv_heads > 65535) return hipErrorInvalidValue;
-    project_append_kernel<M, D><<<dim3((unsigned)(2 * a.slot.n_kv_heads), (unsigned)tiles), kThreads, 0, stream>>>(a);
+    const dim3 grid((unsigned)(2 * a.slot.n_kv_heads), (unsigned)tiles, (unsigned)n_splits);
+    project_append_kernel<M, D><<<grid, kThreads, 0, stream>>>(a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || n_splits == 1) return e;
+    const int64_t threads = n_tok * 2 * a.slot.n_kv_heads * 2 * (D / 64) * 4;
+    project_finish_kernel<M, D><<<dim3((unsigned)((threads + 255) / 256)), 256, 0, stream>>>(a, n_splits);
     return hipGetLastError();
 }
 
@@ -187,10 +289,26 @@ bool project_append_supported(int dtype, int head_dim, int hidden) {
            hidden % kKT == 0;
 }
 
-hipError_t launch_project_append(const ProjArgs &a, int dtype, int head_dim, hipStream_t stream) {
+// Splits of the hidden axis: one while the (head, token tile) grid alone fills the chip; else as
+// many as bring the launch to about one work group per compute unit, each at least 128 wide.
+int project_append_splits(int n_kv_heads, int64_t n_tokens, int hidden) {
+    const int64_t tiles = (n_tokens + kTokens - 1) / kTokens;
+    const int64_t groups = 2 * (int64_t)n_kv_heads * tiles;
+    if (groups >= 128) return 1;
+    int splits = 1;
+    while (groups * splits < 256 && hidden / kKT % (2 * splits) == 0 && hidden / (2 * splits) >= 128) splits *= 2;
+    return splits;
+}
+
+size_t project_append_workspace_bytes(int n_kv_heads, int head_dim, int64_t n_tokens, int hidden) {
+    const int splits = project_append_splits(n_kv_heads, n_tokens, hidden);
+    return splits == 1 ? 0 : (size_t)splits * (size_t)n_tokens * 2 * n_kv_heads * head_dim * sizeof(float);
+}
+
+hipError_t launch_project_append(const ProjArgs &a, int dtype, int head_dim, int n_splits, hipStream_t stream) {
     if (dtype == SKV_BF16)
-        return head_dim == 128 ? launch_j<JBF16, 128>(a, stream) : launch_j<JBF16, 64>(a, stream);
-    return head_dim == 128 ? launch_j<JF16, 128>(a, stream) : launch_j<JF16, 64>(a, stream);
+        return head_dim == 128 ? launch_j<JBF16, 128>(a, n_splits, stream) : launch_j<JBF16, 64>(a, n_splits, stream);
+    return head_dim == 128 ? launch_j<JF16, 128>(a, n_splits, stream) : launch_j<JF16, 64>(a, n_splits, stream);
 }
 
 } // namespace skv

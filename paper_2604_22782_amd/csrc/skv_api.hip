@@ -309,10 +309,17 @@ skv_status_t skv_decode_range_workspace_bytes(const skv_cache_t *c, int32_t seq_
     return SKV_OK;
 }
 
+skv_status_t skv_kv_project_workspace_bytes(const skv_cache_t *c, int32_t max_new, int32_t hidden, size_t *bytes) {
+    if (!c || !bytes || max_new < 0 || hidden < 1) return SKV_ERR_INVALID_ARG;
+    if (!skv::project_append_supported(c->d.dtype, c->d.head_dim, hidden)) return SKV_ERR_UNSUPPORTED;
+    *bytes = skv::project_append_workspace_bytes(c->d.n_kv_heads, c->d.head_dim, (int64_t)c->d.batch * max_new, hidden);
+    return SKV_OK;
+}
+
 skv_status_t skv_kv_project_append(skv_cache_t *c, int32_t layer, const void *x, const void *w_k, const void *w_v,
                                    const float *rope_cos, const float *rope_sin, int32_t rope_positions,
                                    const int32_t *start_pos, const int32_t *new_lens, int32_t max_new,
-                                   int32_t hidden, void *stream) {
+                                   int32_t hidden, void *workspace, size_t workspace_bytes, void *stream) {
     if (!c || !x || !w_k || !w_v || !start_pos || !new_lens) return SKV_ERR_INVALID_ARG;
     if (layer < 0 || layer >= c->d.n_layers || max_new < 0 || hidden < 1) return SKV_ERR_INVALID_ARG;
     if ((rope_cos == nullptr) != (rope_sin == nullptr)) return SKV_ERR_INVALID_ARG;
@@ -321,7 +328,12 @@ skv_status_t skv_kv_project_append(skv_cache_t *c, int32_t layer, const void *x,
     if (!paged_ready(c)) return SKV_ERR_INVALID_ARG;
     if (!skv::project_append_supported(c->d.dtype, c->d.head_dim, hidden)) return SKV_ERR_UNSUPPORTED;
     if (max_new == 0) return SKV_OK;
+    const int64_t n_tokens = (int64_t)c->d.batch * max_new;
+    const int n_splits = skv::project_append_splits(c->d.n_kv_heads, n_tokens, hidden);
+    const size_t need = skv::project_append_workspace_bytes(c->d.n_kv_heads, c->d.head_dim, n_tokens, hidden);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return SKV_ERR_INVALID_ARG;
     skv::ProjArgs a;
+    a.partial = (float *)workspace;
     a.slot = view_of(c, c->slot[layer]);
     a.x = x;
     a.w_k = w_k;
@@ -334,7 +346,7 @@ skv_status_t skv_kv_project_append(skv_cache_t *c, int32_t layer, const void *x,
     a.max_new = max_new;
     a.hidden = hidden;
     a.rope_positions = rope_positions;
-    const hipError_t e = skv::launch_project_append(a, c->d.dtype, c->d.head_dim, (hipStream_t)stream);
+    const hipError_t e = skv::launch_project_append(a, c->d.dtype, c->d.head_dim, n_splits, (hipStream_t)stream);
     return e == hipSuccess ? SKV_OK : hip_fail(e);
 }
 

@@ -75,10 +75,13 @@ struct ProjArgs {
     const void *x, *w_k, *w_v;
     const float *rope_cos, *rope_sin; // both nullptr: no rotation
     const int32_t *start_pos, *new_lens;
+    float *partial;                   // fp32 partial sums when the hidden axis is split
     int32_t batch, max_new, hidden, rope_positions;
 };
 bool project_append_supported(int dtype, int head_dim, int hidden);
-hipError_t launch_project_append(const ProjArgs &a, int dtype, int head_dim, hipStream_t stream);
+int project_append_splits(int n_kv_heads, int64_t n_tokens, int hidden);
+size_t project_append_workspace_bytes(int n_kv_heads, int head_dim, int64_t n_tokens, int hidden);
+hipError_t launch_project_append(const ProjArgs &a, int dtype, int head_dim, int n_splits, hipStream_t stream);
 
 // Training backward (16-bit, head_dim 64 or 128).  delta: [batch][n_q_heads][seq] scratch.
 struct TrainBwdArgs {

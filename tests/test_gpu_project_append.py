@@ -39,6 +39,9 @@ CASES = [
     ("bf16", 1, 128, 512, [400, 400], [10, 0], [300, 257], 300, True, True),
     ("f16", 4, 128, 192, [9, 9], [0, 8], [9, 1], 9, False, True),
     ("bf16", 2, 64, 64, [300], [0], [300], 300, False, True),
+    # few tokens and a long hidden axis: the launch splits the hidden axis and sums fp32 partials
+    ("bf16", 2, 128, 2048, [50, 50, 50], [49, 0, 7], [1, 1, 1], 1, True, True),
+    ("f16", 1, 64, 1024, [40], [2], [33], 33, False, True),
 ]
 
 
@@ -61,8 +64,11 @@ def test_projected_rows_match_oracle(dtype, Hkv, D, hidden, lens, start, new, ma
         cos, sin = d_cos.cpu().double().numpy(), d_sin.cpu().double().numpy()   # the tables as the kernel sees them
     d_start = torch.tensor(start, dtype=torch.int32, device="cuda")
     d_new = torch.tensor(new, dtype=torch.int32, device="cuda")
+    ws_bytes = skv.skv_kv_project_workspace_bytes(cache, max_new, hidden)
+    ws = torch.empty(max(ws_bytes, 4) // 4, dtype=torch.float32, device="cuda")
+    print(f"workspace {ws_bytes} bytes", flush=True)
     for layer in (0, 2):
-        skv.skv_kv_project_append(cache, layer, x.cuda(), wk.cuda(), wv.cuda(), d_cos, d_sin, d_start, d_new, max_new)
+        skv.skv_kv_project_append(cache, layer, x.cuda(), wk.cuda(), wv.cuda(), d_cos, d_sin, d_start, d_new, max_new, ws)
     with pytest.raises(skv.SkvError) as e:          # layer 1 owns no slot: nothing to project, nothing to store
         skv.skv_kv_project_append(cache, 1, x.cuda(), wk.cuda(), wv.cuda(), d_cos, d_sin, d_start, d_new, max_new)
     assert e.value.status == 3
@@ -98,6 +104,7 @@ def test_position_beyond_the_table_or_capacity_is_dropped_and_reported():
     d_cos, d_sin = torch.from_numpy(cos.astype(np.float32)).cuda(), torch.from_numpy(sin.astype(np.float32)).cuda()
     zero = torch.zeros(1, dtype=torch.int32, device="cuda")
     eight = torch.full((1,), 8, dtype=torch.int32, device="cuda")
+    assert skv.skv_kv_project_workspace_bytes(cache, 8, 64) == 0
     skv.skv_kv_project_append(cache, 0, x, wk, wk, d_cos, d_sin, zero, eight, 8)     # table has 4 positions
     assert skv.skv_cache_device_faults(cache) == 1                                    # SKV_FAULT_APPEND_RANGE
     k_pool, v_pool = H.pool_tensors(cache, w)
