@@ -1,0 +1,44 @@
+"""The end-to-end harness against the fp64 decoder oracle on tiny shapes: cached serving
+(pre-fill, then teacher-forced decode steps; owner layers project + append, the others skip) must
+give the logits of the cache-free whole-sequence evaluation, and the cache must have the size the
+paper's KV-MB columns imply."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import decoder_oracle as D
+from workloads import gen
+from workloads.e2e_decoder import SyntheticDecoder
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("hq,hkv,d,group", [(4, 2, 64, 2), (2, 1, 128, 3), (2, 2, 128, 1)])
+def test_cached_serving_matches_whole_sequence_oracle(hq, hkv, d, group):
+    L, hidden, mlp, vocab, B, T, steps = 4, 128, 256, 96, 2, 70, 3
+    m = SyntheticDecoder(L, hidden, hq, hkv, d, mlp, vocab, group=group, seed=5, sigma=0.09)
+    print(f"\nroute {m.route}", flush=True)
+    m.start(B, T + steps)
+    rng = np.random.default_rng(3)
+    tok = torch.from_numpy(rng.integers(0, vocab, (B, T + steps))).cuda()
+    got = [m.prefill(tok[:, :T])]
+    for s in range(steps):                                   # teacher forcing: the oracle sees the same tokens
+        got.append(m.decode_step(tok[:, T + s]))
+    got = torch.stack(got, dim=1).float().cpu().double().numpy()          # [B][1 + steps][V]
+    w = {k: gen.to_f64(v) for k, v in m.w.items()}
+    cos, sin = m.cos.cpu().double().numpy(), m.sin.cpu().double().numpy()
+    want = D.logits_all_positions(w, m.route, tok.cpu().numpy(), hq, hkv, d, cos, sin)[:, T - 1:]
+    err = np.abs(got - want).max()
+    print(f"logits: max |err| {err:.3e}, max |want| {np.abs(want).max():.3e}", flush=True)
+    assert err <= 0.03 * np.abs(want).max()                  # a chain of bf16 roundings through four blocks
+    assert (got.argmax(-1) == want.argmax(-1)).mean() >= 0.75
+    m.close()
+
+
+def test_kv_cache_size_is_the_papers_column():
+    """Tab. 4: 8192 input + 128 generated tokens, Qwen3-8B-scale -> 1170 MB without sharing, 293 with groups of 4."""
+    for g, mb in ((1, 1170.0), (4, 292.5)):
+        m = SyntheticDecoder.__new__(SyntheticDecoder)
+        m.L, m.hq, m.hkv, m.d, m.dtype, m.B = 36, 32, 8, 128, torch.bfloat16, 1
+        m.route = [g * (l // g) for l in range(36)]
+        assert m.kv_cache_bytes(8192 + 128) / 2 ** 20 == mb
