@@ -338,6 +338,52 @@ def run_project(args, torch, skv, H, configs):
     return out
 
 
+def run_e2e(args, torch, skv):
+    """The sweep of the paper's inference benchmark (Tab. 4: batch 1, input 2048..32768, 128 new
+    tokens; Tab. 5: 8192-token context, batch 2..16, 64 new tokens; group sizes 1 and 4) on a
+    synthetic Qwen3-8B-scale decoder: KV-cache MiB, peak device memory, time to first token,
+    decode tokens/s.  Context for the paper's tables, not part of `value`."""
+    from workloads.e2e_decoder import SyntheticDecoder
+    rows = []
+    for g in (1, 4):
+        torch.cuda.empty_cache()
+        m = SyntheticDecoder(group=g, seed=7)
+        w_bytes = sum(t.numel() * t.element_size() for t in m.w.values())
+        m.start(1, 2048 + 8)                                  # untimed warm-up: library set-up, GEMM heuristics
+        nxt = m.prefill(torch.zeros(1, 2048, dtype=torch.int64, device="cuda")).argmax(-1)
+        for _ in range(4):
+            nxt = m.decode_step(nxt).argmax(-1)
+        torch.cuda.synchronize()
+        m.close()
+        for table, batch, T, new in ([("tab4", 1, T, 128) for T in (2048, 8192, 16384, 32768)] +
+                                     [("tab5", B, 8192, 64) for B in (2, 4, 8, 16)]):
+            m.start(batch, T + new)
+            gen_ = torch.Generator(device="cuda").manual_seed(T + batch)
+            tok = torch.randint(0, m.vocab, (batch, T), generator=gen_, device="cuda")
+            torch.cuda.reset_peak_memory_stats()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            nxt = m.prefill(tok).argmax(-1)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(new - 1):
+                nxt = m.decode_step(nxt).argmax(-1)
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            assert skv.skv_cache_device_faults(m.cache) == 0
+            kv = m.kv_cache_bytes(T + new)
+            rows.append({"table": table, "batch": batch, "input": T, "new_tokens": new, "g": g,
+                         "kv_cache_mib": round(kv / 2 ** 20, 1),
+                         "peak_mem_mib": round((torch.cuda.max_memory_allocated() + kv) / 2 ** 20),
+                         "weights_mib": round(w_bytes / 2 ** 20),
+                         "ttft_ms": round((t1 - t0) * 1e3, 1),
+                         "tok_per_s": round(batch * (new - 1) / (t2 - t1), 1)})
+            log(f"[bench] e2e {rows[-1]}")
+            m.close()
+        del m
+    return rows
+
+
 def run_train(args, torch, skv, configs):
     """One R-CLA training pass (Sec. 3.2) over the attention of a Llama-3.1-8B-shaped stack at the
     paper's fine-tuning length: sampled route, forward of every layer against its source layer's
@@ -417,6 +463,8 @@ def main():
     ap.add_argument("--only-prefill", action="store_true", help="profiling aid: measure only the prefill workload")
     ap.add_argument("--only-train", action="store_true", help="profiling aid: measure only the training pass")
     ap.add_argument("--skip-train", action="store_true")
+    ap.add_argument("--e2e", action="store_true",
+                    help="only run the end-to-end sweep of the paper's Tab. 4 / Tab. 5 on a synthetic Qwen3-8B-scale decoder")
     ap.add_argument("--only-project", action="store_true", help="profiling aid: measure only the fused K/V projection")
     ap.add_argument("--skip-project", action="store_true")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
@@ -452,6 +500,9 @@ def main():
 
     if args.only_prefill:
         print(json.dumps({"prefill": run_prefill(args, torch, skv, H, configs)}), flush=True)
+        return
+    if args.e2e:
+        print(json.dumps({"e2e": run_e2e(args, torch, skv)}), flush=True)
         return
     if args.only_project:
         print(json.dumps({"project_append": run_project(args, torch, skv, H, configs)}), flush=True)

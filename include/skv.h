@@ -162,7 +162,8 @@ skv_status_t skv_kv_project_append(skv_cache_t *cache, int32_t layer, const void
                                    const int32_t *new_lens, int32_t max_new, int32_t hidden,
                                    void *workspace, size_t workspace_bytes, void *stream);
 
-/* Scratch bytes skv_attn_decode needs for sequences of up to max_kv_len positions. */
+/* Scratch bytes skv_attn_decode needs for sequences of up to max_kv_len positions: enough for
+ * every call whose max_kv_len hint is at most this one. */
 skv_status_t skv_decode_workspace_bytes(const skv_cache_t *cache, int32_t max_kv_len, size_t *bytes);
 
 /* Sampling-phase attention, Eq. (3.1) for one query token per sequence:

@@ -303,8 +303,17 @@ skv_status_t skv_kv_append(skv_cache_t *c, int32_t layer, const void *k_new, con
 skv_status_t skv_decode_range_workspace_bytes(const skv_cache_t *c, int32_t seq_count, int32_t max_kv_len,
                                               size_t *bytes) {
     if (!c || !bytes || max_kv_len <= 0 || seq_count <= 0 || seq_count > c->d.batch) return SKV_ERR_INVALID_ARG;
-    const int32_t kps = decode_keys_per_split(c, seq_count, max_kv_len);
-    const size_t n_splits = (size_t)(max_kv_len + kps - 1) / kps;
+    // The split count of a launch is not monotone in its length hint (the split length is rounded to
+    // 256 keys), so size for the most splits any hint up to max_kv_len can produce: splits are at
+    // least 256 keys long, and either about 256 / (sequences x kv heads) per sequence or capped at
+    // 2048 keys and more.
+    const int64_t units = (int64_t)seq_count * c->d.n_kv_heads;
+    const int64_t by_len = ((int64_t)max_kv_len + 255) / 256;
+    const int64_t by_units = 256 / units + 2;
+    const int64_t capped = ((int64_t)max_kv_len + kMaxKeysPerSplit / 2 - 1) / (kMaxKeysPerSplit / 2);
+    const int32_t kps = decode_keys_per_split(c, seq_count, max_kv_len); // exact for this hint (covers the tuning knob)
+    const int64_t exact = ((int64_t)max_kv_len + kps - 1) / kps;
+    const size_t n_splits = (size_t)std::max({exact, capped, std::min(by_len, by_units)});
     *bytes = (size_t)seq_count * c->d.n_q_heads * n_splits * (c->d.head_dim + 2) * sizeof(float);
     return SKV_OK;
 }

@@ -42,3 +42,22 @@ def test_kv_cache_size_is_the_papers_column():
         m.L, m.hq, m.hkv, m.d, m.dtype, m.B = 36, 32, 8, 128, torch.bfloat16, 1
         m.route = [g * (l // g) for l in range(36)]
         assert m.kv_cache_bytes(8192 + 128) / 2 ** 20 == mb
+
+
+def test_decode_workspace_sized_for_the_capacity_serves_every_shorter_hint():
+    """A serving loop sizes its scratch once, for the longest context, and passes a growing length
+    hint: the size query must cover every hint up to its argument (split counts are not monotone)."""
+    import paper_2604_22782_amd as skv
+    cache = skv.skv_cache_alloc(n_layers=1, n_q_heads=32, n_kv_heads=8, head_dim=128, batch=1, max_ctx=8320,
+                                dtype=skv.SKV_BF16, route=[0], block_size=0, n_blocks=0)
+    top = skv.skv_decode_workspace_bytes(cache, 8320)
+    assert all(skv.skv_decode_workspace_bytes(cache, n) <= top for n in range(1, 8321, 37))
+    ws = torch.empty(top, dtype=torch.uint8, device="cuda")
+    q = torch.randn(1, 32, 128, device="cuda").to(torch.bfloat16)
+    out = torch.empty_like(q)
+    for n in (1, 255, 257, 4096, 4097, 8193, 8320):
+        lens = torch.tensor([n], dtype=torch.int32, device="cuda")
+        skv.skv_attn_decode(cache, 0, q, out, lens, n, 0.1, ws)          # raised SKV_ERR_INVALID_ARG at 8193 before
+    torch.cuda.synchronize()
+    assert skv.skv_cache_device_faults(cache) == 0
+    cache.free()
