@@ -366,10 +366,18 @@ def run_e2e(args, torch, skv):
             nxt = m.prefill(tok).argmax(-1)
             torch.cuda.synchronize()
             t1 = time.perf_counter()
-            for _ in range(new - 1):
+            half = (new - 1) // 2
+            for _ in range(half):                             # eager: one host call per launch
                 nxt = m.decode_step(nxt).argmax(-1)
             torch.cuda.synchronize()
             t2 = time.perf_counter()
+            m.capture_decode()                                # the same step as one HIP graph
+            torch.cuda.synchronize()
+            t3 = time.perf_counter()
+            for _ in range(new - 1 - half):
+                nxt = m.decode_step_graph(nxt).argmax(-1)
+            torch.cuda.synchronize()
+            t4 = time.perf_counter()
             assert skv.skv_cache_device_faults(m.cache) == 0
             kv = m.kv_cache_bytes(T + new)
             rows.append({"table": table, "batch": batch, "input": T, "new_tokens": new, "g": g,
@@ -377,7 +385,8 @@ def run_e2e(args, torch, skv):
                          "peak_mem_mib": round((torch.cuda.max_memory_allocated() + kv) / 2 ** 20),
                          "weights_mib": round(w_bytes / 2 ** 20),
                          "ttft_ms": round((t1 - t0) * 1e3, 1),
-                         "tok_per_s": round(batch * (new - 1) / (t2 - t1), 1)})
+                         "tok_per_s_eager": round(batch * half / (t2 - t1), 1),
+                         "tok_per_s": round(batch * (new - 1 - half) / (t4 - t3), 1)})
             log(f"[bench] e2e {rows[-1]}")
             m.close()
         del m

@@ -61,3 +61,30 @@ def test_decode_workspace_sized_for_the_capacity_serves_every_shorter_hint():
     torch.cuda.synchronize()
     assert skv.skv_cache_device_faults(cache) == 0
     cache.free()
+
+
+def test_captured_decode_step_replays_like_the_eager_one():
+    """The decode step as a HIP graph: every replay, with eager work and synchronisations in between,
+    gives bit for bit the logits of the eager step run with the same launch sizes."""
+    L, hidden, hq, hkv, d, mlp, vocab, B, T, steps = 4, 128, 4, 2, 64, 256, 96, 2, 40, 6
+    rng = np.random.default_rng(9)
+    tok = torch.from_numpy(rng.integers(0, vocab, (B, T + steps))).cuda()
+    results = {}
+    for mode in ("eager", "graph"):
+        m = SyntheticDecoder(L, hidden, hq, hkv, d, mlp, vocab, group=2, seed=5, sigma=0.09)
+        m.start(B, T + steps)
+        m.prefill(tok[:, :T])
+        if mode == "graph":
+            m.capture_decode()
+        outs = []
+        for s_ in range(steps):
+            if mode == "graph":
+                outs.append(m.decode_step_graph(tok[:, T + s_]).clone())
+                junk = torch.randn(64, 64, device="cuda") @ torch.randn(64, 64, device="cuda")   # eager work between replays
+                torch.cuda.synchronize()
+            else:
+                outs.append(m.decode_step(tok[:, T + s_], hint=T + steps).clone())
+        results[mode] = torch.stack(outs)
+        assert int(m.lens[0]) == T + steps
+        m.close()
+    assert torch.equal(results["eager"], results["graph"])

@@ -76,15 +76,16 @@ class SyntheticDecoder:
         lo, hi = q[..., :half].float(), q[..., half:].float()
         return torch.cat([lo * c - hi * s, hi * c + lo * s], dim=-1).to(q.dtype)
 
-    def _forward(self, tokens, new: int):
+    def _forward(self, tokens, new: int, hint=None):
         """tokens: int64 [B][new]: the next `new` positions of every sequence.  Returns the logits of
-        the last of them, [B][vocab]."""
+        the last of them, [B][vocab].  hint: host bound on the lengths after this call (default: the
+        exact value the host has been counting)."""
         B, w = self.B, self.w
         start = self.lens.clone()
         new_lens = torch.full((B,), new, dtype=torch.int32, device=self.device)
         pos = (start.long()[:, None] + torch.arange(new, device=self.device)[None, :])
         kv_lens = start + new
-        n_after = self.n_host + new
+        n_after = self.n_host + new if hint is None else hint
         x = w["emb"][tokens]
         chunk = 16384                                                     # tokens per MLP slice (bounds the temporaries)
         for l in range(self.L):
@@ -106,12 +107,37 @@ class SyntheticDecoder:
             for i in range(0, B * new, chunk):
                 hs = h2[i:i + chunk]
                 xf[i:i + chunk] += (torch.nn.functional.silu(hs @ w[f"{l}.wg"].T) * (hs @ w[f"{l}.wu"].T)) @ w[f"{l}.wd"].T
-        self.lens = kv_lens
-        self.n_host = n_after
+        self.lens.copy_(kv_lens)          # in place: a captured graph keeps reading and advancing this tensor
+        self.n_host += new
         return self._rmsnorm(x[:, -1], w["final_norm"]) @ w["emb"].T
 
     def prefill(self, tokens):
         return self._forward(tokens, tokens.shape[1])
 
-    def decode_step(self, tokens):
-        return self._forward(tokens.view(self.B, 1), 1)
+    def decode_step(self, tokens, hint=None):
+        return self._forward(tokens.view(self.B, 1), 1, hint)
+
+    # ---- the decode step as one HIP graph ----------------------------------------------------------
+    def capture_decode(self):
+        """Records one decode step (about 20 launches per layer, each far shorter than the time the
+        host needs to issue it) into a HIP graph.  The graph reads its token from a fixed buffer,
+        reads and advances the device-side lengths, and sizes its launches for the full capacity."""
+        self._tok = torch.zeros(self.B, dtype=torch.int64, device=self.device)
+        keep_lens, keep_host = self.lens.clone(), self.n_host
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):                       # warm-up outside the capture (lazy set-up, allocator)
+            for _ in range(2):
+                self._forward(self._tok.view(self.B, 1), 1, hint=self.max_ctx)
+                self.lens.copy_(keep_lens)                  # the rows it wrote are overwritten by the real steps
+        torch.cuda.current_stream().wait_stream(side)
+        self._graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self._graph):
+            self._logits = self._forward(self._tok.view(self.B, 1), 1, hint=self.max_ctx)
+        self.n_host = keep_host
+
+    def decode_step_graph(self, tokens):
+        self._tok.copy_(tokens.view(self.B))
+        self._graph.replay()
+        self.n_host += 1
+        return self._logits
