@@ -214,6 +214,113 @@ __global__ __launch_bounds__(kThreads, 1) void project_append_kernel(ProjArgs a)
                 make_float4(acc[nb][4 * g4], acc[nb][4 * g4 + 1], acc[nb][4 * g4 + 2], acc[nb][4 * g4 + 3]);
 }
 
+// The prompt-sized launch (one split): work group = 256 tokens x TWO heads (2 d features), wave =
+// 64 tokens x one head, so that a weight operand read from LDS feeds two MFMAs and a token tile is
+// staged once per two heads: 0.75 LDS operand reads per MFMA instead of 1.25.
+template <typename M, int D>
+__global__ __launch_bounds__(kThreads, 1) void project_append_wide_kernel(ProjArgs a) {
+    using vec8 = typename M::vec8;
+    constexpr int NB = D / 32;
+    constexpr int kF = 2 * D;                            // features per work group
+    constexpr int NX = kTokens * (kKT / 8) / kThreads;   // x pieces per thread and tile
+    constexpr int NW = kF * (kKT / 8) / kThreads;        // weight pieces per thread and tile
+    constexpr int kStage = (kTokens + kF) * kStride;
+    __shared__ __attribute__((aligned(16))) char lds[2 * kStage];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int tg = wave & 3, hs = wave >> 2;             // token group of 64, head of the pair
+    const int c = lane & 31;
+    const int hh = lane >> 5;
+    const int hkv = a.slot.n_kv_heads;
+    const int64_t n_tok = (int64_t)a.batch * a.max_new;
+    const int64_t tok0 = (int64_t)blockIdx.y * kTokens;
+    const uint16_t *x = (const uint16_t *)a.x;
+    // feature row f of the work group: head 2 blockIdx.x + f / D of the list [K heads, V heads]
+    auto weight_row = [&](int f) {
+        const int kh = 2 * (int)blockIdx.x + f / D;
+        return (const uint16_t *)(kh >= hkv ? a.w_v : a.w_k) + ((int64_t)(kh % hkv) * D + f % D) * a.hidden;
+    };
+
+    struct Slot {
+        uint4 x[NX], w[NW];
+    };
+    Slot s0, s1; // two tiles in flight: with 128 accumulator registers a third does not fit
+    auto issue = [&](int kt, Slot &q) {
+#pragma unroll
+        for (int i = 0; i < NX; ++i) {
+            const int piece = tid + i * kThreads;
+            const int64_t row = tok0 + piece / (kKT / 8);
+            q.x[i] = make_uint4(0, 0, 0, 0);
+            if (row < n_tok) q.x[i] = *(const uint4 *)(x + row * a.hidden + kt * kKT + (piece % (kKT / 8)) * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            const int piece = tid + i * kThreads;
+            q.w[i] = *(const uint4 *)(weight_row(piece / (kKT / 8)) + kt * kKT + (piece % (kKT / 8)) * 8);
+        }
+    };
+    auto park = [&](int stage, const Slot &q) {
+        char *xs = lds + stage * kStage;
+        char *ws = xs + kTokens * kStride;
+#pragma unroll
+        for (int i = 0; i < NX; ++i) {
+            const int piece = tid + i * kThreads;
+            *(uint4 *)(xs + (piece / (kKT / 8)) * kStride + (piece % (kKT / 8)) * 16) = q.x[i];
+        }
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            const int piece = tid + i * kThreads;
+            *(uint4 *)(ws + (piece / (kKT / 8)) * kStride + (piece % (kKT / 8)) * 16) = q.w[i];
+        }
+    };
+
+    f32x16 acc[2][NB];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][i][r] = 0.f;
+
+    const int n_kt = a.hidden / kKT;
+    issue(0, s0);
+    if (1 < n_kt) issue(1, s1);
+    park(0, s0);
+    __syncthreads();
+    auto step = [&](int kt, Slot &mine, const Slot &next) {
+        const char *xs = lds + (kt & 1) * kStage + (64 * tg + c) * kStride + hh * 16;
+        const char *ws = lds + (kt & 1) * kStage + kTokens * kStride + (hs * D + c) * kStride + hh * 16;
+#pragma unroll
+        for (int st = 0; st < kKT / 16; ++st) {
+            const vec8 b0 = __builtin_bit_cast(vec8, *(const uint4 *)(xs + st * 32));
+            const vec8 b1 = __builtin_bit_cast(vec8, *(const uint4 *)(xs + 32 * kStride + st * 32));
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const vec8 wa = __builtin_bit_cast(vec8, *(const uint4 *)(ws + nb * 32 * kStride + st * 32));
+                acc[0][nb] = M::mfma(wa, b0, acc[0][nb]);
+                acc[1][nb] = M::mfma(wa, b1, acc[1][nb]);
+            }
+            if (st & 1) __builtin_amdgcn_sched_barrier(0); // two steps' operands in flight, not four
+        }
+        if (kt + 1 < n_kt) park((kt + 1) & 1, next);
+        __syncthreads();
+        if (kt + 2 < n_kt) issue(kt + 2, mine);
+    };
+    for (int base = 0; base < n_kt; base += 2) { // ring slots named explicitly: fixed registers
+        step(base, s0, s1);
+        if (base + 1 < n_kt) step(base + 1, s1, s0);
+    }
+
+    const int kh = 2 * (int)blockIdx.x + hs;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int64_t m = tok0 + 64 * tg + 32 * t + c;
+        if (m < n_tok) finish_token<M, D>(a, acc[t], m, kh % hkv, kh >= hkv, hh);
+    }
+}
+
 // Adds up the partial sums of the splits.  One thread per (token, K or V head, half hh, feature
 // block nb < NB/2, group g4): the four features 32 nb + 8 g4 + 4 hh .. + 3 of the head and their
 // rotary partners d/2 further on, i.e. what finish_token needs together.
@@ -273,10 +380,14 @@ template <typename M, int D> hipError_t launch_j(const ProjArgs &a, int n_splits
     const int64_t n_tok = (int64_t)a.batch * a.max_new;
     const int64_t tiles = (n_tok + kTokens - 1) / kTokens;
     if (tiles > 65535 || 2 * a.slot.n_kv_heads > 65535) return hipErrorInvalidValue;
+    if (n_splits == 1) {
+        project_append_wide_kernel<M, D><<<dim3((unsigned)a.slot.n_kv_heads, (unsigned)tiles), kThreads, 0, stream>>>(a);
+        return hipGetLastError();
+    }
     const dim3 grid((unsigned)(2 * a.slot.n_kv_heads), (unsigned)tiles, (unsigned)n_splits);
     project_append_kernel<M, D><<<grid, kThreads, 0, stream>>>(a);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || n_splits == 1) return e;
+    if (e != hipSuccess) return e;
     const int64_t threads = n_tok * 2 * a.slot.n_kv_heads * 2 * (D / 64) * 4;
     project_finish_kernel<M, D><<<dim3((unsigned)((threads + 255) / 256)), 256, 0, stream>>>(a, n_splits);
     return hipGetLastError();
