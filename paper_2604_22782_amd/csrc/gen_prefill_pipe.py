@@ -119,6 +119,12 @@ S_EXEC = 54                    # pair
 S_NK1 = 56
 S_SOFF, S_NKM63 = 57, 58       # scalar byte offset of the tile being requested; last needed key - 63
 
+S_PAR = 59                     # 8-wave shape: which of the two waves of its SIMD this wave is
+# 8-wave shape only: the two waves of a SIMD take turns, half step by half step, at being the
+# preferred one (MFMAs issued alternately by two waves of equal priority reach two thirds of the
+# matrix-core rate).  Off by default: measured, it does not change the time of this kernel.
+PRIO = os.environ.get("SKV_GEN_PRIO", "0") == "1" and NQ == 1
+
 FIRST_S, LAST_S = 40, 59
 
 
@@ -463,12 +469,26 @@ def rotate_addresses(A: Asm, vector=True):
         A.e(f"v_add_u32_e32 {vr(VA_CUR)}, {sr(S_ST_CUR)}, {vr(VL)}")
 
 
+def take_turns(A: Asm, h: int, name: str):
+    if not PRIO:
+        return
+    A.e(f"s_cmp_eq_u32 {sr(S_PAR)}, {h}")
+    A.e(f"s_cbranch_scc1 L_HI_{name}{h}_%=")
+    A.e("s_setprio 0")
+    A.e(f"s_branch L_PR_{name}{h}_%=")
+    A.e(f"L_HI_{name}{h}_%=:")
+    A.e("s_setprio 2")
+    A.e(f"L_PR_{name}{h}_%=:")
+
+
 def body(A: Asm, masked: bool, name: str):
     """Tile t for a computing wave: half steps u = 2t and 2t + 1."""
     A.reset_lds(pending_reads(0))
     rotate_addresses(A)
+    take_turns(A, 0, name)
     half_step(A, 0, qk=(KA_CUR, 1, SB), pv=(VA_PRV, 1, PB), sm=(SA, PA, masked),
               nxt=((KA_NXT, 0), (VA_CUR, 0)), extra=None, tagid=name + "0", publish=True)
+    take_turns(A, 1, name)
     half_step(A, 1, qk=(KA_NXT, 0, SA), pv=(VA_CUR, 0, PA), sm=(SB, PB, masked),
               nxt=((KA_NXT, 1), (VA_CUR, 1)), extra=staging_ops(name), tagid=name + "1")
     assert A.lds[-3 * PD:] == pending_reads(2), A.lds[-6:]
@@ -528,6 +548,9 @@ def generate(dt: str) -> list[str]:
     e(f"s_mov_b32 {sr(S_ONES)}, 0x{ones:08x}")
     e(f"s_xor_b32 {sr(S_NCS)}, %[cs], 0x80000000")
     e(f"s_mov_b32 {sr(S_NK1)}, %[nk1]")
+    if PRIO:
+        e(f"s_lshr_b32 {sr(S_PAR)}, %[wv], 2")     # waves w and w + 4 of the work group share a SIMD
+        e(f"s_and_b32 {sr(S_PAR)}, {sr(S_PAR)}, 1")
     e(f"v_and_b32_e32 {vr(LANE)}, 63, %[tid]")
     e(f"v_and_b32_e32 {vr(COL)}, 31, {vr(LANE)}")
     e(f"v_lshrrev_b32_e32 {vr(HH)}, 5, {vr(LANE)}")
