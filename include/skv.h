@@ -238,7 +238,9 @@ skv_status_t skv_train_sample_route(int32_t scheme, int32_t n_layers, int32_t k,
  * dtype SKV_BF16 or SKV_F16, head_dim 64 or 128 (else SKV_ERR_UNSUPPORTED); fp32 accumulation.
  * lse: device float [batch][n_q_heads][seq], receives log sum_j exp(scale <q_i, k_j>) (natural
  * log), which the backward needs.  seq_lens: device int32[batch], each in [1, seq]; rows at or
- * beyond a sequence's length are neither read nor written.  Asynchronous on `stream`. */
+ * beyond a sequence's length are neither read nor written.  Asynchronous on `stream`.
+ * The first training call of a process allocates the 256-byte fault word of these calls (see
+ * skv_train_device_faults); make it outside any stream capture. */
 skv_status_t skv_train_attn_fwd(const void *q, const void *k, const void *v, void *out, float *lse,
                                 const int32_t *seq_lens, int32_t batch, int32_t seq,
                                 int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
