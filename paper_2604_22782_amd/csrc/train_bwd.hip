@@ -162,11 +162,22 @@ __global__ __launch_bounds__(kKvThreads, 1) void dkdv_kernel(TrainBwdArgs a, int
     const int hkv = a.n_kv_heads, hq = a.n_q_heads;
     const int G = hq / hkv;
 
-    // heavy key tiles (the first ones: every later row reads them) first, for the whole launch
+    // block -> (sequence, kv head, key tile).  Work groups are dealt round-robin to the 8 XCDs, each
+    // with an L2 of its own: when the (sequence, kv head) pairs divide by 8, a pair's key tiles all
+    // go to one XCD, so the Q and dO rows they share are fetched into one L2; within a pair the heavy
+    // key tiles (the first ones: every later row reads them) come first.
     const int pairs = a.batch * hkv;
-    const int kt = blockIdx.x / pairs;
-    const int kvh = (blockIdx.x % pairs) % hkv;
-    const int b = (blockIdx.x % pairs) / hkv;
+    int pair, kt;
+    if (pairs % 8 == 0) {
+        const int k = blockIdx.x >> 3;
+        pair = (blockIdx.x & 7) + 8 * (k / n_kt);
+        kt = k % n_kt;
+    } else {
+        pair = blockIdx.x % pairs;
+        kt = blockIdx.x / pairs;
+    }
+    const int kvh = pair % hkv;
+    const int b = pair / hkv;
     const int n = a.seq_lens[b];
     if (n < 1 || n > a.seq) {
         if (tid == 0 && kt == 0 && kvh == 0) atomicOr(a.faults, (uint32_t)SKV_FAULT_KV_LEN);
@@ -378,12 +389,23 @@ __global__ __launch_bounds__(64 * W, 1) void dq_kernel(TrainBwdArgs a, int n_rt)
     const int hkv = a.n_kv_heads, hq = a.n_q_heads;
     const int G = hq / hkv;
 
-    // heavy (late) row tiles first, for the whole launch; the heads of a group are neighbours
-    const int pairs = a.batch * hq;
-    const int rt = n_rt - 1 - blockIdx.x / pairs;
-    const int head = (blockIdx.x % pairs) % hq;
-    const int b = (blockIdx.x % pairs) / hq;
-    const int kvh = head / G;
+    // block -> (sequence, head, row tile): as in dkdv_kernel, the G heads and all row tiles of one
+    // (sequence, kv head) pair go to one XCD when the pairs divide by 8 (they read the same K, V
+    // rows); heavy (late) row tiles first
+    const int pairs = a.batch * hkv;
+    int pair, rem;
+    if (pairs % 8 == 0) {
+        const int k = blockIdx.x >> 3;
+        pair = (blockIdx.x & 7) + 8 * (k / (G * n_rt));
+        rem = k % (G * n_rt);
+    } else {
+        pair = blockIdx.x % pairs;
+        rem = blockIdx.x / pairs;
+    }
+    const int rt = n_rt - 1 - rem / G;
+    const int kvh = pair % hkv;
+    const int head = kvh * G + rem % G;
+    const int b = pair / hkv;
     const int n = a.seq_lens[b];
     if (n < 1 || n > a.seq) return; // reported by dkdv_kernel
     const int q_begin = rt * kRows;
