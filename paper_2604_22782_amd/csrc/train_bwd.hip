@@ -162,22 +162,14 @@ __global__ __launch_bounds__(kKvThreads, 1) void dkdv_kernel(TrainBwdArgs a, int
     const int hkv = a.n_kv_heads, hq = a.n_q_heads;
     const int G = hq / hkv;
 
-    // block -> (sequence, kv head, key tile).  Work groups are dealt round-robin to the 8 XCDs, each
-    // with an L2 of its own: when the (sequence, kv head) pairs divide by 8, a pair's key tiles all
-    // go to one XCD, so the Q and dO rows they share are fetched into one L2; within a pair the heavy
-    // key tiles (the first ones: every later row reads them) come first.
+    // heavy key tiles (the first ones: every later row reads them) first, for the whole launch.
+    // (Sending all key tiles of a (sequence, kv head) pair to one XCD, as dq_kernel does with its row
+    // tiles, raises the HBM traffic here from 4.6 to 5.5-7.3 GiB per launch: the tiles of a pair run at
+    // different rows of Q and dO, more of them than one L2 holds.)
     const int pairs = a.batch * hkv;
-    int pair, kt;
-    if (pairs % 8 == 0) {
-        const int k = blockIdx.x >> 3;
-        pair = (blockIdx.x & 7) + 8 * (k / n_kt);
-        kt = k % n_kt;
-    } else {
-        pair = blockIdx.x % pairs;
-        kt = blockIdx.x / pairs;
-    }
-    const int kvh = pair % hkv;
-    const int b = pair / hkv;
+    const int kt = blockIdx.x / pairs;
+    const int kvh = (blockIdx.x % pairs) % hkv;
+    const int b = (blockIdx.x % pairs) / hkv;
     const int n = a.seq_lens[b];
     if (n < 1 || n > a.seq) {
         if (tid == 0 && kt == 0 && kvh == 0) atomicOr(a.faults, (uint32_t)SKV_FAULT_KV_LEN);
@@ -389,9 +381,10 @@ __global__ __launch_bounds__(64 * W, 1) void dq_kernel(TrainBwdArgs a, int n_rt)
     const int hkv = a.n_kv_heads, hq = a.n_q_heads;
     const int G = hq / hkv;
 
-    // block -> (sequence, head, row tile): as in dkdv_kernel, the G heads and all row tiles of one
-    // (sequence, kv head) pair go to one XCD when the pairs divide by 8 (they read the same K, V
-    // rows); heavy (late) row tiles first
+    // block -> (sequence, head, row tile).  Work groups are dealt round-robin to the 8 XCDs, each with
+    // an L2 of its own: when the (sequence, kv head) pairs divide by 8, the G heads and all row tiles
+    // of a pair go to one XCD (they read the same K, V rows: HBM traffic 5.3 -> 0.8 GiB per launch);
+    // heavy (late) row tiles first
     const int pairs = a.batch * hkv;
     int pair, rem;
     if (pairs % 8 == 0) {
