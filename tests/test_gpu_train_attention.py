@@ -171,3 +171,18 @@ def test_full_size_pass_layer_on_a_sampled_slice():
             print(f"{name}: max |err| {err:.3e}, max |want| {np.abs(want).max():.3e}", flush=True)
             assert err <= _grad_tol("bf16", want), name
         assert not dk[b, n:].any() and not dv[b, n:].any()
+
+
+def test_forward_log_sum_exp_from_the_eight_wave_shape(monkeypatch):
+    """The pipelined kernel's other shape (8 waves of 32 rows) writes the same log-sum-exp."""
+    monkeypatch.setenv("SKV_PREFILL_WAVES", "8")
+    B, S, Hq, Hkv, D = 2, 333, 4, 2, 128
+    qs, ks, vs, _ = _inputs("bf16", B, S, Hq, Hkv, D, seed=8)
+    lens = [333, 97]
+    out, lse = _run_fwd(qs[0], ks[0], vs[0], torch.tensor(lens, dtype=torch.int32, device="cuda"), 0.09)
+    assert skv.skv_last_kernel_name() == "prefill_pipe_kernel"
+    want_o, want_l = T.attn_fwd(gen.to_f64(qs[0]), gen.to_f64(ks[0]), gen.to_f64(vs[0]), 0.09, lens)
+    for b, n in enumerate(lens):
+        assert np.abs(gen.to_f64(out)[b, :n] - want_o[b, :n]).max() <= H.TOL["bf16"]
+        assert np.abs(lse.cpu().double().numpy()[b, :, :n] - want_l[b, :, :n]).max() <= 2e-3
+        assert (lse.cpu().numpy()[b, :, n:] == 7.0).all()
