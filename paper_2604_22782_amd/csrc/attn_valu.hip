@@ -229,15 +229,18 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void attn_valu_kernel(AttnArgs
 }
 
 // Split merge: out = sum_s o_s 2^(m_s - m) / sum_s l_s 2^(m_s - m), m = max_s m_s, over the
-// splits that hold at least one key of the row.  One thread per (row, head, 4 output elements).
+// splits that hold at least one key of the row.  One work group per (row, head): D / 4 lanes cover
+// the output, the 256 / (D / 4) lane groups share the splits (a sequence of 32768 keys has up to
+// 128 of them: one thread walking them all made this launch as long as the attention launch of a
+// single sequence) and add up through LDS.
 template <typename T>
 __global__ __launch_bounds__(256) void split_merge_kernel(AttnArgs a, int D) {
-    const int quads = D / 4;
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t total = (int64_t)a.batch * a.n_q_heads * quads;
-    if (t >= total) return;
-    const int qd = (int)(t % quads);
-    const int64_t rh = t / quads; // row * n_q_heads + head   (decode: row = sequence)
+    __shared__ float s_m[16], s_l[16];
+    __shared__ __attribute__((aligned(16))) float s_o[1024];
+    const int quads = D / 4;            // 16, 32 or 64 lanes per group
+    const int ng = 256 / quads;         // 16, 8 or 4 groups
+    const int qd = threadIdx.x % quads, sg = threadIdx.x / quads;
+    const int64_t rh = blockIdx.x;      // row * n_q_heads + head   (decode: row = sequence)
     const int b = (int)(rh / a.n_q_heads);
     const int kv_end = a.kv_lens[b];
     if (kv_end < 1 || kv_end > a.max_kv_len) return; // the attention kernel wrote zeros
@@ -245,13 +248,26 @@ __global__ __launch_bounds__(256) void split_merge_kernel(AttnArgs a, int D) {
     if (ns == 1) return; // the attention kernel already wrote the final result
     const float *ml = a.part_ml + rh * a.n_splits * 2;
     float m = -INFINITY;
-    for (int s = 0; s < ns; ++s) m = fmaxf(m, ml[2 * s]);
+    for (int s = sg; s < ns; s += ng) m = fmaxf(m, ml[2 * s]);
+    if (qd == 0) s_m[sg] = m;
+    __syncthreads();
+    m = s_m[0];
+    for (int g = 1; g < ng; ++g) m = fmaxf(m, s_m[g]);
     float l = 0.f, o[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < ns; ++s) {
+    for (int s = sg; s < ns; s += ng) {
         const float w = exp2f(ml[2 * s] - m);
         l += ml[2 * s + 1] * w;
         const float4 p = *(const float4 *)(a.part_o + (rh * a.n_splits + s) * D + qd * 4);
         o[0] += p.x * w; o[1] += p.y * w; o[2] += p.z * w; o[3] += p.w * w;
+    }
+    if (qd == 0) s_l[sg] = l;
+    *(float4 *)(s_o + sg * D + qd * 4) = make_float4(o[0], o[1], o[2], o[3]);
+    __syncthreads();
+    if (sg != 0) return;
+    for (int g = 1; g < ng; ++g) { // fixed order: the result does not depend on timing
+        l += s_l[g];
+        const float4 p = *(const float4 *)(s_o + g * D + qd * 4);
+        o[0] += p.x; o[1] += p.y; o[2] += p.z; o[3] += p.w;
     }
     const float inv = 1.f / l;
     typename T::storage *dst = (typename T::storage *)a.out + rh * D + qd * 4;
@@ -305,8 +321,9 @@ hipError_t launch_attn_valu(const AttnArgs &a, int dtype, int head_dim, int grou
 
 hipError_t launch_split_merge(const AttnArgs &a, int dtype, hipStream_t stream) {
     const int D = a.cache.head_dim;
-    const int64_t total = (int64_t)a.batch * a.n_q_heads * (D / 4);
-    const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    const int64_t total = (int64_t)a.batch * a.max_q * a.n_q_heads; // one work group per (row, head)
+    if (total > 0x7fffffff || !(D == 64 || D == 128 || D == 256)) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)total), block(256);
     switch (dtype) {
     case SKV_F32: split_merge_kernel<F32><<<grid, block, 0, stream>>>(a, D); break;
     case SKV_F16: split_merge_kernel<F16><<<grid, block, 0, stream>>>(a, D); break;
