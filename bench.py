@@ -537,10 +537,17 @@ def main():
         line["cross_layer_reuse"] = dec["cross_layer_reuse"]
     if not args.skip_prefill:
         line["prefill"] = run_prefill(args, torch, skv, H, configs)
-    if not args.skip_project:
-        line["project_append"] = run_project(args, torch, skv, H, configs)
-    if not args.skip_train:
-        line["train"] = run_train(args, torch, skv, configs)
+    # the two widenings of the path are reported beside the metric, never instead of it
+    for key, skip, run in (("project_append", args.skip_project, lambda: run_project(args, torch, skv, H, configs)),
+                           ("train", args.skip_train, lambda: run_train(args, torch, skv, configs))):
+        if skip:
+            continue
+        try:
+            line[key] = run()
+        except Exception as e:  # noqa: BLE001 - the headline line must still be printed
+            log(f"[bench] {key} leg failed: {e!r}")
+            line[key] = {"error": repr(e)}
+            torch.cuda.empty_cache()
     if not args.skip_cpu_baseline:
         log("[bench] timing the CPU oracle on a bounded sample ...")
         line["cpu_baseline"] = cpu_baseline_decode(w)
