@@ -81,8 +81,8 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
     using vec8 = typename M::vec8;
     constexpr int NL = Ge::NL, LPR = Ge::LPR, RPL = Ge::RPL;
     __shared__ __attribute__((aligned(16))) char lds[kWaves * Ge::WAVE_BYTES];
-    __shared__ int s_item;
-    extern __shared__ int s_prefix[]; // persistent mode: batch + 1 running split counts
+    __shared__ int s_item, s_n_rem;
+    extern __shared__ int s_prefix[]; // persistent mode: batch + 1 running counts of full splits, then batch uint16
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform on purpose (scalar loads below)
@@ -332,37 +332,74 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
     // Persistent mode: when the sequences have very different lengths, a (split, head, sequence) grid
     // is mostly work groups with nothing to do, each costing a slot and a memory round trip under
     // load.  Instead a fixed number of work groups (two per compute unit) pull items from a counter.
-    // prefix[b] = number of splits of the sequences before b (a sequence with an impossible length
-    // counts one item, which zero-fills its output and raises the fault word).
+    // Order of the items: first every FULL split of every sequence (all keys_per_split long), then
+    // the last, partial split of each sequence, the longest first.  The launch ends when the last
+    // item ends, and with short items last the work groups finish close together (items in sequence
+    // order left the tail to chance: half an item per work group, 8 % of a launch of six items each).
+    // prefix[b] = number of full splits of the sequences before b; order[r] = sequence of the r-th
+    // partial split (a sequence with an impossible length has one, of size 0, which zero-fills its
+    // output and raises the fault word).
+    const int kps = a.keys_per_split;
+    unsigned short *s_order = (unsigned short *)(s_prefix + a.batch + 1);
+    int *s_rem = (int *)lds;                 // set-up scratch in the tile area: partial size, -1 = none
+    int *s_tmp = s_rem + a.batch;
     if (wave == 0) {
         const int per = (a.batch + 63) / 64;
-        int cnt = 0;
+        int cnt_full = 0, cnt_rem = 0;
         for (int i = 0; i < per; ++i) {
             const int bb = lane * per + i;
             if (bb < a.batch) {
                 const int len = a.kv_lens[bb];
-                cnt += (len < 1 || len > a.max_kv_len) ? 1 : (len + a.keys_per_split - 1) / a.keys_per_split;
+                const bool valid = len >= 1 && len <= a.max_kv_len;
+                const int rem = valid ? len % kps : 0;
+                const bool has = !valid || rem > 0;
+                cnt_full += valid ? len / kps : 0;
+                cnt_rem += has;
+                s_rem[bb] = has ? rem : -1;
             }
         }
-        int incl = cnt;
+        int incl_f = cnt_full, incl_r = cnt_rem;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
-            const int up = __shfl_up(incl, d, 64);
-            if (lane >= d) incl += up;
+            const int uf = __shfl_up(incl_f, d, 64), ur = __shfl_up(incl_r, d, 64);
+            if (lane >= d) {
+                incl_f += uf;
+                incl_r += ur;
+            }
         }
-        int run = incl - cnt;
+        int run_f = incl_f - cnt_full, run_r = incl_r - cnt_rem;
         if (lane == 0) s_prefix[0] = 0;
+        if (lane == 63) s_n_rem = incl_r;
         for (int i = 0; i < per; ++i) {
             const int bb = lane * per + i;
             if (bb < a.batch) {
                 const int len = a.kv_lens[bb];
-                run += (len < 1 || len > a.max_kv_len) ? 1 : (len + a.keys_per_split - 1) / a.keys_per_split;
-                s_prefix[bb + 1] = run;
+                run_f += (len >= 1 && len <= a.max_kv_len) ? len / kps : 0;
+                s_prefix[bb + 1] = run_f;
+                if (s_rem[bb] >= 0) s_order[run_r++] = (unsigned short)bb;
             }
         }
     }
     __syncthreads();
-    const int total = s_prefix[a.batch] * hkv;
+    const int n_rem = s_n_rem;
+    if (a.batch <= (int)blockDim.x) { // rank by counting: one partial split per thread
+        int rank = -1, mine = 0;
+        if ((int)threadIdx.x < n_rem) {
+            mine = s_order[threadIdx.x];
+            const int r = s_rem[mine];
+            rank = 0;
+            for (int u = 0; u < n_rem; ++u) {
+                const int other = s_order[u], ro = s_rem[other];
+                rank += (ro > r) || (ro == r && other < mine);
+            }
+            s_tmp[rank] = mine;
+        }
+        __syncthreads();
+        if ((int)threadIdx.x < n_rem) s_order[threadIdx.x] = (unsigned short)s_tmp[threadIdx.x];
+        __syncthreads();
+    }
+    const int total_full = s_prefix[a.batch];
+    const int total = (total_full + n_rem) * hkv;
     int32_t *counter = a.work_counters, *done = a.work_counters + 1;
     int next = blockIdx.x; // the first item needs no ticket; tickets count on from the grid size
     for (;;) {
@@ -376,15 +413,24 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
             next = (int)gridDim.x + __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const int kvh = item % hkv;
         const int j = item / hkv;
-        int lo = 0, hi = a.batch; // largest b with prefix[b] <= j
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (s_prefix[mid] <= j) lo = mid;
-            else hi = mid;
+        int seq, split;
+        if (j < total_full) {
+            int lo = 0, hi = a.batch; // largest b with prefix[b] <= j
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (s_prefix[mid] <= j) lo = mid;
+                else hi = mid;
+            }
+            seq = lo;
+            split = j - s_prefix[lo];
+        } else {
+            seq = s_order[j - total_full];
+            const int len = a.kv_lens[seq];
+            split = (len >= 1 && len <= a.max_kv_len) ? len / kps : 0; // the partial split is the last one
         }
         // all lanes hold the same values; say so to the compiler (scalar registers, scalar loads)
-        process_item(__builtin_amdgcn_readfirstlane(lo), __builtin_amdgcn_readfirstlane(kvh),
-                     __builtin_amdgcn_readfirstlane(j - s_prefix[lo]));
+        process_item(__builtin_amdgcn_readfirstlane(seq), __builtin_amdgcn_readfirstlane(kvh),
+                     __builtin_amdgcn_readfirstlane(split));
     }
     // The last work group to leave puts the counters back to rest for the next launch.
     if (threadIdx.x == 0) {
@@ -409,8 +455,8 @@ hipError_t launch_d(const AttnArgs &a, int group, hipStream_t stream) {
     // could hold many empty splits (more than two splits per sequence); a batch too large for the
     // split-count table in LDS, or a launch with few items, uses the plain grid.
     const int64_t max_items = (int64_t)a.n_splits * a.cache.n_kv_heads * a.batch;
-    if (a.n_splits > 2 && a.batch <= 2048 && a.work_counters != nullptr && max_items > 2 * n_cu) {
-        const size_t dyn = sizeof(int) * (size_t)(a.batch + 1);
+    if (a.n_splits > 2 && a.batch <= 1024 && a.work_counters != nullptr && max_items > 2 * n_cu) {
+        const size_t dyn = sizeof(int) * (size_t)(a.batch + 1) + sizeof(unsigned short) * (size_t)a.batch;
         decode_mfma_kernel<M, D, 4><<<dim3(2 * n_cu), 256, dyn, stream>>>(a, group, 1);
     } else {
         const dim3 grid((unsigned)a.n_splits, (unsigned)a.cache.n_kv_heads, (unsigned)a.batch);
