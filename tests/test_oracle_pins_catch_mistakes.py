@@ -1,0 +1,94 @@
+"""The pins of the two newer oracles must fail when a plausible mistake is planted in the oracle:
+each case edits one line of the oracle's source (a dropped term, a sign, a transposition, a wrong
+index), loads the edited copy as a module and runs the pin tests against it.  Everything here is
+CPU-only and touches no GPU code."""
+import importlib.util
+import os
+import sys
+import types
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _mutant(name, old, new):
+    path = os.path.join(ROOT, "oracle", name + ".py")
+    src = open(path).read()
+    assert src.count(old) == 1, (name, old)          # the edit must hit exactly one place
+    mod = types.ModuleType(f"oracle.{name}_mutant")
+    mod.__package__ = "oracle"
+    mod.__file__ = path
+    exec(compile(src.replace(old, new), path, "exec"), mod.__dict__)
+    return mod
+
+
+def _pins_fail(test_module, attr, mutant, tests, monkeypatch):
+    monkeypatch.setattr(test_module, attr, mutant)
+    failed = []
+    for t in tests:
+        try:
+            t()
+        except Exception:                             # AssertionError, or an error the mistake provokes
+            failed.append(t.__name__)
+    return failed
+
+
+TRAIN_MISTAKES = [
+    ("0xBF58476D1CE4E5B9", "0xBF58476D1CE4E5B7"),                                  # a digit of the generator
+    ("< p else 0", "> p else 0"),                                                    # decision inverted
+    ("route.append(((draw(seed, step, l, 1) >> 32) * l) >> 32)",
+     "route.append(((draw(seed, step, l, 1) >> 32) * (l + 1)) >> 32)"),              # source may be the layer itself
+    ("route.append(l if bernoulli(seed, step, l, p) else k * (l // k))",
+     "route.append(k * (l // k) if bernoulli(seed, step, l, p) else l)"),            # RD-CLA coin swapped
+    ("route.append(k * (l // k))\n        elif scheme == RDCLA_K", "route.append(k * (l // k) + k - 1)\n        elif scheme == RDCLA_K"),  # last layer of the group
+    ("lse[b, h, :n] = (m + np.log(z))[:, 0]", "lse[b, h, :n] = np.log(z)[:, 0]"),  # maximum dropped
+    ("out[b, :n, h] = (e / z) @ v[b, :n, h // G]", "out[b, :n, h] = (e / z) @ v[b, :n, h % (Hq // G)]"),   # wrong kv head
+    ("dv[b, :n, g] += p.T @ do", "dv[b, :n, g] = p.T @ do"),                         # heads of a group not added
+    ("ds = p * (dp - (p * dp).sum(axis=1, keepdims=True))", "ds = p * dp"),          # softmax Jacobian: term dropped
+    ("dq[b, :n, h] = scale * (ds @ k[b, :n, g])", "dq[b, :n, h] = ds @ k[b, :n, g]"),   # scale dropped
+    ("dk[b, :n, g] += scale * (ds.T @ q[b, :n, h])", "dk[b, :n, g] += -scale * (ds.T @ q[b, :n, h])"),  # sign
+    ("dp = do @ v[b, :n, g].T", "dp = do @ k[b, :n, g].T"),                           # wrong operand
+    ("dks[src] += dk", "dks[l] += dk"),                                               # gradient sent to the reader
+]
+
+
+@pytest.mark.parametrize("old,new", TRAIN_MISTAKES)
+def test_training_oracle_pins_catch(old, new, monkeypatch):
+    from tests import test_rcla_train_oracle_pins as pins
+    tests = [pins.test_mix_reproduces_the_published_splitmix64_sequence, pins.test_rcla_sampling_rule_of_sec_3_2,
+             pins.test_ablation_schemes_of_sec_4_2_3, pins.test_forward_closed_forms,
+             lambda: pins.test_backward_against_finite_differences_of_the_forward(None),
+             lambda: pins.test_backward_against_finite_differences_of_the_forward([5, 3]),
+             pins.test_backward_invariants, pins.test_layer_stack_accumulates_the_gradients_of_all_readers]
+    for t in tests:
+        if not hasattr(t, "__name__") or t.__name__ == "<lambda>":
+            t.__name__ = "finite_differences"
+    assert _pins_fail(pins, "T", _mutant("rcla_train_oracle", old, new), tests, monkeypatch), (old, new)
+
+
+PROJECT_MISTAKES = [
+    ('k = np.einsum("bth,fh->btf", x, w_k)', 'k = np.einsum("bth,hf->btf", x, w_k)'),   # weights transposed
+    ('v = np.einsum("bth,fh->btf", x, w_v)', 'v = np.einsum("bth,fh->btf", x, w_k)'),   # V from the K weights
+    ("k[..., :half] = lo * c - hi * s", "k[..., :half] = lo * c + hi * s"),             # rotation sign
+    ("k[..., half:] = hi * c + lo * s", "k[..., half:] = hi * c"),                      # term dropped
+    ("c = rope_cos[positions][:, :, None, :]", "c = rope_cos[positions * 0][:, :, None, :]"),   # position ignored
+    ("lo, hi = k[..., :half].copy(), k[..., half:].copy()", "lo, hi = k[..., 0::2].copy(), k[..., 1::2].copy()"),  # interleaved pairs
+]
+
+
+@pytest.mark.parametrize("old,new", PROJECT_MISTAKES)
+def test_projection_oracle_pins_catch(old, new, monkeypatch):
+    from tests import test_project_oracle_pins as pins
+    tests = [pins.test_identity_weights_and_linearity, pins.test_rotation_properties]
+    assert _pins_fail(pins, "P", _mutant("project_oracle", old, new), tests, monkeypatch), (old, new)
+
+
+def test_the_unedited_oracles_pass_through_the_same_harness(monkeypatch):
+    from tests import test_project_oracle_pins as pp
+    from tests import test_rcla_train_oracle_pins as tp
+    same_t = _mutant("rcla_train_oracle", "RCLA, CLA_K, RDCLA_K = 0, 1, 2", "RCLA, CLA_K, RDCLA_K = 0, 1, 2")
+    same_p = _mutant("project_oracle", "half = head_dim // 2", "half = head_dim // 2")
+    assert _pins_fail(tp, "T", same_t, [tp.test_forward_closed_forms, tp.test_backward_invariants,
+                                        tp.test_ablation_schemes_of_sec_4_2_3], monkeypatch) == []
+    assert _pins_fail(pp, "P", same_p, [pp.test_identity_weights_and_linearity, pp.test_rotation_properties], monkeypatch) == []
