@@ -72,6 +72,12 @@ template <int D> struct Chunked {
     static constexpr int BLOCK32 = 8 * CH;  // 32 rows
     static constexpr int TILE = 16 * CH;    // 64 rows
     __device__ static int piece(int r, int p) { return (r >> 2) * CH + 64 * p + 16 * (r & 3); }
+    // Staging order: 16 consecutive threads take 4 rows x 4 consecutive pieces of a chunk.  Their
+    // 16-byte LDS stores then fall into 16 different bank groups (pieces of one row lie 64 bytes
+    // apart: a thread per piece of one row would hit every bank four times), and each quad of
+    // threads still loads 64 contiguous bytes of one row from memory.  q-th piece -> (row, piece)
+    __device__ static int staged_row(int q) { return 4 * (q / (4 * (D / 8))) + ((q & 15) >> 2); }
+    __device__ static int staged_piece(int q) { return 4 * ((q % (4 * (D / 8))) >> 4) + (q & 3); }
     // lane part of a row-wise read of row c of a 32-row block: pieces 2 s + hh (+ 128 s per step)
     __device__ static int row_lane(int c, int hh) { return (c >> 2) * CH + 16 * (c & 3) + 64 * hh; }
     // lane part of a transposing read: rows 4 hh + sl / 4 of a 16-row step (+ 4 CH per step, + 2 CH
@@ -185,7 +191,7 @@ __global__ __launch_bounds__(kKvThreads, 1) void dkdv_kernel(TrainBwdArgs a, int
 #pragma unroll
         for (int i = 0; i < NKV; ++i) {
             const int piece = tid + i * kKvThreads;
-            const int r = piece / LPR, p = piece % LPR;
+            const int r = C::staged_row(piece), p = C::staged_piece(piece);
             uint4 rk = make_uint4(0, 0, 0, 0), rv = rk;
             if (k0 + r < n) {
                 const int64_t off = (((int64_t)b * a.seq + k0 + r) * hkv + kvh) * D + p * 8;
@@ -210,10 +216,10 @@ __global__ __launch_bounds__(kKvThreads, 1) void dkdv_kernel(TrainBwdArgs a, int
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int piece = tid + i * kKvThreads;
-            const int row = r_first + piece / LPR;
+            const int row = r_first + C::staged_row(piece);
             qr[i] = gr[i] = make_uint4(0, 0, 0, 0);
             if (row < n) {
-                const int64_t off = (((int64_t)b * a.seq + row) * hq + head) * D + (piece % LPR) * 8;
+                const int64_t off = (((int64_t)b * a.seq + row) * hq + head) * D + C::staged_piece(piece) * 8;
                 qr[i] = *(const uint4 *)((const uint16_t *)a.q + off);
                 gr[i] = *(const uint4 *)((const uint16_t *)a.d_out + off);
             }
@@ -234,7 +240,7 @@ __global__ __launch_bounds__(kKvThreads, 1) void dkdv_kernel(TrainBwdArgs a, int
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int piece = tid + i * kKvThreads;
-            const int off = C::piece(piece / LPR, piece % LPR);
+            const int off = C::piece(C::staged_row(piece), C::staged_piece(piece));
             *(uint4 *)(qs + off) = qr[i];
             *(uint4 *)(gs + off) = gr[i];
         }
@@ -439,10 +445,10 @@ __global__ __launch_bounds__(64 * W, 1) void dq_kernel(TrainBwdArgs a, int n_rt)
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int piece = tid + i * NT;
-            const int key = t * kTile + piece / LPR;
+            const int key = t * kTile + C::staged_row(piece);
             kr[i] = vr[i] = make_uint4(0, 0, 0, 0);
             if (key < n_keys) {
-                const int64_t off = (((int64_t)b * a.seq + key) * hkv + kvh) * D + (piece % LPR) * 8;
+                const int64_t off = (((int64_t)b * a.seq + key) * hkv + kvh) * D + C::staged_piece(piece) * 8;
                 kr[i] = *(const uint4 *)((const uint16_t *)a.k + off);
                 vr[i] = *(const uint4 *)((const uint16_t *)a.v + off);
             }
@@ -454,7 +460,7 @@ __global__ __launch_bounds__(64 * W, 1) void dq_kernel(TrainBwdArgs a, int n_rt)
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int piece = tid + i * NT;
-            const int off = C::piece(piece / LPR, piece % LPR);
+            const int off = C::piece(C::staged_row(piece), C::staged_piece(piece));
             *(uint4 *)(ks + off) = kr[i];
             *(uint4 *)(vs + off) = vr[i];
         }
