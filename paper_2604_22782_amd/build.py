@@ -38,9 +38,10 @@ def build_library(verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
     # the instruction streams of the pipelined pre-fill kernel (one per wave shape) are written by a generator
     for nq in (1, 2):
-        subprocess.check_call([sys.executable, os.path.join(CSRC, "gen_prefill_pipe.py"),
-                               os.path.join(OBJ, f"prefill_pipe_body_nq{nq}.inc")],
-                              env={**os.environ, "SKV_GEN_NQ": str(nq)})
+        for paged in (0, 1):
+            subprocess.check_call([sys.executable, os.path.join(CSRC, "gen_prefill_pipe.py"),
+                                   os.path.join(OBJ, f"prefill_pipe_body_nq{nq}{'_paged' if paged else ''}.inc")],
+                                  env={**os.environ, "SKV_GEN_NQ": str(nq), "SKV_GEN_PAGED": str(paged)})
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
     with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
         objs = list(ex.map(_compile, srcs))

@@ -56,6 +56,11 @@ LDS_BYTES = N_STAGE * STAGE
 # registers per lane, so the second wave can issue while the first waits.
 NQ = int(os.environ.get("SKV_GEN_NQ", "2"))
 assert NQ in (1, 2)
+# PAGED = K/V rows are found through a block table (blocks of 2^shift >= 16 positions).  The 16 (or,
+# with 8 waves, 8) rows a wave stages per tile lie inside one block, so a wave needs ONE block id
+# per tile; it is loaded one tile ahead with a vector load (the same counter as the tile loads,
+# which complete in order) and moved to a scalar register.
+PAGED = os.environ.get("SKV_GEN_PAGED", "0") == "1"
 WAVES = 8 // NQ                       # waves per work group (256 query rows)
 THREADS = 64 * WAVES
 CPW = 16 // WAVES                     # 1 KiB chunks per wave, tile and tensor
@@ -89,6 +94,7 @@ ROWB, PIECE = _alloc(), _alloc()       # staging: first row of this lane in a ti
 VOFF = tuple(_alloc() for _ in range(CPW))   # byte offsets of this lane's rows of the tile being fetched
 VBO = tuple(_alloc() for _ in range(CPW))    # ... in tile 0 (constants)
 LIMV = _alloc()                        # byte offset of the lane's piece in the last needed row
+V_BLK, V_TOFF, V_T, V_L4 = _alloc(), _alloc(), _alloc(), _alloc()   # paged: block id, table offset, temp, lane % 4
 NEG_INF = _alloc()
 STG = _alloc()
 Q_OFF, O_OFF, ROW = _per_q(), _per_q(), _per_q()
@@ -119,13 +125,16 @@ S_EXEC = 54                    # pair
 S_NK1 = 56
 S_SOFF, S_NKM63 = 57, 58       # scalar byte offset of the tile being requested; last needed key - 63
 
+TBL = 1 if PAGED else 0         # extra loads per tile in the queue of the tile loads (the block id)
 S_PAR = 59                     # 8-wave shape: which of the two waves of its SIMD this wave is
 # 8-wave shape only: the two waves of a SIMD take turns, half step by half step, at being the
 # preferred one (MFMAs issued alternately by two waves of equal priority reach two thirds of the
 # matrix-core rate).  Off by default: measured, it does not change the time of this kernel.
 PRIO = os.environ.get("SKV_GEN_PRIO", "0") == "1" and NQ == 1
 
-FIRST_S, LAST_S = 40, 59
+S_BLK, S_R0, S_R0W, S_LASTIDX, S_T2 = 60, 61, 62, 63, 64   # paged: block id, first row of the wave's part, ...
+
+FIRST_S, LAST_S = 40, 64 if PAGED else 59
 
 
 class Asm:
@@ -373,7 +382,7 @@ def half_step(A: Asm, hs: int, qk, pv, sm, nxt, extra, tagid: str, cold=False, p
                 # every operand of this half step has been requested: wait for the last one (reads
                 # return in order), for this wave's loads of the tile after next, then meet the others
                 A.wait_lds(("Vh", hs, 7))
-                A.e(f"s_waitcnt vmcnt({2 * CPW})")  # all but the newest loads (the tile requested last) landed
+                A.e(f"s_waitcnt vmcnt({2 * CPW + TBL})")  # all but the newest loads (the tile requested last) landed
                 A.e("s_barrier")
             if g + PD < 8:
                 fetch(hs, g + PD, kcfg, vcfg)
@@ -414,13 +423,59 @@ def pending_reads(hs, with_k=True, with_v=True):
 def clamped_offsets():
     """Byte offsets of the lane's four rows of the tile whose first row is at byte S_SOFF, rows
     past the last needed key repeating it (finite, and masked wherever they are not the real
-    key); the scalar offset then is zero."""
+    key); the scalar offset then is zero.  Paged: S_SOFF is the byte offset of the wave's first row
+    (S_R0 its position), and a row is past the end by position, not by offset."""
     o = []
     for i in range(CPW):
-        o.append(f"v_add_u32_e32 {vr(VOFF[i])}, {sr(S_SOFF)}, {vr(VBO[i])}")
-        o.append(f"v_min_u32_e32 {vr(VOFF[i])}, {vr(LIMV)}, {vr(VOFF[i])}")
+        if PAGED:
+            o.append(f"s_add_u32 {sr(S_T2)}, {sr(S_R0)}, {4 * i}")
+            o.append(f"v_add_u32_e32 {vr(V_T)}, {sr(S_T2)}, {vr(V_L4)}")
+            o.append(f"v_cmp_lt_u32_e32 vcc, {sr(S_NK1)}, {vr(V_T)}")
+            o.append(f"v_add_u32_e32 {vr(VOFF[i])}, {sr(S_SOFF)}, {vr(VBO[i])}")
+            o.append(f"v_cndmask_b32_e32 {vr(VOFF[i])}, {vr(VOFF[i])}, {vr(LIMV)}, vcc")
+        else:
+            o.append(f"v_add_u32_e32 {vr(VOFF[i])}, {sr(S_SOFF)}, {vr(VBO[i])}")
+            o.append(f"v_min_u32_e32 {vr(VOFF[i])}, {vr(LIMV)}, {vr(VOFF[i])}")
     o.append(f"s_mov_b32 {sr(S_SOFF)}, 0")
     return o
+
+
+def paged_tile_offset(tagid: str):
+    """Paged: S_J0 = first position of the tile.  The block id of the wave's part of it has landed in
+    V_BLK; S_SOFF = byte offset of the wave's first row.  Then the id of the next tile is requested."""
+    return [f"s_waitcnt vmcnt({2 * CPW})",                       # the id was requested before the previous tile's loads
+            f"v_readfirstlane_b32 {sr(S_BLK)}, {vr(V_BLK)}",
+            f"s_cmp_lt_u32 {sr(S_BLK)}, %[nblk]",
+            f"s_cbranch_scc0 L_BADBLK_{tagid}_%=\nL_BADRET_{tagid}_%=:",
+            f"s_add_u32 {sr(S_R0)}, {sr(S_J0)}, {sr(S_R0W)}",
+            f"s_and_b32 {sr(S_T2)}, {sr(S_R0)}, %[bsm1]",
+            f"s_lshl_b32 {sr(S_SOFF)}, {sr(S_BLK)}, %[shift]",
+            f"s_add_u32 {sr(S_SOFF)}, {sr(S_SOFF)}, {sr(S_T2)}",
+            f"s_mul_i32 {sr(S_SOFF)}, {sr(S_SOFF)}, %[krb]"] + paged_request_id(64)
+
+
+def paged_request_id(ahead: int):
+    """Requests the block id of the wave's part of the tile `ahead` positions after S_R0's tile (the
+    table index is clamped to the last block the work group needs: tiles past the end repeat it)."""
+    return [f"s_add_u32 {sr(S_T2)}, {sr(S_R0)}, {ahead}",
+            f"s_lshr_b32 {sr(S_T2)}, {sr(S_T2)}, %[shift]",
+            f"s_min_u32 {sr(S_T2)}, {sr(S_T2)}, {sr(S_LASTIDX)}",
+            f"s_lshl_b32 {sr(S_T2)}, {sr(S_T2)}, 2",
+            f"v_mov_b32_e32 {vr(V_TOFF)}, {sr(S_T2)}",
+            f"global_load_dword {vr(V_BLK)}, {vr(V_TOFF)}, %[tbl]"]
+
+
+def bad_block_paths(A: Asm, tags):
+    """Out of line: a block id outside the pool raises the fault word; the rows are read as zeros
+    (an offset past the end of the buffer descriptor)."""
+    for tagid in tags:
+        A.e(f"L_BADBLK_{tagid}_%=:")
+        A.e(f"v_mov_b32_e32 {vr(V_T)}, 2")                        # SKV_FAULT_BLOCK_ID
+        A.e(f"v_mov_b32_e32 {vr(V_TOFF)}, 0")
+        A.e(f"global_atomic_or {vr(V_TOFF)}, {vr(V_T)}, %[flt]")
+        A.e("s_waitcnt vmcnt(0)")                                   # keeps the in-order accounting of the loads simple
+        A.e(f"s_mov_b32 {sr(S_BLK)}, %[nblk]")
+        A.e(f"s_branch L_BADRET_{tagid}_%=")
 
 
 def tile_load(which: str, i: int, base_sreg: int):
@@ -439,9 +494,9 @@ def staging_ops(tagid: str):
     three gaps apart: a burst of them would hold up the in-order stream."""
     head = {0: [f"s_add_u32 {sr(S_STW)}, {sr(S_ST_PRV)}, {sr(S_WBASE)}",
                 f"s_lshl_b32 {sr(S_J0)}, {sr(S_T)}, 6",
-                f"s_add_u32 {sr(S_J0)}, {sr(S_J0)}, 192",
-                f"s_mul_i32 {sr(S_SOFF)}, {sr(S_J0)}, %[krb]",
-                f"s_cmp_le_i32 {sr(S_J0)}, {sr(S_NKM63)}",
+                f"s_add_u32 {sr(S_J0)}, {sr(S_J0)}, 192"] +
+               (paged_tile_offset(tagid) if PAGED else [f"s_mul_i32 {sr(S_SOFF)}, {sr(S_J0)}, %[krb]"]) +
+               [f"s_cmp_le_i32 {sr(S_J0)}, {sr(S_NKM63)}",
                 "\n".join([f"s_cbranch_scc1 L_INRANGE_{tagid}_%="] + clamped_offsets() + [f"L_INRANGE_{tagid}_%=:"])]}
     tail = {}
     n = 0
@@ -496,7 +551,7 @@ def body(A: Asm, masked: bool, name: str):
 
 def body_stage_only(A: Asm):
     rotate_addresses(A, vector=False)
-    A.e(f"s_waitcnt vmcnt({2 * CPW})")
+    A.e(f"s_waitcnt vmcnt({2 * CPW + TBL})")
     A.e("s_barrier")
     head, tail = staging_ops("s")
     for gi in sorted(head):
@@ -585,11 +640,41 @@ def generate(dt: str) -> list[str]:
     e(f"v_lshlrev_b32_e32 {vr(PIECE)}, 4, {vr(TMP[0])}")
     e(f"s_mul_i32 {sr(S_WBASE)}, %[wv], {CPW * CHUNK}")
     e(f"s_add_u32 {sr(S_WBASE)}, {sr(S_WBASE)}, %[lds]")
-    for i in range(CPW):
-        e(f"v_add_u32_e32 {vr(TMP[0])}, {4 * i}, {vr(ROWB)}")
-        e(f"v_mad_u32_u24 {vr(VBO[i])}, {vr(TMP[0])}, %[krb], {vr(PIECE)}")
-    e(f"v_mov_b32_e32 {vr(TMP[0])}, {sr(S_NK1)}")
-    e(f"v_mad_u32_u24 {vr(LIMV)}, {vr(TMP[0])}, %[krb], {vr(PIECE)}")
+    if PAGED:
+        # rows are addressed inside the wave's block: constants (4 i + L % 4) rows + piece; the
+        # block's offset is the scalar part, from the table
+        e(f"s_mov_b32 {sr(S_R0W)}, {sr(S_TMP)}")                  # first row of the wave's part of a tile
+        e(f"v_and_b32_e32 {vr(V_L4)}, 3, {vr(LANE)}")
+        for i in range(CPW):
+            e(f"v_add_u32_e32 {vr(TMP[0])}, {4 * i}, {vr(V_L4)}")
+            e(f"v_mad_u32_u24 {vr(VBO[i])}, {vr(TMP[0])}, %[krb], {vr(PIECE)}")
+        # block ids of the last needed key and of the wave's parts of tiles 0, 1, 2: four loads, one wait
+        e(f"s_lshr_b32 {sr(S_LASTIDX)}, {sr(S_NK1)}, %[shift]")
+        e(f"s_lshl_b32 {sr(S_T2)}, {sr(S_LASTIDX)}, 2")
+        e(f"v_mov_b32_e32 {vr(TMP[4])}, {sr(S_T2)}")
+        e(f"global_load_dword {vr(TMP[8])}, {vr(TMP[4])}, %[tbl]")
+        for x in range(3):
+            e(f"s_add_u32 {sr(S_T2)}, {sr(S_R0W)}, {64 * x}")
+            e(f"s_lshr_b32 {sr(S_T2)}, {sr(S_T2)}, %[shift]")
+            e(f"s_min_u32 {sr(S_T2)}, {sr(S_T2)}, {sr(S_LASTIDX)}")
+            e(f"s_lshl_b32 {sr(S_T2)}, {sr(S_T2)}, 2")
+            e(f"v_mov_b32_e32 {vr(TMP[5 + x])}, {sr(S_T2)}")
+            e(f"global_load_dword {vr(TMP[9 + x])}, {vr(TMP[5 + x])}, %[tbl]")
+        e("s_waitcnt vmcnt(0)")
+        e(f"v_readfirstlane_b32 {sr(S_BLK)}, {vr(TMP[8])}")
+        e(f"s_cmp_lt_u32 {sr(S_BLK)}, %[nblk]")
+        e("s_cbranch_scc0 L_BADBLK_last_%=\nL_BADRET_last_%=:")
+        e(f"s_and_b32 {sr(S_T2)}, {sr(S_NK1)}, %[bsm1]")
+        e(f"s_lshl_b32 {sr(S_TMP)}, {sr(S_BLK)}, %[shift]")
+        e(f"s_add_u32 {sr(S_TMP)}, {sr(S_TMP)}, {sr(S_T2)}")       # physical row of the last needed key
+        e(f"v_mov_b32_e32 {vr(TMP[0])}, {sr(S_TMP)}")
+        e(f"v_mad_u32_u24 {vr(LIMV)}, {vr(TMP[0])}, %[krb], {vr(PIECE)}")
+    else:
+        for i in range(CPW):
+            e(f"v_add_u32_e32 {vr(TMP[0])}, {4 * i}, {vr(ROWB)}")
+            e(f"v_mad_u32_u24 {vr(VBO[i])}, {vr(TMP[0])}, %[krb], {vr(PIECE)}")
+        e(f"v_mov_b32_e32 {vr(TMP[0])}, {sr(S_NK1)}")
+        e(f"v_mad_u32_u24 {vr(LIMV)}, {vr(TMP[0])}, %[krb], {vr(PIECE)}")
     e(f"s_sub_i32 {sr(S_NKM63)}, {sr(S_NK1)}, 63")
 
     A.c("Q^T into AGPRs: lane (row c, k group hh) holds Q[row][16 s + 8 hh, +8); rows past the last valid one repeat it")
@@ -627,7 +712,21 @@ def generate(dt: str) -> list[str]:
 
     A.c("tiles 0, 1, 2 requested")
     for x in range(3):
-        e(f"s_mul_i32 {sr(S_SOFF)}, %[krb], {64 * x}")
+        if PAGED:
+            if x == 2:   # the id of tile 3 joins the queue before the loads of tile 2, as in the loop
+                e(f"s_add_u32 {sr(S_R0)}, {sr(S_R0W)}, 128")
+                for ins in paged_request_id(64):
+                    e(ins)
+            e(f"v_readfirstlane_b32 {sr(S_BLK)}, {vr(TMP[9 + x])}")
+            e(f"s_cmp_lt_u32 {sr(S_BLK)}, %[nblk]")
+            e(f"s_cbranch_scc0 L_BADBLK_p{x}_%=\nL_BADRET_p{x}_%=:")
+            e(f"s_add_u32 {sr(S_R0)}, {sr(S_R0W)}, {64 * x}")
+            e(f"s_and_b32 {sr(S_T2)}, {sr(S_R0)}, %[bsm1]")
+            e(f"s_lshl_b32 {sr(S_SOFF)}, {sr(S_BLK)}, %[shift]")
+            e(f"s_add_u32 {sr(S_SOFF)}, {sr(S_SOFF)}, {sr(S_T2)}")
+            e(f"s_mul_i32 {sr(S_SOFF)}, {sr(S_SOFF)}, %[krb]")
+        else:
+            e(f"s_mul_i32 {sr(S_SOFF)}, %[krb], {64 * x}")
         for ins in clamped_offsets():
             e(ins)
         e(f"s_add_u32 {sr(S_STW)}, {sr(S_WBASE)}, {x * STAGE}")
@@ -654,7 +753,7 @@ def generate(dt: str) -> list[str]:
         e(f"ds_write_b128 {vr(TMP[0])}, {vr(PB, 4)} offset:{16 * THREADS * i}")
     e(f"ds_write_b128 {vr(TMP[1])}, {vr(PB, 4)} offset:{16 * THREADS * full}")
     A.c("Q and tile 0 have landed once at most the newest loads (tiles 1, 2) are outstanding")
-    e(f"s_waitcnt vmcnt({4 * CPW}) lgkmcnt(0)")
+    e(f"s_waitcnt vmcnt({4 * CPW + TBL}) lgkmcnt(0)")
     e("s_barrier")
     e(f"v_mov_b32_e32 {vr(KA_NXT)}, {vr(KL)}")
     e(f"v_add_u32_e32 {vr(VA_CUR)}, {3 * STAGE}, {vr(VL)}")
@@ -774,6 +873,9 @@ def generate(dt: str) -> list[str]:
     A.c("out-of-line: running maximum moved")
     for name in ("f0", "f1", "m0", "m1"):
         rescale_blocks(A, name)
+    if PAGED:
+        A.e("s_branch L_END_%=")
+        bad_block_paths(A, ["last", "p0", "p1", "p2", "f", "m", "s"])
     e("L_END_%=:")
     e("s_waitcnt vmcnt(0) lgkmcnt(0)")
     return A.lines
@@ -790,16 +892,17 @@ def clobbers() -> str:
 def main(out_path: str):
     with open(out_path, "w") as f:
         f.write("// Generated by gen_prefill_pipe.py -- do not edit.\n")
-        f.write(f"#define SKV_PIPE{NQ}_LDS_BYTES {LDS_BYTES}\n")
-        f.write(f"#define SKV_PIPE{NQ}_THREADS {THREADS}\n")
+        tag = f"{NQ}P" if PAGED else f"{NQ}"
+        f.write(f"#define SKV_PIPE{tag}_LDS_BYTES {LDS_BYTES}\n")
+        f.write(f"#define SKV_PIPE{tag}_THREADS {THREADS}\n")
         for dt in ("bf16", "f16"):
-            f.write(f"#define SKV_PIPE{NQ}_ASM_{dt.upper()} \\\n")
+            f.write(f"#define SKV_PIPE{tag}_ASM_{dt.upper()} \\\n")
             for line in generate(dt):
                 if line.startswith("//"):
                     continue
                 f.write(f'    "{line}\\n" \\\n')
             f.write('    ""\n')
-        f.write(f"#define SKV_PIPE{NQ}_CLOBBERS {clobbers()}\n")
+        f.write(f"#define SKV_PIPE{tag}_CLOBBERS {clobbers()}\n")
 
 
 if __name__ == "__main__":

@@ -18,7 +18,9 @@
 #include <cstring>
 
 #include "prefill_pipe_body_nq1.inc"
+#include "prefill_pipe_body_nq1_paged.inc"
 #include "prefill_pipe_body_nq2.inc"
+#include "prefill_pipe_body_nq2_paged.inc"
 
 namespace skv {
 
@@ -42,9 +44,10 @@ __device__ __forceinline__ u32x4 make_srd(const void *base, uint32_t bytes) {
     return r;
 }
 
-template <bool BF16, int NQ>
+template <bool BF16, int NQ, bool PAGED>
 __global__ __launch_bounds__(512 / NQ, 1) void prefill_pipe_kernel(AttnArgs a, int G, int n_qt, int xcd_map) {
     static_assert(SKV_PIPE1_LDS_BYTES == SKV_PIPE2_LDS_BYTES && SKV_PIPE1_THREADS == 512 && SKV_PIPE2_THREADS == 256);
+    static_assert(SKV_PIPE1P_LDS_BYTES == SKV_PIPE2_LDS_BYTES && SKV_PIPE2P_LDS_BYTES == SKV_PIPE2_LDS_BYTES);
     __shared__ __attribute__((aligned(16))) char lds[SKV_PIPE2_LDS_BYTES];
     constexpr int kRowsPerWave = 32 * NQ;
 
@@ -93,9 +96,14 @@ __global__ __launch_bounds__(512 / NQ, 1) void prefill_pipe_kernel(AttnArgs a, i
     const int t_mask = active ? ((p0 + 1) >> 6) : 0; // first tile that touches its diagonal
 
     const int64_t row_bytes = (int64_t)hkv * kD * 2;
-    const char *kbase = (const char *)a.cache.k + ((int64_t)b * a.cache.max_ctx * hkv + kvh) * (kD * 2);
-    const char *vbase = (const char *)a.cache.v + ((int64_t)b * a.cache.max_ctx * hkv + kvh) * (kD * 2);
-    const uint32_t span = (uint32_t)((int64_t)a.cache.max_ctx * row_bytes - (int64_t)kvh * (kD * 2));
+    // contiguous: the descriptor covers this sequence's region of the slot; paged: the whole slot
+    // (rows are found through the block table), from this kv head's first byte on
+    const int64_t seq_rows = PAGED ? 0 : (int64_t)b * a.cache.max_ctx;
+    const int64_t rows_covered = PAGED ? ((int64_t)a.cache.n_blocks << a.cache.block_shift) : a.cache.max_ctx;
+    const char *kbase = (const char *)a.cache.k + (seq_rows * hkv + kvh) * (kD * 2);
+    const char *vbase = (const char *)a.cache.v + (seq_rows * hkv + kvh) * (kD * 2);
+    const uint32_t span = (uint32_t)(rows_covered * row_bytes - (int64_t)kvh * (kD * 2));
+    const int32_t *tbl = PAGED ? a.cache.block_table + (int64_t)b * a.cache.max_blocks_per_seq : nullptr;
     const u32x4 srdk = make_srd(kbase, span);
     const u32x4 srdv = make_srd(vbase, span);
 
@@ -119,27 +127,32 @@ __global__ __launch_bounds__(512 / NQ, 1) void prefill_pipe_kernel(AttnArgs a, i
         [nt] "s"(uni((uint32_t)n_tiles)), [tms] "s"(uni((uint32_t)t_mask)),                            \
         [twl] "s"(uni((uint32_t)tw_last)), [p0] "s"(uni((uint32_t)p0)),                                \
         [cs] "s"(uni(__builtin_bit_cast(uint32_t, cs))), [thr] "s"(uni(__builtin_bit_cast(uint32_t, thr))), \
-        [wv] "s"(uni((uint32_t)wave)), [tid] "v"(tid)
+        [wv] "s"(uni((uint32_t)wave)), [tid] "v"(tid), [tbl] "s"(tbl), [flt] "s"(a.cache.faults),                \
+        [shift] "s"(uni((uint32_t)a.cache.block_shift)), [bsm1] "s"(uni((1u << a.cache.block_shift) - 1u)),           \
+        [nblk] "s"(uni((uint32_t)a.cache.n_blocks))
 
-    if constexpr (NQ == 2) {
-        if constexpr (BF16) {
-            asm volatile(SKV_PIPE2_ASM_BF16 : : SKV_PIPE_OPERANDS : SKV_PIPE2_CLOBBERS);
-        } else {
-            asm volatile(SKV_PIPE2_ASM_F16 : : SKV_PIPE_OPERANDS : SKV_PIPE2_CLOBBERS);
-        }
-    } else {
-        // 512 threads: the compiler keeps to v0..v127 itself (it halves the 256 registers of a wave
-        // between the two files) and says that clobbers above that do nothing for it; they do set the
-        // kernel's register count, which is what they are listed for
+#define SKV_PIPE_RUN(TAG)                                                                              \
+    if constexpr (BF16) {                                                                              \
+        asm volatile(SKV_PIPE##TAG##_ASM_BF16 : : SKV_PIPE_OPERANDS : SKV_PIPE##TAG##_CLOBBERS);      \
+    } else {                                                                                           \
+        asm volatile(SKV_PIPE##TAG##_ASM_F16 : : SKV_PIPE_OPERANDS : SKV_PIPE##TAG##_CLOBBERS);       \
+    }
+    // 512 threads: the compiler keeps to v0..v127 itself (it halves the 256 registers of a wave
+    // between the two files) and says that clobbers above that do nothing for it; they do set the
+    // kernel's register count, which is what they are listed for
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"
-        if constexpr (BF16) {
-            asm volatile(SKV_PIPE1_ASM_BF16 : : SKV_PIPE_OPERANDS : SKV_PIPE1_CLOBBERS);
-        } else {
-            asm volatile(SKV_PIPE1_ASM_F16 : : SKV_PIPE_OPERANDS : SKV_PIPE1_CLOBBERS);
-        }
-#pragma clang diagnostic pop
+    if constexpr (NQ == 2 && !PAGED) {
+        SKV_PIPE_RUN(2)
+    } else if constexpr (NQ == 2 && PAGED) {
+        SKV_PIPE_RUN(2P)
+    } else if constexpr (NQ == 1 && !PAGED) {
+        SKV_PIPE_RUN(1)
+    } else {
+        SKV_PIPE_RUN(1P)
     }
+#pragma clang diagnostic pop
+#undef SKV_PIPE_RUN
 #undef SKV_PIPE_OPERANDS
 }
 
@@ -147,10 +160,16 @@ __global__ __launch_bounds__(512 / NQ, 1) void prefill_pipe_kernel(AttnArgs a, i
 
 bool prefill_pipe_supported(const AttnArgs &a, int dtype, int head_dim) {
     if (!(dtype == SKV_BF16 || dtype == SKV_F16) || head_dim != kD) return false;
-    if (a.cache.block_table != nullptr) return false; // paged caches take the plain kernel
-    // 32-bit byte offsets inside one sequence's region of the slot, 24-bit multiplier operands
+    // 32-bit byte offsets inside one sequence's region of the slot (paged: inside the whole slot, plus
+    // one block, the offset an invalid block id is turned into), 24-bit multiplier operands
     const int64_t row_bytes = (int64_t)a.cache.n_kv_heads * kD * 2;
     if (row_bytes >= (1 << 24) || a.cache.max_ctx >= (1 << 24)) return false;
+    if (a.cache.block_table != nullptr) {
+        // a wave stages 16 (8) consecutive positions per tile: they must lie in one block
+        if (a.cache.block_shift < 4) return false;
+        const int64_t rows = ((int64_t)a.cache.n_blocks + 1) << a.cache.block_shift;
+        return rows < (1 << 24) && rows * row_bytes < ((int64_t)1 << 32) && (int64_t)a.n_q_heads * kD * 2 < (1 << 24);
+    }
     if ((int64_t)a.cache.max_ctx * row_bytes >= ((int64_t)1 << 32)) return false;
     if ((int64_t)a.n_q_heads * kD * 2 >= (1 << 24)) return false;
     return true;
@@ -167,17 +186,16 @@ hipError_t launch_prefill_pipe(const AttnArgs &a, int dtype, int group, hipStrea
     const char *shape = getenv("SKV_PREFILL_WAVES");
     const bool eight = shape != nullptr && strcmp(shape, "8") == 0;
     const dim3 grid((unsigned)blocks);
+    const bool paged = a.cache.block_table != nullptr;
+#define SKV_PIPE_LAUNCH(BF, NQ_, PG) prefill_pipe_kernel<BF, NQ_, PG><<<grid, 512 / NQ_, 0, stream>>>(a, group, n_qt, xcd_map)
     if (eight) {
-        if (dtype == SKV_BF16)
-            prefill_pipe_kernel<true, 1><<<grid, 512, 0, stream>>>(a, group, n_qt, xcd_map);
-        else
-            prefill_pipe_kernel<false, 1><<<grid, 512, 0, stream>>>(a, group, n_qt, xcd_map);
+        if (dtype == SKV_BF16) { if (paged) SKV_PIPE_LAUNCH(true, 1, true); else SKV_PIPE_LAUNCH(true, 1, false); }
+        else { if (paged) SKV_PIPE_LAUNCH(false, 1, true); else SKV_PIPE_LAUNCH(false, 1, false); }
     } else {
-        if (dtype == SKV_BF16)
-            prefill_pipe_kernel<true, 2><<<grid, 256, 0, stream>>>(a, group, n_qt, xcd_map);
-        else
-            prefill_pipe_kernel<false, 2><<<grid, 256, 0, stream>>>(a, group, n_qt, xcd_map);
+        if (dtype == SKV_BF16) { if (paged) SKV_PIPE_LAUNCH(true, 2, true); else SKV_PIPE_LAUNCH(true, 2, false); }
+        else { if (paged) SKV_PIPE_LAUNCH(false, 2, true); else SKV_PIPE_LAUNCH(false, 2, false); }
     }
+#undef SKV_PIPE_LAUNCH
     set_last_kernel_name("prefill_pipe_kernel");
     return hipGetLastError();
 }

@@ -98,7 +98,9 @@ def test_device_side_bad_lengths_and_block_ids_are_contained():
     op = torch.zeros_like(qp)
     ql = torch.tensor([60, 60], dtype=torch.int32, device="cuda")
     skv.skv_attn_prefill(cache, 1, qp, op, ql, lens, 60, 100, w.scale)
+    assert skv.skv_last_kernel_name() == "prefill_pipe_kernel"      # its paged variant checks the ids too
     assert skv.skv_cache_device_faults(cache) & 2
+    assert torch.isfinite(op.float()).all()
     skv.skv_kv_append(cache, 0, k, k, torch.zeros(2, dtype=torch.int32, device="cuda"), four, 4)
     assert skv.skv_cache_device_faults(cache) & 2
     torch.cuda.synchronize()

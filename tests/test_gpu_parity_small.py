@@ -137,6 +137,11 @@ PREFILL_CASES = [
     ("bf16", 4, 1, 128, [700, 900, 64, 300], [700, 333, 0, 1], [0, 0, 2, 2], False),
     ("f16", 2, 2, 128, [513, 1025], [513, 257], [0, 1], False),
     ("bf16", 8, 1, 128, [320, 65], [129, 65], [0], False),
+    # the same through a block table: the pipelined kernel's paged variant (one block id per wave
+    # and tile), lengths that end inside a block, a tile, a 256-row group; chunk offsets; MHA
+    ("bf16", 4, 1, 128, [700, 900, 64, 300], [700, 333, 0, 1], [0, 0, 2, 2], True),
+    ("f16", 2, 2, 128, [513, 1025, 17], [513, 257, 17], [0, 1], True),
+    ("bf16", 8, 1, 128, [320, 65, 1], [129, 65, 1], [0], True),
 ]
 
 
@@ -162,7 +167,7 @@ def test_prefill_matches_oracle_exhaustively(dtype, hq, hkv, d, kv_lens, q_lens,
     assert skv.skv_cache_device_faults(cache) == 0
 
 
-@pytest.mark.parametrize("case", [c for c in PREFILL_CASES if c[0] != "f32" and c[3] == 128 and not c[7]])
+@pytest.mark.parametrize("case", [c for c in PREFILL_CASES if c[0] != "f32" and c[3] == 128])
 def test_prefill_shape_with_eight_waves_matches_oracle(case, monkeypatch):
     """The pipelined kernel in its other shape (8 waves of 32 rows, two per SIMD instead of 4 waves
     of 64 rows), which the library picks at launch time from the environment."""

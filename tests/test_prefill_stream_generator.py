@@ -10,31 +10,35 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _load(nq):
-    """The generator fixes the wave shape (row blocks of 32 per wave) when it is imported."""
+def _load(nq, paged=0):
+    """The generator fixes the wave shape (row blocks of 32 per wave) and the cache addressing
+    (contiguous or through a block table) when it is imported."""
     spec = importlib.util.spec_from_file_location(
-        f"gen_prefill_pipe_nq{nq}", os.path.join(ROOT, "paper_2604_22782_amd", "csrc", "gen_prefill_pipe.py"))
+        f"gen_prefill_pipe_nq{nq}_{paged}", os.path.join(ROOT, "paper_2604_22782_amd", "csrc", "gen_prefill_pipe.py"))
     mod = importlib.util.module_from_spec(spec)
-    old = os.environ.get("SKV_GEN_NQ")
-    os.environ["SKV_GEN_NQ"] = str(nq)
+    keep = {k: os.environ.get(k) for k in ("SKV_GEN_NQ", "SKV_GEN_PAGED")}
+    os.environ["SKV_GEN_NQ"], os.environ["SKV_GEN_PAGED"] = str(nq), str(paged)
     try:
         spec.loader.exec_module(mod)
     finally:
-        if old is None:
-            del os.environ["SKV_GEN_NQ"]
-        else:
-            os.environ["SKV_GEN_NQ"] = old
+        for k, v in keep.items():
+            if v is None:
+                del os.environ[k]
+            else:
+                os.environ[k] = v
     return mod
 
 
-GEN = {1: _load(1), 2: _load(2)}
-G = GEN[2]
+GEN = {(nq, paged): _load(nq, paged) for nq in (1, 2) for paged in (0, 1)}
+G = GEN[(2, 0)]
 
 
+@pytest.mark.parametrize("paged", [0, 1])
 @pytest.mark.parametrize("nq", [1, 2])
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
-def test_stream_is_generated_and_self_consistent(dt, nq):
-    G = GEN[nq]
+def test_stream_is_generated_and_self_consistent(dt, nq, paged):
+    G = GEN[(nq, paged)]
+    assert G.PAGED == bool(paged)
     assert (G.NQ, G.WAVES * G.NQ, G.THREADS) == (nq, 8, 512 // nq)
     lines = [l for l in G.generate(dt) if not l.startswith("//")]
     text = "\n".join(lines)
@@ -65,9 +69,9 @@ def test_stream_is_generated_and_self_consistent(dt, nq):
         assert G.FIRST_S <= lo <= hi <= G.LAST_S
 
 
-@pytest.mark.parametrize("nq", [1, 2])
-def test_hazard_check_accepts_the_stream_and_rejects_a_planted_read(nq):
-    G = GEN[nq]
+@pytest.mark.parametrize("nq,paged", [(1, 0), (2, 0), (2, 1)])
+def test_hazard_check_accepts_the_stream_and_rejects_a_planted_read(nq, paged):
+    G = GEN[(nq, paged)]
     lines = G.generate("bf16")
     G.check_mfma_results(lines)                      # the real stream: fine
     i = next(k for k, l in enumerate(lines) if l.startswith("v_mfma") and " v[" in l.split(",")[0])
