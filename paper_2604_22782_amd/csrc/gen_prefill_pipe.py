@@ -35,6 +35,10 @@ Register map (per lane):
   v[128:...]  rings of K / V^T operands read from LDS, then softmax state, lane constants, addresses
   v[0:23], s[0:39] are left to the compiler for the operands of the asm statement.
 
+Variants (environment, read when the generator runs): SKV_GEN_NQ=1 writes the 8-wave shape (32
+rows per wave, two waves per SIMD; the register map above halves), SKV_GEN_PAGED=1 the stream for
+caches addressed through a block table (one block id per wave and tile, see PAGED below).
+
 Hazards the hardware does not interlock (MFMA result read by the vector ALU, transcendental
 result read by the next instruction, lane-swap operands, M0 written right before a load to LDS)
 are kept apart by construction or by s_nop; see the comments at the emit sites.
