@@ -119,3 +119,34 @@ def test_config3_llama3_prefill_bf16_full_size():
     assert skv.skv_last_kernel_name() == "prefill_pipe_kernel"
     assert worst <= H.TOL["bf16"]
     cache.free()
+
+
+def test_config3_shape_in_16_token_blocks_prefill_full_size():
+    """The prefill workload's shape stored through a block table (random permutation of the physical
+    blocks): the pipelined kernel's paged variant at full size, sampled rows against the oracle."""
+    w = configs.llama3_prefill(n_layers=4)
+    S = int(w.kv_lens.max())
+    table, n_blocks = configs._paged(w.kv_lens, 16, np.random.default_rng(33))
+    w.block_size, w.block_table, w.n_blocks, w.max_ctx = 16, table, n_blocks, table.shape[1] * 16
+    cache, _ = H.alloc_cache(w)
+    H.fill_by_append(cache, w)
+    d_lens = torch.from_numpy(w.kv_lens).cuda()
+    rng = np.random.default_rng(w.seed)
+    fixed_rows = [0, 15, 16, 63, 64, 255, 256, 4095, 4096, S - 257, S - 17, S - 1]
+    worst = 0.0
+    for layer in range(w.n_layers):
+        q = w.q_prefill(layer, 0, w.batch, 0, S, "cuda")
+        out = torch.empty_like(q)
+        skv.skv_attn_prefill(cache, layer, q, out, d_lens, d_lens, S, S, w.scale)
+        b = int(rng.integers(w.batch))
+        for h in rng.choice(w.n_q_heads, 2, replace=False).tolist():
+            K, V = H.oracle_kv_rows(w, layer, b, h // w.group, S)
+            rows = fixed_rows + rng.integers(0, S, 6).tolist()
+            qh, oh = gen.to_f64(q[b, rows, h]), gen.to_f64(out[b, rows, h])
+            for i, r in enumerate(rows):
+                worst = max(worst, float(np.abs(oh[i] - O.attn_one(qh[i], K[: r + 1], V[: r + 1], w.scale)).max()))
+        print(f"layer {layer}: worst so far {worst:.3e}", flush=True)
+    assert skv.skv_cache_device_faults(cache) == 0
+    assert skv.skv_last_kernel_name() == "prefill_pipe_kernel"
+    assert worst <= H.TOL["bf16"]
+    cache.free()
