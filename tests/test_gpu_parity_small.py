@@ -279,3 +279,32 @@ def test_prefill_with_growing_scores_rescales_often(dtype, waves, monkeypatch):
             assert err <= H.TOL[dtype], (layer, b, err)
     assert skv.skv_cache_device_faults(cache) == 0
     cache.free()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("block", [32, 128])
+def test_paged_prefill_with_larger_blocks(block):
+    """Blocks of 32 and 128 positions (the pipelined kernel's paged variant takes any power of two
+    from 16 on: a wave's rows of a tile lie inside one block, at an offset that now varies)."""
+    lens = np.array([700, 333, 129], dtype=np.int32)
+    w = configs.Workload("blk", "bf16", 2, 4, 2, 128, 3, [0, 0], lens, 1.0, 0.5, seed=61)
+    table, n_blocks = configs._paged(lens, block, np.random.default_rng(block))
+    w.block_size, w.block_table, w.n_blocks, w.max_ctx = block, table, n_blocks, table.shape[1] * block
+    cache, _ = H.alloc_cache(w)
+    H.fill_by_append(cache, w)
+    oc = H.oracle_cache(w)
+    q_lens = [700, 100, 129]
+    d_q = torch.tensor(q_lens, dtype=torch.int32, device="cuda")
+    d_kv = torch.from_numpy(lens).cuda()
+    for layer in (0, 1):
+        q = w.q_prefill(layer, 0, 3, 0, 700, "cuda")
+        out = torch.full_like(q, 7.0)
+        skv.skv_attn_prefill(cache, layer, q, out, d_q, d_kv, 700, 700, w.scale)
+        assert skv.skv_last_kernel_name() == "prefill_pipe_kernel"
+        want = O.prefill(oc, layer, gen.to_f64(q), q_lens, lens, w.scale)
+        got = gen.to_f64(out)
+        for b, nq in enumerate(q_lens):
+            assert np.abs(got[b, :nq] - want[b, :nq]).max() <= H.TOL["bf16"], (layer, b)
+            assert (got[b, nq:] == 7.0).all()
+    assert skv.skv_cache_device_faults(cache) == 0
+    cache.free()
