@@ -149,6 +149,9 @@ skv_status_t skv_kv_append(skv_cache_t *cache, int32_t layer, const void *k_new,
  * pairs with i + head_dim / 2:  k'_i = k_i cos - k_(i+d/2) sin,  k'_(i+d/2) = k_(i+d/2) cos +
  * k_i sin, with the table row of the token's position start_pos[b] + i (a position beyond the
  * table drops the row and sets SKV_FAULT_APPEND_RANGE).  V is never rotated.
+ * k_norm_weight: device float[head_dim] or NULL.  Not NULL: every head's key vector is normalised
+ * before the rotation, k <- k / sqrt(mean_d(k^2) + k_norm_eps) * k_norm_weight[d] (the per-head key
+ * normalisation of the Qwen3 family); V is never normalised.
  * workspace: device scratch of skv_kv_project_workspace_bytes(cache, max_new, hidden) bytes (0 for
  * prompts: only launches of few tokens split the hidden axis over work groups, so that the weights
  * stream at the full HBM rate, and keep fp32 partial sums there); may be NULL when that is 0.
@@ -158,7 +161,8 @@ skv_status_t skv_kv_project_workspace_bytes(const skv_cache_t *cache, int32_t ma
                                             size_t *bytes);
 skv_status_t skv_kv_project_append(skv_cache_t *cache, int32_t layer, const void *x, const void *w_k,
                                    const void *w_v, const float *rope_cos, const float *rope_sin,
-                                   int32_t rope_positions, const int32_t *start_pos,
+                                   int32_t rope_positions, const float *k_norm_weight, float k_norm_eps,
+                                   const int32_t *start_pos,
                                    const int32_t *new_lens, int32_t max_new, int32_t hidden,
                                    void *workspace, size_t workspace_bytes, void *stream);
 

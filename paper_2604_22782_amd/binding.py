@@ -191,9 +191,11 @@ def skv_kv_project_workspace_bytes(cache: Cache, max_new: int, hidden: int) -> i
 
 
 def skv_kv_project_append(cache: Cache, layer: int, x, w_k, w_v, rope_cos, rope_sin, start_pos, new_lens,
-                          max_new: int, workspace=None, stream=None):
+                          max_new: int, workspace=None, stream=None, k_norm_weight=None, k_norm_eps: float = 1e-6):
     """x: [batch][max_new][hidden]; w_k, w_v: [n_kv_heads * head_dim][hidden]; rope_cos, rope_sin:
-    float32 [positions][head_dim / 2] or None."""
+    float32 [positions][head_dim / 2] or None; k_norm_weight: float32 [head_dim] or None."""
+    if k_norm_weight is not None and k_norm_weight.dtype != torch.float32:
+        raise ValueError("k_norm_weight is float32 [head_dim]")
     hidden = x.shape[-1]
     if w_k.shape[-1] != hidden or w_v.shape[-1] != hidden or w_k.dtype != x.dtype or w_v.dtype != x.dtype:
         raise ValueError("w_k and w_v are [n_kv_heads * head_dim][hidden] in the dtype of x")
@@ -204,7 +206,8 @@ def skv_kv_project_append(cache: Cache, layer: int, x, w_k, w_v, rope_cos, rope_
         n_pos = rope_cos.shape[0]
     wb = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib().skv_kv_project_append(cache.handle, layer, _ptr(x), _ptr(w_k), _ptr(w_v), _ptr(rope_cos),
-                                       _ptr(rope_sin), n_pos, _ptr(start_pos), _ptr(new_lens), max_new, hidden,
+                                       _ptr(rope_sin), n_pos, _ptr(k_norm_weight), ctypes.c_float(k_norm_eps),
+                                       _ptr(start_pos), _ptr(new_lens), max_new, hidden,
                                        _ptr(workspace), ctypes.c_size_t(wb), _stream(stream)), "skv_kv_project_append")
 
 

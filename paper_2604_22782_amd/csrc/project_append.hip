@@ -70,6 +70,25 @@ __device__ __forceinline__ void finish_token(const ProjArgs &a, f32x16 (&acc)[D 
         if (hh == 0) atomicOr(a.slot.faults, (uint32_t)SKV_FAULT_BLOCK_ID);
         return;
     }
+    if (!is_v && a.k_norm_weight != nullptr) { // the lane and its partner (l ^ 32) hold the head's d features of the token
+        float ss = 0.f;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) ss += acc[nb][r] * acc[nb][r];
+        ss += __shfl_xor(ss, 32, 64);
+        const float inv = rsqrtf(ss * (1.f / D) + a.k_norm_eps);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const float4 wv = *(const float4 *)(a.k_norm_weight + 32 * nb + 8 * g4 + 4 * hh);
+                acc[nb][4 * g4] *= inv * wv.x;
+                acc[nb][4 * g4 + 1] *= inv * wv.y;
+                acc[nb][4 * g4 + 2] *= inv * wv.z;
+                acc[nb][4 * g4 + 3] *= inv * wv.w;
+            }
+    }
     if (rotate) { // feature f < d/2 pairs with f + d/2: blocks nb and nb + NB/2, same element
         const float *ct = a.rope_cos + pos * (D / 2) + 4 * hh;
         const float *st = a.rope_sin + pos * (D / 2) + 4 * hh;
@@ -349,6 +368,16 @@ __global__ __launch_bounds__(256) void project_finish_kernel(ProjArgs a, int n_s
     }
     const int head = kh % hkv;
     const bool is_v = kh >= hkv;
+    if (!is_v && a.k_norm_weight != nullptr) {
+        // the 4 (D / 64) 2 threads of this (token, head) are neighbours in the wave and hold its d features
+        float ss = lo.x * lo.x + lo.y * lo.y + lo.z * lo.z + lo.w * lo.w + hi.x * hi.x + hi.y * hi.y + hi.z * hi.z + hi.w * hi.w;
+#pragma unroll
+        for (int d = 1; d < 4 * (NB / 2) * 2; d <<= 1) ss += __shfl_xor(ss, d, 64);
+        const float inv = rsqrtf(ss * (1.f / D) + a.k_norm_eps);
+        const float4 wl = *(const float4 *)(a.k_norm_weight + f_lo), wh = *(const float4 *)(a.k_norm_weight + f_hi);
+        lo = make_float4(lo.x * inv * wl.x, lo.y * inv * wl.y, lo.z * inv * wl.z, lo.w * inv * wl.w);
+        hi = make_float4(hi.x * inv * wh.x, hi.y * inv * wh.y, hi.z * inv * wh.z, hi.w * inv * wh.w);
+    }
     const int b = (int)(m / a.max_new);
     const int i = (int)(m - (int64_t)b * a.max_new);
     if (i >= a.new_lens[b]) return;

@@ -327,12 +327,14 @@ skv_status_t skv_kv_project_workspace_bytes(const skv_cache_t *c, int32_t max_ne
 
 skv_status_t skv_kv_project_append(skv_cache_t *c, int32_t layer, const void *x, const void *w_k, const void *w_v,
                                    const float *rope_cos, const float *rope_sin, int32_t rope_positions,
-                                   const int32_t *start_pos, const int32_t *new_lens, int32_t max_new,
-                                   int32_t hidden, void *workspace, size_t workspace_bytes, void *stream) {
+                                   const float *k_norm_weight, float k_norm_eps, const int32_t *start_pos,
+                                   const int32_t *new_lens, int32_t max_new, int32_t hidden, void *workspace,
+                                   size_t workspace_bytes, void *stream) {
     if (!c || !x || !w_k || !w_v || !start_pos || !new_lens) return SKV_ERR_INVALID_ARG;
     if (layer < 0 || layer >= c->d.n_layers || max_new < 0 || hidden < 1) return SKV_ERR_INVALID_ARG;
     if ((rope_cos == nullptr) != (rope_sin == nullptr)) return SKV_ERR_INVALID_ARG;
     if (rope_cos != nullptr && rope_positions < 1) return SKV_ERR_INVALID_ARG;
+    if (k_norm_weight != nullptr && !(k_norm_eps >= 0.f)) return SKV_ERR_INVALID_ARG;
     if (c->route[layer] != layer) return SKV_ERR_NOT_OWNER;
     if (!paged_ready(c)) return SKV_ERR_INVALID_ARG;
     if (!skv::project_append_supported(c->d.dtype, c->d.head_dim, hidden)) return SKV_ERR_UNSUPPORTED;
@@ -349,6 +351,8 @@ skv_status_t skv_kv_project_append(skv_cache_t *c, int32_t layer, const void *x,
     a.w_v = w_v;
     a.rope_cos = rope_cos;
     a.rope_sin = rope_sin;
+    a.k_norm_weight = k_norm_weight;
+    a.k_norm_eps = k_norm_eps;
     a.start_pos = start_pos;
     a.new_lens = new_lens;
     a.batch = c->d.batch;

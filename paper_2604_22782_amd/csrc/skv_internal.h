@@ -74,6 +74,8 @@ struct ProjArgs {
     SlotView slot;
     const void *x, *w_k, *w_v;
     const float *rope_cos, *rope_sin; // both nullptr: no rotation
+    const float *k_norm_weight;       // nullptr: K heads are not normalised; else head_dim weights
+    float k_norm_eps;
     const int32_t *start_pos, *new_lens;
     float *partial;                   // fp32 partial sums when the hidden axis is split
     int32_t batch, max_new, hidden, rope_positions;

@@ -64,11 +64,16 @@ def test_projected_rows_match_oracle(dtype, Hkv, D, hidden, lens, start, new, ma
         cos, sin = d_cos.cpu().double().numpy(), d_sin.cpu().double().numpy()   # the tables as the kernel sees them
     d_start = torch.tensor(start, dtype=torch.int32, device="cuda")
     d_new = torch.tensor(new, dtype=torch.int32, device="cuda")
+    norm_w = d_norm = None
+    if hidden % 128 == 0:          # half of the cases also normalise the keys per head
+        d_norm = (1.0 + 0.2 * torch.randn(D, generator=g)).float().cuda()
+        norm_w = d_norm.cpu().double().numpy()
     ws_bytes = skv.skv_kv_project_workspace_bytes(cache, max_new, hidden)
     ws = torch.empty(max(ws_bytes, 4) // 4, dtype=torch.float32, device="cuda")
     print(f"workspace {ws_bytes} bytes", flush=True)
     for layer in (0, 2):
-        skv.skv_kv_project_append(cache, layer, x.cuda(), wk.cuda(), wv.cuda(), d_cos, d_sin, d_start, d_new, max_new, ws)
+        skv.skv_kv_project_append(cache, layer, x.cuda(), wk.cuda(), wv.cuda(), d_cos, d_sin, d_start, d_new, max_new, ws,
+                                  k_norm_weight=d_norm, k_norm_eps=1e-5)
     with pytest.raises(skv.SkvError) as e:          # layer 1 owns no slot: nothing to project, nothing to store
         skv.skv_kv_project_append(cache, 1, x.cuda(), wk.cuda(), wv.cuda(), d_cos, d_sin, d_start, d_new, max_new)
     assert e.value.status == 3
@@ -76,7 +81,8 @@ def test_projected_rows_match_oracle(dtype, Hkv, D, hidden, lens, start, new, ma
 
     positions = np.array(start)[:, None] + np.arange(max_new)[None, :]
     positions = np.minimum(positions, (cos.shape[0] - 1) if rope else positions)   # rows beyond new_lens are not compared
-    want_k, want_v = P.project_kv(gen.to_f64(x), gen.to_f64(wk), gen.to_f64(wv), Hkv, D, positions, cos, sin)
+    want_k, want_v = P.project_kv(gen.to_f64(x), gen.to_f64(wk), gen.to_f64(wv), Hkv, D, positions, cos, sin,
+                                  k_norm_weight=norm_w, k_norm_eps=1e-5)
     k_pool, v_pool = H.pool_tensors(cache, w)
     for slot in (0, 1):
         for b in range(B):

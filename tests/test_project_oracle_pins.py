@@ -62,3 +62,32 @@ def test_rotation_properties():
     x2 = rng.standard_normal((1, 1, 2 * D))
     k2, _ = P.project_kv(x2, np.eye(2 * D), np.eye(2 * D), 2, D, np.array([[9]]), cos, sin)
     assert np.allclose(k2[0, 0, 1], rot(x2[0, 0, D:], 9)) and np.allclose(k2[0, 0, 0], rot(x2[0, 0, :D], 9))
+
+
+def test_key_normalisation():
+    rng = np.random.default_rng(3)
+    B, T, Hkv, D = 2, 4, 3, 8
+    hidden = Hkv * D
+    x = rng.standard_normal((B, T, hidden))
+    wk, wv = rng.standard_normal((hidden, hidden)), rng.standard_normal((hidden, hidden))
+    cos, sin = _tables(16, D)
+    pos = np.array([[0, 3, 7, 15], [1, 2, 4, 8]])
+    ones = np.ones(D)
+    k, v = P.project_kv(x, wk, wv, Hkv, D, pos, cos, sin, k_norm_weight=ones, k_norm_eps=0.0)
+    k_plain, v_plain = P.project_kv(x, wk, wv, Hkv, D, pos, cos, sin)
+    assert np.allclose((k * k).mean(axis=-1), 1.0)               # every head's key has unit root-mean-square (the rotation keeps it)
+    assert np.array_equal(v, v_plain)                            # V is not normalised
+    # the direction is kept: normalised key = plain key / its rms, head by head
+    rms = np.sqrt((k_plain * k_plain).mean(axis=-1, keepdims=True))
+    assert np.allclose(k, k_plain / rms)
+    # scaling the input leaves the normalised keys alone; the weight scales feature d before the rotation
+    k2, _ = P.project_kv(5.0 * x, wk, wv, Hkv, D, pos, cos, sin, k_norm_weight=ones, k_norm_eps=0.0)
+    assert np.allclose(k2, k)
+    w = rng.uniform(0.5, 2.0, D)
+    kw, _ = P.project_kv(x, wk, wv, Hkv, D, k_norm_weight=w, k_norm_eps=0.0)        # no rotation
+    k1, _ = P.project_kv(x, wk, wv, Hkv, D, k_norm_weight=ones, k_norm_eps=0.0)
+    assert np.allclose(kw, k1 * w)
+    # eps enters under the root
+    ke, _ = P.project_kv(x, wk, wv, Hkv, D, k_norm_weight=ones, k_norm_eps=0.5)
+    kp, _ = P.project_kv(x, wk, wv, Hkv, D)
+    assert np.allclose(ke, kp / np.sqrt((kp * kp).mean(axis=-1, keepdims=True) + 0.5))
