@@ -324,12 +324,12 @@ def run_project(args, torch, skv, H, configs):
         r = {"tokens": tokens, "hidden": hidden, "launch_us": round(us, 1),
              "tflops": round(flops / (us * 1e-6) / 1e12, 1), "gbs": round(nbytes / (us * 1e-6) / 1e9, 1)}
         if regime == "prefill":
-            r["roofline"] = {"bound": "mfma", "kernel": "project_append_kernel", "achieved": r["tflops"],
+            r["roofline"] = {"bound": "mfma", "kernel": "project_append_tile_kernel", "achieved": r["tflops"],
                              "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                              "frac": round(r["tflops"] / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
                              "algorithmic_flops_per_launch": flops}
         else:
-            r["roofline"] = {"bound": "hbm", "kernel": "project_append_kernel", "achieved": r["gbs"],
+            r["roofline"] = {"bound": "hbm", "kernel": "project_append_kernel + project_finish_kernel", "achieved": r["gbs"],
                              "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(r["gbs"] / HBM_PEAK_GBS, 4),
                              "traffic": None, "algorithmic_bytes_per_launch": nbytes}
         out[regime] = r

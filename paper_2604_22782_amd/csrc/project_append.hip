@@ -12,6 +12,8 @@
 // lane, and a token's row is written by two lanes.
 #include "skv_internal.h"
 
+#include <cstdlib>
+
 namespace skv {
 
 namespace {
@@ -340,6 +342,189 @@ __global__ __launch_bounds__(kThreads, 1) void project_append_wide_kernel(ProjAr
     }
 }
 
+// The prompt-sized launch for shapes whose [K heads, V heads] list divides into tiles of 256 features:
+// work group = 4 waves (one per SIMD) = 256 tokens x 256 features, wave = 128 x 128 (16 accumulator
+// blocks: an operand read from LDS feeds four MFMAs, 0.5 reads per MFMA).  The hidden axis moves
+// in slots of 64 elements through all 160 KiB of LDS: three slots of token rows, two of weight rows;
+// the rows go from memory straight into LDS (buffer loads with the lds bit: no staging registers,
+// no LDS store instructions).
+// A load instruction fills 1 KiB = 8 rows x 128 bytes (whole cache lines: with 64-byte row pieces
+// the L2 saw twice the requests and delivered a third less); inside it lane L = 8 g + s writes 16
+// bytes at 16 L and fetches row g, piece s ^ (r / 2) with r = the row's index among its 16: eight
+// neighbouring lanes fetch the 128 contiguous bytes of one row (one access of the vector cache;
+// with a row per lane the loads ran at a lane per clock), and the exclusive-or puts the 16 rows of
+// one piece into 16 different bank groups for the 128-bit operand reads (no bank conflicts).
+// The barrier at the start of slot t publishes it (each wave has waited for its own loads) and
+// releases slot t - 1; during slot t the weight rows of slot t + 1 and then the token rows of slot
+// t + 2 are requested, one load after every four MFMAs; the MFMAs of the last step of slot t - 1
+// run after the barrier, over the first operand reads of slot t.
+constexpr int kGT = 256;                    // tokens = features per work group
+constexpr int kSub = 64;                    // hidden elements per ring slot
+constexpr int kRingX = 3, kRingW = 2;       // slots of token rows, slots of weight rows
+constexpr int kHalfSlot = kGT * kSub * 2;   // bytes of the token rows (or of the weight rows) of a slot
+// s_waitcnt operands that wait for the vector memory counter alone (bits 3:0 and 15:14; the other counters at their maxima)
+constexpr int kVmcnt0 = 0x0f70;
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+__device__ __forceinline__ uint32_t uni(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
+
+// Raw buffer descriptor: 48-bit base, stride 0, byte count, 32-bit untyped data.
+__device__ __forceinline__ u32x4 make_srd(const void *base, uint32_t bytes) {
+    const uint64_t p = (uint64_t)base;
+    u32x4 r;
+    r[0] = uni((uint32_t)p);
+    r[1] = uni((uint32_t)(p >> 32) & 0xffffu);
+    r[2] = uni(bytes);
+    r[3] = 0x00020000u;
+    return r;
+}
+
+// 64 lanes x 16 bytes from srd + voff + soff to LDS bytes lds_dst + 16 lane.  Written as an
+// instruction of its own, not through the compiler's builtin: the compiler would wait for ALL
+// outstanding loads of this kind before any later LDS read, and the ring lives on loads that stay
+// in flight across two barriers.  The kernel counts them itself (s_waitcnt vmcnt).
+// (M0, which carries the LDS address, is named as clobbered; the compiler notes that it does not
+// save it, and this kernel has no other use of it.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void load_chunk_to_lds(u32x4 srd, uint32_t lds_dst, int voff, int soff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_dst), "v"(voff), "s"(srd), "s"(soff)
+                 : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
+template <typename M, int D>
+__global__ __launch_bounds__(256, 1) void project_append_tile_kernel(ProjArgs a) {
+    using vec8 = typename M::vec8;
+    constexpr int NB = D / 32;
+    constexpr int HW = 128 / D;                          // heads per wave
+    __shared__ __attribute__((aligned(1024))) char lds[(kRingX + kRingW) * kHalfSlot]; // all 160 KiB
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tg = wave & 1, fg = wave >> 1;             // token half, feature half of the work group's tile
+    const int c = lane & 31;
+    const int hh = lane >> 5;
+    const int hkv = a.slot.n_kv_heads;
+    const int64_t n_tok = (int64_t)a.batch * a.max_new;
+    // work groups that share a token tile run on one XCD (ids are dealt to the 8 XCDs in turn)
+    const int n_ft = 2 * hkv * D / kGT;
+    const int64_t id = blockIdx.x, n_tt = gridDim.x / n_ft;
+    const bool by_xcd = n_tt % 8 == 0;
+    const int ft = (int)((by_xcd ? id >> 3 : id) % n_ft);
+    const int64_t tt = by_xcd ? ((id >> 3) / n_ft) * 8 + (id & 7) : id / n_ft;
+    const int64_t tok0 = tt * kGT;
+
+    // the 64 weight rows this wave stages: features 64 wave .. + 63 of the tile, inside one head
+    const int kh_w = (ft * kGT + 64 * wave) / D;
+    const uint16_t *w_rows = (const uint16_t *)(kh_w >= hkv ? a.w_v : a.w_k) +
+                             ((int64_t)(kh_w % hkv) * D + (ft * kGT + 64 * wave) % D) * a.hidden;
+    const int64_t rows_left = n_tok - tok0 - 64 * wave;  // token rows this wave stages: 64 wave .. + 63 of the tile
+    const uint32_t x_bytes = rows_left <= 0 ? 0u : (uint32_t)((rows_left < 64 ? rows_left : 64) * a.hidden * 2);
+    const u32x4 x_srd = make_srd((const uint16_t *)a.x + (rows_left > 0 ? (tok0 + 64 * wave) * a.hidden : 0), x_bytes);
+    const u32x4 w_srd = make_srd(w_rows, 64u * a.hidden * 2u);
+    const uint32_t lds_base = uni((uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds);
+    // even chunks of a slot hold rows 0..7 of a group of 16, odd chunks rows 8..15 (r / 2 = 4 + g / 2)
+    const int voff = ((lane >> 3) * a.hidden + ((lane & 7) ^ (lane >> 4)) * 8) * 2;
+    const int row8 = 8 * a.hidden * 2;                   // bytes between the first rows of two chunks
+    const int n_sub = a.hidden / kSub;
+    // chunk c (of 8) of the wave's token rows / weight rows of slot `sub`
+    auto request_x = [&](int sub, int c) {
+        load_chunk_to_lds(x_srd, lds_base + (sub % kRingX) * kHalfSlot + (8 * wave + c) * 1024, voff ^ ((c & 1) * 64),
+                          uni(c * row8 + sub * kSub * 2));
+    };
+    auto request_w = [&](int sub, int c) {
+        load_chunk_to_lds(w_srd, lds_base + (kRingX + (sub & 1)) * kHalfSlot + (8 * wave + c) * 1024,
+                          voff ^ ((c & 1) * 64), uni(c * row8 + sub * kSub * 2));
+    };
+
+    f32x16 acc[4][4]; // [token block][feature block of the wave]
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][i][r] = 0.f;
+
+    // operand address of row c of a 32-row block, k-step 0 of a slot; k-step j is the same address ^ 32 j
+    const int rd0 = 128 * c + 16 * (hh ^ ((c >> 1) & 7));
+    const int x_rd = 16 * tg * 1024 + rd0, w_rd = kRingX * kHalfSlot + 16 * fg * 1024 + rd0;
+    uint4 xa[4], wa[4], xb[4], wb[4];
+    auto fetch = [&](int sub, int step, uint4 (&xo)[4], uint4 (&wo)[4]) {
+        const char *xs = lds + (sub % kRingX) * kHalfSlot, *ws = lds + (sub & 1) * kHalfSlot;
+        const int flip = step * 32;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            xo[i] = *(const uint4 *)(xs + ((x_rd ^ flip) + i * 4096));
+            wo[i] = *(const uint4 *)(ws + ((w_rd ^ flip) + i * 4096));
+        }
+    };
+    // 16 MFMAs; after every four of them `between(i)` may send loads out.  All loads of a slot at
+    // once would hold the wave at the memory pipeline (16 cycles per load, four waves) while the
+    // matrix cores idle: measured, the two phases simply added up.
+    auto multiply = [&](const uint4 (&xo)[4], const uint4 (&wo)[4], auto between) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                acc[t][i] = M::mfma(__builtin_bit_cast(vec8, wo[i]), __builtin_bit_cast(vec8, xo[t]), acc[t][i]);
+            between(i);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    auto nothing = [](int) {};
+
+#pragma unroll
+    for (int c = 0; c < 8; ++c) request_x(0, c);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) request_w(0, c);
+    if (1 < n_sub) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) request_x(1, c);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) xb[i] = wb[i] = make_uint4(0, 0, 0, 0); // the first turn multiplies zeros
+    for (int sub = 0; sub < n_sub; ++sub) {
+        // own loads of this slot; the eight token loads of the next slot, issued after them, may still fly
+        if (sub + 1 < n_sub) __builtin_amdgcn_s_waitcnt(kVmcnt0 | 8);
+        else __builtin_amdgcn_s_waitcnt(kVmcnt0);
+        __syncthreads();
+        const bool more_w = sub + 1 < n_sub, more_x = sub + 2 < n_sub;
+        fetch(sub, 0, xa, wa);
+        multiply(xb, wb, [&](int i) { // last step of the slot before
+            if (more_w) request_w(sub + 1, i);
+        });
+        fetch(sub, 1, xb, wb);
+        multiply(xa, wa, [&](int i) {
+            if (more_w) request_w(sub + 1, 4 + i);
+        });
+        fetch(sub, 2, xa, wa);
+        multiply(xb, wb, [&](int i) {
+            if (more_x) request_x(sub + 2, i);
+        });
+        fetch(sub, 3, xb, wb);
+        multiply(xa, wa, [&](int i) {
+            if (more_x) request_x(sub + 2, 4 + i);
+        });
+    }
+    multiply(xb, wb, nothing);
+
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int64_t m = tok0 + 128 * tg + 32 * t + c;
+#pragma unroll
+        for (int h = 0; h < HW; ++h) {
+            const int kh = (ft * kGT + 128 * fg) / D + h;
+            f32x16(&part)[NB] = *(f32x16(*)[NB]) & acc[t][h * NB];
+            if (m < n_tok) finish_token<M, D>(a, part, m, kh % hkv, kh >= hkv, hh);
+        }
+    }
+}
+
 // Adds up the partial sums of the splits.  One thread per (token, K or V head, half hh, feature
 // block nb < NB/2, group g4): the four features 32 nb + 8 g4 + 4 hh .. + 3 of the head and their
 // rotary partners d/2 further on, i.e. what finish_token needs together.
@@ -409,6 +594,13 @@ template <typename M, int D> hipError_t launch_j(const ProjArgs &a, int n_splits
     const int64_t n_tok = (int64_t)a.batch * a.max_new;
     const int64_t tiles = (n_tok + kTokens - 1) / kTokens;
     if (tiles > 65535 || 2 * a.slot.n_kv_heads > 65535) return hipErrorInvalidValue;
+    if (n_splits == 1 && (2 * a.slot.n_kv_heads * D) % kGT == 0 && a.hidden % kSub == 0 && a.hidden <= (1 << 20) &&
+        std::getenv("SKV_PROJECT_KERNEL") == nullptr) {
+        const int64_t groups = ((n_tok + kGT - 1) / kGT) * (2 * a.slot.n_kv_heads * D / kGT);
+        if (groups > 0x7fffffff) return hipErrorInvalidValue;
+        project_append_tile_kernel<M, D><<<dim3((unsigned)groups), 256, 0, stream>>>(a);
+        return hipGetLastError();
+    }
     if (n_splits == 1) {
         project_append_wide_kernel<M, D><<<dim3((unsigned)a.slot.n_kv_heads, (unsigned)tiles), kThreads, 0, stream>>>(a);
         return hipGetLastError();

@@ -42,6 +42,12 @@ CASES = [
     # few tokens and a long hidden axis: the launch splits the hidden axis and sums fp32 partials
     ("bf16", 2, 128, 2048, [50, 50, 50], [49, 0, 7], [1, 1, 1], 1, True, True),
     ("f16", 1, 64, 1024, [40], [2], [33], 33, False, True),
+    # prompt-sized launches (one split, 256 x 256 tiles straight into LDS): ragged last tile whose
+    # upper waves stage no token at all, 2 to 10 ring slots, tile order by XCD (8 | token tiles) and plain
+    ("bf16", 4, 128, 64, [4200], [0], [4111], 4111, False, True),
+    ("f16", 8, 64, 128, [1100, 1100, 1100, 1100], [0, 5, 0, 76], [1024, 1024, 1024, 1024], 1024, True, True),
+    ("bf16", 8, 128, 192, [2100], [17], [2048], 2048, True, False),
+    ("f16", 2, 128, 320, [8300, 8300], [0, 0], [8192, 7000], 8192, False, True),
 ]
 
 
