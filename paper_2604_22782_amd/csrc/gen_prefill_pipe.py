@@ -19,9 +19,12 @@ so the three stages of three consecutive half tiles are in flight at once.
 
 K/V tiles (64 keys) go from HBM straight into LDS (buffer_load ... lds, no registers): lane L of
 such a load writes 16 bytes at M0 + 16 L, so one instruction fills a 1 KiB chunk = 4 rows.  Inside
-a chunk the 16-byte piece p of row r sits at 64 p + 16 r (piece-major), and chunks are 1088 bytes
-apart: both the 128-bit K operand reads (16 lanes = 16 consecutive rows, one piece) and the
-transposing 64-bit V reads (4 rows x 32 bytes per 16 lanes) then touch every bank exactly once.
+a chunk the 16-byte piece p of row r sits at 256 (p / 4) + 64 r + 16 (p % 4), so that four
+neighbouring lanes fetch the 64 contiguous bytes of one row (the vector cache handles them as one
+access), and chunks are 1040 bytes apart: both the 128-bit K operand reads (16 lanes = 16
+consecutive rows, one piece) and the transposing 64-bit V reads (4 rows x 32 bytes per 16 lanes)
+then touch every bank exactly once.  (SKV_GEN_ROWQ=0 writes the earlier layout, 64 p + 16 r with
+chunks 1088 apart: a row per lane, four cache accesses where the other needs one.)
 Four tile stages form a ring.  Tile t+3 is requested in the second half of tile t (its stage held
 tile t-1, last read in the first half); one barrier per tile, placed after every wave has waited
 for its own loads of tile t+1 and for its last reads of tile t-1, publishes the former and
@@ -48,7 +51,11 @@ from __future__ import annotations
 import os
 import sys
 
-CHUNK = 1088              # 4 rows x 256 bytes + 64 bytes of padding
+# ROWQ = layout of a 1 KiB chunk (4 rows x 16 pieces of 16 bytes).  1: lane L = 16 (p / 4) + 4 r + p % 4,
+# four neighbouring lanes fetch the 64 contiguous bytes of one row (one access of the vector cache
+# per four lanes), chunks 1040 bytes apart.  0: lane L = 4 p + r (a row per lane), chunks 1088 apart.
+ROWQ = os.environ.get("SKV_GEN_ROWQ", "1") == "1"
+CHUNK = 1040 if ROWQ else 1088   # 4 rows x 256 bytes + padding that turns the bank groups from chunk to chunk
 T_BYTES = 16 * CHUNK      # one tensor (K or V) of a 64-key tile
 STAGE = 2 * T_BYTES       # K then V
 N_STAGE = 4
@@ -311,7 +318,8 @@ def rescale_blocks(A: Asm, tagid: str):
 # ---- operand reads -----------------------------------------------------------------------------
 def k_read(A: Asm, addr: int, kb: int, g: int, tag):
     dst = KO + 4 * (g % RING)
-    A.lds_op(f"ds_read_b128 {vr(dst, 4)}, {vr(addr)} offset:{kb * 8 * CHUNK + g * 128}", tag)
+    step = 256 * (g // 2) + 32 * (g % 2) if ROWQ else 128 * g     # pieces 2 g, 2 g + 1 of the row
+    A.lds_op(f"ds_read_b128 {vr(dst, 4)}, {vr(addr)} offset:{kb * 8 * CHUNK + step}", tag)
 
 
 def v_read(A: Asm, addr: int, kb: int, g: int, tag_lo, tag_hi):
@@ -483,7 +491,7 @@ def bad_block_paths(A: Asm, tags):
 
 
 def tile_load(which: str, i: int, base_sreg: int):
-    """Chunk 4 w + i of K or V: lane L fetches piece L / 4 of row 4 (4 w + i) + L % 4.  Returns
+    """Chunk 4 w + i of K or V: lane L fetches its piece of its row of the chunk (see ROWQ).  Returns
     (M0 write, load): another instruction must be issued between the two."""
     srd, off = ("%[srdk]", 0) if which == "k" else ("%[srdv]", T_BYTES)
     return (f"s_add_u32 m0, {sr(base_sreg)}, {off + i * CHUNK}",
@@ -617,8 +625,12 @@ def generate(dt: str) -> list[str]:
     e(f"v_lshrrev_b32_e32 {vr(TMP[0])}, 2, {vr(COL)}")
     e(f"v_mul_u32_u24_e32 {vr(TMP[0])}, {CHUNK}, {vr(TMP[0])}")
     e(f"v_and_b32_e32 {vr(TMP[1])}, 3, {vr(COL)}")
-    e(f"v_lshlrev_b32_e32 {vr(TMP[1])}, 4, {vr(TMP[1])}")
-    e(f"v_lshl_add_u32 {vr(TMP[1])}, {vr(HH)}, 6, {vr(TMP[1])}")
+    if ROWQ:      # 64 r + 16 hh (+ 256 (s / 2) + 32 (s % 2) per k step)
+        e(f"v_lshlrev_b32_e32 {vr(TMP[1])}, 6, {vr(TMP[1])}")
+        e(f"v_lshl_add_u32 {vr(TMP[1])}, {vr(HH)}, 4, {vr(TMP[1])}")
+    else:         # 16 r + 64 hh (+ 128 s per k step)
+        e(f"v_lshlrev_b32_e32 {vr(TMP[1])}, 4, {vr(TMP[1])}")
+        e(f"v_lshl_add_u32 {vr(TMP[1])}, {vr(HH)}, 6, {vr(TMP[1])}")
     e(f"v_add3_u32 {vr(KL)}, {vr(TMP[0])}, {vr(TMP[1])}, %[lds]")
     # V^T operand through the transposing read: lane (sl = lane % 16, a = (lane / 16) % 2, hh) reads
     # 8 bytes of key row 4 hh + sl / 4 (chunk hh, row sl / 4), d offset 16 a + 4 (sl % 4) of the d
@@ -626,29 +638,37 @@ def generate(dt: str) -> list[str]:
     e(f"v_and_b32_e32 {vr(TMP[0])}, 15, {vr(LANE)}")
     e(f"v_bfe_u32 {vr(TMP[1])}, {vr(LANE)}, 4, 1")
     e(f"v_mul_u32_u24_e32 {vr(TMP[2])}, {CHUNK}, {vr(HH)}")
-    e(f"v_lshl_add_u32 {vr(TMP[2])}, {vr(TMP[1])}, 7, {vr(TMP[2])}")
+    # byte offset in the chunk: ROWQ 64 row + 32 a + 16 (piece % 2), else 128 a + 64 (piece % 2) + 16 row
+    e(f"v_lshl_add_u32 {vr(TMP[2])}, {vr(TMP[1])}, {5 if ROWQ else 7}, {vr(TMP[2])}")
     e(f"v_bfe_u32 {vr(TMP[3])}, {vr(TMP[0])}, 1, 1")
-    e(f"v_lshl_add_u32 {vr(TMP[2])}, {vr(TMP[3])}, 6, {vr(TMP[2])}")
+    e(f"v_lshl_add_u32 {vr(TMP[2])}, {vr(TMP[3])}, {4 if ROWQ else 6}, {vr(TMP[2])}")
     e(f"v_lshrrev_b32_e32 {vr(TMP[3])}, 2, {vr(TMP[0])}")
-    e(f"v_lshl_add_u32 {vr(TMP[2])}, {vr(TMP[3])}, 4, {vr(TMP[2])}")
+    e(f"v_lshl_add_u32 {vr(TMP[2])}, {vr(TMP[3])}, {6 if ROWQ else 4}, {vr(TMP[2])}")
     e(f"v_and_b32_e32 {vr(TMP[3])}, 1, {vr(TMP[0])}")
     e(f"v_lshl_add_u32 {vr(TMP[2])}, {vr(TMP[3])}, 3, {vr(TMP[2])}")
     e(f"s_add_u32 {sr(S_TMP)}, %[lds], {T_BYTES}")
     e(f"v_add_u32_e32 {vr(VL)}, {sr(S_TMP)}, {vr(TMP[2])}")
-    # staging: wave w fills chunks 4 w .. 4 w + 3 of each tensor; its lane L fetches piece L / 4 of
-    # row L % 4 of the chunk
+    # staging: wave w fills chunks 4 w .. 4 w + 3 of each tensor
     e(f"s_lshl_b32 {sr(S_TMP)}, %[wv], {2 + CPW.bit_length() - 1}")
-    e(f"v_and_b32_e32 {vr(TMP[0])}, 3, {vr(LANE)}")
-    e(f"v_add_u32_e32 {vr(ROWB)}, {sr(S_TMP)}, {vr(TMP[0])}")
-    e(f"v_lshrrev_b32_e32 {vr(TMP[0])}, 2, {vr(LANE)}")
-    e(f"v_lshlrev_b32_e32 {vr(PIECE)}, 4, {vr(TMP[0])}")
+    if ROWQ:      # row (L / 4) % 4, piece 4 (L / 16) + L % 4
+        e(f"v_bfe_u32 {vr(TMP[0])}, {vr(LANE)}, 2, 2")
+        e(f"v_add_u32_e32 {vr(ROWB)}, {sr(S_TMP)}, {vr(TMP[0])}")
+        e(f"v_lshrrev_b32_e32 {vr(TMP[0])}, 4, {vr(LANE)}")
+        e(f"v_and_b32_e32 {vr(TMP[1])}, 3, {vr(LANE)}")
+        e(f"v_lshl_add_u32 {vr(TMP[0])}, {vr(TMP[0])}, 2, {vr(TMP[1])}")
+        e(f"v_lshlrev_b32_e32 {vr(PIECE)}, 4, {vr(TMP[0])}")
+    else:         # row L % 4, piece L / 4
+        e(f"v_and_b32_e32 {vr(TMP[0])}, 3, {vr(LANE)}")
+        e(f"v_add_u32_e32 {vr(ROWB)}, {sr(S_TMP)}, {vr(TMP[0])}")
+        e(f"v_lshrrev_b32_e32 {vr(TMP[0])}, 2, {vr(LANE)}")
+        e(f"v_lshlrev_b32_e32 {vr(PIECE)}, 4, {vr(TMP[0])}")
     e(f"s_mul_i32 {sr(S_WBASE)}, %[wv], {CPW * CHUNK}")
     e(f"s_add_u32 {sr(S_WBASE)}, {sr(S_WBASE)}, %[lds]")
     if PAGED:
         # rows are addressed inside the wave's block: constants (4 i + L % 4) rows + piece; the
         # block's offset is the scalar part, from the table
         e(f"s_mov_b32 {sr(S_R0W)}, {sr(S_TMP)}")                  # first row of the wave's part of a tile
-        e(f"v_and_b32_e32 {vr(V_L4)}, 3, {vr(LANE)}")
+        e(f"v_bfe_u32 {vr(V_L4)}, {vr(LANE)}, 2, 2" if ROWQ else f"v_and_b32_e32 {vr(V_L4)}, 3, {vr(LANE)}")
         for i in range(CPW):
             e(f"v_add_u32_e32 {vr(TMP[0])}, {4 * i}, {vr(V_L4)}")
             e(f"v_mad_u32_u24 {vr(VBO[i])}, {vr(TMP[0])}, %[krb], {vr(PIECE)}")

@@ -84,10 +84,29 @@ def test_hazard_check_accepts_the_stream_and_rejects_a_planted_read(nq, paged):
     G.check_mfma_results(ok)
 
 
-def test_lds_layout_is_bank_conflict_free():
-    """64 banks x 4 bytes.  K operand: a pass of 16 lanes reads 16 bytes each of rows c = 0..15, same
-    piece; V operand: a pass of 16 lanes reads 8 bytes each (4 rows x 4 x 8 bytes).  Every pass must
-    touch each bank at most once."""
+def _piece_offset(rowq, piece, row):
+    """Byte offset inside a 1 KiB chunk of the 16-byte piece `piece` (0..15) of row `row` (0..3)."""
+    return 256 * (piece >> 2) + 64 * row + 16 * (piece & 3) if rowq else 64 * piece + 16 * row
+
+
+@pytest.mark.parametrize("rowq", [1, 0])
+def test_lds_layout_is_bank_conflict_free(rowq):
+    """64 banks x 4 bytes.  A load writes lane L's 16 bytes at 16 L of its chunk: the lane-to-(row,
+    piece) map of the layout must fill the chunk exactly, with four neighbouring lanes on one row's
+    64 contiguous bytes in the row-quad layout.  K operand: a pass of 16 lanes reads 16 bytes each
+    of rows c = 0..15, same piece; V operand: a pass of 16 lanes reads 8 bytes each (4 rows x 4 x 8
+    bytes).  Every pass must touch each bank at most once."""
+    chunk = 1040 if rowq else 1088
+    assert G.CHUNK == (1040 if G.ROWQ else 1088)
+    for lane in range(64):
+        row, piece = ((lane >> 2) & 3, 4 * (lane >> 4) + (lane & 3)) if rowq else (lane & 3, lane >> 2)
+        assert _piece_offset(rowq, piece, row) == 16 * lane
+    if rowq:
+        for quad in range(16):
+            rows = {(lane >> 2) & 3 for lane in range(4 * quad, 4 * quad + 4)}
+            pieces = sorted(4 * (lane >> 4) + (lane & 3) for lane in range(4 * quad, 4 * quad + 4))
+            assert len(rows) == 1 and pieces == list(range(pieces[0], pieces[0] + 4)) and pieces[0] % 4 == 0
+
     def banks(addr, nbytes):
         return [((addr + b) // 4) % 64 for b in range(0, nbytes, 4)]
     for hh in range(2):
@@ -95,16 +114,15 @@ def test_lds_layout_is_bank_conflict_free():
             for base_c in (0, 16):
                 used = []
                 for c in range(base_c, base_c + 16):
-                    a = (c >> 2) * G.CHUNK + 16 * (c & 3) + 64 * hh + 128 * s
-                    used += banks(a, 16)
+                    used += banks((c >> 2) * chunk + _piece_offset(rowq, 2 * s + hh, c & 3), 16)
                 assert len(used) == len(set(used)) == 64
     for hh in range(2):
         for a in range(2):
             for db in range(4):
                 used = []
-                for sl in range(16):
-                    addr = hh * G.CHUNK + 128 * a + 64 * ((sl & 3) >> 1) + 16 * (sl >> 2) + 8 * (sl & 1) + 256 * db
-                    used += banks(addr, 8)
+                for sl in range(16):   # key row 4 hh + sl / 4, d offset 32 db + 16 a + 4 (sl % 4): 8 bytes
+                    d_byte = 2 * (32 * db + 16 * a + 4 * (sl & 3))
+                    used += banks(hh * chunk + _piece_offset(rowq, d_byte // 16, sl >> 2) + d_byte % 16, 8)
                 assert len(used) == len(set(used)) == 32
     # the ring fits the 160 KiB of LDS of a compute unit
     assert G.LDS_BYTES <= 160 * 1024
