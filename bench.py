@@ -323,15 +323,18 @@ def run_project(args, torch, skv, H, configs):
         nbytes = 2 * (2 * F * hidden + tokens * hidden + 2 * tokens * F)     # weights + x read, K/V rows written
         r = {"tokens": tokens, "hidden": hidden, "launch_us": round(us, 1),
              "tflops": round(flops / (us * 1e-6) / 1e12, 1), "gbs": round(nbytes / (us * 1e-6) / 1e9, 1)}
+        parts = [measured_traffic(kn) for kn in ("project_append_kernel", "project_finish_kernel")]
+        split_traffic = sum(parts) if all(p is not None for p in parts) else None
         if regime == "prefill":
             r["roofline"] = {"bound": "mfma", "kernel": "project_append_tile_kernel", "achieved": r["tflops"],
                              "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                             "frac": round(r["tflops"] / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                             "frac": round(r["tflops"] / MFMA_BF16_PEAK_TFLOPS, 4),
+                             "traffic": measured_traffic("project_append_tile_kernel"),
                              "algorithmic_flops_per_launch": flops}
         else:
             r["roofline"] = {"bound": "hbm", "kernel": "project_append_kernel + project_finish_kernel", "achieved": r["gbs"],
                              "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(r["gbs"] / HBM_PEAK_GBS, 4),
-                             "traffic": None, "algorithmic_bytes_per_launch": nbytes}
+                             "traffic": split_traffic, "algorithmic_bytes_per_launch": nbytes}
         out[regime] = r
         cache.free()
         torch.cuda.empty_cache()
