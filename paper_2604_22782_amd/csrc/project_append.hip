@@ -545,9 +545,24 @@ __global__ __launch_bounds__(256) void project_finish_kernel(ProjArgs a, int n_s
     if (m >= n_tok) return;
     const int f_lo = 32 * nb + 8 * g4 + 4 * hh, f_hi = f_lo + D / 2;
     float4 lo = make_float4(0.f, 0.f, 0.f, 0.f), hi = lo;
-    for (int s = 0; s < n_splits; ++s) {
-        const float *part = a.partial + (((int64_t)s * n_tok + m) * 2 * hkv + kh) * D;
-        const float4 u = *(const float4 *)(part + f_lo), v = *(const float4 *)(part + f_hi);
+    const float *part0 = a.partial + (m * 2 * hkv + kh) * D;
+    const int64_t split_stride = n_tok * 2 * hkv * D;
+    int s = 0;
+    for (; s + 4 <= n_splits; s += 4) { // eight loads in flight (the split counts are powers of two); summed in split order
+        float4 u[4], v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            u[j] = *(const float4 *)(part0 + (s + j) * split_stride + f_lo);
+            v[j] = *(const float4 *)(part0 + (s + j) * split_stride + f_hi);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            lo.x += u[j].x; lo.y += u[j].y; lo.z += u[j].z; lo.w += u[j].w;
+            hi.x += v[j].x; hi.y += v[j].y; hi.z += v[j].z; hi.w += v[j].w;
+        }
+    }
+    for (; s < n_splits; ++s) {
+        const float4 u = *(const float4 *)(part0 + s * split_stride + f_lo), v = *(const float4 *)(part0 + s * split_stride + f_hi);
         lo.x += u.x; lo.y += u.y; lo.z += u.z; lo.w += u.w;
         hi.x += v.x; hi.y += v.y; hi.z += v.z; hi.w += v.w;
     }
