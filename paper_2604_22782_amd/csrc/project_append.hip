@@ -642,6 +642,10 @@ int project_append_splits(int n_kv_heads, int64_t n_tokens, int hidden) {
     const int64_t tiles = (n_tokens + kTokens - 1) / kTokens;
     const int64_t groups = 2 * (int64_t)n_kv_heads * tiles;
     if (groups >= 128) return 1;
+    if (const char *e = std::getenv("SKV_PROJECT_SPLITS")) { // tuning aid: a power of two that divides the tiles of the hidden axis
+        const int want = atoi(e);
+        if (want >= 1 && (want & (want - 1)) == 0 && hidden / kKT % want == 0) return want;
+    }
     int splits = 1;
     while (groups * splits < 256 && hidden / kKT % (2 * splits) == 0 && hidden / (2 * splits) >= 128) splits *= 2;
     return splits;
