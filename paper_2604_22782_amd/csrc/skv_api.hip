@@ -617,7 +617,14 @@ const char *skv_status_str(skv_status_t s) {
 
 skv_status_t skv_calib_mfma_bf16(const void *operands, float *sink, int32_t blocks, int32_t iters, void *stream) {
     if (!operands || !sink || blocks < 1 || iters < 1 || iters > (1 << 20)) return SKV_ERR_INVALID_ARG;
-    const hipError_t e = skv::launch_calib_mfma(operands, sink, blocks, iters, (hipStream_t)stream);
+    const hipError_t e = skv::launch_calib_mfma(operands, sink, blocks, iters, 0, (hipStream_t)stream);
+    return e == hipSuccess ? SKV_OK : hip_fail(e);
+}
+
+skv_status_t skv_calib_mfma_mix_bf16(const void *operands, float *sink, int32_t blocks, int32_t iters, int32_t mix,
+                                     void *stream) {
+    if (!operands || !sink || blocks < 1 || iters < 1 || iters > (1 << 20) || mix < 0 || mix > 3) return SKV_ERR_INVALID_ARG;
+    const hipError_t e = skv::launch_calib_mfma(operands, sink, blocks, iters, mix, (hipStream_t)stream);
     return e == hipSuccess ? SKV_OK : hip_fail(e);
 }
 

@@ -99,7 +99,7 @@ struct TrainBwdArgs {
 hipError_t launch_train_bwd(const TrainBwdArgs &a, int dtype, int head_dim, hipStream_t stream);
 
 // Measurement aid: back-to-back MFMAs on caller-given operands (16 blocks of 64 lanes x 16 bytes).
-hipError_t launch_calib_mfma(const void *operands, float *sink, int blocks, int iters, hipStream_t stream);
+hipError_t launch_calib_mfma(const void *operands, float *sink, int blocks, int iters, int mix, hipStream_t stream);
 
 void set_last_kernel_name(const char *name);
 

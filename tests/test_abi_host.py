@@ -114,6 +114,7 @@ def test_null_handles_and_no_device_behaviour():
     assert lib.skv_attn_prefill(None, 0, None, None, None, None, 1, 1, ctypes.c_float(1.0), None) == 1
     assert lib.skv_cache_bytes(None, None) == 1
     assert lib.skv_calib_mfma_bf16(None, None, 1, 1, None) == 1
+    assert lib.skv_calib_mfma_mix_bf16(None, None, 1, 1, 0, None) == 1
     assert lib.skv_kv_project_append(None, 0, None, None, None, None, None, 0, None, ctypes.c_float(0.0), None, None, 1, 64, None, 0, None) == 1
     assert lib.skv_kv_project_workspace_bytes(None, 1, 64, ctypes.byref(n)) == 1
     import torch

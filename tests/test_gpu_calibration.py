@@ -31,5 +31,12 @@ def test_mfma_calibration_kernel_result():
             rows = [8 * (r // 4) + 4 * (l // 32) + r % 4 for r in range(16)]
             total[l] += acc[rows, l % 32].sum()
     assert np.allclose(got, total[None, :], rtol=1e-4, atol=1e-3)
+    # the variants with vector and LDS work between the MFMAs compute the same thing
+    for mix in (0, 1, 2, 3):
+        other = torch.full_like(sink, float("nan"))
+        skv.skv_calib_mfma_mix_bf16(ops.cuda(), other, blocks, iters, mix)
+        assert torch.equal(other, sink), mix
+    with pytest.raises(skv.SkvError):
+        skv.skv_calib_mfma_mix_bf16(ops.cuda(), sink, blocks, iters, 4)
     with pytest.raises(skv.SkvError):
         skv.skv_calib_mfma_bf16(ops.cuda(), sink, blocks, 0)
