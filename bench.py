@@ -310,9 +310,10 @@ def run_project(args, torch, skv, H, configs):
         start = torch.full((w.batch,), S - new, dtype=torch.int32, device="cuda")
         lens = torch.full((w.batch,), new, dtype=torch.int32, device="cuda")
         layer = w.owner_layers[0]
-        reps = 20 if regime == "prefill" else 200
+        reps = 40 if regime == "prefill" else 200
+        warm = 30 if regime == "prefill" else 50     # ~15 ms of load: the clocks need that long to settle after an idle gap
         ws = torch.empty(max(skv.skv_kv_project_workspace_bytes(cache, new, hidden), 4) // 4, dtype=torch.float32, device="cuda")
-        for _ in range(3):
+        for _ in range(warm):
             skv.skv_kv_project_append(cache, layer, x, wk, wv, cos, sin, start, lens, new, ws)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
