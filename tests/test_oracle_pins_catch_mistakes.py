@@ -16,6 +16,8 @@ def _mutant(name, old, new):
     path = os.path.join(ROOT, "oracle", name + ".py")
     src = open(path).read()
     assert src.count(old) == 1, (name, old)          # the edit must hit exactly one place
+    if old.startswith("    if k_norm_weight is not None:"):    # the normalisation moves behind the rotation
+        src = src.replace("    return k, v", "    if k_norm_weight is not None:\n        k = k / np.sqrt((k * k).mean(axis=-1, keepdims=True) + k_norm_eps) * k_norm_weight\n    return k, v")
     mod = types.ModuleType(f"oracle.{name}_mutant")
     mod.__package__ = "oracle"
     mod.__file__ = path
@@ -74,13 +76,21 @@ PROJECT_MISTAKES = [
     ("k[..., half:] = hi * c + lo * s", "k[..., half:] = hi * c"),                      # term dropped
     ("c = rope_cos[positions][:, :, None, :]", "c = rope_cos[positions * 0][:, :, None, :]"),   # position ignored
     ("lo, hi = k[..., :half].copy(), k[..., half:].copy()", "lo, hi = k[..., 0::2].copy(), k[..., 1::2].copy()"),  # interleaved pairs
+    # the optional per-head normalisation of K
+    ("(k * k).mean(axis=-1, keepdims=True) + k_norm_eps", "(k * k).sum(axis=-1, keepdims=True) + k_norm_eps"),   # sum for mean
+    ("(k * k).mean(axis=-1, keepdims=True) + k_norm_eps", "(k * k).mean(axis=-1, keepdims=True)"),               # eps dropped
+    ("(k * k).mean(axis=-1, keepdims=True) + k_norm_eps", "(k * k).mean(axis=(-2, -1), keepdims=True) + k_norm_eps"),   # over all heads
+    ("+ k_norm_eps) * k_norm_weight", "+ k_norm_eps) * k_norm_weight[::-1]"),                                     # weight reversed
+    ("k = k / np.sqrt((k * k).mean(", "v = v / np.sqrt((k * k).mean("),                                          # V normalised, K not
+    ("    if k_norm_weight is not None:\n        k = k / np.sqrt((k * k).mean(axis=-1, keepdims=True) + k_norm_eps) * k_norm_weight\n    if rope_cos is not None:",
+     "    if rope_cos is not None:"),                                                                             # (first half of moving the normalisation behind the rotation)
 ]
 
 
 @pytest.mark.parametrize("old,new", PROJECT_MISTAKES)
 def test_projection_oracle_pins_catch(old, new, monkeypatch):
     from tests import test_project_oracle_pins as pins
-    tests = [pins.test_identity_weights_and_linearity, pins.test_rotation_properties]
+    tests = [pins.test_identity_weights_and_linearity, pins.test_rotation_properties, pins.test_key_normalisation]
     assert _pins_fail(pins, "P", _mutant("project_oracle", old, new), tests, monkeypatch), (old, new)
 
 

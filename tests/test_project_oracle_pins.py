@@ -91,3 +91,10 @@ def test_key_normalisation():
     ke, _ = P.project_kv(x, wk, wv, Hkv, D, k_norm_weight=ones, k_norm_eps=0.5)
     kp, _ = P.project_kv(x, wk, wv, Hkv, D)
     assert np.allclose(ke, kp / np.sqrt((kp * kp).mean(axis=-1, keepdims=True) + 0.5))
+    # the normalisation (weight included) comes BEFORE the rotation: rotating the normalised,
+    # unrotated keys (identity weights, no normalisation) gives the same result
+    kn, _ = P.project_kv(x, wk, wv, Hkv, D, k_norm_weight=w, k_norm_eps=1e-3)
+    eye = np.eye(hidden)
+    want, _ = P.project_kv(kn.reshape(B, T, hidden), eye, eye, Hkv, D, pos, cos, sin)
+    got, _ = P.project_kv(x, wk, wv, Hkv, D, pos, cos, sin, k_norm_weight=w, k_norm_eps=1e-3)
+    assert np.allclose(got, want) and not np.allclose(got, kn)
