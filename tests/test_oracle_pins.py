@@ -294,6 +294,9 @@ def test_append_only_for_owner_layers_and_bit_image():
     assert not c.bits_k.any() and not c.bits_v.any()
     c.append(2, kf, vf, kb, vb, [4, 7], [3, 2])
     assert np.array_equal(c.bits_k[1, 0, 4:7], kb[0]) and np.array_equal(c.bits_v[1, 1, 7:9], vb[1, :2])
+    # the value image follows the same rows: K from the K rows, V from the V rows
+    assert np.array_equal(c.vals_k[1, 0, 4:7], kf[0]) and np.array_equal(c.vals_v[1, 0, 4:7], vf[0])
+    assert np.array_equal(c.vals_k[1, 1, 7:9], kf[1, :2]) and np.array_equal(c.vals_v[1, 1, 7:9], vf[1, :2])
     assert not c.bits_k[0].any() and not c.bits_k[1, 1, :7].any() and not c.bits_k[1, 1, 9:].any()
     assert not c.bits_k[1, 0, :4].any() and not c.bits_k[1, 0, 7:].any()
     with pytest.raises(ValueError):

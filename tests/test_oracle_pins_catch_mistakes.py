@@ -1,4 +1,4 @@
-"""The pins of the two newer oracles must fail when a plausible mistake is planted in the oracle:
+"""The pins of the oracles must fail when a plausible mistake is planted in the oracle:
 each case edits one line of the oracle's source (a dropped term, a sign, a transposition, a wrong
 index), loads the edited copy as a module and runs the pin tests against it.  Everything here is
 CPU-only and touches no GPU code."""
@@ -18,6 +18,7 @@ def _mutant(name, old, new):
     assert src.count(old) == 1, (name, old)          # the edit must hit exactly one place
     if old.startswith("    if k_norm_weight is not None:"):    # the normalisation moves behind the rotation
         src = src.replace("    return k, v", "    if k_norm_weight is not None:\n        k = k / np.sqrt((k * k).mean(axis=-1, keepdims=True) + k_norm_eps) * k_norm_weight\n    return k, v")
+    import oracle  # noqa: F401  (the edited copy keeps the package's relative imports)
     mod = types.ModuleType(f"oracle.{name}_mutant")
     mod.__package__ = "oracle"
     mod.__file__ = path
@@ -31,8 +32,8 @@ def _pins_fail(test_module, attr, mutant, tests, monkeypatch):
     for t in tests:
         try:
             t()
-        except Exception:                             # AssertionError, or an error the mistake provokes
-            failed.append(t.__name__)
+        except (Exception, pytest.fail.Exception):    # AssertionError, an error the mistake provokes, "did not raise"
+            failed.append(getattr(t, "__name__", "case"))
     return failed
 
 
@@ -102,3 +103,66 @@ def test_the_unedited_oracles_pass_through_the_same_harness(monkeypatch):
     assert _pins_fail(tp, "T", same_t, [tp.test_forward_closed_forms, tp.test_backward_invariants,
                                         tp.test_ablation_schemes_of_sec_4_2_3], monkeypatch) == []
     assert _pins_fail(pp, "P", same_p, [pp.test_identity_weights_and_linearity, pp.test_rotation_properties], monkeypatch) == []
+
+MAIN_MISTAKES = [
+    ("route.append(max(earlier))", "route.append(min(earlier))"),                          # farthest instead of nearest owner
+    ("        if route[r] != r:\n", "        if False:\n"),                                # a source that owns no slot is accepted
+    ("if not 0 <= r <= l:", "if not 0 <= r:"),                                              # a later layer as source is accepted
+    ("rank = {l: i for i, l in enumerate(own)}", "rank = {l: l for i, l in enumerate(own)}"),   # slot = layer number, not its rank
+    ("return 2 * n_cached_layers * n_kv_heads * head_dim * elem_bytes", "return n_cached_layers * n_kv_heads * head_dim * elem_bytes"),   # K only
+    ("    scores = scale * (K @ q)\n", "    scores = K @ q\n"),                             # scale dropped
+    ("    return w / np.sum(w)\n", "    return w / np.max(w)\n"),                           # normalised by the maximum
+    ("K = cache.vals_k[s, b, : pos_q + 1, h // G, :]", "K = cache.vals_k[s, b, : pos_q, h // G, :]"),        # the token does not see its own key
+    ("V = cache.vals_v[s, b, : pos_q + 1, h // G, :]", "V = cache.vals_v[s, b, : pos_q + 1, h % hkv, :]"),   # interleaved instead of contiguous head groups
+    ("    s = cache.slot[layer]\n    K =", "    s = cache.slot[max(layer - 1, 0)]\n    K ="),  # the neighbour's slot
+    ("Hq, n - nq + i, q[b, i, h], scale)", "Hq, i, q[b, i, h], scale)"),                   # rows aligned to the start of the cache
+    ("Hq, n - 1, q[b, h], scale)", "Hq, n - 2, q[b, h], scale)"),                           # decode one position early
+    ("l = sum(s[1] * np.exp(s[0] - m) for s in states)", "l = sum(s[1] for s in states)"),  # merge: sums not rescaled
+    ("        if self.route[layer] != layer:\n", "        if False:\n"),                    # a non-owner may append
+    ("self.vals_v[s, b, p0 + i] = v_vals[b, i]", "self.vals_v[s, b, p0 + i] = k_vals[b, i]"),   # V rows from K
+    ("blk = int(block_table[b][pos // block_size])", "blk = int(block_table[b][pos % block_size])"),   # block index from the offset
+]
+
+
+@pytest.mark.parametrize("old,new", MAIN_MISTAKES)
+def test_main_oracle_pins_catch(old, new, monkeypatch):
+    from tests import test_oracle_pins as pins
+    tests = []
+    for name in dir(pins):
+        if not name.startswith("test_"):
+            continue
+        fn = getattr(pins, name)
+        marks = [m for m in getattr(fn, "pytestmark", []) if m.name == "parametrize"]
+        if not marks:
+            tests.append(fn)
+            continue
+        assert len(marks) == 1                         # one parametrize per pin: expand it by hand
+        names = [a.strip() for a in marks[0].args[0].split(",")]
+        for values in marks[0].args[1]:
+            values = values if len(names) > 1 else (values,)
+            tests.append((lambda f, kw: (lambda: f(**kw)))(fn, dict(zip(names, values))))
+    assert len(tests) >= 30
+    failed = _pins_fail(pins, "O", _mutant("skv_oracle", old, new), tests, monkeypatch)
+    assert failed, (old, new)
+
+DECODER_MISTAKES = [
+    ("return x / np.sqrt((x * x).mean(axis=-1, keepdims=True) + eps) * w", "return x / np.sqrt((x * x).sum(axis=-1, keepdims=True) + eps) * w"),   # sum for mean
+    ("return np.concatenate([lo * c - hi * s, hi * c + lo * s], axis=-1)", "return np.concatenate([lo * c + hi * s, hi * c - lo * s], axis=-1)"),    # rotation the other way
+    ("        k, v = kv[src]\n", "        k, v = kv[max(s for s in kv)]\n"),                       # the latest cache instead of the routed one
+    ("k[b, : t + 1, hd // G], v[b, : t + 1, hd // G], scale)", "k[b, : t + 1, hd % n_kv_heads], v[b, : t + 1, hd % n_kv_heads], scale)"),   # head grouping
+    ("k[b, : t + 1, hd // G], v[b, : t + 1, hd // G], scale)", "k[b, :, hd // G], v[b, :, hd // G], scale)"),                                 # no causal mask
+    ('        x = x + np.einsum("btf,hf->bth", attn.reshape(B, T, -1), w[f"{l}.wo"])', '        x = np.einsum("btf,hf->bth", attn.reshape(B, T, -1), w[f"{l}.wo"])'),   # residual dropped
+    ("gate / (1.0 + np.exp(-gate)) * up", "1.0 / (1.0 + np.exp(-gate)) * up"),                       # sigmoid for silu
+    ('h2 = rmsnorm(x, w[f"{l}.norm2"])', 'h2 = rmsnorm(x, w[f"{l}.norm1"])'),                          # wrong norm weights
+    ('return np.einsum("bth,vh->btv", rmsnorm(x, w["final_norm"]), w["emb"])', 'return np.einsum("bth,vh->btv", x, w["emb"])'),   # final norm dropped
+    ("scale = 1.0 / np.sqrt(head_dim)", "scale = 1.0 / head_dim"),                                    # softmax scale
+]
+
+
+@pytest.mark.parametrize("old,new", DECODER_MISTAKES)
+def test_decoder_oracle_pins_catch(old, new, monkeypatch):
+    from tests import test_decoder_oracle_pins as pins
+    tests = [pins.test_rmsnorm_and_causality_and_skipped_projections,
+             pins.test_identity_route_is_a_standard_decoder_built_from_library_routines,
+             pins.test_a_layer_reads_the_layer_its_route_names_not_the_latest_cache]
+    assert _pins_fail(pins, "D", _mutant("decoder_oracle", old, new), tests, monkeypatch), (old, new)
