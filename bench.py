@@ -355,7 +355,7 @@ def run_e2e(args, torch, skv):
     rows = []
     for g in (1, 4):
         torch.cuda.empty_cache()
-        m = SyntheticDecoder(group=g, seed=7)
+        m = SyntheticDecoder(group=g, seed=7, qk_norm=True)   # Qwen3's block: q and k heads are RMS-normalised
         w_bytes = sum(t.numel() * t.element_size() for t in m.w.values())
         m.start(1, 2048 + 8)                                  # untimed warm-up: library set-up, GEMM heuristics
         nxt = m.prefill(torch.zeros(1, 2048, dtype=torch.int64, device="cuda")).argmax(-1)

@@ -9,7 +9,9 @@ one token at a time, Update only for owners) must give the same logits at every 
 Layer (pre-norm, as in the Llama / Qwen families the paper uses; its own text does not spell the
 block out): h = RMSNorm(x); q = rope(h Wq^T); owners: k = rope(h Wk^T), v = h Wv^T;
 x += Attn(q, k_src, v_src) Wo^T; h2 = RMSNorm(x); x += (silu(h2 Wg^T) * (h2 Wu^T)) Wd^T.
-Logits = RMSNorm(x) E^T with the embedding table E (tied).  No per-head q/k normalisation.
+Logits = RMSNorm(x) E^T with the embedding table E (tied).  Where the weights hold "{l}.q_norm" /
+"{l}.k_norm" vectors (Qwen3), every head's q and k are RMS-normalised over the head dimension and
+scaled by them before the rotation.
 """
 from __future__ import annotations
 
@@ -33,7 +35,7 @@ def rope_heads(x, positions, cos, sin):
 
 def logits_all_positions(w, route, tokens, n_q_heads, n_kv_heads, head_dim, cos, sin):
     """w: dict of float64 arrays (emb [V][h], final_norm [h], per layer l: norm1, wq, wk, wv, wo,
-    norm2, wg, wu, wd under keys f"{l}.name"; wk, wv only for owners).  tokens: int [B][T].
+    norm2, wg, wu, wd under keys f"{l}.name"; wk, wv only for owners; optional q_norm, k_norm [d]).  tokens: int [B][T].
     Returns logits [B][T][V]."""
     B, T = tokens.shape
     G = n_q_heads // n_kv_heads
@@ -43,9 +45,13 @@ def logits_all_positions(w, route, tokens, n_q_heads, n_kv_heads, head_dim, cos,
     kv = {}
     for l, src in enumerate(route):
         h = rmsnorm(x, w[f"{l}.norm1"])
-        q = rope_heads(np.einsum("bth,fh->btf", h, w[f"{l}.wq"]).reshape(B, T, n_q_heads, head_dim), pos, cos, sin)
+        q = np.einsum("bth,fh->btf", h, w[f"{l}.wq"]).reshape(B, T, n_q_heads, head_dim)
+        if f"{l}.q_norm" in w:
+            q = rmsnorm(q, w[f"{l}.q_norm"])
+        q = rope_heads(q, pos, cos, sin)
         if src == l:
-            kv[l] = P.project_kv(h, w[f"{l}.wk"], w[f"{l}.wv"], n_kv_heads, head_dim, pos, cos, sin)
+            kv[l] = P.project_kv(h, w[f"{l}.wk"], w[f"{l}.wv"], n_kv_heads, head_dim, pos, cos, sin,
+                                 k_norm_weight=w.get(f"{l}.k_norm"), k_norm_eps=1e-6)
         k, v = kv[src]
         attn = np.zeros_like(q)
         for b in range(B):

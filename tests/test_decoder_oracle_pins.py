@@ -1,11 +1,12 @@
 """Pins of the end-to-end decoder oracle (oracle/decoder_oracle.py): properties the paper's
 inference scheme fixes, checked without any cache."""
 import numpy as np
+import pytest
 
 from oracle import decoder_oracle as D
 
 
-def _weights(L, hidden, hq, hkv, d, mlp, vocab, route, seed=0, all_kv=False):
+def _weights(L, hidden, hq, hkv, d, mlp, vocab, route, seed=0, all_kv=False, qk_norm=False):
     rng = np.random.default_rng(seed)
     w = {"emb": rng.standard_normal((vocab, hidden)) * 0.3, "final_norm": np.ones(hidden)}
     for l in range(L):
@@ -19,6 +20,9 @@ def _weights(L, hidden, hq, hkv, d, mlp, vocab, route, seed=0, all_kv=False):
         w[f"{l}.wg"] = rng.standard_normal((mlp, hidden)) * 0.2
         w[f"{l}.wu"] = rng.standard_normal((mlp, hidden)) * 0.2
         w[f"{l}.wd"] = rng.standard_normal((hidden, mlp)) * 0.2
+        if qk_norm:
+            w[f"{l}.q_norm"] = rng.uniform(0.5, 1.5, d)
+            w[f"{l}.k_norm"] = rng.uniform(0.5, 1.5, d)
     return w
 
 
@@ -63,10 +67,12 @@ def test_rmsnorm_and_causality_and_skipped_projections():
     assert np.allclose(scaled[:, 0], base[:, 0]) and not np.allclose(scaled[:, 1:], base[:, 1:])
 
 
-def test_identity_route_is_a_standard_decoder_built_from_library_routines():
+@pytest.mark.parametrize("qk_norm", [False, True])
+def test_identity_route_is_a_standard_decoder_built_from_library_routines(qk_norm):
     """With every layer its own source (no sharing) the decoder is the standard pre-norm block of
-    the Llama / Qwen families.  Here it is put together from torch's routines (rms_norm, silu,
-    scaled_dot_product_attention with its own causal mask and its own grouping of the heads,
+    the Llama / Qwen families (with qk_norm: Qwen3's, whose q and k heads pass an RMS normalisation
+    of their own before the rotation).  Here it is put together from torch's routines (rms_norm,
+    silu, scaled_dot_product_attention with its own causal mask and its own grouping of the heads,
     linear) in float64; only the rotary rotation is written out, in the rotate-half form."""
     import torch
     import torch.nn.functional as F
@@ -75,7 +81,7 @@ def test_identity_route_is_a_standard_decoder_built_from_library_routines():
     route = list(range(L))
     B, T = 2, 7
     cos, sin = _tables(T, d)
-    w = _weights(L, hidden, hq, hkv, d, mlp, vocab, route, seed=5)
+    w = _weights(L, hidden, hq, hkv, d, mlp, vocab, route, seed=5, qk_norm=qk_norm)
     tok = np.random.default_rng(6).integers(0, vocab, (B, T))
     got = D.logits_all_positions(w, route, tok, hq, hkv, d, cos, sin)
 
@@ -92,6 +98,9 @@ def test_identity_route_is_a_standard_decoder_built_from_library_routines():
         q = F.linear(h, t[f"{l}.wq"]).view(B, T, hq, d).transpose(1, 2)
         k = F.linear(h, t[f"{l}.wk"]).view(B, T, hkv, d).transpose(1, 2)
         v = F.linear(h, t[f"{l}.wv"]).view(B, T, hkv, d).transpose(1, 2)
+        if qk_norm:
+            q = F.rms_norm(q, (d,), t[f"{l}.q_norm"], eps=1e-6)
+            k = F.rms_norm(k, (d,), t[f"{l}.k_norm"], eps=1e-6)
         o = F.scaled_dot_product_attention(rope(q), rope(k), v, is_causal=True, enable_gqa=True)
         x = x + F.linear(o.transpose(1, 2).reshape(B, T, hq * d), t[f"{l}.wo"])
         h2 = F.rms_norm(x, (hidden,), t[f"{l}.norm2"], eps=1e-6)

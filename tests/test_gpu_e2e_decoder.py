@@ -13,10 +13,11 @@ from workloads.e2e_decoder import SyntheticDecoder
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("hq,hkv,d,group", [(4, 2, 64, 2), (2, 1, 128, 3), (2, 2, 128, 1)])
-def test_cached_serving_matches_whole_sequence_oracle(hq, hkv, d, group):
+@pytest.mark.parametrize("hq,hkv,d,group,qk_norm", [(4, 2, 64, 2, False), (2, 1, 128, 3, False), (2, 2, 128, 1, False),
+                                                    (4, 2, 128, 2, True), (2, 1, 64, 4, True)])
+def test_cached_serving_matches_whole_sequence_oracle(hq, hkv, d, group, qk_norm):
     L, hidden, mlp, vocab, B, T, steps = 4, 128, 256, 96, 2, 70, 3
-    m = SyntheticDecoder(L, hidden, hq, hkv, d, mlp, vocab, group=group, seed=5, sigma=0.09)
+    m = SyntheticDecoder(L, hidden, hq, hkv, d, mlp, vocab, group=group, seed=5, sigma=0.09, qk_norm=qk_norm)
     print(f"\nroute {m.route}", flush=True)
     m.start(B, T + steps)
     rng = np.random.default_rng(3)

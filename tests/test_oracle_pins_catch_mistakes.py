@@ -156,6 +156,9 @@ DECODER_MISTAKES = [
     ('h2 = rmsnorm(x, w[f"{l}.norm2"])', 'h2 = rmsnorm(x, w[f"{l}.norm1"])'),                          # wrong norm weights
     ('return np.einsum("bth,vh->btv", rmsnorm(x, w["final_norm"]), w["emb"])', 'return np.einsum("bth,vh->btv", x, w["emb"])'),   # final norm dropped
     ("scale = 1.0 / np.sqrt(head_dim)", "scale = 1.0 / head_dim"),                                    # softmax scale
+    ('        if f"{l}.q_norm" in w:\n            q = rmsnorm(q, w[f"{l}.q_norm"])\n        q = rope_heads(q, pos, cos, sin)',
+     '        q = rope_heads(q, pos, cos, sin)\n        if f"{l}.q_norm" in w:\n            q = rmsnorm(q, w[f"{l}.q_norm"])'),   # q normalised after the rotation
+    ('k_norm_weight=w.get(f"{l}.k_norm"), k_norm_eps=1e-6)', 'k_norm_weight=w.get(f"{l}.q_norm"), k_norm_eps=1e-6)'),   # k with q's weights
 ]
 
 
@@ -163,6 +166,7 @@ DECODER_MISTAKES = [
 def test_decoder_oracle_pins_catch(old, new, monkeypatch):
     from tests import test_decoder_oracle_pins as pins
     tests = [pins.test_rmsnorm_and_causality_and_skipped_projections,
-             pins.test_identity_route_is_a_standard_decoder_built_from_library_routines,
+             lambda: pins.test_identity_route_is_a_standard_decoder_built_from_library_routines(False),
+             lambda: pins.test_identity_route_is_a_standard_decoder_built_from_library_routines(True),
              pins.test_a_layer_reads_the_layer_its_route_names_not_the_latest_cache]
     assert _pins_fail(pins, "D", _mutant("decoder_oracle", old, new), tests, monkeypatch), (old, new)

@@ -4,8 +4,8 @@ Sec. 4.3, Tab. 4 / Tab. 5) that serves with the library's depth-shared cache.
 The K/V side of every layer is the library: owner layers project and append (skv_kv_project_append),
 the other layers of a sharing group skip their K/V projections altogether, all layers attend
 through skv_attn_prefill / skv_attn_decode over the slot they are routed to.  Everything else of
-the block (norms, query / output / MLP projections, rotary encoding of the queries, the logits) is
-plain PyTorch: this file is a measurement harness around the path, not part of it.  Weights are
+the block (norms, query / output / MLP projections, normalisation and rotary encoding of the
+queries, the logits) is plain PyTorch: this file is a measurement harness around the path, not part of it.  Weights are
 random; tokens are synthetic; decoding is greedy.
 """
 from __future__ import annotations
@@ -20,10 +20,10 @@ import paper_2604_22782_amd as skv
 
 class SyntheticDecoder:
     def __init__(self, n_layers=36, hidden=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, mlp=12288,
-                 vocab=151936, group=1, seed=0, dtype=torch.bfloat16, device="cuda", sigma=0.02):
+                 vocab=151936, group=1, seed=0, dtype=torch.bfloat16, device="cuda", sigma=0.02, qk_norm=False):
         self.L, self.hidden, self.hq, self.hkv, self.d, self.mlp, self.vocab = n_layers, hidden, n_q_heads, n_kv_heads, head_dim, mlp, vocab
         self.route = [group * (l // group) for l in range(n_layers)]       # leader = first layer of each group
-        self.dtype, self.device = dtype, device
+        self.dtype, self.device, self.qk_norm = dtype, device, qk_norm
         g = torch.Generator(device=device).manual_seed(seed)
         mk = lambda *shape: (torch.randn(*shape, generator=g, device=device, dtype=torch.float32) * sigma).to(dtype)
         self.w = {"emb": mk(vocab, hidden), "final_norm": torch.ones(hidden, device=device, dtype=dtype)}
@@ -31,9 +31,13 @@ class SyntheticDecoder:
             self.w[f"{l}.norm1"] = (1.0 + 0.1 * torch.randn(hidden, generator=g, device=device)).to(dtype)
             self.w[f"{l}.norm2"] = (1.0 + 0.1 * torch.randn(hidden, generator=g, device=device)).to(dtype)
             self.w[f"{l}.wq"] = mk(n_q_heads * head_dim, hidden)
+            if qk_norm:                                                    # per-head RMS normalisation of q and k (Qwen3)
+                self.w[f"{l}.q_norm"] = 1.0 + 0.1 * torch.randn(head_dim, generator=g, device=device)
             if self.route[l] == l:                                         # non-owners have no K/V projection
                 self.w[f"{l}.wk"] = mk(n_kv_heads * head_dim, hidden)
                 self.w[f"{l}.wv"] = mk(n_kv_heads * head_dim, hidden)
+                if qk_norm:
+                    self.w[f"{l}.k_norm"] = 1.0 + 0.1 * torch.randn(head_dim, generator=g, device=device)
             self.w[f"{l}.wo"] = mk(hidden, n_q_heads * head_dim)
             self.w[f"{l}.wg"] = mk(mlp, hidden)
             self.w[f"{l}.wu"] = mk(mlp, hidden)
@@ -90,11 +94,15 @@ class SyntheticDecoder:
         chunk = 16384                                                     # tokens per MLP slice (bounds the temporaries)
         for l in range(self.L):
             h = self._rmsnorm(x, w[f"{l}.norm1"])
-            q = self._rope_q((h @ w[f"{l}.wq"].T).view(B, new, self.hq, self.d), pos).contiguous()
+            q = (h @ w[f"{l}.wq"].T).view(B, new, self.hq, self.d)
+            if self.qk_norm:
+                qf = q.float()
+                q = (qf * torch.rsqrt(qf.pow(2).mean(-1, keepdim=True) + 1e-6) * w[f"{l}.q_norm"]).to(q.dtype)
+            q = self._rope_q(q, pos).contiguous()
             if self.route[l] == l:
                 ws = self.proj_ws if new == 1 else None
                 skv.skv_kv_project_append(self.cache, l, h.contiguous(), w[f"{l}.wk"], w[f"{l}.wv"], self.cos, self.sin,
-                                          start, new_lens, new, ws)
+                                          start, new_lens, new, ws, k_norm_weight=w.get(f"{l}.k_norm"), k_norm_eps=1e-6)
             out = torch.empty_like(q)
             if new == 1:
                 skv.skv_attn_decode(self.cache, l, q.view(B, self.hq, self.d), out.view(B, self.hq, self.d), kv_lens,
