@@ -153,8 +153,9 @@ skv_status_t skv_kv_append(skv_cache_t *cache, int32_t layer, const void *k_new,
  * before the rotation, k <- k / sqrt(mean_d(k^2) + k_norm_eps) * k_norm_weight[d] (the per-head key
  * normalisation of the Qwen3 family); V is never normalised.
  * workspace: device scratch of skv_kv_project_workspace_bytes(cache, max_new, hidden) bytes (0 for
- * prompts: only launches of few tokens split the hidden axis over work groups, so that the weights
- * stream at the full HBM rate, and keep fp32 partial sums there); may be NULL when that is 0.
+ * large prompts: launches too small to fill the chip -- one decode token per sequence, or a prompt
+ * of a few thousand tokens -- split the hidden axis over work groups and keep fp32 partial sums
+ * there); may be NULL when that is 0.
  * SKV_ERR_NOT_OWNER for a layer without a slot (nothing is computed: that is the saving);
  * SKV_ERR_UNSUPPORTED unless the cache is 16-bit, head_dim 64 or 128 and hidden a multiple of 64. */
 skv_status_t skv_kv_project_workspace_bytes(const skv_cache_t *cache, int32_t max_new, int32_t hidden,

@@ -431,15 +431,16 @@ __global__ __launch_bounds__(256, 1) void project_append_tile_kernel(ProjArgs a)
     // even chunks of a slot hold rows 0..7 of a group of 16, odd chunks rows 8..15 (r / 2 = 4 + g / 2)
     const int voff = ((lane >> 3) * a.hidden + ((lane & 7) ^ (lane >> 4)) * 8) * 2;
     const int row8 = 8 * a.hidden * 2;                   // bytes between the first rows of two chunks
-    const int n_sub = a.hidden / kSub;
+    const int n_sub = a.hidden / kSub / (int)gridDim.y;  // slots of this split of the hidden axis
+    const int sub0 = (int)blockIdx.y * n_sub;
     // chunk c (of 8) of the wave's token rows / weight rows of slot `sub`
     auto request_x = [&](int sub, int c) {
         load_chunk_to_lds(x_srd, lds_base + (sub % kRingX) * kHalfSlot + (8 * wave + c) * 1024, voff ^ ((c & 1) * 64),
-                          uni(c * row8 + sub * kSub * 2));
+                          uni(c * row8 + (sub0 + sub) * kSub * 2));
     };
     auto request_w = [&](int sub, int c) {
         load_chunk_to_lds(w_srd, lds_base + (kRingX + (sub & 1)) * kHalfSlot + (8 * wave + c) * 1024,
-                          voff ^ ((c & 1) * 64), uni(c * row8 + sub * kSub * 2));
+                          voff ^ ((c & 1) * 64), uni(c * row8 + (sub0 + sub) * kSub * 2));
     };
 
     f32x16 acc[4][4]; // [token block][feature block of the wave]
@@ -520,7 +521,19 @@ __global__ __launch_bounds__(256, 1) void project_append_tile_kernel(ProjArgs a)
         for (int h = 0; h < HW; ++h) {
             const int kh = (ft * kGT + 128 * fg) / D + h;
             f32x16(&part)[NB] = *(f32x16(*)[NB]) & acc[t][h * NB];
-            if (m < n_tok) finish_token<M, D>(a, part, m, kh % hkv, kh >= hkv, hh);
+            if (m >= n_tok) continue;
+            if (gridDim.y == 1) {
+                finish_token<M, D>(a, part, m, kh % hkv, kh >= hkv, hh);
+                continue;
+            }
+            // a split of the hidden axis: fp32 partial sums, partial[split][token][K or V head][feature]
+            float *dst = a.partial + (((int64_t)blockIdx.y * n_tok + m) * 2 * hkv + kh) * D + 4 * hh;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4)
+                    *(float4 *)(dst + 32 * nb + 8 * g4) =
+                        make_float4(part[nb][4 * g4], part[nb][4 * g4 + 1], part[nb][4 * g4 + 2], part[nb][4 * g4 + 3]);
         }
     }
 }
@@ -605,25 +618,33 @@ __global__ __launch_bounds__(256) void project_finish_kernel(ProjArgs a, int n_s
     *(uint2 *)(dst + f_hi) = make_uint2(M::pack2(hi.x, hi.y), M::pack2(hi.z, hi.w));
 }
 
+// The tile kernel takes the launches whose (head, 256-token tile) grid the one-head kernel would
+// run unsplit, on shapes whose [K heads, V heads] list divides into tiles of 256 features.
+bool tile_kernel_takes(int n_kv_heads, int head_dim, int64_t n_tokens, int hidden) {
+    const int64_t tiles = (n_tokens + kTokens - 1) / kTokens;
+    return 2 * (int64_t)n_kv_heads * tiles >= 128 && (2 * n_kv_heads * head_dim) % kGT == 0 && hidden % kSub == 0 &&
+           hidden <= (1 << 20) && std::getenv("SKV_PROJECT_KERNEL") == nullptr;
+}
+
 template <typename M, int D> hipError_t launch_j(const ProjArgs &a, int n_splits, hipStream_t stream) {
     const int64_t n_tok = (int64_t)a.batch * a.max_new;
     const int64_t tiles = (n_tok + kTokens - 1) / kTokens;
     if (tiles > 65535 || 2 * a.slot.n_kv_heads > 65535) return hipErrorInvalidValue;
-    if (n_splits == 1 && (2 * a.slot.n_kv_heads * D) % kGT == 0 && a.hidden % kSub == 0 && a.hidden <= (1 << 20) &&
-        std::getenv("SKV_PROJECT_KERNEL") == nullptr) {
+    hipError_t e = hipSuccess;
+    if (tile_kernel_takes(a.slot.n_kv_heads, D, n_tok, a.hidden)) {
         const int64_t groups = ((n_tok + kGT - 1) / kGT) * (2 * a.slot.n_kv_heads * D / kGT);
         if (groups > 0x7fffffff) return hipErrorInvalidValue;
-        project_append_tile_kernel<M, D><<<dim3((unsigned)groups), 256, 0, stream>>>(a);
-        return hipGetLastError();
-    }
-    if (n_splits == 1) {
+        project_append_tile_kernel<M, D><<<dim3((unsigned)groups, (unsigned)n_splits), 256, 0, stream>>>(a);
+        e = hipGetLastError();
+    } else if (n_splits == 1) {
         project_append_wide_kernel<M, D><<<dim3((unsigned)a.slot.n_kv_heads, (unsigned)tiles), kThreads, 0, stream>>>(a);
         return hipGetLastError();
+    } else {
+        const dim3 grid((unsigned)(2 * a.slot.n_kv_heads), (unsigned)tiles, (unsigned)n_splits);
+        project_append_kernel<M, D><<<grid, kThreads, 0, stream>>>(a);
+        e = hipGetLastError();
     }
-    const dim3 grid((unsigned)(2 * a.slot.n_kv_heads), (unsigned)tiles, (unsigned)n_splits);
-    project_append_kernel<M, D><<<grid, kThreads, 0, stream>>>(a);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || n_splits == 1) return e;
     const int64_t threads = n_tok * 2 * a.slot.n_kv_heads * 2 * (D / 64) * 4;
     project_finish_kernel<M, D><<<dim3((unsigned)((threads + 255) / 256)), 256, 0, stream>>>(a, n_splits);
     return hipGetLastError();
@@ -636,23 +657,30 @@ bool project_append_supported(int dtype, int head_dim, int hidden) {
            hidden % kKT == 0;
 }
 
-// Splits of the hidden axis: one while the (head, token tile) grid alone fills the chip; else as
-// many as bring the launch to about one work group per compute unit, each at least 128 wide.
-int project_append_splits(int n_kv_heads, int64_t n_tokens, int hidden) {
+// Splits of the hidden axis.  Tile kernel (prompts): one while its 256 x 256 tiles alone give
+// about a work group per compute unit (8192 tokens at 8 kv heads of 128); below that as many as get
+// there, each at least 512 wide -- a prompt of 2048 tokens would otherwise occupy a quarter of the
+// chip.  One-head kernel (few tokens): as many as bring the launch to about one work group per
+// compute unit, each at least 128 wide.
+int project_append_splits(int n_kv_heads, int head_dim, int64_t n_tokens, int hidden) {
+    const char *e = std::getenv("SKV_PROJECT_SPLITS"); // tuning aid: a power of two that divides the tiles of the hidden axis
+    const int want = e ? atoi(e) : 0;
+    if (want >= 1 && (want & (want - 1)) == 0 && hidden / kKT % want == 0) return want;
+    int splits = 1;
+    if (tile_kernel_takes(n_kv_heads, head_dim, n_tokens, hidden)) {
+        const int64_t groups = ((n_tokens + kGT - 1) / kGT) * (2 * n_kv_heads * head_dim / kGT);
+        while (groups * splits < 192 && hidden / kSub % (2 * splits) == 0 && hidden / (2 * splits) >= 512) splits *= 2;
+        return splits;
+    }
     const int64_t tiles = (n_tokens + kTokens - 1) / kTokens;
     const int64_t groups = 2 * (int64_t)n_kv_heads * tiles;
     if (groups >= 128) return 1;
-    if (const char *e = std::getenv("SKV_PROJECT_SPLITS")) { // tuning aid: a power of two that divides the tiles of the hidden axis
-        const int want = atoi(e);
-        if (want >= 1 && (want & (want - 1)) == 0 && hidden / kKT % want == 0) return want;
-    }
-    int splits = 1;
     while (groups * splits < 256 && hidden / kKT % (2 * splits) == 0 && hidden / (2 * splits) >= 128) splits *= 2;
     return splits;
 }
 
 size_t project_append_workspace_bytes(int n_kv_heads, int head_dim, int64_t n_tokens, int hidden) {
-    const int splits = project_append_splits(n_kv_heads, n_tokens, hidden);
+    const int splits = project_append_splits(n_kv_heads, head_dim, n_tokens, hidden);
     return splits == 1 ? 0 : (size_t)splits * (size_t)n_tokens * 2 * n_kv_heads * head_dim * sizeof(float);
 }
 

@@ -340,7 +340,7 @@ skv_status_t skv_kv_project_append(skv_cache_t *c, int32_t layer, const void *x,
     if (!skv::project_append_supported(c->d.dtype, c->d.head_dim, hidden)) return SKV_ERR_UNSUPPORTED;
     if (max_new == 0) return SKV_OK;
     const int64_t n_tokens = (int64_t)c->d.batch * max_new;
-    const int n_splits = skv::project_append_splits(c->d.n_kv_heads, n_tokens, hidden);
+    const int n_splits = skv::project_append_splits(c->d.n_kv_heads, c->d.head_dim, n_tokens, hidden);
     const size_t need = skv::project_append_workspace_bytes(c->d.n_kv_heads, c->d.head_dim, n_tokens, hidden);
     if (need > 0 && (!workspace || workspace_bytes < need)) return SKV_ERR_INVALID_ARG;
     skv::ProjArgs a;

@@ -81,7 +81,7 @@ struct ProjArgs {
     int32_t batch, max_new, hidden, rope_positions;
 };
 bool project_append_supported(int dtype, int head_dim, int hidden);
-int project_append_splits(int n_kv_heads, int64_t n_tokens, int hidden);
+int project_append_splits(int n_kv_heads, int head_dim, int64_t n_tokens, int hidden);
 size_t project_append_workspace_bytes(int n_kv_heads, int head_dim, int64_t n_tokens, int hidden);
 hipError_t launch_project_append(const ProjArgs &a, int dtype, int head_dim, int n_splits, hipStream_t stream);
 

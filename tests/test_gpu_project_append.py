@@ -48,6 +48,10 @@ CASES = [
     ("f16", 8, 64, 128, [1100, 1100, 1100, 1100], [0, 5, 0, 76], [1024, 1024, 1024, 1024], 1024, True, True),
     ("bf16", 8, 128, 192, [2100], [17], [2048], 2048, True, False),
     ("f16", 2, 128, 320, [8300, 8300], [0, 0], [8192, 7000], 8192, False, True),
+    # mid-sized prompts: the 256 x 256 tiles alone would leave most of the chip idle, so the hidden axis
+    # is split over them as well (2 and 4 splits), partial sums finished by the second kernel
+    ("bf16", 8, 128, 1024, [2100], [17], [2048], 2048, True, True),
+    ("f16", 8, 128, 2048, [1100, 1100], [0, 3], [1024, 1000], 1024, False, True),
 ]
 
 

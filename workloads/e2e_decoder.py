@@ -100,7 +100,10 @@ class SyntheticDecoder:
                 q = (qf * torch.rsqrt(qf.pow(2).mean(-1, keepdim=True) + 1e-6) * w[f"{l}.q_norm"]).to(q.dtype)
             q = self._rope_q(q, pos).contiguous()
             if self.route[l] == l:
-                ws = self.proj_ws if new == 1 else None
+                need = skv.skv_kv_project_workspace_bytes(self.cache, new, self.hidden)
+                if need > self.proj_ws.numel():                 # prompts only: a captured decode step never gets here
+                    self.proj_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+                ws = self.proj_ws
                 skv.skv_kv_project_append(self.cache, l, h.contiguous(), w[f"{l}.wk"], w[f"{l}.wv"], self.cos, self.sin,
                                           start, new_lens, new, ws, k_norm_weight=w.get(f"{l}.k_norm"), k_norm_eps=1e-6)
             out = torch.empty_like(q)
