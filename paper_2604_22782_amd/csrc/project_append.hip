@@ -358,6 +358,10 @@ __global__ __launch_bounds__(kThreads, 1) void project_append_wide_kernel(ProjAr
 // releases slot t - 1; during slot t the weight rows of slot t + 1 and then the token rows of slot
 // t + 2 are requested, one load after every four MFMAs; the MFMAs of the last step of slot t - 1
 // run after the barrier, over the first operand reads of slot t.
+// grid = (token tiles x feature tiles, splits of the hidden axis).  With one split the work group
+// finishes its rows itself (normalisation, rotation, rounding, store into the slot); with more
+// (prompts too short to give every compute unit a tile) it stores fp32 partial sums like the
+// one-head kernel, and project_finish_kernel completes them.
 constexpr int kGT = 256;                    // tokens = features per work group
 constexpr int kSub = 64;                    // hidden elements per ring slot
 constexpr int kRingX = 3, kRingW = 2;       // slots of token rows, slots of weight rows
