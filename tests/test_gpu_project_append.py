@@ -132,3 +132,52 @@ def test_position_beyond_the_table_or_capacity_is_dropped_and_reported():
                                   None, None, zero, eight, 8)
     assert e.value.status == 6                                                        # hidden not a multiple of 64
     cache.free()
+
+
+def test_projection_at_the_size_the_benchmark_times_sampled_rows():
+    """The prompt of the prefill workload (4 x 8192 tokens, hidden 4096, 8 kv heads of 128, bf16:
+    the launch bench.py times, tile kernel, one split) and one decode token of the decode workload
+    (64 tokens: hidden axis split 16 ways): sampled token rows against the fp64 oracle, every other
+    row of the pools untouched where the update does not reach."""
+    from workloads import configs
+    hidden, rng = 4096, np.random.default_rng(8)
+    for w, new in ((configs.llama3_prefill(), None), (configs.llama3_decode(n_layers=2), 1)):
+        S = int(w.kv_lens.max())
+        new = S if new is None else new
+        B, Hkv, D = w.batch, w.n_kv_heads, w.head_dim
+        print(f"\nprojection at bench size: {B} x {new} tokens, hidden {hidden}", flush=True)
+        cache, _ = H.alloc_cache(w)
+        g = torch.Generator(device="cuda").manual_seed(7)
+        x = torch.randn(B, new, hidden, generator=g, device="cuda").to(torch.bfloat16)
+        wk = (torch.randn(Hkv * D, hidden, generator=g, device="cuda") / hidden ** 0.5).to(torch.bfloat16)
+        wv = (torch.randn(Hkv * D, hidden, generator=g, device="cuda") / hidden ** 0.5).to(torch.bfloat16)
+        cos, sin = _tables(S, D)
+        d_cos, d_sin = torch.from_numpy(cos.astype(np.float32)).cuda(), torch.from_numpy(sin.astype(np.float32)).cuda()
+        cos, sin = d_cos.cpu().double().numpy(), d_sin.cpu().double().numpy()
+        start = torch.full((B,), S - new, dtype=torch.int32, device="cuda")
+        lens = torch.full((B,), new, dtype=torch.int32, device="cuda")
+        ws = torch.empty(max(skv.skv_kv_project_workspace_bytes(cache, new, hidden), 4) // 4, dtype=torch.float32, device="cuda")
+        layer = w.owner_layers[0]
+        skv.skv_kv_project_append(cache, layer, x, wk, wv, d_cos, d_sin, start, lens, new, ws)
+        assert skv.skv_cache_device_faults(cache) == 0
+        k_pool, v_pool = H.pool_tensors(cache, w)
+        slot = 0
+        wk64, wv64 = gen.to_f64(wk.cpu()), gen.to_f64(wv.cpu())
+        worst = 0.0
+        for b in range(B) if new > 1 else rng.choice(B, 8, replace=False):
+            rows = np.unique(np.concatenate([[0, new - 1], rng.integers(0, new, 14)])) if new > 1 else np.array([0])
+            xs = gen.to_f64(x[b, torch.from_numpy(rows).cuda()].cpu())[None]            # [1][n][hidden]
+            pos = (S - new + rows)[None]
+            want_k, want_v = P.project_kv(xs, wk64, wv64, Hkv, D, pos, cos, sin)
+            got_k = gen.to_f64(k_pool[slot][torch.from_numpy(b * w.max_ctx + S - new + rows)].view(torch.bfloat16))
+            got_v = gen.to_f64(v_pool[slot][torch.from_numpy(b * w.max_ctx + S - new + rows)].view(torch.bfloat16))
+            worst = max(worst, np.abs(got_k - want_k[0]).max(), np.abs(got_v - want_v[0]).max())
+            assert (np.abs(got_k - want_k[0]) <= 2.0 ** -8 * np.abs(want_k[0]) + 2e-3).all(), b
+            assert (np.abs(got_v - want_v[0]) <= 2.0 ** -8 * np.abs(want_v[0]) + 2e-3).all(), b
+        print(f"worst |err| {worst:.2e}", flush=True)
+        assert worst <= H.TOL["bf16"]
+        if new == 1:      # positions before the appended one keep the zeros the pool was allocated with
+            assert not k_pool[slot][: S - 1].any()
+        cache.free()
+        del x, k_pool, v_pool
+        torch.cuda.empty_cache()
