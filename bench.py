@@ -217,7 +217,7 @@ def mfma_only_rate(torch, skv):
     out = {}
     # the third figure: Gaussian operands plus, per MFMA and independent of it, the vector
     # instructions of a softmax and the LDS operand reads of the pre-fill kernel (nothing waits
-    # for anything: the most any schedule of that instruction mix could reach under the power limit)
+    # for anything: an estimate of what that instruction mix can reach under the power limit)
     for name, t, mix in (("zeros", ops["zeros"], 0), ("gaussian", ops["gaussian"], 0),
                          ("gaussian_with_softmax_and_lds_reads", ops["gaussian"], 3)):
         best = float("inf")

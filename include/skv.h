@@ -287,8 +287,8 @@ skv_status_t skv_calib_mfma_bf16(const void *operands, float *sink, int32_t bloc
  * flash-attention tile does per MFMA: mix bit 0 = four vector instructions per MFMA (three fma, one
  * exp2), bit 1 = LDS operand reads at the pre-fill kernel's rate (one 128-bit and two transposing
  * 64-bit reads per four MFMAs).  Nothing in it waits for anything, so a lower rate than
- * skv_calib_mfma_bf16's is the price of that work in power, i.e. in clock; mix = 3 is the bound the
- * pre-fill kernel's schedule could reach at best.  The sink receives the same values as with
+ * skv_calib_mfma_bf16's is the price of that work in power, i.e. in clock, and in issue slots; mix = 3
+ * estimates what the pre-fill kernel's instruction mix can reach on this device.  The sink receives the same values as with
  * mix = 0.  Arguments as above; mix outside [0, 3] -> SKV_ERR_INVALID_ARG. */
 skv_status_t skv_calib_mfma_mix_bf16(const void *operands, float *sink, int32_t blocks, int32_t iters,
                                      int32_t mix, void *stream);
