@@ -459,18 +459,23 @@ __global__ __launch_bounds__(256, 1) void project_append_tile_kernel(ProjArgs a)
     const int rd0 = 128 * c + 16 * (hh ^ ((c >> 1) & 7));
     const int x_rd = 16 * tg * 1024 + rd0, w_rd = kRingX * kHalfSlot + 16 * fg * 1024 + rd0;
     uint4 xa[4], wa[4], xb[4], wb[4];
-    auto fetch = [&](int sub, int step, uint4 (&xo)[4], uint4 (&wo)[4]) {
+    // Operands of k-step `step` of slot `sub`, a quarter at a time: part 0, 1 = token blocks 0-1, 2-3
+    // (all four are needed by the first MFMAs of the step), part 2, 3 = weight blocks 0-1, 2-3.
+    auto fetch_part = [&](int sub, int step, int part, uint4 (&xo)[4], uint4 (&wo)[4]) {
         const char *xs = lds + (sub % kRingX) * kHalfSlot, *ws = lds + (sub & 1) * kHalfSlot;
         const int flip = step * 32;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            xo[i] = *(const uint4 *)(xs + ((x_rd ^ flip) + i * 4096));
-            wo[i] = *(const uint4 *)(ws + ((w_rd ^ flip) + i * 4096));
+        if (part < 2) {
+            xo[2 * part] = *(const uint4 *)(xs + ((x_rd ^ flip) + (2 * part) * 4096));
+            xo[2 * part + 1] = *(const uint4 *)(xs + ((x_rd ^ flip) + (2 * part + 1) * 4096));
+        } else {
+            wo[2 * part - 4] = *(const uint4 *)(ws + ((w_rd ^ flip) + (2 * part - 4) * 4096));
+            wo[2 * part - 3] = *(const uint4 *)(ws + ((w_rd ^ flip) + (2 * part - 3) * 4096));
         }
     };
-    // 16 MFMAs; after every four of them `between(i)` may send loads out.  All loads of a slot at
-    // once would hold the wave at the memory pipeline (16 cycles per load, four waves) while the
-    // matrix cores idle: measured, the two phases simply added up.
+    // 16 MFMAs; after every four of them `between(i)` reads a quarter of the next step's operands
+    // and may send loads out.  All loads of a slot at once would hold the wave at the memory
+    // pipeline (16 cycles per load, four waves) while the matrix cores idle: measured, the two
+    // phases simply added up.
     auto multiply = [&](const uint4 (&xo)[4], const uint4 (&wo)[4], auto between) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -499,20 +504,20 @@ __global__ __launch_bounds__(256, 1) void project_append_tile_kernel(ProjArgs a)
         else __builtin_amdgcn_s_waitcnt(kVmcnt0);
         __syncthreads();
         const bool more_w = sub + 1 < n_sub, more_x = sub + 2 < n_sub;
-        fetch(sub, 0, xa, wa);
-        multiply(xb, wb, [&](int i) { // last step of the slot before
+        multiply(xb, wb, [&](int i) { // last step of the slot before; step 0 of this slot is read meanwhile
+            fetch_part(sub, 0, i, xa, wa);
             if (more_w) request_w(sub + 1, i);
         });
-        fetch(sub, 1, xb, wb);
         multiply(xa, wa, [&](int i) {
+            fetch_part(sub, 1, i, xb, wb);
             if (more_w) request_w(sub + 1, 4 + i);
         });
-        fetch(sub, 2, xa, wa);
         multiply(xb, wb, [&](int i) {
+            fetch_part(sub, 2, i, xa, wa);
             if (more_x) request_x(sub + 2, i);
         });
-        fetch(sub, 3, xb, wb);
         multiply(xa, wa, [&](int i) {
+            fetch_part(sub, 3, i, xb, wb);
             if (more_x) request_x(sub + 2, 4 + i);
         });
     }
