@@ -459,31 +459,29 @@ __global__ __launch_bounds__(256, 1) void project_append_tile_kernel(ProjArgs a)
     const int rd0 = 128 * c + 16 * (hh ^ ((c >> 1) & 7));
     const int x_rd = 16 * tg * 1024 + rd0, w_rd = kRingX * kHalfSlot + 16 * fg * 1024 + rd0;
     uint4 xa[4], wa[4], xb[4], wb[4];
-    // Operands of k-step `step` of slot `sub`, a quarter at a time: part 0, 1 = token blocks 0-1, 2-3
-    // (all four are needed by the first MFMAs of the step), part 2, 3 = weight blocks 0-1, 2-3.
+    // Operands of k-step `step` of slot `sub`, one block at a time: parts 0..3 = token blocks (all
+    // four are needed by the first MFMAs of the step), parts 4..7 = weight blocks.
     auto fetch_part = [&](int sub, int step, int part, uint4 (&xo)[4], uint4 (&wo)[4]) {
         const char *xs = lds + (sub % kRingX) * kHalfSlot, *ws = lds + (sub & 1) * kHalfSlot;
         const int flip = step * 32;
-        if (part < 2) {
-            xo[2 * part] = *(const uint4 *)(xs + ((x_rd ^ flip) + (2 * part) * 4096));
-            xo[2 * part + 1] = *(const uint4 *)(xs + ((x_rd ^ flip) + (2 * part + 1) * 4096));
-        } else {
-            wo[2 * part - 4] = *(const uint4 *)(ws + ((w_rd ^ flip) + (2 * part - 4) * 4096));
-            wo[2 * part - 3] = *(const uint4 *)(ws + ((w_rd ^ flip) + (2 * part - 3) * 4096));
-        }
+        if (part < 4) xo[part] = *(const uint4 *)(xs + ((x_rd ^ flip) + part * 4096));
+        else wo[part - 4] = *(const uint4 *)(ws + ((w_rd ^ flip) + (part - 4) * 4096));
     };
-    // 16 MFMAs; after every four of them `between(i)` reads a quarter of the next step's operands
-    // and may send loads out.  All loads of a slot at once would hold the wave at the memory
-    // pipeline (16 cycles per load, four waves) while the matrix cores idle: measured, the two
-    // phases simply added up.
+    // 16 MFMAs; after every two of them `between(j)`, j = 0..7, reads one block of the next step's
+    // operands and, on odd j, may send a load out.  All loads of a slot at once would hold the wave
+    // at the memory pipeline (16 cycles per load, four waves) while the matrix cores idle: measured,
+    // the two phases simply added up; operand reads in a burst of eight cost 2.5 % against two at a time.
     auto multiply = [&](const uint4 (&xo)[4], const uint4 (&wo)[4], auto between) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+            for (int t = 0; t < 4; ++t) {
                 acc[t][i] = M::mfma(__builtin_bit_cast(vec8, wo[i]), __builtin_bit_cast(vec8, xo[t]), acc[t][i]);
-            between(i);
-            __builtin_amdgcn_sched_barrier(0);
+                if (t & 1) {
+                    between(2 * i + (t >> 1));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
         }
     };
     auto nothing = [](int) {};
@@ -504,21 +502,21 @@ __global__ __launch_bounds__(256, 1) void project_append_tile_kernel(ProjArgs a)
         else __builtin_amdgcn_s_waitcnt(kVmcnt0);
         __syncthreads();
         const bool more_w = sub + 1 < n_sub, more_x = sub + 2 < n_sub;
-        multiply(xb, wb, [&](int i) { // last step of the slot before; step 0 of this slot is read meanwhile
-            fetch_part(sub, 0, i, xa, wa);
-            if (more_w) request_w(sub + 1, i);
+        multiply(xb, wb, [&](int j) { // last step of the slot before; step 0 of this slot is read meanwhile
+            fetch_part(sub, 0, j, xa, wa);
+            if (more_w && (j & 1)) request_w(sub + 1, j >> 1);
         });
-        multiply(xa, wa, [&](int i) {
-            fetch_part(sub, 1, i, xb, wb);
-            if (more_w) request_w(sub + 1, 4 + i);
+        multiply(xa, wa, [&](int j) {
+            fetch_part(sub, 1, j, xb, wb);
+            if (more_w && (j & 1)) request_w(sub + 1, 4 + (j >> 1));
         });
-        multiply(xb, wb, [&](int i) {
-            fetch_part(sub, 2, i, xa, wa);
-            if (more_x) request_x(sub + 2, i);
+        multiply(xb, wb, [&](int j) {
+            fetch_part(sub, 2, j, xa, wa);
+            if (more_x && (j & 1)) request_x(sub + 2, j >> 1);
         });
-        multiply(xa, wa, [&](int i) {
-            fetch_part(sub, 3, i, xb, wb);
-            if (more_x) request_x(sub + 2, 4 + i);
+        multiply(xa, wa, [&](int j) {
+            fetch_part(sub, 3, j, xb, wb);
+            if (more_x && (j & 1)) request_x(sub + 2, 4 + (j >> 1));
         });
     }
     multiply(xb, wb, nothing);
