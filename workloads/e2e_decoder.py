@@ -32,7 +32,7 @@ class SyntheticDecoder:
             self.w[f"{l}.norm2"] = (1.0 + 0.1 * torch.randn(hidden, generator=g, device=device)).to(dtype)
             self.w[f"{l}.wq"] = mk(n_q_heads * head_dim, hidden)
             if qk_norm:                                                    # per-head RMS normalisation of q and k (Qwen3)
-                self.w[f"{l}.q_norm"] = 1.0 + 0.1 * torch.randn(head_dim, generator=g, device=device)
+                self.w[f"{l}.q_norm"] = (1.0 + 0.1 * torch.randn(head_dim, generator=g, device=device)).to(dtype)
             if self.route[l] == l:                                         # non-owners have no K/V projection
                 self.w[f"{l}.wk"] = mk(n_kv_heads * head_dim, hidden)
                 self.w[f"{l}.wv"] = mk(n_kv_heads * head_dim, hidden)
@@ -71,12 +71,11 @@ class SyntheticDecoder:
     # ---- the block -------------------------------------------------------------------------------
     @staticmethod
     def _rmsnorm(x, w, eps=1e-6):
-        xf = x.float()
-        return (xf * torch.rsqrt(xf.pow(2).mean(-1, keepdim=True) + eps)).to(x.dtype) * w
+        return torch.nn.functional.rms_norm(x, (x.shape[-1],), w, eps)   # one launch
 
-    def _rope_q(self, q, pos):
+    def _rope_q(self, q, c, s):
+        """c, s: [B][new][1][d/2] rows of the tables at the tokens' positions (gathered once per call)."""
         half = self.d // 2
-        c, s = self.cos[pos][:, :, None, :], self.sin[pos][:, :, None, :]
         lo, hi = q[..., :half].float(), q[..., half:].float()
         return torch.cat([lo * c - hi * s, hi * c + lo * s], dim=-1).to(q.dtype)
 
@@ -91,14 +90,14 @@ class SyntheticDecoder:
         kv_lens = start + new
         n_after = self.n_host + new if hint is None else hint
         x = w["emb"][tokens]
+        rope_c, rope_s = self.cos[pos][:, :, None, :], self.sin[pos][:, :, None, :]
         chunk = 16384                                                     # tokens per MLP slice (bounds the temporaries)
         for l in range(self.L):
             h = self._rmsnorm(x, w[f"{l}.norm1"])
             q = (h @ w[f"{l}.wq"].T).view(B, new, self.hq, self.d)
             if self.qk_norm:
-                qf = q.float()
-                q = (qf * torch.rsqrt(qf.pow(2).mean(-1, keepdim=True) + 1e-6) * w[f"{l}.q_norm"]).to(q.dtype)
-            q = self._rope_q(q, pos).contiguous()
+                q = self._rmsnorm(q, w[f"{l}.q_norm"])
+            q = self._rope_q(q, rope_c, rope_s).contiguous()
             if self.route[l] == l:
                 need = skv.skv_kv_project_workspace_bytes(self.cache, new, self.hidden)
                 if need > self.proj_ws.numel():                 # prompts only: a captured decode step never gets here
