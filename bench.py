@@ -208,6 +208,7 @@ def mfma_only_rate(torch, skv):
     256 compute units, with all-zero operands and with Gaussian ones (a different operand pair for
     every instruction, as in attention).  The second figure is what the power limit of the device
     leaves of the first."""
+    from paper_2604_22782_amd import calib
     blocks, iters = 256, 6000                      # about 3 ms per launch
     sink = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
     gen_ = torch.Generator(device="cpu").manual_seed(1234)
@@ -224,7 +225,7 @@ def mfma_only_rate(torch, skv):
         for rep in range(5):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            skv.skv_calib_mfma_mix_bf16(t, sink, blocks, iters, mix)
+            calib.skv_calib_mfma_mix_bf16(t, sink, blocks, iters, mix)
             e1.record()
             torch.cuda.synchronize()
             if rep >= 2:

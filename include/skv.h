@@ -14,9 +14,8 @@
  *     the memory lives.  Device pointers are ordinary HIP allocations (for example the storage
  *     of a PyTorch-ROCm tensor).  `stream` is a hipStream_t passed as void* (NULL = default).
  *   - Every compute call only ENQUEUES work on `stream`: no synchronisation, no allocation.
- *     Caller-owned buffers must stay alive until that work has run.  Calls on ONE cache must not
- *     overlap in time (enqueue them on one stream, or order the streams): the attention kernels
- *     keep small work counters in the cache object.
+ *     Caller-owned buffers must stay alive until that work has run.  Calls that share a workspace
+ *     must not overlap in time: enqueue them on one stream, or order the streams.
  *   - Layers, heads, positions and slots are 0-based (the paper counts layers from 1).
  *   - Query head h reads kv head h / (n_q_heads / n_kv_heads).
  *   - The query at absolute position p sees cached positions 0..p.
@@ -106,11 +105,15 @@ skv_status_t skv_cache_bytes(const skv_cache_desc_t *desc, size_t *total_bytes);
 
 /* ---- cache object --------------------------------------------------------------------------- */
 
-/* Validates the descriptor, copies the route, allocates the pools unless the caller gave them,
- * and zero-fills library-allocated pools.  *out is set only on SKV_OK.  Synchronous. */
+/* The cache of Sec. 3.1.1 under a sharing strategy (Sec. 3.1.3): one K and one V slot per owner
+ * layer instead of per layer, sized as skv_cache_bytes says.  Validates the descriptor, copies the
+ * route, allocates the pools unless the caller gave them, and zero-fills library-allocated pools.
+ * *out is set only on SKV_OK.  Synchronous.  Ownership: the handle and library-allocated pools
+ * belong to the library until skv_cache_free; caller pools and the block table are only borrowed. */
 skv_status_t skv_cache_alloc(const skv_cache_desc_t *desc, skv_cache_t **out);
 
-/* Frees the handle and library-allocated pools (never caller pools).  NULL is accepted.
+/* Ends the life of a cache made by skv_cache_alloc (Sec. 3.1.1: the cache lives for one generation
+ * request).  Frees the handle and library-allocated pools (never caller pools).  NULL is accepted.
  * The caller must have synchronised all streams that still use the cache. */
 skv_status_t skv_cache_free(skv_cache_t *cache);
 
@@ -168,7 +171,10 @@ skv_status_t skv_kv_project_append(skv_cache_t *cache, int32_t layer, const void
                                    void *workspace, size_t workspace_bytes, void *stream);
 
 /* Scratch bytes skv_attn_decode needs for sequences of up to max_kv_len positions: enough for
- * every call whose max_kv_len hint is at most this one. */
+ * every call whose max_kv_len hint is at most this one.  The scratch holds what the sampling-phase
+ * attention of Eq. (3.1) keeps between its two launches when the key axis is split: per (sequence,
+ * query head, split) the running maximum, the sum of weights and the unnormalised output in fp32,
+ * plus 256 bytes of work counters. */
 skv_status_t skv_decode_workspace_bytes(const skv_cache_t *cache, int32_t max_kv_len, size_t *bytes);
 
 /* Sampling-phase attention, Eq. (3.1) for one query token per sequence:
@@ -243,9 +249,9 @@ skv_status_t skv_train_sample_route(int32_t scheme, int32_t n_layers, int32_t k,
  * dtype SKV_BF16 or SKV_F16, head_dim 64 or 128 (else SKV_ERR_UNSUPPORTED); fp32 accumulation.
  * lse: device float [batch][n_q_heads][seq], receives log sum_j exp(scale <q_i, k_j>) (natural
  * log), which the backward needs.  seq_lens: device int32[batch], each in [1, seq]; rows at or
- * beyond a sequence's length are neither read nor written.  Asynchronous on `stream`.
- * The first training call of a process allocates the 256-byte fault word of these calls (see
- * skv_train_device_faults); make it outside any stream capture. */
+ * beyond a sequence's length are neither read nor written.  Asynchronous on `stream`; allocates
+ * nothing (the fault word of the training calls, see skv_train_device_faults, is a device variable
+ * of the library). */
 skv_status_t skv_train_attn_fwd(const void *q, const void *k, const void *v, void *out, float *lse,
                                 const int32_t *seq_lens, int32_t batch, int32_t seq,
                                 int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
@@ -271,27 +277,6 @@ skv_status_t skv_train_attn_bwd(const void *q, const void *k, const void *v, con
 /* Reads and clears the fault word of the training calls (a sequence length outside [1, seq] sets
  * SKV_FAULT_KV_LEN and nothing is computed for that sequence).  Synchronises the device. */
 skv_status_t skv_train_device_faults(uint32_t *faults);
-
-/* ---- measurement aid (no part of the attention path) --------------------------------------- */
-/* Runs iters x 32 back-to-back v_mfma_f32_32x32x16_bf16 (32768 flop each) on every one of the
- * 4 * blocks waves of the launch (work groups of 256 threads, one wave per SIMD) and nothing else:
- * the rate the matrix cores of this device reach with the given operand values, the yardstick for
- * the pre-fill kernel's MFMA utilisation.  operands: device, 16 KiB = 16 blocks of 64 lanes x
- * 8 bf16 (A and B operand of 8 steps; every instruction takes a different pair).  sink: device
- * float[blocks * 256], receives one value per lane so that the work cannot be dropped.
- * Asynchronous on `stream`; the caller times it.  1 <= iters <= 2^20, else SKV_ERR_INVALID_ARG. */
-skv_status_t skv_calib_mfma_bf16(const void *operands, float *sink, int32_t blocks, int32_t iters,
-                                 void *stream);
-
-/* The same MFMA stream with, between the MFMAs and independent of them, the other work a
- * flash-attention tile does per MFMA: mix bit 0 = four vector instructions per MFMA (three fma, one
- * exp2), bit 1 = LDS operand reads at the pre-fill kernel's rate (one 128-bit and two transposing
- * 64-bit reads per four MFMAs).  Nothing in it waits for anything, so a lower rate than
- * skv_calib_mfma_bf16's is the price of that work in power, i.e. in clock, and in issue slots; mix = 3
- * estimates what the pre-fill kernel's instruction mix can reach on this device.  The sink receives the same values as with
- * mix = 0.  Arguments as above; mix outside [0, 3] -> SKV_ERR_INVALID_ARG. */
-skv_status_t skv_calib_mfma_mix_bf16(const void *operands, float *sink, int32_t blocks, int32_t iters,
-                                     int32_t mix, void *stream);
 
 #ifdef __cplusplus
 }

@@ -11,7 +11,7 @@ __all__ = [
     "skv_cache_free", "skv_cache_info", "skv_cache_slot_of_layer", "skv_cache_set_block_table",
     "skv_cache_device_faults", "skv_kv_append", "skv_kv_project_append", "skv_kv_project_workspace_bytes", "skv_decode_workspace_bytes", "skv_attn_decode",
     "skv_decode_range_workspace_bytes", "skv_attn_decode_range", "skv_attn_prefill", "skv_status_str", "skv_last_hip_error", "skv_last_kernel_name",
-    "skv_calib_mfma_bf16", "skv_calib_mfma_mix_bf16", "skv_train_sample_route", "skv_train_attn_fwd", "skv_train_bwd_workspace_bytes",
+    "skv_train_sample_route", "skv_train_attn_fwd", "skv_train_bwd_workspace_bytes",
     "skv_train_attn_bwd", "skv_train_device_faults", "SKV_TRAIN_RCLA", "SKV_TRAIN_CLA_K", "SKV_TRAIN_RDCLA_K",
 ]
 
@@ -296,22 +296,6 @@ def skv_train_device_faults() -> int:
     out = ctypes.c_uint32(0)
     _check(lib().skv_train_device_faults(ctypes.byref(out)), "skv_train_device_faults")
     return out.value
-
-
-def skv_calib_mfma_bf16(operands, sink, blocks: int, iters: int, stream=None):
-    """operands: 16 KiB device tensor; sink: float32 device tensor of blocks * 256 elements."""
-    if operands.numel() * operands.element_size() < 16384 or sink.numel() < blocks * 256 or sink.dtype != torch.float32:
-        raise ValueError("skv_calib_mfma_bf16: operands need 16 KiB, sink blocks * 256 floats")
-    _check(lib().skv_calib_mfma_bf16(_ptr(operands), _ptr(sink), blocks, iters, _stream(stream)),
-           "skv_calib_mfma_bf16")
-
-
-def skv_calib_mfma_mix_bf16(operands, sink, blocks: int, iters: int, mix: int, stream=None):
-    """mix bit 0: four vector instructions per MFMA; bit 1: LDS operand reads at the pre-fill kernel's rate."""
-    if operands.numel() * operands.element_size() < 16384 or sink.numel() < blocks * 256 or sink.dtype != torch.float32:
-        raise ValueError("skv_calib_mfma_mix_bf16: operands need 16 KiB, sink blocks * 256 floats")
-    _check(lib().skv_calib_mfma_mix_bf16(_ptr(operands), _ptr(sink), blocks, iters, mix, _stream(stream)),
-           "skv_calib_mfma_mix_bf16")
 
 
 def skv_status_str(status: int) -> str:

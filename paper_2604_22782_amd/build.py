@@ -12,6 +12,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libskv.so")
+CALIB_LIB = os.path.join(PKG, "libskv_calib.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -36,20 +37,22 @@ def _compile(src: str) -> str:
 
 def build_library(verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    # the instruction streams of the pipelined pre-fill kernel (one per wave shape) are written by a generator
-    for nq in (1, 2):
-        for paged in (0, 1):
-            subprocess.check_call([sys.executable, os.path.join(CSRC, "gen_prefill_pipe.py"),
-                                   os.path.join(OBJ, f"prefill_pipe_body_nq{nq}{'_paged' if paged else ''}.inc")],
-                                  env={**os.environ, "SKV_GEN_NQ": str(nq), "SKV_GEN_PAGED": str(paged)})
+    # the instruction streams of the pipelined pre-fill kernel (contiguous and paged caches) are
+    # written by a generator
+    for paged in (0, 1):
+        subprocess.check_call([sys.executable, os.path.join(CSRC, "gen_prefill_pipe.py"),
+                               os.path.join(OBJ, f"prefill_pipe_body_nq2{'_paged' if paged else ''}.inc"),
+                               "--paged", str(paged)])
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
-    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
-        objs = list(ex.map(_compile, srcs))
-    tmp = LIB + ".tmp"
-    subprocess.check_call([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp, *objs])
-    os.replace(tmp, LIB)
+    calib = sorted(glob.glob(os.path.join(PKG, "csrc_calib", "*.hip")))
+    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(srcs) + len(calib))) as ex:
+        objs = list(ex.map(_compile, srcs + calib))
+    for lib, parts in ((LIB, objs[:len(srcs)]), (CALIB_LIB, objs[len(srcs):])):
+        tmp = lib + ".tmp"
+        subprocess.check_call([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp, *parts])
+        os.replace(tmp, lib)
     if verbose:
-        print(f"built {LIB} from {len(srcs)} sources")
+        print(f"built {LIB} from {len(srcs)} sources and {CALIB_LIB} (the benchmark's measurement aid) from {len(calib)}")
     return LIB
 
 

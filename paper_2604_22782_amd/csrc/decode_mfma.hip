@@ -59,6 +59,9 @@ struct MF16 {
 };
 
 constexpr int kTile = 32; // keys per wave tile
+// A launch whose K/V slice is at most this large uses cached loads (the memory-side cache of the
+// device holds 256 MiB; see the cross-layer reuse measurements for the choice).
+constexpr int64_t kOnChipBytes = (int64_t)192 << 20;
 
 template <int D> struct Geo {
     static constexpr int LPR = D / 8;            // lanes per 16-bit row (16 bytes each)
@@ -75,7 +78,10 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const char *p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(p));
 }
 
-template <typename M, int D, int kWaves>
+// kStream: the K/V loads carry the non-temporal hint (every byte is used once: stream it past the
+// caches).  Without it the rows are cached as usual, which is what lets the next layer of a sharing
+// group find a small slot slice on chip.
+template <typename M, int D, int kWaves, bool kStream>
 __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a, int G, int persistent) {
     using Ge = Geo<D>;
     using vec8 = typename M::vec8;
@@ -159,11 +165,14 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
             vr[t] = make_uint4(0, 0, 0, 0);
             const int32_t r = row_of(j0, blk, t);
             if (r >= 0) {
-                // every K/V byte is used once by this kernel: stream it past the caches ("nt" loads:
-                // +6..10 % bandwidth on all decode workloads)
                 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-                kr[t] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4 *)(kp + r * row_elems)));
-                vr[t] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4 *)(vp + r * row_elems)));
+                if constexpr (kStream) { // "nt" loads: +6..10 % bandwidth on launches far larger than the caches
+                    kr[t] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4 *)(kp + r * row_elems)));
+                    vr[t] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4 *)(vp + r * row_elems)));
+                } else {
+                    kr[t] = *(const uint4 *)(kp + r * row_elems);
+                    vr[t] = *(const uint4 *)(vp + r * row_elems);
+                }
             }
         }
     };
@@ -400,7 +409,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
     }
     const int total_full = s_prefix[a.batch];
     const int total = (total_full + n_rem) * hkv;
-    int32_t *counter = a.work_counters, *done = a.work_counters + 1;
+    int32_t *counter = a.work_counters; // zero when the launch starts (cleared by the launcher)
     int next = blockIdx.x; // the first item needs no ticket; tickets count on from the grid size
     for (;;) {
         if (threadIdx.x == 0) s_item = next;
@@ -432,14 +441,12 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
         process_item(__builtin_amdgcn_readfirstlane(seq), __builtin_amdgcn_readfirstlane(kvh),
                      __builtin_amdgcn_readfirstlane(split));
     }
-    // The last work group to leave puts the counters back to rest for the next launch.
-    if (threadIdx.x == 0) {
-        const int left = __hip_atomic_fetch_add(done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (left == (int)gridDim.x - 1) {
-            __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
+}
+
+// Clears the work counter of the persistent launch shape (a kernel, not a memset: the call may be
+// recorded into a HIP graph).
+__global__ void clear_counter_kernel(int32_t *counter) {
+    if (threadIdx.x < 2) counter[threadIdx.x] = 0;
 }
 
 template <typename M, int D>
@@ -455,12 +462,21 @@ hipError_t launch_d(const AttnArgs &a, int group, hipStream_t stream) {
     // could hold many empty splits (more than two splits per sequence); a batch too large for the
     // split-count table in LDS, or a launch with few items, uses the plain grid.
     const int64_t max_items = (int64_t)a.n_splits * a.cache.n_kv_heads * a.batch;
+    // Cache policy of the K/V loads: stream past the caches unless everything the launch can read
+    // (sequences x longest length x K and V rows) is small enough to stay on chip until the next
+    // layer of the sharing group reads it again.
+    const int64_t slice_bytes = (int64_t)a.batch * a.max_kv_len * a.cache.n_kv_heads * D * 2 * 2;
+    const int forced = tuning().decode_loads;
+    const bool stream_loads = forced ? forced == 1 : slice_bytes > kOnChipBytes;
     if (a.n_splits > 2 && a.batch <= 1024 && a.work_counters != nullptr && max_items > 2 * n_cu) {
         const size_t dyn = sizeof(int) * (size_t)(a.batch + 1) + sizeof(unsigned short) * (size_t)a.batch;
-        decode_mfma_kernel<M, D, 4><<<dim3(2 * n_cu), 256, dyn, stream>>>(a, group, 1);
+        clear_counter_kernel<<<1, 64, 0, stream>>>(a.work_counters);
+        if (stream_loads) decode_mfma_kernel<M, D, 4, true><<<dim3(2 * n_cu), 256, dyn, stream>>>(a, group, 1);
+        else decode_mfma_kernel<M, D, 4, false><<<dim3(2 * n_cu), 256, dyn, stream>>>(a, group, 1);
     } else {
         const dim3 grid((unsigned)a.n_splits, (unsigned)a.cache.n_kv_heads, (unsigned)a.batch);
-        decode_mfma_kernel<M, D, 4><<<grid, 256, 0, stream>>>(a, group, 0);
+        if (stream_loads) decode_mfma_kernel<M, D, 4, true><<<grid, 256, 0, stream>>>(a, group, 0);
+        else decode_mfma_kernel<M, D, 4, false><<<grid, 256, 0, stream>>>(a, group, 0);
     }
     set_last_kernel_name("decode_mfma_kernel");
     return hipGetLastError();

@@ -14,11 +14,6 @@
 // cannot touch foreign memory.  Offsets are 32-bit, hence the 4 GiB limit in pipe_supported().
 #include "skv_internal.h"
 
-#include <cstdlib>
-#include <cstring>
-
-#include "prefill_pipe_body_nq1.inc"
-#include "prefill_pipe_body_nq1_paged.inc"
 #include "prefill_pipe_body_nq2.inc"
 #include "prefill_pipe_body_nq2_paged.inc"
 
@@ -46,8 +41,7 @@ __device__ __forceinline__ u32x4 make_srd(const void *base, uint32_t bytes) {
 
 template <bool BF16, int NQ, bool PAGED>
 __global__ __launch_bounds__(512 / NQ, 1) void prefill_pipe_kernel(AttnArgs a, int G, int n_qt, int xcd_map) {
-    static_assert(SKV_PIPE1_LDS_BYTES == SKV_PIPE2_LDS_BYTES && SKV_PIPE1_THREADS == 512 && SKV_PIPE2_THREADS == 256);
-    static_assert(SKV_PIPE1P_LDS_BYTES == SKV_PIPE2_LDS_BYTES && SKV_PIPE2P_LDS_BYTES == SKV_PIPE2_LDS_BYTES);
+    static_assert(SKV_PIPE2_THREADS == 256 && SKV_PIPE2P_THREADS == 256 && SKV_PIPE2P_LDS_BYTES == SKV_PIPE2_LDS_BYTES);
     __shared__ __attribute__((aligned(16))) char lds[SKV_PIPE2_LDS_BYTES];
     constexpr int kRowsPerWave = 32 * NQ;
 
@@ -137,19 +131,13 @@ __global__ __launch_bounds__(512 / NQ, 1) void prefill_pipe_kernel(AttnArgs a, i
     } else {                                                                                           \
         asm volatile(SKV_PIPE##TAG##_ASM_F16 : : SKV_PIPE_OPERANDS : SKV_PIPE##TAG##_CLOBBERS);       \
     }
-    // 512 threads: the compiler keeps to v0..v127 itself (it halves the 256 registers of a wave
-    // between the two files) and says that clobbers above that do nothing for it; they do set the
-    // kernel's register count, which is what they are listed for
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"
-    if constexpr (NQ == 2 && !PAGED) {
+    static_assert(NQ == 2);
+    if constexpr (!PAGED) {
         SKV_PIPE_RUN(2)
-    } else if constexpr (NQ == 2 && PAGED) {
-        SKV_PIPE_RUN(2P)
-    } else if constexpr (NQ == 1 && !PAGED) {
-        SKV_PIPE_RUN(1)
     } else {
-        SKV_PIPE_RUN(1P)
+        SKV_PIPE_RUN(2P)
     }
 #pragma clang diagnostic pop
 #undef SKV_PIPE_RUN
@@ -181,20 +169,11 @@ hipError_t launch_prefill_pipe(const AttnArgs &a, int dtype, int group, hipStrea
     const int64_t blocks = (int64_t)pairs * group * n_qt;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     const int xcd_map = (pairs % 8) == 0;
-    // SKV_PREFILL_WAVES=8 picks the shape with 8 waves of 32 rows (two waves per SIMD); read at every
-    // launch so that one process can time and test both shapes
-    const char *shape = getenv("SKV_PREFILL_WAVES");
-    const bool eight = shape != nullptr && strcmp(shape, "8") == 0;
     const dim3 grid((unsigned)blocks);
     const bool paged = a.cache.block_table != nullptr;
 #define SKV_PIPE_LAUNCH(BF, NQ_, PG) prefill_pipe_kernel<BF, NQ_, PG><<<grid, 512 / NQ_, 0, stream>>>(a, group, n_qt, xcd_map)
-    if (eight) {
-        if (dtype == SKV_BF16) { if (paged) SKV_PIPE_LAUNCH(true, 1, true); else SKV_PIPE_LAUNCH(true, 1, false); }
-        else { if (paged) SKV_PIPE_LAUNCH(false, 1, true); else SKV_PIPE_LAUNCH(false, 1, false); }
-    } else {
-        if (dtype == SKV_BF16) { if (paged) SKV_PIPE_LAUNCH(true, 2, true); else SKV_PIPE_LAUNCH(true, 2, false); }
-        else { if (paged) SKV_PIPE_LAUNCH(false, 2, true); else SKV_PIPE_LAUNCH(false, 2, false); }
-    }
+    if (dtype == SKV_BF16) { if (paged) SKV_PIPE_LAUNCH(true, 2, true); else SKV_PIPE_LAUNCH(true, 2, false); }
+    else { if (paged) SKV_PIPE_LAUNCH(false, 2, true); else SKV_PIPE_LAUNCH(false, 2, false); }
 #undef SKV_PIPE_LAUNCH
     set_last_kernel_name("prefill_pipe_kernel");
     return hipGetLastError();

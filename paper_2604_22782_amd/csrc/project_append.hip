@@ -630,7 +630,7 @@ __global__ __launch_bounds__(256) void project_finish_kernel(ProjArgs a, int n_s
 bool tile_kernel_takes(int n_kv_heads, int head_dim, int64_t n_tokens, int hidden) {
     const int64_t tiles = (n_tokens + kTokens - 1) / kTokens;
     return 2 * (int64_t)n_kv_heads * tiles >= 128 && (2 * n_kv_heads * head_dim) % kGT == 0 && hidden % kSub == 0 &&
-           hidden <= (1 << 20) && std::getenv("SKV_PROJECT_KERNEL") == nullptr;
+           hidden <= (1 << 20) && !tuning().project_wide;
 }
 
 template <typename M, int D> hipError_t launch_j(const ProjArgs &a, int n_splits, hipStream_t stream) {
@@ -670,8 +670,7 @@ bool project_append_supported(int dtype, int head_dim, int hidden) {
 // chip.  One-head kernel (few tokens): as many as bring the launch to about one work group per
 // compute unit, each at least 128 wide.
 int project_append_splits(int n_kv_heads, int head_dim, int64_t n_tokens, int hidden) {
-    const char *e = std::getenv("SKV_PROJECT_SPLITS"); // tuning aid: a power of two that divides the tiles of the hidden axis
-    const int want = e ? atoi(e) : 0;
+    const int want = tuning().project_splits; // developer knob: a power of two that divides the tiles of the hidden axis
     if (want >= 1 && (want & (want - 1)) == 0 && hidden / kKT % want == 0) return want;
     int splits = 1;
     if (tile_kernel_takes(n_kv_heads, head_dim, n_tokens, hidden)) {

@@ -40,12 +40,7 @@ skv_status_t hip_fail(hipError_t e) {
 // Pre-fill kernel choice: pipelined -> plain MFMA -> vector ALU.
 skv_status_t launch_prefill(const skv::AttnArgs &a, int dtype, int head_dim, int g, hipStream_t stream) {
     hipError_t e;
-    // SKV_PREFILL_KERNEL=plain keeps the pipelined kernel out (for A/B timing and fault finding)
-    static const bool no_pipe = [] {
-        const char *v = getenv("SKV_PREFILL_KERNEL");
-        return v && strcmp(v, "plain") == 0;
-    }();
-    if (!no_pipe && skv::prefill_pipe_supported(a, dtype, head_dim))
+    if (!skv::tuning().prefill_plain && skv::prefill_pipe_supported(a, dtype, head_dim))
         e = skv::launch_prefill_pipe(a, dtype, g, stream);
     else if (skv::prefill_mfma_supported(dtype, head_dim, g))
         e = skv::launch_prefill_mfma(a, dtype, head_dim, g, stream);
@@ -113,14 +108,11 @@ skv::SlotView view_of(const skv_cache *c, int slot) {
 // Key-axis chunk covered by one work item of the decode kernels.  Deterministic in
 // (batch, n_kv_heads, max_kv_len) so that the workspace size and the launch agree.
 constexpr int64_t kMaxKeysPerSplit = 4096;
+// The workspace of a decode call starts with the work counters of the persistent launch shape.
+constexpr size_t kCounterBytes = 256;
 
 int32_t decode_keys_per_split(const skv_cache *c, int32_t n_seqs, int32_t max_kv_len) {
-    static const int forced = [] { // tuning knob: SKV_DECODE_KEYS_PER_SPLIT=<multiple of 128>
-        const char *e = getenv("SKV_DECODE_KEYS_PER_SPLIT");
-        const int v = e ? atoi(e) : 0;
-        return v > 0 && v % 128 == 0 ? v : 0;
-    }();
-    if (forced) return forced;
+    if (const int forced = skv::tuning().decode_keys_per_split) return forced;
     // About one work group per compute unit (256) when every sequence is max_kv_len long, within
     // 256..2048 keys.  Measured on the Llama-3-8B decode shape (4096 keys, 8 kv heads): with two
     // tiles per wave in flight the kernel gains from long splits (fewer pipeline fills, partial
@@ -142,6 +134,31 @@ bool paged_ready(const skv_cache *c) { return c->d.block_size == 0 || c->block_t
 
 namespace skv {
 void set_last_kernel_name(const char *name) { g_last_kernel = name; }
+
+// Developer knobs for A/B timing.  The environment is read ONCE, at the first call that asks, and
+// only if it holds SKV_TUNING=1; without that the defaults below are what runs.
+//   SKV_DECODE_KEYS_PER_SPLIT=<multiple of 128>  key-axis chunk of the decode kernel
+//   SKV_DECODE_LOADS=nt|cached                   cache policy of the decode kernel's K/V loads
+//   SKV_PREFILL_KERNEL=plain                     keep the pipelined pre-fill kernel out
+//   SKV_PROJECT_KERNEL=wide                      keep the tile projection kernel out
+//   SKV_PROJECT_SPLITS=<power of two>            hidden-axis splits of the projection
+const Tuning &tuning() {
+    static const Tuning t = [] {
+        Tuning r;
+        const char *on = getenv("SKV_TUNING");
+        if (on == nullptr || strcmp(on, "1") != 0) return r;
+        if (const char *e = getenv("SKV_DECODE_KEYS_PER_SPLIT")) {
+            const int v = atoi(e);
+            if (v > 0 && v % 128 == 0) r.decode_keys_per_split = v;
+        }
+        if (const char *e = getenv("SKV_DECODE_LOADS")) r.decode_loads = strcmp(e, "nt") == 0 ? 1 : strcmp(e, "cached") == 0 ? 2 : 0;
+        if (const char *e = getenv("SKV_PREFILL_KERNEL")) r.prefill_plain = strcmp(e, "plain") == 0;
+        if (const char *e = getenv("SKV_PROJECT_KERNEL")) r.project_wide = strcmp(e, "wide") == 0;
+        if (const char *e = getenv("SKV_PROJECT_SPLITS")) r.project_splits = atoi(e);
+        return r;
+    }();
+    return t;
+}
 } // namespace skv
 
 extern "C" {
@@ -314,7 +331,7 @@ skv_status_t skv_decode_range_workspace_bytes(const skv_cache_t *c, int32_t seq_
     const int32_t kps = decode_keys_per_split(c, seq_count, max_kv_len); // exact for this hint (covers the tuning knob)
     const int64_t exact = ((int64_t)max_kv_len + kps - 1) / kps;
     const size_t n_splits = (size_t)std::max({exact, capped, std::min(by_len, by_units)});
-    *bytes = (size_t)seq_count * c->d.n_q_heads * n_splits * (c->d.head_dim + 2) * sizeof(float);
+    *bytes = kCounterBytes + (size_t)seq_count * c->d.n_q_heads * n_splits * (c->d.head_dim + 2) * sizeof(float);
     return SKV_OK;
 }
 
@@ -405,9 +422,9 @@ skv_status_t skv_attn_decode_range(skv_cache_t *c, int32_t layer, int32_t seq_be
     a.keys_per_split = decode_keys_per_split(c, seq_count, max_kv_len);
     a.n_splits = (max_kv_len + a.keys_per_split - 1) / a.keys_per_split;
     a.scale_log2e = scale * 1.4426950408889634f;
-    a.part_o = (float *)workspace;
+    a.work_counters = (int32_t *)workspace; // cleared by the launcher whenever the kernel uses them
+    a.part_o = (float *)((char *)workspace + kCounterBytes);
     a.part_ml = a.part_o + (size_t)seq_count * c->d.n_q_heads * a.n_splits * c->d.head_dim;
-    a.work_counters = (int32_t *)c->faults + 16; // inside the cache's zero-initialised 256-byte device block
 
     const int g = c->d.n_q_heads / c->d.n_kv_heads;
     hipError_t e;
@@ -493,18 +510,26 @@ skv_status_t skv_train_sample_route(int32_t scheme, int32_t n_layers, int32_t k,
 }
 
 namespace {
-// Device fault word of the training calls: allocated on first use, kept until the process ends.
+// Fault word of the training calls: a device variable of the library (zero from load time on), so
+// that no compute call allocates.  Every device holds its own copy at its own address.
+__device__ __attribute__((aligned(256))) uint32_t g_train_faults[64];
+
 skv_status_t train_fault_word(uint32_t **out) {
+    constexpr int kMaxDevices = 64;
     static std::mutex mu;
-    static uint32_t *word = nullptr;
+    static uint32_t *word[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return SKV_ERR_UNSUPPORTED;
     std::lock_guard<std::mutex> lock(mu);
-    if (word == nullptr) {
-        hipError_t e = hipMalloc((void **)&word, 256);
-        if (e != hipSuccess) { word = nullptr; return hip_fail(e); }
-        e = hipMemset(word, 0, 256);
+    if (word[dev] == nullptr) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_train_faults));
         if (e != hipSuccess) return hip_fail(e);
+        word[dev] = (uint32_t *)p;
     }
-    *out = word;
+    *out = word[dev];
     return SKV_OK;
 }
 
@@ -613,19 +638,6 @@ const char *skv_status_str(skv_status_t s) {
     case SKV_ERR_HIP: return "SKV_ERR_HIP";
     }
     return "SKV_ERR_UNKNOWN";
-}
-
-skv_status_t skv_calib_mfma_bf16(const void *operands, float *sink, int32_t blocks, int32_t iters, void *stream) {
-    if (!operands || !sink || blocks < 1 || iters < 1 || iters > (1 << 20)) return SKV_ERR_INVALID_ARG;
-    const hipError_t e = skv::launch_calib_mfma(operands, sink, blocks, iters, 0, (hipStream_t)stream);
-    return e == hipSuccess ? SKV_OK : hip_fail(e);
-}
-
-skv_status_t skv_calib_mfma_mix_bf16(const void *operands, float *sink, int32_t blocks, int32_t iters, int32_t mix,
-                                     void *stream) {
-    if (!operands || !sink || blocks < 1 || iters < 1 || iters > (1 << 20) || mix < 0 || mix > 3) return SKV_ERR_INVALID_ARG;
-    const hipError_t e = skv::launch_calib_mfma(operands, sink, blocks, iters, mix, (hipStream_t)stream);
-    return e == hipSuccess ? SKV_OK : hip_fail(e);
 }
 
 int32_t skv_last_hip_error(void) { return g_last_hip_error; }

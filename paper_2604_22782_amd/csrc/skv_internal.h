@@ -39,7 +39,7 @@ struct AttnArgs {
     const int32_t *kv_lens; // [batch]
     float *part_o;          // split partials [rows*n_q_heads][n_splits][head_dim]
     float *part_ml;         // [rows*n_q_heads][n_splits][2]  (max, sum)
-    int32_t *work_counters; // two device words, zero at rest: next work item, work groups that left
+    int32_t *work_counters; // one device word (256-byte block): next work item of the persistent launch shape
     int32_t batch;
     int32_t max_q;          // query rows per sequence in q/out (1 for decode)
     int32_t n_q_heads;
@@ -98,9 +98,16 @@ struct TrainBwdArgs {
 };
 hipError_t launch_train_bwd(const TrainBwdArgs &a, int dtype, int head_dim, hipStream_t stream);
 
-// Measurement aid: back-to-back MFMAs on caller-given operands (16 blocks of 64 lanes x 16 bytes).
-hipError_t launch_calib_mfma(const void *operands, float *sink, int blocks, int iters, int mix, hipStream_t stream);
-
 void set_last_kernel_name(const char *name);
+
+// Developer knobs (see tuning() in skv_api.hip); all zero / false unless SKV_TUNING=1 is set.
+struct Tuning {
+    int decode_keys_per_split = 0; // 0 = chosen by the library
+    int decode_loads = 0;          // 0 = chosen by the library, 1 = non-temporal, 2 = cached
+    bool prefill_plain = false;
+    bool project_wide = false;
+    int project_splits = 0;
+};
+const Tuning &tuning();
 
 } // namespace skv

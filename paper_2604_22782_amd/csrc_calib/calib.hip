@@ -3,9 +3,10 @@
 // the nominal rate (one instruction per 32 clocks and SIMD at the boost clock); with operands like
 // the ones attention feeds them (Gaussian values, a different operand pair for every instruction)
 // the power limit lowers the clock, and that lower rate is what the pre-fill kernel competes with.
-#include "skv_internal.h"
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
-namespace skv {
+#include "skv_calib.h"
 
 namespace {
 
@@ -89,8 +90,6 @@ __global__ __launch_bounds__(256) void calib_mfma_kernel(const u32x4 *__restrict
     sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = side == 123456.789f ? side : s;
 }
 
-} // namespace
-
 hipError_t launch_calib_mfma(const void *operands, float *sink, int blocks, int iters, int mix, hipStream_t stream) {
     const dim3 grid((unsigned)blocks);
     const u32x4 *ops = (const u32x4 *)operands;
@@ -104,4 +103,22 @@ hipError_t launch_calib_mfma(const void *operands, float *sink, int blocks, int 
     return hipGetLastError();
 }
 
-} // namespace skv
+} // namespace
+
+extern "C" {
+
+int32_t skv_calib_mfma_mix_bf16(const void *operands, float *sink, int32_t blocks, int32_t iters, int32_t mix,
+                                void *stream) {
+    if (!operands || !sink || blocks < 1 || iters < 1 || iters > (1 << 20) || mix < 0 || mix > 3) return 1;
+    if (launch_calib_mfma(operands, sink, blocks, iters, mix, (hipStream_t)stream) != hipSuccess) {
+        (void)hipGetLastError();
+        return 7;
+    }
+    return 0;
+}
+
+int32_t skv_calib_mfma_bf16(const void *operands, float *sink, int32_t blocks, int32_t iters, void *stream) {
+    return skv_calib_mfma_mix_bf16(operands, sink, blocks, iters, 0, stream);
+}
+
+} // extern "C"

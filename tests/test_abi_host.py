@@ -30,6 +30,19 @@ def test_library_exports_every_declared_symbol():
     assert declared == {n for n in skv.__all__ if n.startswith("skv_")}   # binding uses the same names
 
 
+def test_calibration_library_exports_its_header():
+    """The benchmark's measurement aid is a library of its own; the product library does not export it."""
+    from paper_2604_22782_amd import calib
+    header = open(os.path.join(ROOT, "include", "skv_calib.h")).read()
+    declared = set(re.findall(r"\b(skv_calib_[a-z0-9_]+)\s*\(", header))
+    assert declared == {"skv_calib_mfma_bf16", "skv_calib_mfma_mix_bf16"}
+    for name in declared:
+        assert hasattr(calib.lib(), name)
+        assert not hasattr(skv.lib(), name)
+    assert calib.lib().skv_calib_mfma_bf16(None, None, 1, 1, None) == 1
+    assert calib.lib().skv_calib_mfma_mix_bf16(None, None, 1, 1, 0, None) == 1
+
+
 def test_status_strings():
     for code, name in skv.STATUS.items():
         assert skv.skv_status_str(code) == name
@@ -113,8 +126,6 @@ def test_null_handles_and_no_device_behaviour():
     assert lib.skv_decode_range_workspace_bytes(None, 1, 1, ctypes.byref(n)) == 1
     assert lib.skv_attn_prefill(None, 0, None, None, None, None, 1, 1, ctypes.c_float(1.0), None) == 1
     assert lib.skv_cache_bytes(None, None) == 1
-    assert lib.skv_calib_mfma_bf16(None, None, 1, 1, None) == 1
-    assert lib.skv_calib_mfma_mix_bf16(None, None, 1, 1, 0, None) == 1
     assert lib.skv_kv_project_append(None, 0, None, None, None, None, None, 0, None, ctypes.c_float(0.0), None, None, 1, 64, None, 0, None) == 1
     assert lib.skv_kv_project_workspace_bytes(None, 1, 64, ctypes.byref(n)) == 1
     import torch

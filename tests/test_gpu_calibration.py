@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 import torch
 
-import paper_2604_22782_amd as skv
+from paper_2604_22782_amd import calib as skv
 
 pytestmark = pytest.mark.gpu
 
@@ -36,7 +36,7 @@ def test_mfma_calibration_kernel_result():
         other = torch.full_like(sink, float("nan"))
         skv.skv_calib_mfma_mix_bf16(ops.cuda(), other, blocks, iters, mix)
         assert torch.equal(other, sink), mix
-    with pytest.raises(skv.SkvError):
+    with pytest.raises(RuntimeError):
         skv.skv_calib_mfma_mix_bf16(ops.cuda(), sink, blocks, iters, 4)
-    with pytest.raises(skv.SkvError):
+    with pytest.raises(RuntimeError):
         skv.skv_calib_mfma_bf16(ops.cuda(), sink, blocks, 0)

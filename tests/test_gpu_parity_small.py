@@ -167,15 +167,6 @@ def test_prefill_matches_oracle_exhaustively(dtype, hq, hkv, d, kv_lens, q_lens,
     assert skv.skv_cache_device_faults(cache) == 0
 
 
-@pytest.mark.parametrize("case", [c for c in PREFILL_CASES if c[0] != "f32" and c[3] == 128])
-def test_prefill_shape_with_eight_waves_matches_oracle(case, monkeypatch):
-    """The pipelined kernel in its other shape (8 waves of 32 rows, two per SIMD instead of 4 waves
-    of 64 rows), which the library picks at launch time from the environment."""
-    monkeypatch.setenv("SKV_PREFILL_WAVES", "8")
-    test_prefill_matches_oracle_exhaustively(*case)
-    assert skv.skv_last_kernel_name() == "prefill_pipe_kernel"
-
-
 def test_decode_equals_last_prefill_row_and_chunked_prefill():
     w = _small("bf16", 8, 2, 128, 2, [384, 200], [0, 0])
     cache, _ = H.alloc_cache(w)
@@ -247,12 +238,10 @@ def test_scale_must_be_positive():
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
-@pytest.mark.parametrize("waves", ["4", "8"])
-def test_prefill_with_growing_scores_rescales_often(dtype, waves, monkeypatch):
+def test_prefill_with_growing_scores_rescales_often(dtype):
     """Keys whose norm grows with the position: the running row maximum keeps jumping by far more
     than the lazy-rescale threshold, so the rescale path of the prefill kernels (new maximum,
     deferred O and row-sum rescale) runs on most tiles instead of once."""
-    monkeypatch.setenv("SKV_PREFILL_WAVES", waves)
     tdt = {"bf16": torch.bfloat16, "f16": torch.float16}[dtype]
     B, S, Hq, Hkv, D = 2, 700, 2, 1, 128
     route = [0, 0]

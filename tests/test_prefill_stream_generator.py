@@ -10,26 +10,16 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _load(nq, paged=0):
-    """The generator fixes the wave shape (row blocks of 32 per wave) and the cache addressing
-    (contiguous or through a block table) when it is imported."""
+def _load():
     spec = importlib.util.spec_from_file_location(
-        f"gen_prefill_pipe_nq{nq}_{paged}", os.path.join(ROOT, "paper_2604_22782_amd", "csrc", "gen_prefill_pipe.py"))
+        "gen_prefill_pipe", os.path.join(ROOT, "paper_2604_22782_amd", "csrc", "gen_prefill_pipe.py"))
     mod = importlib.util.module_from_spec(spec)
-    keep = {k: os.environ.get(k) for k in ("SKV_GEN_NQ", "SKV_GEN_PAGED")}
-    os.environ["SKV_GEN_NQ"], os.environ["SKV_GEN_PAGED"] = str(nq), str(paged)
-    try:
-        spec.loader.exec_module(mod)
-    finally:
-        for k, v in keep.items():
-            if v is None:
-                del os.environ[k]
-            else:
-                os.environ[k] = v
+    spec.loader.exec_module(mod)
     return mod
 
 
-GEN = {(nq, paged): _load(nq, paged) for nq in (1, 2) for paged in (0, 1)}
+MOD = _load()
+GEN = {(nq, paged): MOD.generator(nq, bool(paged)) for nq in (1, 2) for paged in (0, 1)}
 G = GEN[(2, 0)]
 
 
@@ -84,28 +74,26 @@ def test_hazard_check_accepts_the_stream_and_rejects_a_planted_read(nq, paged):
     G.check_mfma_results(ok)
 
 
-def _piece_offset(rowq, piece, row):
+def _piece_offset(piece, row):
     """Byte offset inside a 1 KiB chunk of the 16-byte piece `piece` (0..15) of row `row` (0..3)."""
-    return 256 * (piece >> 2) + 64 * row + 16 * (piece & 3) if rowq else 64 * piece + 16 * row
+    return 256 * (piece >> 2) + 64 * row + 16 * (piece & 3)
 
 
-@pytest.mark.parametrize("rowq", [1, 0])
-def test_lds_layout_is_bank_conflict_free(rowq):
+def test_lds_layout_is_bank_conflict_free():
     """64 banks x 4 bytes.  A load writes lane L's 16 bytes at 16 L of its chunk: the lane-to-(row,
     piece) map of the layout must fill the chunk exactly, with four neighbouring lanes on one row's
-    64 contiguous bytes in the row-quad layout.  K operand: a pass of 16 lanes reads 16 bytes each
-    of rows c = 0..15, same piece; V operand: a pass of 16 lanes reads 8 bytes each (4 rows x 4 x 8
-    bytes).  Every pass must touch each bank at most once."""
-    chunk = 1040 if rowq else 1088
-    assert G.CHUNK == (1040 if G.ROWQ else 1088)
+    64 contiguous bytes.  K operand: a pass of 16 lanes reads 16 bytes each of rows c = 0..15, same
+    piece; V operand: a pass of 16 lanes reads 8 bytes each (4 rows x 4 x 8 bytes).  Every pass must
+    touch each bank at most once."""
+    chunk = G.CHUNK
+    assert chunk == 1040
     for lane in range(64):
-        row, piece = ((lane >> 2) & 3, 4 * (lane >> 4) + (lane & 3)) if rowq else (lane & 3, lane >> 2)
-        assert _piece_offset(rowq, piece, row) == 16 * lane
-    if rowq:
-        for quad in range(16):
-            rows = {(lane >> 2) & 3 for lane in range(4 * quad, 4 * quad + 4)}
-            pieces = sorted(4 * (lane >> 4) + (lane & 3) for lane in range(4 * quad, 4 * quad + 4))
-            assert len(rows) == 1 and pieces == list(range(pieces[0], pieces[0] + 4)) and pieces[0] % 4 == 0
+        row, piece = (lane >> 2) & 3, 4 * (lane >> 4) + (lane & 3)
+        assert _piece_offset(piece, row) == 16 * lane
+    for quad in range(16):
+        rows = {(lane >> 2) & 3 for lane in range(4 * quad, 4 * quad + 4)}
+        pieces = sorted(4 * (lane >> 4) + (lane & 3) for lane in range(4 * quad, 4 * quad + 4))
+        assert len(rows) == 1 and pieces == list(range(pieces[0], pieces[0] + 4)) and pieces[0] % 4 == 0
 
     def banks(addr, nbytes):
         return [((addr + b) // 4) % 64 for b in range(0, nbytes, 4)]
@@ -114,7 +102,7 @@ def test_lds_layout_is_bank_conflict_free(rowq):
             for base_c in (0, 16):
                 used = []
                 for c in range(base_c, base_c + 16):
-                    used += banks((c >> 2) * chunk + _piece_offset(rowq, 2 * s + hh, c & 3), 16)
+                    used += banks((c >> 2) * chunk + _piece_offset(2 * s + hh, c & 3), 16)
                 assert len(used) == len(set(used)) == 64
     for hh in range(2):
         for a in range(2):
@@ -122,7 +110,7 @@ def test_lds_layout_is_bank_conflict_free(rowq):
                 used = []
                 for sl in range(16):   # key row 4 hh + sl / 4, d offset 32 db + 16 a + 4 (sl % 4): 8 bytes
                     d_byte = 2 * (32 * db + 16 * a + 4 * (sl & 3))
-                    used += banks(hh * chunk + _piece_offset(rowq, d_byte // 16, sl >> 2) + d_byte % 16, 8)
+                    used += banks(hh * chunk + _piece_offset(d_byte // 16, sl >> 2) + d_byte % 16, 8)
                 assert len(used) == len(set(used)) == 32
     # the ring fits the 160 KiB of LDS of a compute unit
     assert G.LDS_BYTES <= 160 * 1024
