@@ -204,6 +204,20 @@ skv_status_t skv_attn_decode_range(skv_cache_t *cache, int32_t layer, int32_t se
                                    const void *q, void *out, const int32_t *kv_lens, int32_t max_kv_len,
                                    float scale, void *workspace, size_t workspace_bytes, void *stream);
 
+/* skv_attn_decode for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and errors as skv_attn_decode, but the split partials and the work counter live
+ * in a scratch array that is part of the library's device image (skv_static_scratch_bytes: 64 MiB per
+ * device, present from load time until the process ends); the call allocates and frees nothing.
+ * SKV_ERR_CAPACITY if skv_decode_workspace_bytes(cache, max_kv_len) exceeds that size (nothing is
+ * enqueued).  Every call on one device shares that device's scratch: two calls that overlap in
+ * time on one device race (keep them on one stream or order the streams), whatever their caches.
+ * The first call on a device looks the array's address up (no allocation); make it outside a
+ * stream capture. */
+skv_status_t skv_static_scratch_bytes(size_t *bytes);
+skv_status_t skv_attn_decode_static(skv_cache_t *cache, int32_t layer, const void *q, void *out,
+                                    const int32_t *kv_lens, int32_t max_kv_len, float scale, void *stream);
+
 /* Pre-fill-phase attention: q_lens[b] query rows per sequence; row i sits at absolute position
  * kv_lens[b] - q_lens[b] + i and sees cached positions 0..that position of the routed slot.
  * q, out: device [batch][max_q][n_q_heads][head_dim]; rows i >= q_lens[b] are neither read nor

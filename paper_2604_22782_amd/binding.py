@@ -10,7 +10,7 @@ __all__ = [
     "skv_route_from_strategy", "skv_route_validate", "skv_cache_bytes", "skv_cache_alloc",
     "skv_cache_free", "skv_cache_info", "skv_cache_slot_of_layer", "skv_cache_set_block_table",
     "skv_cache_device_faults", "skv_kv_append", "skv_kv_project_append", "skv_kv_project_workspace_bytes", "skv_decode_workspace_bytes", "skv_attn_decode",
-    "skv_decode_range_workspace_bytes", "skv_attn_decode_range", "skv_attn_prefill", "skv_status_str", "skv_last_hip_error", "skv_last_kernel_name",
+    "skv_decode_range_workspace_bytes", "skv_attn_decode_range", "skv_static_scratch_bytes", "skv_attn_decode_static", "skv_attn_prefill", "skv_status_str", "skv_last_hip_error", "skv_last_kernel_name",
     "skv_train_sample_route", "skv_train_attn_fwd", "skv_train_bwd_workspace_bytes",
     "skv_train_attn_bwd", "skv_train_device_faults", "SKV_TRAIN_RCLA", "SKV_TRAIN_CLA_K", "SKV_TRAIN_RDCLA_K",
 ]
@@ -240,6 +240,17 @@ def skv_attn_decode_range(cache: Cache, layer: int, seq_begin: int, seq_count: i
     _check(lib().skv_attn_decode_range(cache.handle, layer, seq_begin, seq_count, _ptr(q), _ptr(out),
                                        _ptr(kv_lens), max_kv_len, ctypes.c_float(scale), _ptr(workspace),
                                        ctypes.c_size_t(wb), _stream(stream)), "skv_attn_decode_range")
+
+
+def skv_static_scratch_bytes() -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().skv_static_scratch_bytes(ctypes.byref(out)), "skv_static_scratch_bytes")
+    return out.value
+
+
+def skv_attn_decode_static(cache: Cache, layer: int, q, out, kv_lens, max_kv_len: int, scale: float, stream=None):
+    _check(lib().skv_attn_decode_static(cache.handle, layer, _ptr(q), _ptr(out), _ptr(kv_lens), max_kv_len,
+                                        ctypes.c_float(scale), _stream(stream)), "skv_attn_decode_static")
 
 
 def skv_attn_prefill(cache: Cache, layer: int, q, out, q_lens, kv_lens, max_q: int, max_kv_len: int,

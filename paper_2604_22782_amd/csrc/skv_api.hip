@@ -444,6 +444,52 @@ skv_status_t skv_attn_decode(skv_cache_t *c, int32_t layer, const void *q, void 
                                  workspace_bytes, stream);
 }
 
+namespace {
+// Scratch of skv_attn_decode_static: device memory that exists from the moment the library is loaded
+// (one copy per device, held until the process ends).  In host code the array's name is only a
+// stand-in; its device address comes from hipGetSymbolAddress, once per device.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+__device__ __attribute__((aligned(256))) unsigned char scratch[kStaticScratchBytes];
+
+skv_status_t static_scratch(void **out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void *ptr[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return SKV_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(mu);
+    if (ptr[dev] == nullptr) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e);
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return SKV_OK;
+}
+} // namespace
+
+skv_status_t skv_static_scratch_bytes(size_t *bytes) {
+    if (!bytes) return SKV_ERR_INVALID_ARG;
+    *bytes = kStaticScratchBytes;
+    return SKV_OK;
+}
+
+skv_status_t skv_attn_decode_static(skv_cache_t *c, int32_t layer, const void *q, void *out, const int32_t *kv_lens,
+                                    int32_t max_kv_len, float scale, void *stream) {
+    if (!c || max_kv_len <= 0) return SKV_ERR_INVALID_ARG;
+    size_t need = 0;
+    if (skv_status_t st = skv_decode_workspace_bytes(c, max_kv_len, &need); st != SKV_OK) return st;
+    if (need > kStaticScratchBytes) return SKV_ERR_CAPACITY;
+    void *ws = nullptr;
+    if (skv_status_t st = static_scratch(&ws); st != SKV_OK) return st;
+    // the kernels take the scratch as they take a caller's workspace; the work counter at its start is
+    // cleared in-stream by the launcher, every split partial is written before the merge reads it
+    return skv_attn_decode_range(c, layer, 0, c->d.batch, q, out, kv_lens, max_kv_len, scale, ws, need, stream);
+}
+
 skv_status_t skv_attn_prefill(skv_cache_t *c, int32_t layer, const void *q, void *out,
                               const int32_t *q_lens, const int32_t *kv_lens, int32_t max_q,
                               int32_t max_kv_len, float scale, void *stream) {
