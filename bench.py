@@ -33,13 +33,46 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+TRAFFIC_FILE = os.path.join("profiles", "hbm_traffic.json")
+# sources a kernel is built from: the committed counter summary names their hash, and a summary
+# taken from other sources than the ones on disk is not reported
+KERNEL_SOURCES = {
+    "decode_mfma_kernel": ["decode_mfma.hip"], "append_rows_kernel": ["append.hip"],
+    "prefill_pipe_kernel": ["prefill_pipe.hip", "gen_prefill_pipe.py"],
+    "dkdv_kernel": ["train_bwd.hip"], "dq_kernel": ["train_bwd.hip"], "delta_kernel": ["train_bwd.hip"],
+    "project_append_tile_kernel": ["project_append.hip"], "project_append_kernel": ["project_append.hip"],
+    "project_finish_kernel": ["project_append.hip"],
+}
+
+
+def source_sha(kernel):
+    import hashlib
+    h = hashlib.sha256()
+    for f in KERNEL_SOURCES.get(kernel, []):
+        h.update(open(os.path.join(ROOT, "paper_2604_22782_amd", "csrc", f), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def measured_traffic(kernel):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary (or None)."""
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None if
+    there is none for the kernel's present sources."""
     try:
-        t = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic.json")))[kernel]
+        t = json.load(open(os.path.join(ROOT, TRAFFIC_FILE)))[kernel]
+        if t.get("source_sha16") != source_sha(kernel):
+            return None
         return int(t["FETCH_SIZE"]["bytes"] + t["WRITE_SIZE"]["bytes"])
     except Exception:
         return None
+
+
+def traffic_fields(kernels):
+    """`traffic` is not measured by this run (counters need the profiler): it is the committed
+    rocprofv3 FETCH_SIZE + WRITE_SIZE summary of the same command, valid only for unchanged sources."""
+    parts = [measured_traffic(k) for k in kernels]
+    ok = all(p is not None for p in parts)
+    return {"traffic": sum(parts) if ok else None,
+            "traffic_source": f"{TRAFFIC_FILE} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this "
+                              f"command; " + ("kernel sources unchanged since)" if ok else "none for the present sources)")}
 
 
 def cpu_baseline_decode(w, seconds_budget=12.0):
@@ -78,58 +111,18 @@ def cpu_baseline_decode(w, seconds_budget=12.0):
                       f"heads x {n} keys, repeated {reps}x ({dt:.1f} s); bytes counted as for the GPU (16-bit K/V)"}
 
 
-def cross_layer_reuse_sweep(args, torch, skv, w, cache, qs, outs, new_k, new_v, d_lens, d_start, ones, ctx,
-                            step_bytes):
-    """The layers of one sharing group read the same slot.  Walk them group by group and, inside a
-    group, chunk by chunk over the sequences (all layers of the group on chunk 0, then on chunk 1,
-    ...): once a chunk's slice of the slot fits the on-chip caches, only the first layer of the group
-    reads it from HBM.  Same work and same algorithmic bytes as the plain step; chunk = batch is the
-    plain layer-by-layer order."""
-    groups = {}
-    for l in range(w.n_layers):
-        groups.setdefault(int(w.route[l]), []).append(l)
-    row = w.n_kv_heads * w.head_dim * w.elem_bytes
-    points = []
-    steps = max(3, min(args.steps, 10))
-    for chunk in (w.batch, 32, 16, 8, 4):
-        if chunk > w.batch or w.batch % chunk:
-            continue
-        n = skv.skv_decode_range_workspace_bytes(cache, chunk, ctx)
-        wsr = torch.empty(n // 4 + 1, dtype=torch.float32, device="cuda")
-
-        def step():
-            for owner, layers in groups.items():
-                skv.skv_kv_append(cache, owner, new_k[owner], new_v[owner], d_start, ones, 1)
-                for b0 in range(0, w.batch, chunk):
-                    for l in layers:
-                        skv.skv_attn_decode_range(cache, l, b0, chunk, qs[l][b0:], outs[l][b0:], d_lens[b0:],
-                                                  ctx, w.scale, wsr)
-        for _ in range(2):
-            step()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            step()
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / steps
-        points.append({"chunk_seqs": chunk, "slot_slice_MiB": round(chunk * ctx * row * 2 / 2**20, 1),
-                       "ms_per_step": round(dt * 1e3, 3), "GB/s": round(step_bytes / dt / 1e9, 1)})
-        del wsr
-    assert skv.skv_cache_device_faults(cache) == 0
-    return {"schedule": "per sharing group: for each chunk of sequences, every layer of the group "
-                        "(skv_attn_decode_range)", "layers_per_group": w.n_layers // len(groups),
-            "unit_note": "GB/s = algorithmic bytes of the step / time; above the HBM peak means reuse on chip",
-            "points": points}
+def _newest_rows(w, which, l, ctx):
+    """The K/V row of each sequence's newest position."""
+    import torch
+    if int(w.kv_lens.min()) == ctx:
+        return w.kv_rows(which, l, 0, w.batch, ctx - 1, ctx, "cuda")
+    return torch.cat([w.kv_rows(which, l, b, b + 1, int(n) - 1, int(n), "cuda") for b, n in enumerate(w.kv_lens)])
 
 
-def run_decode(args, torch, skv, H, configs):
-    if args.decode_workload == "qwen3_paged":
-        w = configs.qwen3_paged_decode()
-    elif args.decode_workload == "llama2_mha":
-        w = configs.llama2_mha_decode(batch=args.mha_batch)
-    else:
-        w = configs.llama3_decode()
-    log(f"[bench] workload {w.name}: B={w.batch} ctx={int(w.kv_lens[0])} layers={w.n_layers} slots={len(w.owner_layers)}")
+def run_decode(args, torch, skv, H, w, steps, warmup, headline=False):
+    """One decode token per step over all layers of workload w: owner layers append the new K/V row,
+    every layer attends over its routed slot.  Returns the step rate and the roofline of the call."""
+    log(f"[bench] workload {w.name}: B={w.batch} ctx={int(w.kv_lens.max())} layers={w.n_layers} slots={len(w.owner_layers)}")
     cache, _ = H.alloc_cache(w)
     t0 = time.perf_counter()
     H.fill_by_append(cache, w, lens=w.kv_lens - 1, chunk_tokens=args.fill_chunk_tokens)
@@ -140,14 +133,8 @@ def run_decode(args, torch, skv, H, configs):
     ones = torch.ones(w.batch, dtype=torch.int32, device="cuda")
     ws = H.workspace_for(cache, ctx)
     qs = [w.q_decode(l, "cuda") for l in range(w.n_layers)]
-
-    def newest_rows(which, l):   # the K/V row of each sequence's newest position
-        if int(w.kv_lens.min()) == ctx:
-            return w.kv_rows(which, l, 0, w.batch, ctx - 1, ctx, "cuda")
-        return torch.cat([w.kv_rows(which, l, b, b + 1, int(n) - 1, int(n), "cuda") for b, n in enumerate(w.kv_lens)])
-
-    new_k = {l: newest_rows("k", l) for l in w.owner_layers}
-    new_v = {l: newest_rows("v", l) for l in w.owner_layers}
+    new_k = {l: _newest_rows(w, "k", l, ctx) for l in w.owner_layers}
+    new_v = {l: _newest_rows(w, "v", l, ctx) for l in w.owner_layers}
     outs = [torch.empty_like(qs[0]) for _ in range(w.n_layers)]
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(w.n_layers)]
 
@@ -161,18 +148,18 @@ def run_decode(args, torch, skv, H, configs):
             if timed_events:
                 ev[l][1].record()
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     kernel_name = skv.skv_last_kernel_name()
     # dominant kernel: events around each layer's decode call (kernel + its small merge launch)
     per_call = []
-    for _ in range(max(3, min(args.steps, 10))):
+    for _ in range(max(3, min(steps, 10))):
         step(timed_events=True)
         torch.cuda.synchronize()
         per_call += [ev[l][0].elapsed_time(ev[l][1]) for l in range(w.n_layers)]
@@ -181,26 +168,168 @@ def run_decode(args, torch, skv, H, configs):
     layer_bytes = w.decode_bytes_per_layer()
     append_bytes = len(w.owner_layers) * 2 * 2 * w.batch * w.n_kv_heads * w.head_dim * w.elem_bytes
     step_bytes = layer_bytes * w.n_layers + append_bytes
-    ms_per_step = dt / args.steps * 1e3
-    value = step_bytes / (dt / args.steps) / 1e9
+    ms_per_step = dt / steps * 1e3
+    value = step_bytes / (dt / steps) / 1e9
     achieved = layer_bytes / (call_ms * 1e-3) / 1e9
-    reuse = None
-    if args.reuse_sweep and not w.block_size:
-        reuse = cross_layer_reuse_sweep(args, torch, skv, w, cache, qs, outs, new_k, new_v, d_lens, d_start,
-                                        ones, ctx, step_bytes)
-    res = {
-        "value": round(value, 1), "ms_per_step": round(ms_per_step, 4), "cross_layer_reuse": reuse,
-        "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     # the committed counter summary was taken on the default workload only
-                     "traffic": measured_traffic(kernel_name) if args.decode_workload == "llama3_decode" else None,
-                     "launch_us": round(call_ms * 1e3, 2), "algorithmic_bytes_per_launch": layer_bytes},
-        "workload": w,
-    }
+    roof = {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4)}
+    # the committed counter summary was taken on the headline workload only
+    roof.update(traffic_fields([kernel_name]) if headline else {"traffic": None})
+    roof.update({"launch_us": round(call_ms * 1e3, 2), "algorithmic_bytes_per_launch": layer_bytes})
+    res = {"value": round(value, 1), "ms_per_step": round(ms_per_step, 4), "steps": steps, "roofline": roof,
+           "config": {"workload": w.name, "batch": w.batch, "max_context": ctx, "layers": w.n_layers,
+                      "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
+                      "slots": len(w.owner_layers), "sum_kv_len": int(w.kv_lens.sum()), "paged": bool(w.block_size),
+                      "dtype": w.dtype, "step": "append(owner)+decode per layer"}}
     cache.free()
-    del ws, qs, outs
+    del ws, qs, outs, new_k, new_v
     torch.cuda.empty_cache()
     return res
+
+
+def run_append(args, torch, skv, H, configs):
+    """The cache update of the owner layers (Alg. 2, "Update") alone, against the HBM copy roofline:
+    the rows of a whole prompt (the prefill workload: 4 x 8192 rows of 2 KiB, K and V: 128 MiB read and
+    128 MiB written per owner layer) and of one decode token (the decode workload: 64 rows).
+    Algorithmic bytes = new rows x 2 (K, V) x row bytes, read once and written once."""
+    out = {}
+    for regime, w, new in (("prompt", configs.llama3_prefill(), None), ("decode_token", configs.llama3_decode(n_layers=8), 1)):
+        S = int(w.kv_lens.max())
+        new = S if new is None else new
+        cache, _ = H.alloc_cache(w)
+        owners = w.owner_layers
+        # sources and destination slots rotate so that no launch finds its rows in the on-chip caches
+        n_src = 4 if regime == "prompt" else len(owners)
+        k_new = [w.kv_rows("k", owners[i % len(owners)], 0, w.batch, S - new, S, "cuda") for i in range(n_src)]
+        v_new = [w.kv_rows("v", owners[i % len(owners)], 0, w.batch, S - new, S, "cuda") for i in range(n_src)]
+        start = torch.full((w.batch,), S - new, dtype=torch.int32, device="cuda")
+        lens = torch.full((w.batch,), new, dtype=torch.int32, device="cuda")
+        reps = 40 if regime == "prompt" else 400
+        for i in range(8):
+            skv.skv_kv_append(cache, owners[i % len(owners)], k_new[i % n_src], v_new[i % n_src], start, lens, new)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            skv.skv_kv_append(cache, owners[i % len(owners)], k_new[i % n_src], v_new[i % n_src], start, lens, new)
+        e1.record()
+        torch.cuda.synchronize()
+        assert skv.skv_cache_device_faults(cache) == 0
+        us = e0.elapsed_time(e1) / reps * 1e3
+        nbytes = 2 * (w.batch * new * 2 * w.n_kv_heads * w.head_dim * w.elem_bytes)
+        gbs = nbytes / (us * 1e-6) / 1e9
+        out[regime] = {"workload": w.name, "rows": w.batch * new, "launch_us": round(us, 2),
+                       "roofline": {"bound": "hbm", "kernel": "append_rows_kernel", "achieved": round(gbs, 1),
+                                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
+                                    "traffic": None, "algorithmic_bytes_per_launch": nbytes}}
+        log(f"[bench] append {regime}: {us:.1f} us, {gbs:.0f} GB/s")
+        cache.free()
+        del k_new, v_new
+        torch.cuda.empty_cache()
+    return out
+
+
+def run_small_launches(args, torch, skv, H, configs):
+    """Decode bandwidth against the size of the launch: the decode workload's shape with 1 .. 64
+    sequences of 4096 positions per launch (16 MiB .. 1 GiB of K and V), through
+    skv_attn_decode_range.  Launches rotate over the 16 slots and over the sequences, so every launch
+    reads rows that were last touched at least 1 GiB of traffic ago (nothing is found on chip)."""
+    w = configs.llama3_decode()
+    cache, _ = H.alloc_cache(w)
+    H.fill_by_append(cache, w, chunk_tokens=args.fill_chunk_tokens)
+    ctx = int(w.kv_lens.max())
+    d_lens = torch.from_numpy(w.kv_lens).cuda()
+    q = w.q_decode(0, "cuda")
+    out = torch.empty_like(q)
+    row = w.n_kv_heads * w.head_dim * w.elem_bytes
+    points = []
+    for n_seq in (1, 2, 4, 8, 16, 32, 64):
+        ws = torch.empty(skv.skv_decode_range_workspace_bytes(cache, n_seq, ctx) // 4 + 1, dtype=torch.float32, device="cuda")
+        launches = []
+        for i in range(64):            # (layer, first sequence): 64 distinct slices, >= 1 GiB apart in time
+            layer = (2 * i) % w.n_layers
+            b0 = ((i // 16) * n_seq) % w.batch if n_seq < w.batch else 0
+            launches.append((layer, b0))
+        def run():
+            for layer, b0 in launches:
+                skv.skv_attn_decode_range(cache, layer, b0, n_seq, q[b0:], out[b0:], d_lens[b0:], ctx, w.scale, ws)
+        run()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 3
+        e0.record()
+        for _ in range(reps):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / (reps * len(launches)) * 1e3
+        nbytes = n_seq * ctx * 2 * row + 2 * n_seq * w.n_q_heads * w.head_dim * w.elem_bytes
+        points.append({"sequences": n_seq, "launch_MiB": round(n_seq * ctx * 2 * row / 2**20, 1), "launch_us": round(us, 2),
+                       "GB/s": round(nbytes / (us * 1e-6) / 1e9, 1), "frac": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)})
+        log(f"[bench] small launch {points[-1]}")
+        del ws
+    assert skv.skv_cache_device_faults(cache) == 0
+    cache.free()
+    torch.cuda.empty_cache()
+    return {"shape": "llama3_8b decode: 32 q / 8 kv heads, d 128, 4096 positions per sequence, bf16; "
+                     "launch_us includes the merge launch where the key axis is split", "points": points}
+
+
+def run_cross_layer_reuse(args, torch, skv, H, configs):
+    """The closing remark of Sec. 4.3: the layers of a sharing group read the same K, V, so a backend
+    could serve the later ones from on-chip memory.  At the sizes of the paper's own benchmark (Tab. 4:
+    batch 1, 2K .. 32K positions; Tab. 5: 8K positions, batch 2 .. 16; Qwen3-8B heads; groups of 2, 4, 8)
+    a layer's slice of its slot is 8 .. 512 MiB, around the 256 MiB memory-side cache of the device.
+    Per point: a stack of n_groups x g layers (enough groups that their slices together exceed 1 GiB,
+    so the first reader of a group always finds its slice in HBM only), one decode token through all
+    layers in order, HIP events around every call; reported per reader position within the group."""
+    import math as _m
+    points = []
+    row = 8 * 128 * 2
+    grid = [(1, T, 4) for T in (2048, 8192, 16384, 32768)] + [(B, 8192, 4) for B in (2, 4, 8, 16)] + \
+           [(1, 8192, 2), (1, 8192, 8), (4, 8192, 2), (4, 8192, 8)]
+    for batch, ctx, g in grid:
+        slice_bytes = batch * ctx * 2 * row
+        n_groups = max(2, _m.ceil((1 << 30) / slice_bytes) + 1)
+        L = n_groups * g
+        w = configs.Workload(f"reuse_b{batch}_t{ctx}_g{g}", "bf16", L, 32, 8, 128, batch, configs.grouped_route(L, g),
+                             np.full(batch, ctx), 1.0, 0.5, seed=1100 + g)
+        cache, _ = H.alloc_cache(w)
+        H.fill_by_append(cache, w, chunk_tokens=args.fill_chunk_tokens)
+        d_lens = torch.from_numpy(w.kv_lens).cuda()
+        ws = H.workspace_for(cache, ctx)
+        q = [w.q_decode(l % 8, "cuda") for l in range(8)]
+        out = torch.empty_like(q[0])
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(L)]
+
+        def one_pass(timed):
+            for l in range(L):
+                if timed:
+                    ev[l][0].record()
+                skv.skv_attn_decode(cache, l, q[l % 8], out, d_lens, ctx, w.scale, ws)
+                if timed:
+                    ev[l][1].record()
+        one_pass(False)
+        per = [[] for _ in range(g)]
+        for _ in range(3):
+            one_pass(True)
+            torch.cuda.synchronize()
+            for l in range(L):
+                per[l % g].append(ev[l][0].elapsed_time(ev[l][1]) * 1e3)
+        assert skv.skv_cache_device_faults(cache) == 0
+        nbytes = w.decode_bytes_per_layer()
+        first = float(np.mean(per[0]))
+        later = float(np.mean([x for r in per[1:] for x in r]))
+        group_us = first + (g - 1) * later
+        points.append({"batch": batch, "ctx": ctx, "g": g, "slice_MiB": round(slice_bytes / 2**20, 1), "groups": n_groups,
+                       "first_reader_us": round(first, 2), "later_readers_us": round(later, 2),
+                       "first_reader_GB/s": round(nbytes / first / 1e3, 1), "later_readers_GB/s": round(nbytes / later / 1e3, 1),
+                       "group_GB/s": round(g * nbytes / group_us / 1e3, 1)})
+        log(f"[bench] reuse {points[-1]}")
+        cache.free()
+        del ws, q, out
+        torch.cuda.empty_cache()
+    return {"note": "GB/s = algorithmic bytes of a call / its time between HIP events (kernel + merge launch); above the "
+                    "8000 GB/s HBM peak means the slice came from on-chip memory; FETCH_SIZE per reader: "
+                    "profiles/decode_mfma_kernel_cross_layer_reuse.txt", "points": points}
 
 
 def mfma_only_rate(torch, skv):
@@ -281,7 +410,7 @@ def run_prefill(args, torch, skv, H, configs):
            "roofline": {"bound": "mfma", "kernel": skv.skv_last_kernel_name(), "achieved": round(tflops_kernel, 1),
                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                         "frac": round(tflops_kernel / MFMA_BF16_PEAK_TFLOPS, 4),
-                        "traffic": measured_traffic(skv.skv_last_kernel_name()),
+                        **traffic_fields([skv.skv_last_kernel_name()]),
                         "launch_us": round(call_ms * 1e3, 1), "algorithmic_flops_per_launch": flops}}
     cache.free()
     # the published peak is what "frac" is quoted on; the rates an MFMA-only kernel reaches on this
@@ -329,18 +458,17 @@ def run_project(args, torch, skv, H, configs):
         nbytes = 2 * (2 * F * hidden + tokens * hidden + 2 * tokens * F)     # weights + x read, K/V rows written
         r = {"tokens": tokens, "hidden": hidden, "launch_us": round(us, 1),
              "tflops": round(flops / (us * 1e-6) / 1e12, 1), "gbs": round(nbytes / (us * 1e-6) / 1e9, 1)}
-        parts = [measured_traffic(kn) for kn in ("project_append_kernel", "project_finish_kernel")]
-        split_traffic = sum(parts) if all(p is not None for p in parts) else None
         if regime == "prefill":
             r["roofline"] = {"bound": "mfma", "kernel": "project_append_tile_kernel", "achieved": r["tflops"],
                              "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                              "frac": round(r["tflops"] / MFMA_BF16_PEAK_TFLOPS, 4),
-                             "traffic": measured_traffic("project_append_tile_kernel"),
+                             **traffic_fields(["project_append_tile_kernel"]),
                              "algorithmic_flops_per_launch": flops}
         else:
             r["roofline"] = {"bound": "hbm", "kernel": "project_append_kernel + project_finish_kernel", "achieved": r["gbs"],
                              "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(r["gbs"] / HBM_PEAK_GBS, 4),
-                             "traffic": split_traffic, "algorithmic_bytes_per_launch": nbytes}
+                             **traffic_fields(["project_append_kernel", "project_finish_kernel"]),
+                             "algorithmic_bytes_per_launch": nbytes}
         out[regime] = r
         cache.free()
         torch.cuda.empty_cache()
@@ -454,8 +582,6 @@ def run_train(args, torch, skv, configs):
     # consecutive calls is one call
     bwd_ms = float(np.mean([ev[l + 1][2].elapsed_time(ev[l][2]) for l in range(L - 1)]))
     assert skv.skv_train_device_faults() == 0
-    parts = [measured_traffic(kn) for kn in ("delta_kernel", "dkdv_kernel", "dq_kernel")]
-    bwd_traffic = sum(parts) if all(p is not None for p in parts) else None
     f_fwd = w.prefill_flops_per_layer()          # two causal products
     f_bwd = f_fwd * 5 // 2                       # five: dV, dP, dQ, dK and the recomputed scores
     return {"workload": "llama3_8b_rcla_train_attention_bf16",
@@ -465,7 +591,8 @@ def run_train(args, torch, skv, configs):
             "fwd": {"launch_us": round(fwd_ms * 1e3, 1), "achieved": round(f_fwd / (fwd_ms * 1e-3) / 1e12, 1)},
             "roofline": {"bound": "mfma", "kernel": "delta_kernel + dkdv_kernel + dq_kernel", "achieved": round(f_bwd / (bwd_ms * 1e-3) / 1e12, 1),
                          "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": round(f_bwd / (bwd_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": bwd_traffic,
+                         "frac": round(f_bwd / (bwd_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                         **traffic_fields(["delta_kernel", "dkdv_kernel", "dq_kernel"]),
                          "launch_us": round(bwd_ms * 1e3, 1), "algorithmic_flops_per_launch": f_bwd}}
 
 
@@ -475,20 +602,22 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--skip-prefill", action="store_true")
-    ap.add_argument("--reuse-sweep", action="store_true",
-                    help="also time the group-by-group, chunk-by-chunk decode schedule (skv_attn_decode_range) "
-                         "that lets the later layers of a sharing group find their slot slice in the on-chip caches")
-    ap.add_argument("--only-prefill", action="store_true", help="profiling aid: measure only the prefill workload")
-    ap.add_argument("--only-train", action="store_true", help="profiling aid: measure only the training pass")
-    ap.add_argument("--skip-train", action="store_true")
+    ap.add_argument("--only", default=None,
+                    choices=["prefill", "train", "project", "append", "small-launches", "reuse", "workloads", "e2e"],
+                    help="profiling aid: measure only this leg and print its object")
+    ap.add_argument("--only-prefill", action="store_true", help="same as --only prefill")
+    ap.add_argument("--only-train", action="store_true", help="same as --only train")
+    ap.add_argument("--only-project", action="store_true", help="same as --only project")
     ap.add_argument("--e2e", action="store_true",
                     help="only run the end-to-end sweep of the paper's Tab. 4 / Tab. 5 on a synthetic Qwen3-8B-scale decoder")
-    ap.add_argument("--only-project", action="store_true", help="profiling aid: measure only the fused K/V projection")
+    ap.add_argument("--skip-train", action="store_true")
     ap.add_argument("--skip-project", action="store_true")
+    ap.add_argument("--skip-extras", action="store_true",
+                    help="leave out the legs beside the metric: the other decode workloads, append, small launches, reuse")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--decode-workload", default="llama3_decode", choices=["llama3_decode", "qwen3_paged", "llama2_mha"],
-                    help="decode workload to time (default: the one the metric is quoted on)")
-    ap.add_argument("--mha-batch", type=int, default=32, help="batch of the llama2_mha workload")
+                    help="decode workload of the headline step (default: the one the metric is quoted on)")
+    ap.add_argument("--mha-batch", type=int, default=32, help="batch of the llama2_mha workload when it is the headline")
     ap.add_argument("--fill-chunk-tokens", type=int, default=1 << 19,
                     help="tokens generated per append call while the cache is filled (bounds the temporaries)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -497,6 +626,8 @@ def main():
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1")
         sys.exit(2)
+    only = args.only or ("prefill" if args.only_prefill else "train" if args.only_train else
+                         "project" if args.only_project else "e2e" if args.e2e else None)
 
     import torch
     import paper_2604_22782_amd as skv
@@ -516,46 +647,59 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
 
-    if args.only_prefill:
-        print(json.dumps({"prefill": run_prefill(args, torch, skv, H, configs)}), flush=True)
+    def other_workloads():
+        """The remaining decode workloads of the metric: paged + ragged (Qwen3-8B shape) and MHA in
+        fp16 (Llama-2-7B shape) at batch 32 and at the largest batch that fits (256 sequences, 256 GiB)."""
+        out = {}
+        for key, w in (("qwen3_8b_paged", configs.qwen3_paged_decode()),
+                       ("llama2_7b_mha_b32", configs.llama2_mha_decode(batch=32)),
+                       ("llama2_7b_mha_b256", configs.llama2_mha_decode(batch=256))):
+            out[key] = run_decode(args, torch, skv, H, w, steps=max(3, args.steps // 4), warmup=1)
+        return out
+
+    legs = {
+        "prefill": lambda: run_prefill(args, torch, skv, H, configs),
+        "train": lambda: run_train(args, torch, skv, configs),
+        "project": lambda: run_project(args, torch, skv, H, configs),
+        "append": lambda: run_append(args, torch, skv, H, configs),
+        "small-launches": lambda: run_small_launches(args, torch, skv, H, configs),
+        "reuse": lambda: run_cross_layer_reuse(args, torch, skv, H, configs),
+        "workloads": other_workloads,
+        "e2e": lambda: run_e2e(args, torch, skv),
+    }
+    names = {"project": "project_append", "small-launches": "decode_small_launches", "reuse": "cross_layer_reuse",
+             "workloads": "decode_workloads"}
+    if only:
+        print(json.dumps({names.get(only, only): legs[only]()}), flush=True)
         return
-    if args.e2e:
-        print(json.dumps({"e2e": run_e2e(args, torch, skv)}), flush=True)
-        return
-    if args.only_project:
-        print(json.dumps({"project_append": run_project(args, torch, skv, H, configs)}), flush=True)
-        return
-    if args.only_train:
-        print(json.dumps({"train": run_train(args, torch, skv, configs)}), flush=True)
-        return
-    dec = run_decode(args, torch, skv, H, configs)
-    w = dec.pop("workload")
+
+    if args.decode_workload == "qwen3_paged":
+        w = configs.qwen3_paged_decode()
+    elif args.decode_workload == "llama2_mha":
+        w = configs.llama2_mha_decode(batch=args.mha_batch)
+    else:
+        w = configs.llama3_decode()
+    dec = run_decode(args, torch, skv, H, w, args.steps, args.warmup, headline=args.decode_workload == "llama3_decode")
     line = {
         "metric": "routed decode attn HBM GB/s (% of peak) + prefill MFMA util %, 1 MI355X",
         "value": dec["value"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": dec["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": w.name, "batch": w.batch, "max_context": int(w.kv_lens.max()), "layers": w.n_layers,
-                   "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
-                   "slots": len(w.owner_layers), "sum_kv_len": int(w.kv_lens.sum()), "paged": bool(w.block_size),
-                   "step": "append(owner)+decode per layer"},
+        "dtype": w.dtype, "data": "synthetic", "config": dec["config"],
         "pct_of_hbm_peak": round(100 * dec["value"] / HBM_PEAK_GBS, 2),
         "roofline": dec["roofline"],
     }
-    if dec.get("cross_layer_reuse"):
-        line["cross_layer_reuse"] = dec["cross_layer_reuse"]
     if not args.skip_prefill:
         line["prefill"] = run_prefill(args, torch, skv, H, configs)
-    # the two widenings of the path are reported beside the metric, never instead of it
-    for key, skip, run in (("project_append", args.skip_project, lambda: run_project(args, torch, skv, H, configs)),
-                           ("train", args.skip_train, lambda: run_train(args, torch, skv, configs))):
-        if skip:
-            continue
+    # everything below is reported beside the metric, never instead of it
+    order = [] if args.skip_extras else ["workloads", "append", "small-launches", "reuse"]
+    order += [] if args.skip_project else ["project"]
+    order += [] if args.skip_train else ["train"]
+    for key in order:
         try:
-            line[key] = run()
+            line[names.get(key, key)] = legs[key]()
         except Exception as e:  # noqa: BLE001 - the headline line must still be printed
             log(f"[bench] {key} leg failed: {e!r}")
-            line[key] = {"error": repr(e)}
+            line[names.get(key, key)] = {"error": repr(e)}
             torch.cuda.empty_cache()
     if not args.skip_cpu_baseline:
         log("[bench] timing the CPU oracle on a bounded sample ...")
