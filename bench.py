@@ -125,7 +125,9 @@ def run_decode(args, torch, skv, H, w, steps, warmup, headline=False):
     log(f"[bench] workload {w.name}: B={w.batch} ctx={int(w.kv_lens.max())} layers={w.n_layers} slots={len(w.owner_layers)}")
     cache, _ = H.alloc_cache(w)
     t0 = time.perf_counter()
-    H.fill_by_append(cache, w, lens=w.kv_lens - 1, chunk_tokens=args.fill_chunk_tokens)
+    # the fill's temporaries grow with the row width: keep them at the size they have for 8 kv heads
+    chunk = max(1 << 14, args.fill_chunk_tokens * 1024 // (w.n_kv_heads * w.head_dim))
+    H.fill_by_append(cache, w, lens=w.kv_lens - 1, chunk_tokens=chunk)
     log(f"[bench] cache of {skv.skv_cache_info(cache)[3] * 2 / 2**30:.1f} GiB filled through skv_kv_append in {time.perf_counter() - t0:.1f} s")
     ctx = int(w.kv_lens.max())
     d_lens = torch.from_numpy(w.kv_lens).cuda()
@@ -166,7 +168,9 @@ def run_decode(args, torch, skv, H, w, steps, warmup, headline=False):
     call_ms = float(np.mean(per_call))
     assert skv.skv_cache_device_faults(cache) == 0
     layer_bytes = w.decode_bytes_per_layer()
-    append_bytes = len(w.owner_layers) * 2 * 2 * w.batch * w.n_kv_heads * w.head_dim * w.elem_bytes
+    # the new rows are read in the activation dtype and written in the slot's element type
+    stored = (w.head_dim + 1) if w.kv8 else w.head_dim * w.elem_bytes
+    append_bytes = len(w.owner_layers) * 2 * w.batch * w.n_kv_heads * (w.head_dim * w.elem_bytes + stored)
     step_bytes = layer_bytes * w.n_layers + append_bytes
     ms_per_step = dt / steps * 1e3
     value = step_bytes / (dt / steps) / 1e9
@@ -180,7 +184,8 @@ def run_decode(args, torch, skv, H, w, steps, warmup, headline=False):
            "config": {"workload": w.name, "batch": w.batch, "max_context": ctx, "layers": w.n_layers,
                       "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
                       "slots": len(w.owner_layers), "sum_kv_len": int(w.kv_lens.sum()), "paged": bool(w.block_size),
-                      "dtype": w.dtype, "step": "append(owner)+decode per layer"}}
+                      "dtype": w.dtype, "slots_dtype": "e4m3 + power-of-two scale per (position, kv head)" if w.kv8 else w.dtype,
+                      "step": "append(owner)+decode per layer"}}
     cache.free()
     del ws, qs, outs, new_k, new_v
     torch.cuda.empty_cache()
@@ -651,9 +656,13 @@ def main():
         """The remaining decode workloads of the metric: paged + ragged (Qwen3-8B shape) and MHA in
         fp16 (Llama-2-7B shape) at batch 32 and at the largest batch that fits (256 sequences, 256 GiB)."""
         out = {}
+        kv8 = {"llama3_8b_kv8": configs.llama3_decode(), "qwen3_8b_paged_kv8": configs.qwen3_paged_decode()}
+        for w in kv8.values():          # the same workloads over 8-bit slots: half the bytes per cached position
+            w.kv8 = True
+            w.name += "_kv8"
         for key, w in (("qwen3_8b_paged", configs.qwen3_paged_decode()),
                        ("llama2_7b_mha_b32", configs.llama2_mha_decode(batch=32)),
-                       ("llama2_7b_mha_b256", configs.llama2_mha_decode(batch=256))):
+                       ("llama2_7b_mha_b256", configs.llama2_mha_decode(batch=256)), *kv8.items()):
             out[key] = run_decode(args, torch, skv, H, w, steps=max(3, args.steps // 4), warmup=1)
         return out
 

@@ -32,6 +32,19 @@
  *   paged      (block_size  > 0):  K and V pools are [n_slots][n_blocks][block_size][n_kv_heads][head_dim];
  *       logical (b, pos) lives in physical block table[b][pos / block_size] at offset
  *       pos % block_size.  One table serves every slot.
+ *
+ * 8-bit slots (dtype SKV_BF16_KV8 / SKV_F16_KV8).  The paper leaves the composition of depth-wise
+ * sharing with KV quantisation open (Sec. 5, Limitations); this library's reading: the head_dim
+ * values x of one (position, kv head) of K (and likewise of V) are stored as head_dim e4m3 codes
+ * (the 8-bit float of the OCP 8-bit floating point specification: 4 exponent bits of bias 7, 3
+ * mantissa bits, largest value 448) and one exponent byte:
+ *     e = the smallest integer with max|x| * 2^-e <= 448, clamped to [-127, 127] (0 if all x are 0),
+ *     code_i = x_i * 2^-e rounded to the nearest e4m3 number, ties to the even code; byte = e + 127.
+ * skv_kv_append does this conversion; attention reads code * 2^e, which is exact in bf16 / fp16,
+ * so Eq. (3.1) is evaluated on the stored values exactly as on a 16-bit cache.  The K and V pools
+ * then have 1-byte elements in the layouts above, and a third pool holds the exponent bytes as
+ * uint16 [n_slots][rows][n_kv_heads] (low byte: K, high byte: V; rows as in the K / V pools).
+ * head_dim must be 64 or 128.
  */
 #ifndef SKV_H
 #define SKV_H
@@ -56,7 +69,10 @@ typedef enum {
     SKV_ERR_HIP = 7          /* a HIP call failed; see skv_last_hip_error */
 } skv_status_t;
 
-typedef enum { SKV_F32 = 0, SKV_F16 = 1, SKV_BF16 = 2 } skv_dtype_t;
+/* SKV_F32 / SKV_F16 / SKV_BF16: slots, queries, new rows and outputs all have this type.
+ * SKV_BF16_KV8 / SKV_F16_KV8: queries, new rows and outputs are bf16 / fp16, the slots hold 8-bit
+ * codes (see "8-bit slots" below). */
+typedef enum { SKV_F32 = 0, SKV_F16 = 1, SKV_BF16 = 2, SKV_BF16_KV8 = 3, SKV_F16_KV8 = 4 } skv_dtype_t;
 
 /* Bits of the per-cache device fault word. */
 enum {
@@ -79,7 +95,9 @@ typedef struct {
     const int32_t *route; /* host, n_layers entries, copied by skv_cache_alloc */
     void *k_pool;        /* device, optional caller-owned storage for K; NULL = library allocates */
     void *v_pool;        /* device, same for V; both or neither */
-    size_t pool_bytes;   /* size of EACH caller pool; must be >= skv_cache_bytes / 2 */
+    size_t pool_bytes;   /* size of EACH caller pool; must be >= the K pool's bytes (skv_cache_pool_bytes) */
+    void *scale_pool;    /* device, 8-bit slots with caller pools only: storage of the exponent bytes */
+    size_t scale_pool_bytes; /* its size; must be >= the scale pool's bytes (skv_cache_pool_bytes) */
 } skv_cache_desc_t;
 
 /* ---- routing (host only, no device needed) ------------------------------------------------ */
@@ -103,6 +121,12 @@ skv_status_t skv_route_validate(const int32_t *route, int32_t n_layers, int32_t 
  * i.e. the footprint M = L x (T + t) x S of Sec. 3.1.1 with L replaced by |S|. */
 skv_status_t skv_cache_bytes(const skv_cache_desc_t *desc, size_t *total_bytes);
 
+/* The parts of skv_cache_bytes: bytes of the K pool (the V pool has the same size) and of the pool
+ * of exponent bytes (0 unless the slots are 8-bit): total = 2 * kv_pool_bytes + scale_pool_bytes,
+ * i.e. per cached position and kv head 2 * head_dim * sizeof(element) (+ 2 for 8-bit slots).
+ * Either out pointer may be NULL. */
+skv_status_t skv_cache_pool_bytes(const skv_cache_desc_t *desc, size_t *kv_pool_bytes, size_t *scale_pool_bytes);
+
 /* ---- cache object --------------------------------------------------------------------------- */
 
 /* The cache of Sec. 3.1.1 under a sharing strategy (Sec. 3.1.3): one K and one V slot per owner
@@ -122,6 +146,8 @@ skv_status_t skv_cache_info(const skv_cache_t *cache, int32_t *n_slots, void **k
                             void **v_pool_device, size_t *pool_bytes_each);
 skv_status_t skv_cache_slot_of_layer(const skv_cache_t *cache, int32_t layer, int32_t *slot,
                                      int32_t *is_owner);
+/* 8-bit slots: the pool of exponent bytes (device pointer, bytes); NULL / 0 for other caches. */
+skv_status_t skv_cache_scale_info(const skv_cache_t *cache, void **scale_pool_device, size_t *scale_pool_bytes);
 
 /* Paged caches: borrow the block table, device int32 [batch][max_blocks_per_seq].  Must be set
  * before the first append / attention call and stay alive while the cache is used. */
@@ -136,7 +162,9 @@ skv_status_t skv_cache_device_faults(skv_cache_t *cache, uint32_t *faults);
 /* "Update K_l, V_l", allowed only if layer owns a slot (else SKV_ERR_NOT_OWNER, cache untouched).
  * k_new, v_new: device [batch][max_new][n_kv_heads][head_dim]; row i < new_lens[b] of sequence b
  * is written, bit for bit, to position start_pos[b] + i of the layer's slot; other rows are
- * ignored.  start_pos, new_lens: device int32[batch]. */
+ * ignored.  start_pos, new_lens: device int32[batch].  8-bit slots: k_new, v_new are bf16 / fp16 and
+ * every (row, kv head) piece is converted to codes and an exponent byte as stated at the top (the
+ * conversion is deterministic: the stored bytes have exactly one correct value). */
 skv_status_t skv_kv_append(skv_cache_t *cache, int32_t layer, const void *k_new, const void *v_new,
                            const int32_t *start_pos, const int32_t *new_lens, int32_t max_new,
                            void *stream);

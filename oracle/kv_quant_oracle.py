@@ -62,6 +62,14 @@ def scale_exponent(amax: float) -> int:
     return max(-127, min(127, e))
 
 
+def scale_exponents(amax: np.ndarray) -> np.ndarray:
+    """scale_exponent for an array of row maxima (the same rule, element by element)."""
+    amax = np.asarray(amax, dtype=np.float64)
+    f, k = np.frexp(amax)
+    e = np.where(f <= 0.875, k - 9, k - 8)
+    return np.where(amax == 0.0, 0, np.clip(e, -127, 127)).astype(np.int64)
+
+
 def round_to_e4m3(y: np.ndarray) -> np.ndarray:
     """Nearest e4m3 code of every element of y (|y| <= 448), ties to the even code."""
     y = np.asarray(y, dtype=np.float64)
@@ -81,13 +89,9 @@ def quantise_rows(x: np.ndarray):
     x = np.asarray(x, dtype=np.float64)
     lead = x.shape[:-1]
     flat = x.reshape(-1, x.shape[-1])
-    codes = np.empty(flat.shape, dtype=np.uint8)
-    ebyte = np.empty(flat.shape[0], dtype=np.uint8)
-    for r in range(flat.shape[0]):
-        e = scale_exponent(float(np.abs(flat[r]).max()))
-        codes[r] = round_to_e4m3(np.ldexp(flat[r], -e))
-        ebyte[r] = e + 127
-    return codes.reshape(x.shape), ebyte.reshape(lead)
+    e = scale_exponents(np.abs(flat).max(axis=1))
+    codes = round_to_e4m3(np.ldexp(flat, -e[:, None]))
+    return codes.reshape(x.shape), (e + 127).astype(np.uint8).reshape(lead)
 
 
 def dequantise_rows(codes: np.ndarray, ebyte: np.ndarray) -> np.ndarray:

@@ -6,7 +6,8 @@ import os
 import torch
 
 __all__ = [
-    "SkvError", "Cache", "lib", "SKV_F32", "SKV_F16", "SKV_BF16", "STATUS", "dtype_code",
+    "SkvError", "Cache", "lib", "SKV_F32", "SKV_F16", "SKV_BF16", "SKV_BF16_KV8", "SKV_F16_KV8", "STATUS", "dtype_code",
+    "skv_cache_pool_bytes", "skv_cache_scale_info",
     "skv_route_from_strategy", "skv_route_validate", "skv_cache_bytes", "skv_cache_alloc",
     "skv_cache_free", "skv_cache_info", "skv_cache_slot_of_layer", "skv_cache_set_block_table",
     "skv_cache_device_faults", "skv_kv_append", "skv_kv_project_append", "skv_kv_project_workspace_bytes", "skv_decode_workspace_bytes", "skv_attn_decode",
@@ -15,7 +16,7 @@ __all__ = [
     "skv_train_attn_bwd", "skv_train_device_faults", "SKV_TRAIN_RCLA", "SKV_TRAIN_CLA_K", "SKV_TRAIN_RDCLA_K",
 ]
 
-SKV_F32, SKV_F16, SKV_BF16 = 0, 1, 2
+SKV_F32, SKV_F16, SKV_BF16, SKV_BF16_KV8, SKV_F16_KV8 = 0, 1, 2, 3, 4
 SKV_TRAIN_RCLA, SKV_TRAIN_CLA_K, SKV_TRAIN_RDCLA_K = 0, 1, 2
 STATUS = {0: "SKV_OK", 1: "SKV_ERR_INVALID_ARG", 2: "SKV_ERR_BAD_ROUTE", 3: "SKV_ERR_NOT_OWNER",
           4: "SKV_ERR_CAPACITY", 5: "SKV_ERR_OOM", 6: "SKV_ERR_UNSUPPORTED", 7: "SKV_ERR_HIP"}
@@ -36,7 +37,8 @@ class _Desc(ctypes.Structure):
                 ("n_layers", "n_q_heads", "n_kv_heads", "head_dim", "batch", "max_ctx", "dtype",
                  "block_size", "n_blocks")] + [
         ("route", ctypes.POINTER(ctypes.c_int32)), ("k_pool", ctypes.c_void_p),
-        ("v_pool", ctypes.c_void_p), ("pool_bytes", ctypes.c_size_t)]
+        ("v_pool", ctypes.c_void_p), ("pool_bytes", ctypes.c_size_t),
+        ("scale_pool", ctypes.c_void_p), ("scale_pool_bytes", ctypes.c_size_t)]
 
 
 def lib() -> ctypes.CDLL:
@@ -56,7 +58,10 @@ def lib() -> ctypes.CDLL:
     return _lib
 
 
-def dtype_code(dt: torch.dtype) -> int:
+def dtype_code(dt: torch.dtype, kv8: bool = False) -> int:
+    """Descriptor dtype of a cache whose queries / new rows / outputs have torch dtype dt; kv8: 8-bit slots."""
+    if kv8:
+        return {torch.float16: SKV_F16_KV8, torch.bfloat16: SKV_BF16_KV8}[dt]
     return {torch.float32: SKV_F32, torch.float16: SKV_F16, torch.bfloat16: SKV_BF16}[dt]
 
 
@@ -88,12 +93,12 @@ def _stream(stream):
 
 
 def _desc(n_layers, n_q_heads, n_kv_heads, head_dim, batch, max_ctx, dtype, route, block_size=0,
-          n_blocks=0, k_pool=None, v_pool=None, pool_bytes=0):
+          n_blocks=0, k_pool=None, v_pool=None, pool_bytes=0, scale_pool=None, scale_pool_bytes=0):
     route_arr = _i32(route) if route is not None else None
     d = _Desc(n_layers, n_q_heads, n_kv_heads, head_dim, batch, max_ctx, dtype, block_size, n_blocks,
               ctypes.cast(route_arr, ctypes.POINTER(ctypes.c_int32)) if route_arr is not None else None,
-              _ptr(k_pool), _ptr(v_pool), pool_bytes)
-    d._keep = (route_arr, k_pool, v_pool)
+              _ptr(k_pool), _ptr(v_pool), pool_bytes, _ptr(scale_pool), scale_pool_bytes)
+    d._keep = (route_arr, k_pool, v_pool, scale_pool)
     return d
 
 
@@ -138,11 +143,26 @@ def skv_cache_bytes(**desc):
     return out.value
 
 
+def skv_cache_pool_bytes(**desc):
+    """-> (bytes of the K pool (= of the V pool), bytes of the pool of exponent bytes)"""
+    d = _desc(**desc)
+    kv, sc = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(lib().skv_cache_pool_bytes(ctypes.byref(d), ctypes.byref(kv), ctypes.byref(sc)), "skv_cache_pool_bytes")
+    return kv.value, sc.value
+
+
+def skv_cache_scale_info(cache: "Cache"):
+    """-> (scale_pool_ptr, scale_pool_bytes)"""
+    sp, sb = ctypes.c_void_p(0), ctypes.c_size_t(0)
+    _check(lib().skv_cache_scale_info(cache.handle, ctypes.byref(sp), ctypes.byref(sb)), "skv_cache_scale_info")
+    return sp.value, sb.value
+
+
 def skv_cache_alloc(**desc) -> Cache:
     d = _desc(**desc)
     h = ctypes.c_void_p(0)
     _check(lib().skv_cache_alloc(ctypes.byref(d), ctypes.byref(h)), "skv_cache_alloc")
-    return Cache(h, [desc.get("k_pool"), desc.get("v_pool")])
+    return Cache(h, [desc.get("k_pool"), desc.get("v_pool"), desc.get("scale_pool")])
 
 
 def skv_cache_free(cache: Cache):

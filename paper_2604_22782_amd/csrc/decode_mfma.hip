@@ -21,7 +21,7 @@
 // (Merging in the same launch by the last work group to finish was measured and rejected: making
 // the partials visible across the per-XCD L2s costs each work group either an L2 write-back or
 // the round trip of write-through stores, which is more than the small merge launch.)
-#include <cstdlib>
+#include <type_traits>
 
 #include "skv_internal.h"
 
@@ -59,12 +59,17 @@ struct MF16 {
 };
 
 constexpr int kTile = 32; // keys per wave tile
-// A launch whose K/V slice is at most this large uses cached loads (the memory-side cache of the
-// device holds 256 MiB; see the cross-layer reuse measurements for the choice).
-constexpr int64_t kOnChipBytes = (int64_t)192 << 20;
+// A launch on a slot that several layers read, whose K/V slice is at most this large, uses cached
+// loads: the memory-side cache of the device (256 MiB) then serves the other layers of the sharing
+// group.  Measured per call, first / later reader of a group: 128 MiB slice 36.5 / 29.5 us cached
+// against 33.6 / 31.7 us streaming; 256 MiB 60.9 / 48.1 against 56.7 / 54.1; 512 MiB 111.6 / 108.9
+// against 101.7 / 98.1 (streaming wins: nothing is left on chip for the next reader).
+constexpr int64_t kOnChipBytes = (int64_t)256 << 20;
 
-template <int D> struct Geo {
-    static constexpr int LPR = D / 8;            // lanes per 16-bit row (16 bytes each)
+// KV8: the slot holds 8-bit codes (16 per 16-byte piece) that are converted to the 16-bit type on
+// their way into LDS; everything behind the LDS tile is the same for both kinds of slot.
+template <int D, bool KV8> struct Geo {
+    static constexpr int LPR = KV8 ? D / 16 : D / 8; // lanes per row (16 bytes each)
     static constexpr int RPL = 64 / LPR;         // rows per wave-wide load
     static constexpr int NL = kTile / RPL;       // loads per tile and tensor
     static constexpr int K_STRIDE = D * 2 + 16;  // LDS row strides in bytes: chosen so that the 16 rows
@@ -81,9 +86,9 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const char *p) {
 // kStream: the K/V loads carry the non-temporal hint (every byte is used once: stream it past the
 // caches).  Without it the rows are cached as usual, which is what lets the next layer of a sharing
 // group find a small slot slice on chip.
-template <typename M, int D, int kWaves, bool kStream>
+template <typename M, int D, int kWaves, bool kStream, bool KV8>
 __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a, int G, int persistent) {
-    using Ge = Geo<D>;
+    using Ge = Geo<D, KV8>;
     using vec8 = typename M::vec8;
     constexpr int NL = Ge::NL, LPR = Ge::LPR, RPL = Ge::RPL;
     __shared__ __attribute__((aligned(16))) char lds[kWaves * Ge::WAVE_BYTES];
@@ -128,9 +133,11 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
     char *vs = ks + Ge::K_BYTES;
     const int lrow = lane / LPR;   // row inside one wave-wide load
     const int lcol = lane % LPR;   // 16-byte piece inside the row
-    const uint16_t *kp = (const uint16_t *)a.cache.k + (int64_t)kvh * D + lcol * 8;
-    const uint16_t *vp = (const uint16_t *)a.cache.v + (int64_t)kvh * D + lcol * 8;
-    const int64_t row_elems = (int64_t)hkv * D;
+    constexpr int EB = KV8 ? 1 : 2; // bytes per slot element
+    const char *kp = (const char *)a.cache.k + ((int64_t)kvh * D) * EB + lcol * 16;
+    const char *vp = (const char *)a.cache.v + ((int64_t)kvh * D) * EB + lcol * 16;
+    const int64_t row_bytes = (int64_t)hkv * D * EB;
+    const uint16_t *sp = KV8 ? a.cache.scales + kvh : nullptr; // 8-bit slots: exponent bytes of K (low) and V (high) per row
 
     // Paged caches: the (at most four) block ids a 32-key tile touches are fetched with SCALAR loads
     // one tile ahead.  They have a counter of their own, so waiting for them never drains the
@@ -158,20 +165,23 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
         }
         return (id << shift) + (key & ((1 << shift) - 1));
     };
-    auto issue = [&](int j0, const int32_t *blk, uint4 *kr, uint4 *vr) {
+    auto issue = [&](int j0, const int32_t *blk, uint4 *kr, uint4 *vr, uint16_t *sr) {
 #pragma unroll
         for (int t = 0; t < NL; ++t) {
             kr[t] = make_uint4(0, 0, 0, 0);
             vr[t] = make_uint4(0, 0, 0, 0);
+            if constexpr (KV8) sr[t] = 0x7f7f; // scale 1 for rows that are not loaded (their codes are zero)
             const int32_t r = row_of(j0, blk, t);
             if (r >= 0) {
                 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
                 if constexpr (kStream) { // "nt" loads: +6..10 % bandwidth on launches far larger than the caches
-                    kr[t] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4 *)(kp + r * row_elems)));
-                    vr[t] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4 *)(vp + r * row_elems)));
+                    kr[t] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4 *)(kp + r * row_bytes)));
+                    vr[t] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4 *)(vp + r * row_bytes)));
+                    if constexpr (KV8) sr[t] = __builtin_nontemporal_load(sp + (int64_t)r * hkv);
                 } else {
-                    kr[t] = *(const uint4 *)(kp + r * row_elems);
-                    vr[t] = *(const uint4 *)(vp + r * row_elems);
+                    kr[t] = *(const uint4 *)(kp + r * row_bytes);
+                    vr[t] = *(const uint4 *)(vp + r * row_bytes);
+                    if constexpr (KV8) sr[t] = sp[(int64_t)r * hkv];
                 }
             }
         }
@@ -198,32 +208,44 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
     // from LDS; the block ids run one more tile ahead.
     int32_t blk[4] = {0, 0, 0, 0};
     int tt_issue = wave; // next tile of this wave to request
-    auto issue_next = [&](uint4 *kr, uint4 *vr) {
+    auto issue_next = [&](uint4 *kr, uint4 *vr, uint16_t *sr) {
         if (tt_issue < n_tiles) {
-            issue(tile_j0(tt_issue), blk, kr, vr);
+            issue(tile_j0(tt_issue), blk, kr, vr, sr);
             tt_issue += kWaves;
             if (tt_issue < n_tiles) blocks_of(tile_j0(tt_issue), blk);
         }
     };
     uint4 krA[NL], vrA[NL], krB[NL], vrB[NL];
+    uint16_t srA[KV8 ? NL : 1], srB[KV8 ? NL : 1];
     if (wave < n_tiles) blocks_of(tile_j0(wave), blk);
-    issue_next(krA, vrA);
-    issue_next(krB, vrB);
+    issue_next(krA, vrA, srA);
+    issue_next(krB, vrB, srB);
 
-    auto process = [&](int tt, uint4 *kr, uint4 *vr) {
+    auto process = [&](int tt, uint4 *kr, uint4 *vr, uint16_t *sr) {
         const int j0 = tile_j0(tt);
         // park the tile in LDS: row-major, 16-byte pieces, padded row stride
 #pragma unroll
         for (int t = 0; t < NL; ++t) {
-            *(uint4 *)(ks + (RPL * t + lrow) * Ge::K_STRIDE + lcol * 16) = kr[t];
-            *(uint4 *)(vs + (RPL * t + lrow) * Ge::V_STRIDE + lcol * 16) = vr[t];
+            if constexpr (KV8) { // 16 codes x 2^e -> two pieces of eight 16-bit values, exactly
+                constexpr bool bf = std::is_same<M, MBF16>::value;
+                uint4 lo, hi;
+                dequant_piece<bf>(kr[t], scale_of_byte(sr[t] & 0xffu), lo, hi);
+                *(uint4 *)(ks + (RPL * t + lrow) * Ge::K_STRIDE + lcol * 32) = lo;
+                *(uint4 *)(ks + (RPL * t + lrow) * Ge::K_STRIDE + lcol * 32 + 16) = hi;
+                dequant_piece<bf>(vr[t], scale_of_byte(sr[t] >> 8), lo, hi);
+                *(uint4 *)(vs + (RPL * t + lrow) * Ge::V_STRIDE + lcol * 32) = lo;
+                *(uint4 *)(vs + (RPL * t + lrow) * Ge::V_STRIDE + lcol * 32 + 16) = hi;
+            } else {
+                *(uint4 *)(ks + (RPL * t + lrow) * Ge::K_STRIDE + lcol * 16) = kr[t];
+                *(uint4 *)(vs + (RPL * t + lrow) * Ge::V_STRIDE + lcol * 16) = vr[t];
+            }
         }
         // the tile is exchanged between the lanes of this wave only: order the LDS traffic for the
         // compiler (the hardware runs one wave's LDS operations in order)
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        issue_next(kr, vr); // the freed register set requests the tile after the one in flight
+        issue_next(kr, vr, sr); // the freed register set requests the tile after the one in flight
 
         // S^T = K Q^T for keys [j0, j0+16) and [j0+16, j0+32)
         f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
@@ -284,8 +306,8 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
         __builtin_amdgcn_wave_barrier();
     };
     for (int tt = wave; tt < n_tiles; tt += 2 * kWaves) {
-        process(tt, krA, vrA);
-        if (tt + kWaves < n_tiles) process(tt + kWaves, krB, vrB);
+        process(tt, krA, vrA, srA);
+        if (tt + kWaves < n_tiles) process(tt + kWaves, krB, vrB, srB);
     }
 
     // ---- merge the four waves through LDS --------------------------------------------------
@@ -449,7 +471,7 @@ __global__ void clear_counter_kernel(int32_t *counter) {
     if (threadIdx.x < 2) counter[threadIdx.x] = 0;
 }
 
-template <typename M, int D>
+template <typename M, int D, bool KV8>
 hipError_t launch_d(const AttnArgs &a, int group, hipStream_t stream) {
     static const int n_cu = [] {
         int dev = 0, cus = 0;
@@ -465,18 +487,18 @@ hipError_t launch_d(const AttnArgs &a, int group, hipStream_t stream) {
     // Cache policy of the K/V loads: stream past the caches unless everything the launch can read
     // (sequences x longest length x K and V rows) is small enough to stay on chip until the next
     // layer of the sharing group reads it again.
-    const int64_t slice_bytes = (int64_t)a.batch * a.max_kv_len * a.cache.n_kv_heads * D * 2 * 2;
+    const int64_t slice_bytes = (int64_t)a.batch * a.max_kv_len * a.cache.n_kv_heads * D * 2 * (KV8 ? 1 : 2);
     const int forced = tuning().decode_loads;
-    const bool stream_loads = forced ? forced == 1 : slice_bytes > kOnChipBytes;
+    const bool stream_loads = forced ? forced == 1 : (a.slot_readers < 2 || slice_bytes > kOnChipBytes);
     if (a.n_splits > 2 && a.batch <= 1024 && a.work_counters != nullptr && max_items > 2 * n_cu) {
         const size_t dyn = sizeof(int) * (size_t)(a.batch + 1) + sizeof(unsigned short) * (size_t)a.batch;
         clear_counter_kernel<<<1, 64, 0, stream>>>(a.work_counters);
-        if (stream_loads) decode_mfma_kernel<M, D, 4, true><<<dim3(2 * n_cu), 256, dyn, stream>>>(a, group, 1);
-        else decode_mfma_kernel<M, D, 4, false><<<dim3(2 * n_cu), 256, dyn, stream>>>(a, group, 1);
+        if (stream_loads) decode_mfma_kernel<M, D, 4, true, KV8><<<dim3(2 * n_cu), 256, dyn, stream>>>(a, group, 1);
+        else decode_mfma_kernel<M, D, 4, false, KV8><<<dim3(2 * n_cu), 256, dyn, stream>>>(a, group, 1);
     } else {
         const dim3 grid((unsigned)a.n_splits, (unsigned)a.cache.n_kv_heads, (unsigned)a.batch);
-        if (stream_loads) decode_mfma_kernel<M, D, 4, true><<<grid, 256, 0, stream>>>(a, group, 0);
-        else decode_mfma_kernel<M, D, 4, false><<<grid, 256, 0, stream>>>(a, group, 0);
+        if (stream_loads) decode_mfma_kernel<M, D, 4, true, KV8><<<grid, 256, 0, stream>>>(a, group, 0);
+        else decode_mfma_kernel<M, D, 4, false, KV8><<<grid, 256, 0, stream>>>(a, group, 0);
     }
     set_last_kernel_name("decode_mfma_kernel");
     return hipGetLastError();
@@ -485,15 +507,22 @@ hipError_t launch_d(const AttnArgs &a, int group, hipStream_t stream) {
 } // namespace
 
 bool decode_mfma_supported(int dtype, int head_dim, int group) {
-    return (dtype == SKV_BF16 || dtype == SKV_F16) && (head_dim == 64 || head_dim == 128) && group <= 16;
+    const int act = dtype_act(dtype);
+    return (act == SKV_BF16 || act == SKV_F16) && (head_dim == 64 || head_dim == 128) && group <= 16;
 }
 
 hipError_t launch_decode_mfma(const AttnArgs &a, int dtype, int head_dim, int group, hipStream_t stream) {
     if (a.batch > 65535 || a.cache.n_kv_heads > 65535) return hipErrorInvalidValue;
-    if (dtype == SKV_BF16) {
-        return head_dim == 128 ? launch_d<MBF16, 128>(a, group, stream) : launch_d<MBF16, 64>(a, group, stream);
+    if (dtype_kv8(dtype)) {
+        if (a.cache.scales == nullptr) return hipErrorInvalidValue;
+        if (dtype_act(dtype) == SKV_BF16)
+            return head_dim == 128 ? launch_d<MBF16, 128, true>(a, group, stream) : launch_d<MBF16, 64, true>(a, group, stream);
+        return head_dim == 128 ? launch_d<MF16, 128, true>(a, group, stream) : launch_d<MF16, 64, true>(a, group, stream);
     }
-    return head_dim == 128 ? launch_d<MF16, 128>(a, group, stream) : launch_d<MF16, 64>(a, group, stream);
+    if (dtype == SKV_BF16) {
+        return head_dim == 128 ? launch_d<MBF16, 128, false>(a, group, stream) : launch_d<MBF16, 64, false>(a, group, stream);
+    }
+    return head_dim == 128 ? launch_d<MF16, 128, false>(a, group, stream) : launch_d<MF16, 64, false>(a, group, stream);
 }
 
 } // namespace skv

@@ -112,6 +112,9 @@ def generator(nq: int = 2, paged: bool = False):
     STG = _alloc()
     Q_OFF, O_OFF, ROW = _per_q(), _per_q(), _per_q()
     TMP = tuple(range(_alloc(16, 2), _next[0]))   # scratch; TMP[4:6] and TMP[12:14] are 64-bit store operands
+    NT = 8                                 # weights of the fast stream on their way from v_exp to row sum and packing
+    EXPT = tuple(_alloc() for _ in range(NT))
+    L_PREV = _per_q()                      # row sums before the half step of the fast stream
     LAST_V = (_next[0] + 7) // 8 * 8 - 1
     assert LAST_V < 256 and PD < RING and TMP[4] % 2 == 0 and TMP[12] % 2 == 0
 
@@ -188,6 +191,34 @@ def generator(nq: int = 2, paged: bool = False):
 
 
     # ---- softmax of one half tile (vector ALU stream) ------------------------------------------------
+    def fast_stream(A: Asm, s_cur: int, p_cur: int):
+        """The softmax of a half tile without a running maximum (bf16 weights, tiles below the
+        diagonal): weight = 2^score, straight from the accumulators.  Q was multiplied by
+        scale x log2(e) when it was loaded, so the accumulators hold the exponents; bf16 has the
+        exponent range of fp32, so no reference point is needed while the row sums stay inside
+        [2^-64, 2^64] -- half_step() checks that after every half tile and leaves for the general
+        stream (running maximum, rescale) otherwise.  The scores stay intact in s_cur (the weights
+        go through EXPT), so the half tile can be redone there.  Per score: v_exp, v_add, half a
+        v_cvt_pk -- the maximum (v_max3 per two scores) and the subtraction (one per score) of the
+        general stream are gone."""
+        assert A.dt == "bf16"
+        o = [f"v_mov_b32_e32 {vr(L_PREV[q])}, {vr(L_SUM[q])}" for q in range(NQ)]
+        S = [[s_cur + 16 * q + r for r in range(16)] for q in range(NQ)]
+        elems = [(i % NQ, i // NQ) for i in range(NEL)]
+        lag = 4
+        assert NT > lag + NQ
+        for i in range(NEL + lag):
+            if i < NEL:
+                q, r = elems[i]
+                o.append(f"v_exp_f32_e32 {vr(EXPT[i % NT])}, {vr(S[q][r])}")
+            if i >= lag:
+                j = i - lag
+                q, r = elems[j]
+                o.append(f"v_add_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}, {vr(EXPT[j % NT])}")
+                if r % 2 == 1:      # its partner (q, r - 1) was element j - NQ
+                    o.append(f"v_cvt_pk_bf16_f32 {vr(p_cur + 8 * q + r // 2)}, {vr(EXPT[(j - NQ) % NT])}, {vr(EXPT[j % NT])}")
+        return o
+
     def softmax_stream(A: Asm, s_cur: int, p_cur: int, masked: bool, tagid: str):
         """Returns a list of instruction strings.  s_cur: 32 registers [nq][16], element r of a block is
         key 8 (r / 4) + 4 hh + (r % 4) of the half tile.  p_cur: 16 registers [nq][2][4]."""
@@ -229,7 +260,7 @@ def generator(nq: int = 2, paged: bool = False):
             o.append(f"v_cmp_lt_f32_e32 vcc, %[thr], {vr(DIFF[0])}")
         # one entry: nothing may be scheduled between the branch and the label its target returns to
         o.append(f"s_cbranch_vccnz L_RESC_{tagid}_%=\nL_RET_{tagid}_%=:")
-        # weights 2^(cs s - cs m), their row sums and their 16-bit form, software-pipelined element by
+        # weights 2^(s - m) (s already in log2 units: Q was scaled at load), their row sums and their 16-bit form, software-pipelined element by
         # element so that the slow transcendental instructions are spread evenly between the MFMAs
         # (a run of them would leave the matrix cores waiting for the in-order instruction stream).
         # A v_exp result is first read two instructions later; v_dot2 would sum the rounded pairs in one
@@ -247,7 +278,7 @@ def generator(nq: int = 2, paged: bool = False):
         for i in range(NEL + USE_LAG):
             if i < NEL:
                 q, r = elems[i]
-                o.append(f"v_fma_f32 {vr(S[q][r])}, {vr(S[q][r])}, %[cs], {vr(NEG_MC[q])}")
+                o.append(f"v_add_f32_e32 {vr(S[q][r])}, {vr(NEG_MC[q])}, {vr(S[q][r])}")
             if EXP_LAG <= i < NEL + EXP_LAG:
                 q, r = elems[i - EXP_LAG]
                 o.append(f"v_exp_f32_e32 {vr(S[q][r])}, {vr(S[q][r])}")
@@ -268,13 +299,11 @@ def generator(nq: int = 2, paged: bool = False):
         for q in range(NQ):
             A.e(f"v_sub_f32_e32 {vr(ALPHA[q])}, {vr(M_RUN[q])}, {vr(M_NEW[q])}")
         for q in range(NQ):
-            A.e(f"v_mul_f32_e32 {vr(ALPHA[q])}, %[cs], {vr(ALPHA[q])}")
+            A.e(f"v_mov_b32_e32 {vr(M_RUN[q])}, {vr(M_NEW[q])}")
         for q in range(NQ):
             A.e(f"v_exp_f32_e32 {vr(ALPHA[q])}, {vr(ALPHA[q])}")
         for q in range(NQ):
-            A.e(f"v_mov_b32_e32 {vr(M_RUN[q])}, {vr(M_NEW[q])}")
-        for q in range(NQ):
-            A.e(f"v_mul_f32_e32 {vr(NEG_MC[q])}, {sr(S_NCS)}, {vr(M_NEW[q])}")
+            A.e(f"v_mul_f32_e32 {vr(NEG_MC[q])}, -1.0, {vr(M_NEW[q])}")
         for q in range(NQ):  # >= 4 instructions after the exponentials
             A.e(f"v_mul_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}, {vr(ALPHA[q])}")
         A.e(f"s_mov_b32 {sr(S_FLAG)}, 1")
@@ -316,7 +345,8 @@ def generator(nq: int = 2, paged: bool = False):
         """One half step.
         qk  = (K address register, key block, S destination base) or None
         pv  = (V address register, key block, P source base) or None
-        sm  = (S source base, P destination base, masked) or None
+        sm  = (S source base, P destination base, masked[, fast]) or None; fast: the stream without a
+              running maximum (fast_stream), followed by the range check of the row sums
         nxt = ((K address register, key block) or None, (V address register, key block) or None):
               operands of the next half step's first PD groups, fetched at the end of this one
         extra = ({gap: [instructions issued first]}, {gap: [instructions issued last]}) (staging)
@@ -324,7 +354,8 @@ def generator(nq: int = 2, paged: bool = False):
               newly published tile) the wave waits for its loads of that tile and for its own
               outstanding operand reads, then meets the other waves at the barrier.
         hs  = serial number of the half step inside the emitted code (tags of its operand reads)."""
-        valu = softmax_stream(A, sm[0], sm[1], sm[2], tagid) if sm else []
+        fast = bool(sm) and len(sm) > 3 and sm[3]
+        valu = [] if not sm else fast_stream(A, sm[0], sm[1]) if fast else softmax_stream(A, sm[0], sm[1], sm[2], tagid)
         # MFMAs of the half step in issue order; a "gap" of other instructions follows each of them
         slots = []
         for g in range(8):
@@ -394,7 +425,20 @@ def generator(nq: int = 2, paged: bool = False):
                 A.e(f"v_mfma_f32_32x32x16_{A.dt} {ar(acc, 16)}, {vr(vo, 4)}, {vr(p_src, 4)}, {ar(acc, 16)}")
             for ins in gaps[si]:
                 A.e(ins)
-        if sm:
+        if fast:
+            # every row sum inside [2^-64, 2^64]?  One unsigned compare per row block: the bit pattern of
+            # a positive float minus that of 2^-64 is below that of 2^64 minus that of 2^-64 exactly then
+            # (smaller sums wrap around, infinities and NaNs are above).  Otherwise redo the half tile
+            # with a running maximum and stay with the general stream (out of line, never returns).
+            for q in range(NQ):
+                A.e(f"v_subrev_u32_e32 {vr(TMP[q])}, 0x1f800000, {vr(L_SUM[q])}")
+            A.e(f"v_cmp_lt_u32_e32 vcc, 0x40000000, {vr(TMP[0])}")
+            for q in range(1, NQ):
+                A.e(f"s_mov_b64 {sr(S_CMP, 2)}, vcc")
+                A.e(f"v_cmp_lt_u32_e32 vcc, 0x40000000, {vr(TMP[q])}")
+                A.e(f"s_or_b64 vcc, vcc, {sr(S_CMP, 2)}")
+            A.e(f"s_cbranch_vccnz L_FALL_{tagid}_%=")
+        elif sm:
             A.e(f"s_cmp_lg_u32 {sr(S_FLAG)}, 0")
             A.e(f"s_cbranch_scc1 L_RESO_{tagid}_%=")
             A.e(f"L_RESO_RET_{tagid}_%=:")
@@ -515,15 +559,54 @@ def generator(nq: int = 2, paged: bool = False):
             A.e(f"v_add_u32_e32 {vr(VA_CUR)}, {sr(S_ST_CUR)}, {vr(VL)}")
 
 
-    def body(A: Asm, masked: bool, name: str):
-        """Tile t for a computing wave: half steps u = 2t and 2t + 1."""
+    def body(A: Asm, masked: bool, name: str, fast=False, entries=False):
+        """Tile t for a computing wave: half steps u = 2t and 2t + 1.  entries: labels at the start of
+        the second half step and behind it, where a wave that left the fast stream joins this body
+        (the matrix-core, LDS and staging instructions of all bodies are the same, so the counters of
+        outstanding LDS reads and loads agree at these points)."""
         A.reset_lds(pending_reads(0))
         rotate_addresses(A)
-        half_step(A, 0, qk=(KA_CUR, 1, SB), pv=(VA_PRV, 1, PB), sm=(SA, PA, masked),
+        half_step(A, 0, qk=(KA_CUR, 1, SB), pv=(VA_PRV, 1, PB), sm=(SA, PA, masked, fast),
                   nxt=((KA_NXT, 0), (VA_CUR, 0)), extra=None, tagid=name + "0", publish=True)
-        half_step(A, 1, qk=(KA_NXT, 0, SA), pv=(VA_CUR, 0, PA), sm=(SB, PB, masked),
+        if entries:
+            A.e(f"L_ENTRY_{name}1_%=:")
+        half_step(A, 1, qk=(KA_NXT, 0, SA), pv=(VA_CUR, 0, PA), sm=(SB, PB, masked, fast),
                   nxt=((KA_NXT, 1), (VA_CUR, 1)), extra=staging_ops(name), tagid=name + "1")
+        if entries:
+            A.e(f"L_TAIL_{name}_%=:")
         assert A.lds[-3 * PD:] == pending_reads(2), A.lds[-6:]
+
+
+    def fallback_block(A: Asm, tagid: str, s_cur: int, p_cur: int, resume: str):
+        """Out of line, reached from the range check of the fast stream's half step `tagid`: a row sum
+        left [2^-64, 2^64] (scores far above or below zero).  The scores of the half tile are still in
+        s_cur: put the row sums back, give the rows a running maximum (0, the reference point the fast
+        stream used, if the row already has weight; none yet otherwise), redo the softmax of the half
+        tile with the general stream and continue in the general loop at `resume`."""
+        x = "x" + tagid[-1]
+        A.e(f"L_FALL_{tagid}_%=:")
+        A.e("s_nop 7")                        # the MFMAs issued last retire before anything below
+        A.e("s_nop 7")
+        for q in range(NQ):
+            A.e(f"v_mov_b32_e32 {vr(L_SUM[q])}, {vr(L_PREV[q])}")
+        for q in range(NQ):
+            A.e(f"v_mov_b32_e32 {vr(T_MAX[q])}, {vr(L_PREV[q])}")
+            A.e(f"v_mov_b32_e32 {vr(T_MAX2[q])}, {vr(L_PREV[q])}")
+        A.e("s_nop 1")
+        for q in range(NQ):
+            A.e(f"v_permlane32_swap_b32_e32 {vr(T_MAX[q])}, {vr(T_MAX2[q])}")
+        A.e("s_nop 1")
+        for q in range(NQ):                   # the row's sum over both lane halves
+            A.e(f"v_add_f32_e32 {vr(T_MAX[q])}, {vr(T_MAX[q])}, {vr(T_MAX2[q])}")
+        for q in range(NQ):
+            A.e(f"v_cmp_eq_f32_e32 vcc, 0, {vr(T_MAX[q])}")
+            A.e(f"v_cndmask_b32_e32 {vr(M_RUN[q])}, 0, {vr(NEG_INF)}, vcc")
+        for ins in softmax_stream(A, s_cur, p_cur, False, x):
+            A.e(ins)
+        A.e(f"s_cmp_lg_u32 {sr(S_FLAG)}, 0")
+        A.e(f"s_cbranch_scc1 L_RESO_{x}_%=")
+        A.e(f"L_RESO_RET_{x}_%=:")
+        A.e(f"s_branch {resume}")
 
 
     def body_stage_only(A: Asm):
@@ -577,7 +660,6 @@ def generator(nq: int = 2, paged: bool = False):
 
         A.c("lane constants")
         e(f"s_mov_b32 {sr(S_ONES)}, 0x{ones:08x}")
-        e(f"s_xor_b32 {sr(S_NCS)}, %[cs], 0x80000000")
         e(f"s_mov_b32 {sr(S_NK1)}, %[nk1]")
         e(f"v_and_b32_e32 {vr(LANE)}, 63, %[tid]")
         e(f"v_and_b32_e32 {vr(COL)}, 31, {vr(LANE)}")
@@ -724,7 +806,38 @@ def generator(nq: int = 2, paged: bool = False):
         for i in range(full):
             e(f"ds_write_b128 {vr(TMP[0])}, {vr(PB, 4)} offset:{16 * THREADS * i}")
         e(f"ds_write_b128 {vr(TMP[1])}, {vr(PB, 4)} offset:{16 * THREADS * full}")
-        A.c("Q and tile 0 have landed once at most the newest loads (tiles 1, 2) are outstanding")
+        A.c("Q has landed once only the tile loads are outstanding: multiply it by scale x log2(e) and round it to")
+        A.c("16 bits again, so that the MFMAs deliver the exponents of the weights (runs while tiles 0..2 are in flight)")
+        e(f"s_waitcnt vmcnt({6 * CPW + TBL})")
+        for base in range(0, 32 * NQ, 4):
+            regs = [A_Q + base + k for k in range(4)]
+            for k, a in enumerate(regs):
+                e(f"v_accvgpr_read_b32 {vr(TMP[k])}, {ar(a)}")
+            if dt == "bf16":
+                for k in range(4):
+                    e(f"v_lshlrev_b32_e32 {vr(TMP[4 + k])}, 16, {vr(TMP[k])}")
+                for k in range(4):
+                    e(f"v_and_b32_e32 {vr(TMP[k])}, 0xffff0000, {vr(TMP[k])}")
+            else:
+                for k in range(4):
+                    e(f"v_cvt_f32_f16_e32 {vr(TMP[4 + k])}, {vr(TMP[k])}")
+                for k in range(4):
+                    e(f"v_lshrrev_b32_e32 {vr(TMP[k])}, 16, {vr(TMP[k])}")
+                for k in range(4):
+                    e(f"v_cvt_f32_f16_e32 {vr(TMP[k])}, {vr(TMP[k])}")
+            for k in range(8):
+                e(f"v_mul_f32_e32 {vr(TMP[k])}, %[cs], {vr(TMP[k])}")
+            if dt == "bf16":
+                for k in range(4):
+                    e(f"v_cvt_pk_bf16_f32 {vr(TMP[k])}, {vr(TMP[4 + k])}, {vr(TMP[k])}")
+            else:
+                for k in range(8):
+                    e(f"v_cvt_f16_f32_e32 {vr(TMP[k])}, {vr(TMP[k])}")
+                for k in range(4):
+                    e(f"v_pack_b32_f16 {vr(TMP[k])}, {vr(TMP[4 + k])}, {vr(TMP[k])}")
+            for k, a in enumerate(regs):
+                e(f"v_accvgpr_write_b32 {ar(a)}, {vr(TMP[k])}")
+        A.c("tile 0 has landed once at most the newest loads (tiles 1, 2) are outstanding")
         e(f"s_waitcnt vmcnt({4 * CPW + TBL}) lgkmcnt(0)")
         e("s_barrier")
         e(f"v_mov_b32_e32 {vr(KA_NXT)}, {vr(KL)}")
@@ -735,13 +848,33 @@ def generator(nq: int = 2, paged: bool = False):
         half_step(A, -1, qk=(KA_NXT, 0, SA), pv=None, sm=None, nxt=((KA_NXT, 1), (VA_CUR, 1)), extra=[],
                   tagid="pro", cold=True)
 
-        A.c("tiles entirely below the wave's diagonal")
+        n_pro = len(A.lines)
+        fast = dt == "bf16"
+        if fast:
+            A.c("tiles entirely below the wave's diagonal, bf16: weights without a running maximum")
+            e("L_FAST_%=:")
+            e(f"s_cmp_ge_i32 {sr(S_T)}, %[tms]")
+            e("s_cbranch_scc1 L_FAST_END_%=")
+            n0 = len(A.lines)
+            body(A, False, "f", fast=True)
+            check_mfma_results(A.lines[:n0] + A.lines[n0:] * 2)   # after the prologue, and around the loop
+            e(f"s_add_u32 {sr(S_T)}, {sr(S_T)}, 1")
+            e("s_branch L_FAST_%=")
+            e("L_FAST_END_%=:")
+            A.c("rows that went through the fast stream have weight relative to the reference point 0")
+            e(f"s_cmp_eq_u32 {sr(S_T)}, 0")
+            e("s_cbranch_scc1 L_FULL_END_%=")
+            for q in range(NQ):
+                e(f"v_mov_b32_e32 {vr(M_RUN[q])}, 0")
+            e("s_branch L_FULL_END_%=")
+
+        A.c("tiles entirely below the wave's diagonal, general stream (fp16; bf16 after leaving the fast stream)")
         e("L_FULL_%=:")
         e(f"s_cmp_ge_i32 {sr(S_T)}, %[tms]")
         e("s_cbranch_scc1 L_FULL_END_%=")
         n0 = len(A.lines)
-        body(A, False, "f")
-        check_mfma_results(A.lines[:n0] + A.lines[n0:] * 2)   # after the prologue, and around the loop
+        body(A, False, "g", entries=fast)
+        check_mfma_results(A.lines[:n_pro] + A.lines[n0:] * 2)   # after the prologue, and around the loop
         e(f"s_add_u32 {sr(S_T)}, {sr(S_T)}, 1")
         e("s_branch L_FULL_%=")
         e("L_FULL_END_%=:")
@@ -759,7 +892,9 @@ def generator(nq: int = 2, paged: bool = False):
         n1 = len(A.lines)
         body(A, True, "m")
         check_mfma_results(A.lines[n0:n1] + A.lines[n1:] * 2)  # unmasked -> masked, masked -> masked
-        check_mfma_results(A.lines[:n0] + A.lines[n1:])        # prologue -> masked
+        check_mfma_results(A.lines[:n_pro] + A.lines[n1:])     # prologue -> masked
+        if fast:
+            check_mfma_results(A.lines[n_pro:n0] + A.lines[n1:])   # fast -> masked
         e(f"s_add_u32 {sr(S_T)}, {sr(S_T)}, 1")
         e("s_branch L_MASK_%=")
         e("L_MASK_END_%=:")
@@ -839,11 +974,16 @@ def generator(nq: int = 2, paged: bool = False):
         e("s_branch L_STAGE_LOOP_%=")
 
         A.c("out-of-line: running maximum moved")
-        for name in ("f0", "f1", "m0", "m1"):
+        for name in ("g0", "g1", "m0", "m1") + (("x0", "x1") if fast else ()):
             rescale_blocks(A, name)
+        if fast:
+            A.c("out-of-line: a row sum of the fast stream left its range")
+            fallback_block(A, "f0", SA, PA, "L_ENTRY_g1_%=")
+            fallback_block(A, "f1", SB, PB, "L_TAIL_g_%=")
+            A.e("s_branch L_END_%=")
         if PAGED:
             A.e("s_branch L_END_%=")
-            bad_block_paths(A, ["last", "p0", "p1", "p2", "f", "m", "s"])
+            bad_block_paths(A, ["last", "p0", "p1", "p2", "g", "m", "s"] + (["f"] if fast else []))
         e("L_END_%=:")
         e("s_waitcnt vmcnt(0) lgkmcnt(0)")
         return A.lines

@@ -71,11 +71,17 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const char *p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(p));
 }
 
-template <typename M, int D>
+// KV8: the slot holds 8-bit codes with a power-of-two scale per (row, kv head); a thread then moves
+// one 16-byte piece of 16 codes per tile and tensor and parks it as two pieces of 16-bit values
+// (code x 2^e, exact), so everything behind the LDS tile is the same for both kinds of slot.
+template <typename M, int D, bool KV8>
 __global__ __launch_bounds__(64 * kWaves, 1) void prefill_mfma_kernel(AttnArgs a, int G, int n_qt, int xcd_map) {
     using Ge = Geo<D>;
     using vec8 = typename M::vec8;
-    constexpr int NL = Ge::NL, LPR = Ge::LPR;
+    constexpr int LPR = KV8 ? D / 16 : Ge::LPR;                // 16-byte pieces per slot row
+    constexpr int NL = KV8 ? 1 : Ge::NL;                       // loads per thread, tile and tensor
+    constexpr int EB = KV8 ? 1 : 2;                            // bytes per slot element
+    constexpr bool kAllLoad = kBN * LPR >= 64 * kWaves;        // 8-bit slots of head_dim 64: half the threads load
     __shared__ __attribute__((aligned(16))) char lds[2 * Ge::STAGE_BYTES];
 
     const int tid = threadIdx.x;
@@ -141,12 +147,14 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_mfma_kernel(AttnArgs a
     }
 
     // cooperative tile loads: thread t moves pieces t, t + 512, ... (16 lanes per row => coalesced)
-    const uint16_t *kp = (const uint16_t *)a.cache.k + (int64_t)kvh * D;
-    const uint16_t *vp = (const uint16_t *)a.cache.v + (int64_t)kvh * D;
-    const int64_t row_elems = (int64_t)hkv * D;
+    const char *kp = (const char *)a.cache.k + (int64_t)kvh * D * EB;
+    const char *vp = (const char *)a.cache.v + (int64_t)kvh * D * EB;
+    const int64_t row_bytes = (int64_t)hkv * D * EB;
+    const bool loader = kAllLoad || tid < kBN * LPR;
     auto rows_of = [&](int j0, int32_t *rows) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
+            if (!loader) { rows[i] = -1; continue; }
             // keys past the last needed one repeat it: they are masked anyway, and a real row keeps
             // the V operand finite (0 x NaN from never-written cache memory would poison the sum)
             const int key = min(j0 + (tid + i * 64 * kWaves) / LPR, n_keys - 1);
@@ -155,13 +163,17 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_mfma_kernel(AttnArgs a
             rows[i] = (int32_t)r;
         }
     };
+    uint16_t sr[NL]; // 8-bit slots: exponent bytes (K low, V high) of the row of each piece
+#pragma unroll
+    for (int i = 0; i < NL; ++i) sr[i] = 0x7f7f;
     auto issue = [&](const int32_t *rows, uint4 *kr, uint4 *vr) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             if (rows[i] >= 0) { // a bad block id keeps the previous (finite) piece
-                const int64_t off = rows[i] * row_elems + (tid % LPR) * 8;
+                const int64_t off = rows[i] * row_bytes + (tid % LPR) * 16;
                 kr[i] = *(const uint4 *)(kp + off);
                 vr[i] = *(const uint4 *)(vp + off);
+                if constexpr (KV8) sr[i] = a.cache.scales[(int64_t)rows[i] * hkv + kvh];
             }
         }
     };
@@ -171,8 +183,20 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_mfma_kernel(AttnArgs a
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int piece = tid + i * 64 * kWaves;
-            *(uint4 *)(ks + (piece / LPR) * Ge::K_STRIDE + (piece % LPR) * 16) = kr[i];
-            *(uint4 *)(vs + (piece / LPR) * Ge::V_STRIDE + (piece % LPR) * 16) = vr[i];
+            if constexpr (KV8) {
+                if (!loader) continue;
+                constexpr bool bf = std::is_same<M, PBF16>::value;
+                uint4 lo, hi;
+                dequant_piece<bf>(kr[i], scale_of_byte(sr[i] & 0xffu), lo, hi);
+                *(uint4 *)(ks + (piece / LPR) * Ge::K_STRIDE + (piece % LPR) * 32) = lo;
+                *(uint4 *)(ks + (piece / LPR) * Ge::K_STRIDE + (piece % LPR) * 32 + 16) = hi;
+                dequant_piece<bf>(vr[i], scale_of_byte(sr[i] >> 8), lo, hi);
+                *(uint4 *)(vs + (piece / LPR) * Ge::V_STRIDE + (piece % LPR) * 32) = lo;
+                *(uint4 *)(vs + (piece / LPR) * Ge::V_STRIDE + (piece % LPR) * 32 + 16) = hi;
+            } else {
+                *(uint4 *)(ks + (piece / LPR) * Ge::K_STRIDE + (piece % LPR) * 16) = kr[i];
+                *(uint4 *)(vs + (piece / LPR) * Ge::V_STRIDE + (piece % LPR) * 16) = vr[i];
+            }
         }
     };
 
@@ -318,14 +342,14 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_mfma_kernel(AttnArgs a
         }
 }
 
-template <typename M, int D>
+template <typename M, int D, bool KV8>
 hipError_t launch_p(const AttnArgs &a, int group, hipStream_t stream) {
     const int n_qt = (a.max_q + kBM - 1) / kBM;
     const int pairs = a.batch * a.cache.n_kv_heads;
     const int64_t blocks = (int64_t)pairs * group * n_qt;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     const int xcd_map = (pairs % 8) == 0;
-    prefill_mfma_kernel<M, D><<<dim3((unsigned)blocks), 64 * kWaves, 0, stream>>>(a, group, n_qt, xcd_map);
+    prefill_mfma_kernel<M, D, KV8><<<dim3((unsigned)blocks), 64 * kWaves, 0, stream>>>(a, group, n_qt, xcd_map);
     set_last_kernel_name("prefill_mfma_kernel");
     return hipGetLastError();
 }
@@ -334,14 +358,21 @@ hipError_t launch_p(const AttnArgs &a, int group, hipStream_t stream) {
 
 bool prefill_mfma_supported(int dtype, int head_dim, int group) {
     (void)group;
-    return (dtype == SKV_BF16 || dtype == SKV_F16) && (head_dim == 64 || head_dim == 128);
+    const int act = dtype_act(dtype);
+    return (act == SKV_BF16 || act == SKV_F16) && (head_dim == 64 || head_dim == 128);
 }
 
 hipError_t launch_prefill_mfma(const AttnArgs &a, int dtype, int head_dim, int group, hipStream_t stream) {
-    if (dtype == SKV_BF16) {
-        return head_dim == 128 ? launch_p<PBF16, 128>(a, group, stream) : launch_p<PBF16, 64>(a, group, stream);
+    if (dtype_kv8(dtype)) {
+        if (a.cache.scales == nullptr) return hipErrorInvalidValue;
+        if (dtype_act(dtype) == SKV_BF16)
+            return head_dim == 128 ? launch_p<PBF16, 128, true>(a, group, stream) : launch_p<PBF16, 64, true>(a, group, stream);
+        return head_dim == 128 ? launch_p<PF16, 128, true>(a, group, stream) : launch_p<PF16, 64, true>(a, group, stream);
     }
-    return head_dim == 128 ? launch_p<PF16, 128>(a, group, stream) : launch_p<PF16, 64>(a, group, stream);
+    if (dtype == SKV_BF16) {
+        return head_dim == 128 ? launch_p<PBF16, 128, false>(a, group, stream) : launch_p<PBF16, 64, false>(a, group, stream);
+    }
+    return head_dim == 128 ? launch_p<PF16, 128, false>(a, group, stream) : launch_p<PF16, 64, false>(a, group, stream);
 }
 
 } // namespace skv

@@ -16,9 +16,10 @@ struct skv_cache {
     std::vector<int32_t> route;  // host copy
     std::vector<int32_t> slot;   // slot_of_layer
     int32_t n_slots = 0;
-    void *k_pool = nullptr, *v_pool = nullptr;
+    void *k_pool = nullptr, *v_pool = nullptr, *scale_pool = nullptr;
     bool owns_pools = false;
     size_t pool_bytes_each = 0;
+    size_t scale_pool_bytes = 0; // 8-bit slots: uint16 per (row, kv head), all slots
     size_t slot_bytes = 0;       // bytes of one slot inside a pool
     const int32_t *block_table = nullptr;
     int32_t max_blocks_per_seq = 0;
@@ -40,7 +41,9 @@ skv_status_t hip_fail(hipError_t e) {
 // Pre-fill kernel choice: pipelined -> plain MFMA -> vector ALU.
 skv_status_t launch_prefill(const skv::AttnArgs &a, int dtype, int head_dim, int g, hipStream_t stream) {
     hipError_t e;
-    if (!skv::tuning().prefill_plain && skv::prefill_pipe_supported(a, dtype, head_dim))
+    if (skv::dtype_kv8(dtype)) // 8-bit slots: the kernel that stages tiles through registers converts on the way
+        e = skv::launch_prefill_mfma(a, dtype, head_dim, g, stream);
+    else if (!skv::tuning().prefill_plain && skv::prefill_pipe_supported(a, dtype, head_dim))
         e = skv::launch_prefill_pipe(a, dtype, g, stream);
     else if (skv::prefill_mfma_supported(dtype, head_dim, g))
         e = skv::launch_prefill_mfma(a, dtype, head_dim, g, stream);
@@ -49,7 +52,7 @@ skv_status_t launch_prefill(const skv::AttnArgs &a, int dtype, int head_dim, int
     return e == hipSuccess ? SKV_OK : hip_fail(e);
 }
 
-int elem_bytes(int dtype) { return dtype == SKV_F32 ? 4 : 2; }
+int elem_bytes(int dtype) { return dtype == SKV_F32 ? 4 : skv::dtype_kv8(dtype) ? 1 : 2; } // of a slot element
 
 int ilog2_exact(int v) {
     for (int s = 0; s < 31; ++s)
@@ -61,8 +64,9 @@ skv_status_t check_desc(const skv_cache_desc_t *d, int32_t *n_slots, std::vector
     if (!d || !d->route) return SKV_ERR_INVALID_ARG;
     if (d->n_layers <= 0 || d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->batch <= 0 || d->max_ctx <= 0)
         return SKV_ERR_INVALID_ARG;
-    if (d->dtype != SKV_F32 && d->dtype != SKV_F16 && d->dtype != SKV_BF16) return SKV_ERR_UNSUPPORTED;
+    if (d->dtype < SKV_F32 || d->dtype > SKV_F16_KV8) return SKV_ERR_UNSUPPORTED;
     if (d->head_dim != 64 && d->head_dim != 128 && d->head_dim != 256) return SKV_ERR_UNSUPPORTED;
+    if (skv::dtype_kv8(d->dtype) && d->head_dim == 256) return SKV_ERR_UNSUPPORTED;
     if (d->n_q_heads % d->n_kv_heads) return SKV_ERR_UNSUPPORTED;
     const int g = d->n_q_heads / d->n_kv_heads;
     if (g != 1 && g != 2 && g != 4 && g != 8 && g != 16) return SKV_ERR_UNSUPPORTED;
@@ -72,6 +76,7 @@ skv_status_t check_desc(const skv_cache_desc_t *d, int32_t *n_slots, std::vector
         if (d->n_blocks <= 0) return SKV_ERR_INVALID_ARG;
     }
     if ((d->k_pool == nullptr) != (d->v_pool == nullptr)) return SKV_ERR_INVALID_ARG;
+    if (skv::dtype_kv8(d->dtype) && (d->k_pool == nullptr) != (d->scale_pool == nullptr)) return SKV_ERR_INVALID_ARG;
     std::vector<int32_t> tmp((size_t)d->n_layers);
     int32_t ns = 0;
     skv_status_t st = skv_route_validate(d->route, d->n_layers, tmp.data(), &ns);
@@ -81,17 +86,24 @@ skv_status_t check_desc(const skv_cache_desc_t *d, int32_t *n_slots, std::vector
     return SKV_OK;
 }
 
+size_t slot_rows_of(const skv_cache_desc_t *d) {
+    return d->block_size > 0 ? (size_t)d->n_blocks * d->block_size : (size_t)d->batch * d->max_ctx;
+}
+
 size_t slot_bytes_of(const skv_cache_desc_t *d) {
-    const size_t row = (size_t)d->n_kv_heads * d->head_dim * elem_bytes(d->dtype);
-    const size_t rows = d->block_size > 0 ? (size_t)d->n_blocks * d->block_size
-                                          : (size_t)d->batch * d->max_ctx;
-    return rows * row;
+    return slot_rows_of(d) * (size_t)d->n_kv_heads * d->head_dim * elem_bytes(d->dtype);
+}
+
+// 8-bit slots: the exponent bytes of one slot (uint16 per row and kv head)
+size_t slot_scale_bytes_of(const skv_cache_desc_t *d) {
+    return skv::dtype_kv8(d->dtype) ? slot_rows_of(d) * (size_t)d->n_kv_heads * sizeof(uint16_t) : 0;
 }
 
 skv::SlotView view_of(const skv_cache *c, int slot) {
     skv::SlotView v;
     v.k = (const char *)c->k_pool + (size_t)slot * c->slot_bytes;
     v.v = (const char *)c->v_pool + (size_t)slot * c->slot_bytes;
+    v.scales = c->scale_pool ? (const uint16_t *)((const char *)c->scale_pool + (size_t)slot * slot_scale_bytes_of(&c->d)) : nullptr;
     v.block_table = c->block_table;
     v.faults = c->faults;
     v.max_blocks_per_seq = c->max_blocks_per_seq;
@@ -203,7 +215,16 @@ skv_status_t skv_cache_bytes(const skv_cache_desc_t *desc, size_t *total_bytes) 
     int32_t ns = 0;
     skv_status_t st = check_desc(desc, &ns, nullptr);
     if (st != SKV_OK) return st;
-    *total_bytes = 2 * (size_t)ns * slot_bytes_of(desc);
+    *total_bytes = (size_t)ns * (2 * slot_bytes_of(desc) + slot_scale_bytes_of(desc));
+    return SKV_OK;
+}
+
+skv_status_t skv_cache_pool_bytes(const skv_cache_desc_t *desc, size_t *kv_pool_bytes, size_t *scale_pool_bytes) {
+    int32_t ns = 0;
+    skv_status_t st = check_desc(desc, &ns, nullptr);
+    if (st != SKV_OK) return st;
+    if (kv_pool_bytes) *kv_pool_bytes = (size_t)ns * slot_bytes_of(desc);
+    if (scale_pool_bytes) *scale_pool_bytes = (size_t)ns * slot_scale_bytes_of(desc);
     return SKV_OK;
 }
 
@@ -214,7 +235,9 @@ skv_status_t skv_cache_alloc(const skv_cache_desc_t *desc, skv_cache_t **out) {
     skv_status_t st = check_desc(desc, &ns, &slot);
     if (st != SKV_OK) return st;
     const size_t each = (size_t)ns * slot_bytes_of(desc);
+    const size_t scale_bytes = (size_t)ns * slot_scale_bytes_of(desc);
     if (desc->k_pool && desc->pool_bytes < each) return SKV_ERR_CAPACITY;
+    if (desc->k_pool && desc->scale_pool_bytes < scale_bytes) return SKV_ERR_CAPACITY;
 
     skv_cache *c = new (std::nothrow) skv_cache();
     if (!c) return SKV_ERR_OOM;
@@ -224,6 +247,7 @@ skv_status_t skv_cache_alloc(const skv_cache_desc_t *desc, skv_cache_t **out) {
     c->slot.swap(slot);
     c->n_slots = ns;
     c->pool_bytes_each = each;
+    c->scale_pool_bytes = scale_bytes;
     c->slot_bytes = slot_bytes_of(desc);
     c->block_shift = desc->block_size > 0 ? ilog2_exact(desc->block_size) : 0;
 
@@ -237,16 +261,21 @@ skv_status_t skv_cache_alloc(const skv_cache_desc_t *desc, skv_cache_t **out) {
     if (desc->k_pool) {
         c->k_pool = desc->k_pool;
         c->v_pool = desc->v_pool;
+        c->scale_pool = scale_bytes ? desc->scale_pool : nullptr;
     } else {
         c->owns_pools = true;
         e = hipMalloc(&c->k_pool, each);
         if (e == hipSuccess) e = hipMalloc(&c->v_pool, each);
+        if (e == hipSuccess && scale_bytes) e = hipMalloc(&c->scale_pool, scale_bytes);
         if (e == hipSuccess) e = hipMemset(c->k_pool, 0, each);
         if (e == hipSuccess) e = hipMemset(c->v_pool, 0, each);
+        // exponent byte 127 = scale 1: never-written rows read as zeros, not as 0 x 2^-127
+        if (e == hipSuccess && scale_bytes) e = hipMemset(c->scale_pool, 127, scale_bytes);
         if (e == hipSuccess) e = hipDeviceSynchronize();
         if (e != hipSuccess) {
             if (c->k_pool) (void)hipFree(c->k_pool);
             if (c->v_pool) (void)hipFree(c->v_pool);
+            if (c->scale_pool) (void)hipFree(c->scale_pool);
             (void)hipFree(c->faults);
             delete c;
             return hip_fail(e);
@@ -261,8 +290,10 @@ skv_status_t skv_cache_free(skv_cache_t *c) {
     skv_status_t st = SKV_OK;
     if (c->owns_pools) {
         hipError_t e1 = hipFree(c->k_pool), e2 = hipFree(c->v_pool);
+        hipError_t e3 = c->scale_pool ? hipFree(c->scale_pool) : hipSuccess;
         if (e1 != hipSuccess) st = hip_fail(e1);
         if (e2 != hipSuccess) st = hip_fail(e2);
+        if (e3 != hipSuccess) st = hip_fail(e3);
     }
     hipError_t e = hipFree(c->faults);
     if (e != hipSuccess) st = hip_fail(e);
@@ -277,6 +308,13 @@ skv_status_t skv_cache_info(const skv_cache_t *c, int32_t *n_slots, void **k_poo
     if (k_pool) *k_pool = c->k_pool;
     if (v_pool) *v_pool = c->v_pool;
     if (pool_bytes_each) *pool_bytes_each = c->pool_bytes_each;
+    return SKV_OK;
+}
+
+skv_status_t skv_cache_scale_info(const skv_cache_t *c, void **scale_pool, size_t *scale_pool_bytes) {
+    if (!c) return SKV_ERR_INVALID_ARG;
+    if (scale_pool) *scale_pool = c->scale_pool;
+    if (scale_pool_bytes) *scale_pool_bytes = c->scale_pool_bytes;
     return SKV_OK;
 }
 
@@ -406,6 +444,7 @@ skv_status_t skv_attn_decode_range(skv_cache_t *c, int32_t layer, int32_t seq_be
         const size_t seq_bytes = (size_t)view.max_ctx * c->d.n_kv_heads * c->d.head_dim * elem_bytes(c->d.dtype);
         view.k = (const char *)view.k + (size_t)seq_begin * seq_bytes;
         view.v = (const char *)view.v + (size_t)seq_begin * seq_bytes;
+        if (view.scales != nullptr) view.scales += (size_t)seq_begin * view.max_ctx * c->d.n_kv_heads;
     }
 
     skv::AttnArgs a;
@@ -422,6 +461,7 @@ skv_status_t skv_attn_decode_range(skv_cache_t *c, int32_t layer, int32_t seq_be
     a.keys_per_split = decode_keys_per_split(c, seq_count, max_kv_len);
     a.n_splits = (max_kv_len + a.keys_per_split - 1) / a.keys_per_split;
     a.scale_log2e = scale * 1.4426950408889634f;
+    a.slot_readers = (int32_t)std::count(c->slot.begin(), c->slot.end(), c->slot[layer]);
     a.work_counters = (int32_t *)workspace; // cleared by the launcher whenever the kernel uses them
     a.part_o = (float *)((char *)workspace + kCounterBytes);
     a.part_ml = a.part_o + (size_t)seq_count * c->d.n_q_heads * a.n_splits * c->d.head_dim;
@@ -432,7 +472,7 @@ skv_status_t skv_attn_decode_range(skv_cache_t *c, int32_t layer, int32_t seq_be
         e = skv::launch_decode_mfma(a, c->d.dtype, c->d.head_dim, g, (hipStream_t)stream);
     else
         e = skv::launch_attn_valu(a, c->d.dtype, c->d.head_dim, g, (hipStream_t)stream);
-    if (e == hipSuccess && a.n_splits > 1) e = skv::launch_split_merge(a, c->d.dtype, (hipStream_t)stream);
+    if (e == hipSuccess && a.n_splits > 1) e = skv::launch_split_merge(a, skv::dtype_act(c->d.dtype), (hipStream_t)stream);
     return e == hipSuccess ? SKV_OK : hip_fail(e);
 }
 
@@ -511,6 +551,7 @@ skv_status_t skv_attn_prefill(skv_cache_t *c, int32_t layer, const void *q, void
     a.max_q = max_q;
     a.n_q_heads = c->d.n_q_heads;
     a.max_kv_len = max_kv_len;
+    a.slot_readers = 1;
     a.keys_per_split = max_kv_len; // a prefill row is never split along the key axis
     a.n_splits = 1;
     a.scale_log2e = scale * 1.4426950408889634f;
@@ -597,6 +638,7 @@ skv_status_t skv_train_attn_fwd(const void *q, const void *k, const void *v, voi
     skv::AttnArgs a;
     a.cache.k = k;
     a.cache.v = v;
+    a.cache.scales = nullptr;
     a.cache.block_table = nullptr;
     a.cache.faults = faults;
     a.cache.max_blocks_per_seq = 0;
@@ -617,6 +659,7 @@ skv_status_t skv_train_attn_fwd(const void *q, const void *k, const void *v, voi
     a.n_q_heads = n_q_heads;
     a.max_kv_len = seq;
     a.keys_per_split = seq;
+    a.slot_readers = 1;
     a.n_splits = 1;
     a.scale_log2e = scale * 1.4426950408889634f;
     a.lse = lse;

@@ -12,6 +12,7 @@ namespace skv {
 struct SlotView {
     const void *k;              // base of the slot inside the K pool
     const void *v;              // base of the slot inside the V pool
+    const uint16_t *scales;     // 8-bit slots only: per (row, kv head) the scale exponent bytes of K (low) and V (high)
     const int32_t *block_table; // nullptr = contiguous
     uint32_t *faults;           // device fault word of the cache
     int32_t max_blocks_per_seq; // paged
@@ -31,6 +32,36 @@ __device__ __forceinline__ int64_t slot_row(const SlotView &c, int b, int pos) {
     return ((int64_t)blk << c.block_shift) + (pos & ((1 << c.block_shift) - 1));
 }
 
+// Descriptor dtypes 3 and 4: 16-bit activations over slots of 8-bit codes with power-of-two scales.
+__host__ __device__ constexpr bool dtype_kv8(int dtype) { return dtype == SKV_BF16_KV8 || dtype == SKV_F16_KV8; }
+// dtype of q / out / new rows
+__host__ __device__ constexpr int dtype_act(int dtype) {
+    return dtype == SKV_BF16_KV8 ? SKV_BF16 : dtype == SKV_F16_KV8 ? SKV_F16 : dtype;
+}
+
+// fp32 value 2^(byte - 127) of a scale exponent byte (byte 0, the clamp of absurdly small rows, reads
+// as the exponent field of a zero; the conversion instructions take the exponent field only).
+__device__ __forceinline__ float scale_of_byte(uint32_t byte) { return __builtin_bit_cast(float, byte << 23); }
+
+// One 16-byte piece of 16 e4m3 codes -> the 16 values code x 2^e in the 16-bit type, as two pieces.
+template <bool BF16>
+__device__ __forceinline__ void dequant_piece(uint4 codes, float scale, uint4 &lo, uint4 &hi) {
+    const uint32_t w[4] = {codes.x, codes.y, codes.z, codes.w};
+    uint32_t o[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if constexpr (BF16) {
+            o[2 * i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[i], scale, false));
+            o[2 * i + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[i], scale, true));
+        } else {
+            o[2 * i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w[i], scale, false));
+            o[2 * i + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w[i], scale, true));
+        }
+    }
+    lo = make_uint4(o[0], o[1], o[2], o[3]);
+    hi = make_uint4(o[4], o[5], o[6], o[7]);
+}
+
 struct AttnArgs {
     SlotView cache;
     const void *q;          // [rows][n_q_heads][head_dim]
@@ -46,6 +77,7 @@ struct AttnArgs {
     int32_t max_kv_len;     // host bound on kv_lens
     int32_t keys_per_split; // chunk of the key axis one work item covers
     int32_t n_splits;       // ceil(max_kv_len / keys_per_split)
+    int32_t slot_readers;   // layers routed to the slot being read (decode: picks the cache policy of the loads)
     float scale_log2e;      // softmax scale * log2(e)
     float *lse;             // pre-fill only, may be nullptr: [batch][n_q_heads][max_q] log-sum-exp of the scaled scores
 };

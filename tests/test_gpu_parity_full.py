@@ -13,7 +13,12 @@ from workloads import configs, gen
 pytestmark = pytest.mark.gpu
 
 
-def _decode_sampled(w, seqs_per_layer, heads_per_seq, must_seqs=(), fill_chunk_tokens=1 << 19, skip_if_oom=False):
+def _decode_sampled(w, seqs_per_layer, heads_per_seq, must_seqs=(), fill_chunk_tokens=1 << 19, skip_if_oom=False,
+                    all_kv_heads_every=1):
+    """Per layer: the first and the last sequence of the batch, `must_seqs` and `seqs_per_layer` random
+    ones, `heads_per_seq` random query heads each; on every `all_kv_heads_every`-th layer one random
+    sequence is checked on a query head of EVERY kv head (a head-index mistake confined to some kv heads
+    cannot hide behind the seed)."""
     print(f"\n{w.name}: B={w.batch} layers={w.n_layers} slots={len(w.owner_layers)} "
           f"sum(len)={int(w.kv_lens.sum())}", flush=True)
     torch.cuda.empty_cache()   # hand cached blocks of earlier tests back to the driver
@@ -43,13 +48,16 @@ def _decode_sampled(w, seqs_per_layer, heads_per_seq, must_seqs=(), fill_chunk_t
         q = w.q_decode(layer, "cuda")
         out = H.decode_layer(cache, w, layer, q, d_lens, max_len, ws)
         qh, oh = gen.to_f64(q), gen.to_f64(out)
-        seqs = list(must_seqs) + rng.choice(w.batch, seqs_per_layer, replace=False).tolist()
-        for b in seqs:
+        seqs = [0, w.batch - 1] + list(must_seqs) + rng.choice(w.batch, seqs_per_layer, replace=False).tolist()
+        picks = [(b, h) for b in seqs for h in rng.choice(w.n_q_heads, heads_per_seq, replace=False).tolist()]
+        if layer % all_kv_heads_every == 0:
+            b = int(rng.integers(w.batch))
+            picks += [(b, kvh * G + int(rng.integers(G))) for kvh in range(w.n_kv_heads)]
+        for b, h in picks:
             n = int(w.kv_lens[b])
-            for h in rng.choice(w.n_q_heads, heads_per_seq, replace=False).tolist():
-                K, V = H.oracle_kv_rows(w, layer, b, h // G, n)
-                want = O.attn_one(qh[b, h], K, V, w.scale)
-                worst = max(worst, float(np.abs(oh[b, h] - want).max()))
+            K, V = H.oracle_kv_rows(w, layer, b, h // G, n)
+            want = O.attn_one(qh[b, h], K, V, w.scale)
+            worst = max(worst, float(np.abs(oh[b, h] - want).max()))
         # a layer that shares its slot with the previous layer gives, for the same query, the same bits
         src = w.route[layer]
         if src in prev:
@@ -71,18 +79,18 @@ def test_config2_llama3_decode_bf16_full_size():
 def test_config4_qwen3_paged_ragged_decode_full_size():
     w = configs.qwen3_paged_decode()
     shortest, longest = int(np.argmin(w.kv_lens)), int(np.argmax(w.kv_lens))
-    _decode_sampled(w, seqs_per_layer=1, heads_per_seq=2, must_seqs=(shortest, longest))
+    _decode_sampled(w, seqs_per_layer=1, heads_per_seq=1, must_seqs=(shortest, longest))
 
 
 def test_config5_llama2_mha_decode_f16_batch32():
-    _decode_sampled(configs.llama2_mha_decode(batch=32), seqs_per_layer=1, heads_per_seq=3)
+    _decode_sampled(configs.llama2_mha_decode(batch=32), seqs_per_layer=1, heads_per_seq=2, all_kv_heads_every=2)
 
 
 def test_config5_llama2_mha_decode_f16_largest_batch_that_fits():
     """One slot per 8 layers: 1 GiB of cache per sequence instead of 8, so 256 sequences of 16384
     tokens (256 GiB) fit the 288 GB of one MI355X."""
-    _decode_sampled(configs.llama2_mha_decode(batch=256), seqs_per_layer=1, heads_per_seq=2,
-                    fill_chunk_tokens=1 << 15, skip_if_oom=True)
+    _decode_sampled(configs.llama2_mha_decode(batch=256), seqs_per_layer=1, heads_per_seq=1,
+                    fill_chunk_tokens=1 << 15, skip_if_oom=True, all_kv_heads_every=4)
 
 
 def test_config3_llama3_prefill_bf16_full_size():

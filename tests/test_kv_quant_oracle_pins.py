@@ -65,6 +65,8 @@ def test_scale_exponent_closed_forms():
         e = Q.scale_exponent(float(amax))
         assert amax * 2.0 ** -e <= 448.0 < amax * 2.0 ** -(e - 1)               # smallest such integer
     assert Q.scale_exponent(1e-45) == -127                                       # clamped
+    amax = np.concatenate([np.exp(rng.uniform(-100, 100, 500)), [0.0, 448.0, 3.5, 1e-45]])
+    assert Q.scale_exponents(amax).tolist() == [Q.scale_exponent(float(a)) for a in amax]
 
 
 @pytest.mark.parametrize("sigma", [1e-3, 0.5, 1.0, 300.0])
@@ -82,12 +84,12 @@ def test_round_trip_error_bounds(sigma):
     assert (np.abs(back).max(axis=1) <= amax * (1 + 2.0 ** -4)).all()
     # the largest element uses the top binade and a half of the code range
     top = np.abs(Q.E4M3_TABLE[codes]).max(axis=1)
-    assert ((top > 224 * (1 - 2.0 ** -4)) & (top <= 448)).all()
+    assert ((top >= 224) & (top <= 448)).all()
     # sign symmetry and idempotence
     c2, e2 = Q.quantise_rows(-x)
     assert np.array_equal(e2, eb) and np.array_equal(c2 & 0x7F, codes & 0x7F)
-    c3, e3 = Q.quantise_rows(back)
-    assert np.array_equal(c3, codes) and np.array_equal(e3, eb)
+    # (a row whose largest code is exactly 224 re-quantises with the exponent one lower: same values)
+    assert np.array_equal(Q.dequantise_rows(*Q.quantise_rows(back)), back)
 
 
 def test_identity_on_representable_rows():

@@ -38,6 +38,7 @@ class Workload:
     block_table: np.ndarray | None = None   # int32[batch][max_blocks_per_seq]
     n_blocks: int = 0
     max_ctx: int = 0           # capacity per sequence (contiguous) / index stride of positions
+    kv8: bool = False          # the cache slots hold 8-bit codes with a power-of-two scale per (position, kv head)
 
     def __post_init__(self):
         self.kv_lens = np.asarray(self.kv_lens, dtype=np.int32)
@@ -65,7 +66,7 @@ class Workload:
     def decode_bytes_per_layer(self) -> int:
         """Algorithmic bytes of one decode launch: K and V rows of every cached position of
         every sequence once, plus Q in and O out."""
-        row = self.n_kv_heads * self.head_dim * self.elem_bytes
+        row = self.n_kv_heads * (self.head_dim + 1) if self.kv8 else self.n_kv_heads * self.head_dim * self.elem_bytes
         qo = 2 * self.batch * self.n_q_heads * self.head_dim * self.elem_bytes
         return int(self.kv_lens.astype(np.int64).sum()) * 2 * row + qo
 

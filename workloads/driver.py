@@ -10,14 +10,17 @@ import paper_2604_22782_amd as skv
 def alloc_cache(w, device="cuda", caller_pools=False):
     desc = dict(n_layers=w.n_layers, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads,
                 head_dim=w.head_dim, batch=w.batch, max_ctx=w.max_ctx,
-                dtype=skv.dtype_code(w.torch_dtype), route=w.route,
+                dtype=skv.dtype_code(w.torch_dtype, getattr(w, "kv8", False)), route=w.route,
                 block_size=w.block_size, n_blocks=w.n_blocks)
     pools = None
     if caller_pools:
-        each = skv.skv_cache_bytes(**desc) // 2
+        each, sc = skv.skv_cache_pool_bytes(**desc)
         pools = (torch.zeros(each, dtype=torch.uint8, device=device),
                  torch.zeros(each, dtype=torch.uint8, device=device))
         desc.update(k_pool=pools[0], v_pool=pools[1], pool_bytes=each)
+        if sc:
+            pools += (torch.full((sc,), 127, dtype=torch.uint8, device=device),)
+            desc.update(scale_pool=pools[2], scale_pool_bytes=sc)
     cache = skv.skv_cache_alloc(**desc)
     if w.block_size:
         table = torch.from_numpy(np.ascontiguousarray(w.block_table)).to(device)
@@ -39,6 +42,12 @@ def pool_tensors(cache, w):
         outs.append(host)
     rows = w.n_blocks * w.block_size if w.block_size else w.batch * w.max_ctx
     shape = (n_slots, rows, w.n_kv_heads, w.head_dim)
+    if getattr(w, "kv8", False):   # codes of K, codes of V, exponent bytes [slot][row][kv head][K, V]
+        sp, sb = skv.skv_cache_scale_info(cache)
+        host = torch.empty(sb, dtype=torch.uint8)
+        rc = hip.hipMemcpy(ctypes.c_void_p(host.data_ptr()), ctypes.c_void_p(sp), ctypes.c_size_t(sb), 2)
+        assert rc == 0, rc
+        return [o.view(shape) for o in outs] + [host.view(n_slots, rows, w.n_kv_heads, 2)]
     view = {2: torch.int16, 4: torch.int32}[w.elem_bytes]
     return [o.view(view).view(shape) for o in outs]
 
