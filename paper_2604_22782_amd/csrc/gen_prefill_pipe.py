@@ -114,11 +114,12 @@ def generator(nq: int = 2, paged: bool = False):
     TMP = tuple(range(_alloc(16, 2), _next[0]))   # scratch; TMP[4:6] and TMP[12:14] are 64-bit store operands
     NT = 8                                 # weights of the fast stream on their way from v_exp to row sum and packing
     EXPT = tuple(_alloc() for _ in range(NT))
-    L_PREV = _per_q()                      # row sums before the half step of the fast stream
+    P_SUM = _per_q()                       # fast stream: row sums of the half tile
     LAST_V = (_next[0] + 7) // 8 * 8 - 1
     assert LAST_V < 256 and PD < RING and TMP[4] % 2 == 0 and TMP[12] % 2 == 0
 
     A_O, A_Q = 0, 64 * NQ
+    A_QS = 96 * NQ            # bf16: a second copy of Q^T, multiplied by scale x log2(e) (operand of the fast stream)
     # softmax software pipeline: element i gets its fma at step i, its exponential EXP_LAG steps later,
     # and is first read (row sum, 16-bit packing) USE_LAG steps later
     EXP_LAG = 2
@@ -193,16 +194,17 @@ def generator(nq: int = 2, paged: bool = False):
     # ---- softmax of one half tile (vector ALU stream) ------------------------------------------------
     def fast_stream(A: Asm, s_cur: int, p_cur: int):
         """The softmax of a half tile without a running maximum (bf16 weights, tiles below the
-        diagonal): weight = 2^score, straight from the accumulators.  Q was multiplied by
-        scale x log2(e) when it was loaded, so the accumulators hold the exponents; bf16 has the
-        exponent range of fp32, so no reference point is needed while the row sums stay inside
-        [2^-64, 2^64] -- half_step() checks that after every half tile and leaves for the general
-        stream (running maximum, rescale) otherwise.  The scores stay intact in s_cur (the weights
-        go through EXPT), so the half tile can be redone there.  Per score: v_exp, v_add, half a
-        v_cvt_pk -- the maximum (v_max3 per two scores) and the subtraction (one per score) of the
-        general stream are gone."""
+        diagonal): weight = 2^score, straight from the accumulators.  The fast bodies multiply K with
+        the copy of Q that was multiplied by scale x log2(e) and rounded to bf16 again, so the
+        accumulators hold the exponents; bf16 weights have the exponent range of fp32, so no
+        reference point is needed for moderate scores.  half_step() checks after every half tile
+        that each lane's sum of the half tile lies in [2^-40, 2^14] (scores between about -40 and
+        +10 in log2 units, where the second rounding of Q moves a score by a few thousandths) and
+        otherwise leaves for the general stream, which recomputes the scores from the caller's Q and
+        scales them in fp32.  Per score: v_exp, v_add, half a v_cvt_pk -- the maximum (v_max3 per two
+        scores) and the multiply-subtract (one per score) of the general stream are gone."""
         assert A.dt == "bf16"
-        o = [f"v_mov_b32_e32 {vr(L_PREV[q])}, {vr(L_SUM[q])}" for q in range(NQ)]
+        o = []
         S = [[s_cur + 16 * q + r for r in range(16)] for q in range(NQ)]
         elems = [(i % NQ, i // NQ) for i in range(NEL)]
         lag = 4
@@ -214,7 +216,10 @@ def generator(nq: int = 2, paged: bool = False):
             if i >= lag:
                 j = i - lag
                 q, r = elems[j]
-                o.append(f"v_add_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}, {vr(EXPT[j % NT])}")
+                if r == 0:
+                    o.append(f"v_mov_b32_e32 {vr(P_SUM[q])}, {vr(EXPT[j % NT])}")
+                else:
+                    o.append(f"v_add_f32_e32 {vr(P_SUM[q])}, {vr(P_SUM[q])}, {vr(EXPT[j % NT])}")
                 if r % 2 == 1:      # its partner (q, r - 1) was element j - NQ
                     o.append(f"v_cvt_pk_bf16_f32 {vr(p_cur + 8 * q + r // 2)}, {vr(EXPT[(j - NQ) % NT])}, {vr(EXPT[j % NT])}")
         return o
@@ -260,7 +265,7 @@ def generator(nq: int = 2, paged: bool = False):
             o.append(f"v_cmp_lt_f32_e32 vcc, %[thr], {vr(DIFF[0])}")
         # one entry: nothing may be scheduled between the branch and the label its target returns to
         o.append(f"s_cbranch_vccnz L_RESC_{tagid}_%=\nL_RET_{tagid}_%=:")
-        # weights 2^(s - m) (s already in log2 units: Q was scaled at load), their row sums and their 16-bit form, software-pipelined element by
+        # weights 2^(cs s - cs m), their row sums and their 16-bit form, software-pipelined element by
         # element so that the slow transcendental instructions are spread evenly between the MFMAs
         # (a run of them would leave the matrix cores waiting for the in-order instruction stream).
         # A v_exp result is first read two instructions later; v_dot2 would sum the rounded pairs in one
@@ -278,7 +283,7 @@ def generator(nq: int = 2, paged: bool = False):
         for i in range(NEL + USE_LAG):
             if i < NEL:
                 q, r = elems[i]
-                o.append(f"v_add_f32_e32 {vr(S[q][r])}, {vr(NEG_MC[q])}, {vr(S[q][r])}")
+                o.append(f"v_fma_f32 {vr(S[q][r])}, {vr(S[q][r])}, %[cs], {vr(NEG_MC[q])}")
             if EXP_LAG <= i < NEL + EXP_LAG:
                 q, r = elems[i - EXP_LAG]
                 o.append(f"v_exp_f32_e32 {vr(S[q][r])}, {vr(S[q][r])}")
@@ -299,11 +304,13 @@ def generator(nq: int = 2, paged: bool = False):
         for q in range(NQ):
             A.e(f"v_sub_f32_e32 {vr(ALPHA[q])}, {vr(M_RUN[q])}, {vr(M_NEW[q])}")
         for q in range(NQ):
-            A.e(f"v_mov_b32_e32 {vr(M_RUN[q])}, {vr(M_NEW[q])}")
+            A.e(f"v_mul_f32_e32 {vr(ALPHA[q])}, %[cs], {vr(ALPHA[q])}")
         for q in range(NQ):
             A.e(f"v_exp_f32_e32 {vr(ALPHA[q])}, {vr(ALPHA[q])}")
         for q in range(NQ):
-            A.e(f"v_mul_f32_e32 {vr(NEG_MC[q])}, -1.0, {vr(M_NEW[q])}")
+            A.e(f"v_mov_b32_e32 {vr(M_RUN[q])}, {vr(M_NEW[q])}")
+        for q in range(NQ):
+            A.e(f"v_mul_f32_e32 {vr(NEG_MC[q])}, {sr(S_NCS)}, {vr(M_NEW[q])}")
         for q in range(NQ):  # >= 4 instructions after the exponentials
             A.e(f"v_mul_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}, {vr(ALPHA[q])}")
         A.e(f"s_mov_b32 {sr(S_FLAG)}, 1")
@@ -343,7 +350,8 @@ def generator(nq: int = 2, paged: bool = False):
 
     def half_step(A: Asm, hs: int, qk, pv, sm, nxt, extra, tagid: str, cold=False, publish=False):
         """One half step.
-        qk  = (K address register, key block, S destination base) or None
+        qk  = (K address register, key block, S destination base[, scaled]) or None; scaled: multiply with
+              the copy of Q^T that carries scale x log2(e) (fast bodies)
         pv  = (V address register, key block, P source base) or None
         sm  = (S source base, P destination base, masked[, fast]) or None; fast: the stream without a
               running maximum (fast_stream), followed by the range check of the row sums
@@ -417,7 +425,8 @@ def generator(nq: int = 2, paged: bool = False):
             if kind == "qk":
                 s_dst = qk[2] + 16 * q
                 c_in = "0" if g == 0 else vr(s_dst, 16)
-                A.e(f"v_mfma_f32_32x32x16_{A.dt} {vr(s_dst, 16)}, {vr(ko, 4)}, {ar(A_Q + 32 * q + 4 * g, 4)}, {c_in}")
+                a_q = A_QS if (len(qk) > 3 and qk[3]) else A_Q
+                A.e(f"v_mfma_f32_32x32x16_{A.dt} {vr(s_dst, 16)}, {vr(ko, 4)}, {ar(a_q + 32 * q + 4 * g, 4)}, {c_in}")
             else:
                 x, db = g // 4, g % 4
                 p_src = pv[2] + 8 * q + 4 * x
@@ -426,18 +435,21 @@ def generator(nq: int = 2, paged: bool = False):
             for ins in gaps[si]:
                 A.e(ins)
         if fast:
-            # every row sum inside [2^-64, 2^64]?  One unsigned compare per row block: the bit pattern of
-            # a positive float minus that of 2^-64 is below that of 2^64 minus that of 2^-64 exactly then
-            # (smaller sums wrap around, infinities and NaNs are above).  Otherwise redo the half tile
-            # with a running maximum and stay with the general stream (out of line, never returns).
+            # every lane's sum of the half tile inside [2^-40, 2^14]?  One unsigned compare per row block:
+            # the bit pattern of a positive float minus that of 2^-40 is at most that of 2^14 minus that of
+            # 2^-40 exactly then (smaller sums wrap around, infinities and NaNs are above).  Otherwise the
+            # wave leaves for the general stream (out of line, never returns); else the sums join the
+            # running row sums.
             for q in range(NQ):
-                A.e(f"v_subrev_u32_e32 {vr(TMP[q])}, 0x1f800000, {vr(L_SUM[q])}")
-            A.e(f"v_cmp_lt_u32_e32 vcc, 0x40000000, {vr(TMP[0])}")
+                A.e(f"v_subrev_u32_e32 {vr(TMP[q])}, 0x2b800000, {vr(P_SUM[q])}")
+            A.e(f"v_cmp_lt_u32_e32 vcc, 0x1b000000, {vr(TMP[0])}")
             for q in range(1, NQ):
                 A.e(f"s_mov_b64 {sr(S_CMP, 2)}, vcc")
-                A.e(f"v_cmp_lt_u32_e32 vcc, 0x40000000, {vr(TMP[q])}")
+                A.e(f"v_cmp_lt_u32_e32 vcc, 0x1b000000, {vr(TMP[q])}")
                 A.e(f"s_or_b64 vcc, vcc, {sr(S_CMP, 2)}")
             A.e(f"s_cbranch_vccnz L_FALL_{tagid}_%=")
+            for q in range(NQ):
+                A.e(f"v_add_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}, {vr(P_SUM[q])}")
         elif sm:
             A.e(f"s_cmp_lg_u32 {sr(S_FLAG)}, 0")
             A.e(f"s_cbranch_scc1 L_RESO_{tagid}_%=")
@@ -566,32 +578,52 @@ def generator(nq: int = 2, paged: bool = False):
         outstanding LDS reads and loads agree at these points)."""
         A.reset_lds(pending_reads(0))
         rotate_addresses(A)
-        half_step(A, 0, qk=(KA_CUR, 1, SB), pv=(VA_PRV, 1, PB), sm=(SA, PA, masked, fast),
+        half_step(A, 0, qk=(KA_CUR, 1, SB, fast), pv=(VA_PRV, 1, PB), sm=(SA, PA, masked, fast),
                   nxt=((KA_NXT, 0), (VA_CUR, 0)), extra=None, tagid=name + "0", publish=True)
         if entries:
             A.e(f"L_ENTRY_{name}1_%=:")
-        half_step(A, 1, qk=(KA_NXT, 0, SA), pv=(VA_CUR, 0, PA), sm=(SB, PB, masked, fast),
+        half_step(A, 1, qk=(KA_NXT, 0, SA, fast), pv=(VA_CUR, 0, PA), sm=(SB, PB, masked, fast),
                   nxt=((KA_NXT, 1), (VA_CUR, 1)), extra=staging_ops(name), tagid=name + "1")
         if entries:
             A.e(f"L_TAIL_{name}_%=:")
         assert A.lds[-3 * PD:] == pending_reads(2), A.lds[-6:]
 
 
-    def fallback_block(A: Asm, tagid: str, s_cur: int, p_cur: int, resume: str):
-        """Out of line, reached from the range check of the fast stream's half step `tagid`: a row sum
-        left [2^-64, 2^64] (scores far above or below zero).  The scores of the half tile are still in
-        s_cur: put the row sums back, give the rows a running maximum (0, the reference point the fast
-        stream used, if the row already has weight; none yet otherwise), redo the softmax of the half
-        tile with the general stream and continue in the general loop at `resume`."""
+    def recompute_scores(A: Asm, addr: int, kb: int, s_dst: int):
+        """S^T of key block kb of the tile at LDS address `addr` once more, from the caller's Q^T (the
+        fast bodies multiply with its scaled copy).  Used where a wave passes from the fast bodies to
+        the general ones; the operands go through TMP, not through the rings, which already hold
+        operands of the next half step.  The reads are not entered in the generator's count of LDS
+        operations: they are complete when the block ends, so every later wait still covers what it
+        is meant to cover."""
+        for g in range(8):
+            t = TMP[4 * (g % 2)]
+            step = 256 * (g // 2) + 32 * (g % 2)
+            A.e(f"ds_read_b128 {vr(t, 4)}, {vr(addr)} offset:{kb * 8 * CHUNK + step}")
+            A.e("s_waitcnt lgkmcnt(0)")
+            for q in range(NQ):
+                dst = s_dst + 16 * q
+                c_in = "0" if g == 0 else vr(dst, 16)
+                A.e(f"v_mfma_f32_32x32x16_{A.dt} {vr(dst, 16)}, {vr(t, 4)}, {ar(A_Q + 32 * q + 4 * g, 4)}, {c_in}")
+        for _ in range(3):                    # the results are read by the vector ALU next
+            A.e("s_nop 7")
+
+
+    def fallback_block(A: Asm, tagid: str, cur, nxt, p_cur: int, resume: str):
+        """Out of line, reached from the range check of the fast stream's half step `tagid`: the weights
+        of the half tile left the range in which the fast stream is used.  cur, nxt = (K address
+        register, key block, S base) of this half tile and of the next one, whose scores the half step
+        has just formed with the scaled Q: both are formed again from the caller's Q.  The rows get a
+        running maximum (0, the reference point the fast stream used, if the row already has weight;
+        none yet otherwise), the softmax of the half tile is redone with the general stream (the row
+        sums do not contain this half tile yet) and the wave continues in the general loop at `resume`."""
         x = "x" + tagid[-1]
         A.e(f"L_FALL_{tagid}_%=:")
         A.e("s_nop 7")                        # the MFMAs issued last retire before anything below
         A.e("s_nop 7")
         for q in range(NQ):
-            A.e(f"v_mov_b32_e32 {vr(L_SUM[q])}, {vr(L_PREV[q])}")
-        for q in range(NQ):
-            A.e(f"v_mov_b32_e32 {vr(T_MAX[q])}, {vr(L_PREV[q])}")
-            A.e(f"v_mov_b32_e32 {vr(T_MAX2[q])}, {vr(L_PREV[q])}")
+            A.e(f"v_mov_b32_e32 {vr(T_MAX[q])}, {vr(L_SUM[q])}")
+            A.e(f"v_mov_b32_e32 {vr(T_MAX2[q])}, {vr(L_SUM[q])}")
         A.e("s_nop 1")
         for q in range(NQ):
             A.e(f"v_permlane32_swap_b32_e32 {vr(T_MAX[q])}, {vr(T_MAX2[q])}")
@@ -601,7 +633,9 @@ def generator(nq: int = 2, paged: bool = False):
         for q in range(NQ):
             A.e(f"v_cmp_eq_f32_e32 vcc, 0, {vr(T_MAX[q])}")
             A.e(f"v_cndmask_b32_e32 {vr(M_RUN[q])}, 0, {vr(NEG_INF)}, vcc")
-        for ins in softmax_stream(A, s_cur, p_cur, False, x):
+        recompute_scores(A, *cur)
+        recompute_scores(A, *nxt)
+        for ins in softmax_stream(A, cur[2], p_cur, False, x):
             A.e(ins)
         A.e(f"s_cmp_lg_u32 {sr(S_FLAG)}, 0")
         A.e(f"s_cbranch_scc1 L_RESO_{x}_%=")
@@ -660,6 +694,7 @@ def generator(nq: int = 2, paged: bool = False):
 
         A.c("lane constants")
         e(f"s_mov_b32 {sr(S_ONES)}, 0x{ones:08x}")
+        e(f"s_xor_b32 {sr(S_NCS)}, %[cs], 0x80000000")
         e(f"s_mov_b32 {sr(S_NK1)}, %[nk1]")
         e(f"v_and_b32_e32 {vr(LANE)}, 63, %[tid]")
         e(f"v_and_b32_e32 {vr(COL)}, 31, {vr(LANE)}")
@@ -806,37 +841,23 @@ def generator(nq: int = 2, paged: bool = False):
         for i in range(full):
             e(f"ds_write_b128 {vr(TMP[0])}, {vr(PB, 4)} offset:{16 * THREADS * i}")
         e(f"ds_write_b128 {vr(TMP[1])}, {vr(PB, 4)} offset:{16 * THREADS * full}")
-        A.c("Q has landed once only the tile loads are outstanding: multiply it by scale x log2(e) and round it to")
-        A.c("16 bits again, so that the MFMAs deliver the exponents of the weights (runs while tiles 0..2 are in flight)")
-        e(f"s_waitcnt vmcnt({6 * CPW + TBL})")
-        for base in range(0, 32 * NQ, 4):
-            regs = [A_Q + base + k for k in range(4)]
-            for k, a in enumerate(regs):
-                e(f"v_accvgpr_read_b32 {vr(TMP[k])}, {ar(a)}")
-            if dt == "bf16":
+        if dt == "bf16":
+            A.c("Q has landed once only the tile loads are outstanding: a second copy, multiplied by scale x log2(e)")
+            A.c("and rounded to bf16 again, for the fast bodies (runs while tiles 0..2 are in flight)")
+            e(f"s_waitcnt vmcnt({6 * CPW + TBL})")
+            for base in range(0, 32 * NQ, 4):
+                for k in range(4):
+                    e(f"v_accvgpr_read_b32 {vr(TMP[k])}, {ar(A_Q + base + k)}")
                 for k in range(4):
                     e(f"v_lshlrev_b32_e32 {vr(TMP[4 + k])}, 16, {vr(TMP[k])}")
                 for k in range(4):
                     e(f"v_and_b32_e32 {vr(TMP[k])}, 0xffff0000, {vr(TMP[k])}")
-            else:
-                for k in range(4):
-                    e(f"v_cvt_f32_f16_e32 {vr(TMP[4 + k])}, {vr(TMP[k])}")
-                for k in range(4):
-                    e(f"v_lshrrev_b32_e32 {vr(TMP[k])}, 16, {vr(TMP[k])}")
-                for k in range(4):
-                    e(f"v_cvt_f32_f16_e32 {vr(TMP[k])}, {vr(TMP[k])}")
-            for k in range(8):
-                e(f"v_mul_f32_e32 {vr(TMP[k])}, %[cs], {vr(TMP[k])}")
-            if dt == "bf16":
+                for k in range(8):
+                    e(f"v_mul_f32_e32 {vr(TMP[k])}, %[cs], {vr(TMP[k])}")
                 for k in range(4):
                     e(f"v_cvt_pk_bf16_f32 {vr(TMP[k])}, {vr(TMP[4 + k])}, {vr(TMP[k])}")
-            else:
-                for k in range(8):
-                    e(f"v_cvt_f16_f32_e32 {vr(TMP[k])}, {vr(TMP[k])}")
                 for k in range(4):
-                    e(f"v_pack_b32_f16 {vr(TMP[k])}, {vr(TMP[4 + k])}, {vr(TMP[k])}")
-            for k, a in enumerate(regs):
-                e(f"v_accvgpr_write_b32 {ar(a)}, {vr(TMP[k])}")
+                    e(f"v_accvgpr_write_b32 {ar(A_QS + base + k)}, {vr(TMP[k])}")
         A.c("tile 0 has landed once at most the newest loads (tiles 1, 2) are outstanding")
         e(f"s_waitcnt vmcnt({4 * CPW + TBL}) lgkmcnt(0)")
         e("s_barrier")
@@ -845,7 +866,7 @@ def generator(nq: int = 2, paged: bool = False):
 
         A.c("S^T of half tile 0")
         A.reset_lds([])
-        half_step(A, -1, qk=(KA_NXT, 0, SA), pv=None, sm=None, nxt=((KA_NXT, 1), (VA_CUR, 1)), extra=[],
+        half_step(A, -1, qk=(KA_NXT, 0, SA, dt == "bf16"), pv=None, sm=None, nxt=((KA_NXT, 1), (VA_CUR, 1)), extra=[],
                   tagid="pro", cold=True)
 
         n_pro = len(A.lines)
@@ -861,6 +882,10 @@ def generator(nq: int = 2, paged: bool = False):
             e(f"s_add_u32 {sr(S_T)}, {sr(S_T)}, 1")
             e("s_branch L_FAST_%=")
             e("L_FAST_END_%=:")
+            A.c("the scores of the next half tile were formed with the scaled Q: once more from the caller's")
+            for _ in range(2):
+                e("s_nop 7")
+            recompute_scores(A, KA_NXT, 0, SA)
             A.c("rows that went through the fast stream have weight relative to the reference point 0")
             e(f"s_cmp_eq_u32 {sr(S_T)}, 0")
             e("s_cbranch_scc1 L_FULL_END_%=")
@@ -978,8 +1003,8 @@ def generator(nq: int = 2, paged: bool = False):
             rescale_blocks(A, name)
         if fast:
             A.c("out-of-line: a row sum of the fast stream left its range")
-            fallback_block(A, "f0", SA, PA, "L_ENTRY_g1_%=")
-            fallback_block(A, "f1", SB, PB, "L_TAIL_g_%=")
+            fallback_block(A, "f0", (KA_CUR, 0, SA), (KA_CUR, 1, SB), PA, "L_ENTRY_g1_%=")
+            fallback_block(A, "f1", (KA_CUR, 1, SB), (KA_NXT, 0, SA), PB, "L_TAIL_g_%=")
             A.e("s_branch L_END_%=")
         if PAGED:
             A.e("s_branch L_END_%=")
@@ -990,7 +1015,7 @@ def generator(nq: int = 2, paged: bool = False):
 
 
     def clobbers() -> str:
-        n_acc = 96 * NQ
+        n_acc = 128 * NQ
         regs = [f"v{i}" for i in range(FIRST_V, LAST_V + 1)] + [f"a{i}" for i in range(n_acc)]
         regs += [f"s{i}" for i in range(FIRST_S, LAST_S + 1)]
         regs += ["vcc", "scc", "memory"]  # m0 is written too; nothing follows the statement

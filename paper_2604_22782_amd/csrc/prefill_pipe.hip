@@ -109,7 +109,7 @@ __global__ __launch_bounds__(512 / NQ, 1) void prefill_pipe_kernel(AttnArgs a, i
     const uint32_t q_row_stride = (uint32_t)a.n_q_heads * kD * 2;
     const uint32_t rv_clamp = active ? (uint32_t)min(rows_valid, kRowsPerWave) : 1u;
     const float cs = a.scale_log2e;
-    const float thr = 8.0f; // lazy rescale: a row maximum may grow by 2^8 in weight before O is rescaled (scores are in log2 units)
+    const float thr = fminf(8.0f / cs, 3.0e38f); // finite: the first tile (maximum -inf so far) must pass it
 
     const uint32_t lds_base = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)lds);
     const uint32_t tid = threadIdx.x;

@@ -297,3 +297,52 @@ def test_paged_prefill_with_larger_blocks(block):
             assert (got[b, nq:] == 7.0).all()
     assert skv.skv_cache_device_faults(cache) == 0
     cache.free()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("kind", ["high", "low", "jump_even_half_tile", "jump_odd_half_tile", "sink_then_low"])
+def test_prefill_fast_stream_hands_over_on_extreme_scores(kind):
+    """The bf16 pre-fill kernel computes the weights of tiles below the diagonal without a running
+    maximum as long as the row sums stay inside [2^-64, 2^64], and otherwise redoes the half tile
+    with one and continues in the general stream.  Scores far above that range from the first tile
+    on, far below it, jumping up in the first or in the second half of a tile (the two ways out), and
+    a row whose weight sits in the first key while everything after it is far below."""
+    B, S, Hq, Hkv, D = 2, 900, 2, 1, 128
+    route = [0, 0]
+    w = _small("bf16", Hq, Hkv, D, B, [S, 600], route, False, seed=321)
+    g = torch.Generator().manual_seed(17)
+    q = torch.randn(B, S, Hq, D, generator=g)
+    k = torch.randn(B, S, Hkv, D, generator=g)
+    v = torch.randn(B, S, Hkv, D, generator=g)
+    pos = torch.arange(S).view(1, S, 1, 1)
+    if kind == "high":
+        k = k * 20.0                                    # scores of +-100 in log2 units
+    elif kind == "low":
+        u = torch.randn(D, generator=g)
+        q = u.expand(B, S, Hq, D) + 0.05 * q            # every score is about -8 |u|^2 / sqrt(D)
+        k = -8.0 * u.expand(B, S, Hkv, D) + 0.05 * k
+    elif kind.startswith("jump"):
+        at = 320 if kind == "jump_even_half_tile" else 352
+        k = torch.where(pos >= at, k * 30.0, k)
+    else:
+        u = torch.randn(D, generator=g)
+        q = u.expand(B, S, Hq, D) + 0.05 * q
+        k = torch.where(pos == 0, 0.0 * k, -8.0 * u.expand(B, S, Hkv, D) + 0.05 * k)
+    q, k, v = q.to(torch.bfloat16), k.to(torch.bfloat16), v.to(torch.bfloat16)
+    lens = np.array([S, 600], dtype=np.int32)
+    cache, _ = H.alloc_cache(w)
+    d_lens = torch.from_numpy(lens).cuda()
+    zeros = torch.zeros(B, dtype=torch.int32, device="cuda")
+    skv.skv_kv_append(cache, 0, k.cuda(), v.cuda(), zeros, d_lens, S)
+    oc = O.Cache(route, B, w.max_ctx, Hkv, D, np.uint16)
+    oc.append(0, gen.to_f64(k), gen.to_f64(v), gen.to_bits(k), gen.to_bits(v), np.zeros(B, dtype=np.int64), lens)
+    out = torch.full_like(q, 7.0, device="cuda")
+    skv.skv_attn_prefill(cache, 1, q.cuda(), out, d_lens, d_lens, S, S, w.scale)
+    assert skv.skv_last_kernel_name() == "prefill_pipe_kernel"
+    want = O.prefill(oc, 1, gen.to_f64(q), lens, lens, w.scale)
+    got = gen.to_f64(out)
+    for b in range(B):
+        err = float(np.abs(got[b, : lens[b]] - want[b, : lens[b]]).max())
+        assert np.isfinite(got[b, : lens[b]]).all() and err <= H.TOL["bf16"], (kind, b, err)
+    assert skv.skv_cache_device_faults(cache) == 0
+    cache.free()
