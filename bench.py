@@ -127,6 +127,8 @@ def run_decode(args, torch, skv, H, w, steps, warmup, headline=False):
     t0 = time.perf_counter()
     # the fill's temporaries grow with the row width: keep them at the size they have for 8 kv heads
     chunk = max(1 << 14, args.fill_chunk_tokens * 1024 // (w.n_kv_heads * w.head_dim))
+    if skv.skv_cache_info(cache)[3] * 2 > 128 << 30:      # little memory is left beside the cache
+        chunk = min(chunk, 1 << 15)
     H.fill_by_append(cache, w, lens=w.kv_lens - 1, chunk_tokens=chunk)
     log(f"[bench] cache of {skv.skv_cache_info(cache)[3] * 2 / 2**30:.1f} GiB filled through skv_kv_append in {time.perf_counter() - t0:.1f} s")
     ctx = int(w.kv_lens.max())

@@ -154,6 +154,21 @@ skv_status_t skv_cache_scale_info(const skv_cache_t *cache, void **scale_pool_de
 skv_status_t skv_cache_set_block_table(skv_cache_t *cache, const int32_t *table_device,
                                        int32_t max_blocks_per_seq);
 
+/* Temporal eviction (the paper's Sec. 5 names the composition of depth-wise sharing with "temporal
+ * eviction methods" as open; this library's reading is a sliding window with sinks): of the
+ * kv_lens[b] cached positions of sequence b only [0, sink_len[b]) and [first_pos[b], kv_lens[b])
+ * survive; the positions between were dropped from EVERY slot (one dropped block frees its rows in
+ * |S| slots instead of L), their rows and, for a paged cache, their block-table entries are never
+ * read again and may hold anything.  sink_len, first_pos: device int32[batch], borrowed until they
+ * are replaced; both NULL switches eviction off.  sink_len[b] must be a multiple of 32, first_pos[b]
+ * a multiple of the block size (any value for a contiguous cache), 0 <= sink_len[b] <= first_pos[b]
+ * <= kv_lens[b]; other values set SKV_FAULT_KV_LEN and zero the sequence's output.
+ * While eviction is on, skv_attn_decode / _range / _static attend over the surviving positions
+ * only, and their max_kv_len bounds the number of SURVIVING positions per sequence (kv_lens[b]
+ * itself is bounded by the capacity); skv_attn_prefill returns SKV_ERR_UNSUPPORTED, and so does
+ * decode on a float32 cache or with head_dim 256.  Appends are unaffected. */
+skv_status_t skv_cache_set_eviction(skv_cache_t *cache, const int32_t *sink_len, const int32_t *first_pos);
+
 /* Reads and clears the device fault word (synchronises the device). */
 skv_status_t skv_cache_device_faults(skv_cache_t *cache, uint32_t *faults);
 

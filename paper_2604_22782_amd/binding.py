@@ -7,7 +7,7 @@ import torch
 
 __all__ = [
     "SkvError", "Cache", "lib", "SKV_F32", "SKV_F16", "SKV_BF16", "SKV_BF16_KV8", "SKV_F16_KV8", "STATUS", "dtype_code",
-    "skv_cache_pool_bytes", "skv_cache_scale_info",
+    "skv_cache_pool_bytes", "skv_cache_scale_info", "skv_cache_set_eviction",
     "skv_route_from_strategy", "skv_route_validate", "skv_cache_bytes", "skv_cache_alloc",
     "skv_cache_free", "skv_cache_info", "skv_cache_slot_of_layer", "skv_cache_set_block_table",
     "skv_cache_device_faults", "skv_kv_append", "skv_kv_project_append", "skv_kv_project_workspace_bytes", "skv_decode_workspace_bytes", "skv_attn_decode",
@@ -190,6 +190,14 @@ def skv_cache_set_block_table(cache: Cache, table: torch.Tensor):
     _check(lib().skv_cache_set_block_table(cache.handle, _ptr(table), table.shape[1]),
            "skv_cache_set_block_table")
     cache._keep.append(table)
+
+
+def skv_cache_set_eviction(cache: Cache, sink_len, first_pos):
+    """sink_len, first_pos: int32 device tensors [batch], or both None to switch eviction off."""
+    if sink_len is not None:
+        assert sink_len.dtype == torch.int32 and first_pos.dtype == torch.int32
+    _check(lib().skv_cache_set_eviction(cache.handle, _ptr(sink_len), _ptr(first_pos)), "skv_cache_set_eviction")
+    cache._evict = (sink_len, first_pos)
 
 
 def skv_cache_device_faults(cache: Cache) -> int:

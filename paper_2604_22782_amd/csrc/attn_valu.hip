@@ -242,7 +242,8 @@ __global__ __launch_bounds__(256) void split_merge_kernel(AttnArgs a, int D) {
     const int qd = threadIdx.x % quads, sg = threadIdx.x / quads;
     const int64_t rh = blockIdx.x;      // row * n_q_heads + head   (decode: row = sequence)
     const int b = (int)(rh / a.n_q_heads);
-    const int kv_end = a.kv_lens[b];
+    int sink, gap;
+    const int kv_end = a.max_q == 1 ? decode_keys(a, b, sink, gap) : a.kv_lens[b];
     if (kv_end < 1 || kv_end > a.max_kv_len) return; // the attention kernel wrote zeros
     const int ns = (kv_end + a.keys_per_split - 1) / a.keys_per_split;
     if (ns == 1) return; // the attention kernel already wrote the final result

@@ -101,11 +101,14 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
     const int g = lane >> 4; // MFMA k-group
     const int hkv = a.cache.n_kv_heads;
 
+    auto keys_of = [&](int bb, int &sink, int &gap) -> int { return decode_keys(a, bb, sink, gap); };
+
     // One work item = (sequence, kv head, key split).
     auto process_item = [&](const int b, const int kvh, const int split) {
     const int head0 = kvh * G;
-    const int kv_end = a.kv_lens[b];
-    if (kv_end < 1 || kv_end > a.max_kv_len) { // lengths the host promised not to pass
+    int sink, gap;
+    const int kv_end = keys_of(b, sink, gap);
+    if (kv_end < 1) { // lengths the host promised not to pass
         if (threadIdx.x == 0 && split == 0 && kvh == 0) atomicOr(a.cache.faults, (uint32_t)SKV_FAULT_KV_LEN);
         if (split == 0)
             for (int e = threadIdx.x; e < G * D; e += blockDim.x)
@@ -147,17 +150,19 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
     auto blocks_of = [&](int j0, int32_t *blk) {
         if (paged) {
             const int32_t *row = a.cache.block_table + (int64_t)b * a.cache.max_blocks_per_seq;
-            const int first = j0 >> shift;
+            const int first = (j0 + (j0 >= sink ? gap : 0)) >> shift;
 #pragma unroll
             for (int u = 0; u < 4; ++u) blk[u] = row[min(first + u, a.cache.max_blocks_per_seq - 1)];
         }
     };
     // Row number of this lane's key in load t of the tile at j0 (-1 = beyond the range / bad block id).
     auto row_of = [&](int j0, const int32_t *blk, int t) -> int32_t {
-        const int key = j0 + RPL * t + lrow;
-        if (key >= k_end) return -1;
+        const int c = j0 + RPL * t + lrow;
+        if (c >= k_end) return -1;
+        const int skip = j0 >= sink ? gap : 0;        // the whole tile lies on one side of the gap
+        const int key = c + skip;                     // position of the key
         if (!paged) return b * a.cache.max_ctx + key;
-        const int u = (key - j0) >> shift; // 0..3 (0 when a block holds 32 keys or more)
+        const int u = (key >> shift) - ((j0 + skip) >> shift); // 0..3 (0 when a block holds 32 keys or more)
         const int32_t id = u == 0 ? blk[0] : u == 1 ? blk[1] : u == 2 ? blk[2] : blk[3];
         if ((uint32_t)id >= (uint32_t)a.cache.n_blocks) {
             if (lcol == 0) atomicOr(a.cache.faults, (uint32_t)SKV_FAULT_BLOCK_ID);
@@ -380,8 +385,9 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
         for (int i = 0; i < per; ++i) {
             const int bb = lane * per + i;
             if (bb < a.batch) {
-                const int len = a.kv_lens[bb];
-                const bool valid = len >= 1 && len <= a.max_kv_len;
+                int sk, gp;
+                const int len = keys_of(bb, sk, gp);
+                const bool valid = len >= 1;
                 const int rem = valid ? len % kps : 0;
                 const bool has = !valid || rem > 0;
                 cnt_full += valid ? len / kps : 0;
@@ -404,8 +410,9 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
         for (int i = 0; i < per; ++i) {
             const int bb = lane * per + i;
             if (bb < a.batch) {
-                const int len = a.kv_lens[bb];
-                run_f += (len >= 1 && len <= a.max_kv_len) ? len / kps : 0;
+                int sk, gp;
+                const int len = keys_of(bb, sk, gp);
+                run_f += len >= 1 ? len / kps : 0;
                 s_prefix[bb + 1] = run_f;
                 if (s_rem[bb] >= 0) s_order[run_r++] = (unsigned short)bb;
             }
@@ -456,8 +463,9 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
             split = j - s_prefix[lo];
         } else {
             seq = s_order[j - total_full];
-            const int len = a.kv_lens[seq];
-            split = (len >= 1 && len <= a.max_kv_len) ? len / kps : 0; // the partial split is the last one
+            int sk, gp;
+            const int len = keys_of(seq, sk, gp);
+            split = len >= 1 ? len / kps : 0; // the partial split is the last one
         }
         // all lanes hold the same values; say so to the compiler (scalar registers, scalar loads)
         process_item(__builtin_amdgcn_readfirstlane(seq), __builtin_amdgcn_readfirstlane(kvh),

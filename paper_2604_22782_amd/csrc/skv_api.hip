@@ -22,6 +22,7 @@ struct skv_cache {
     size_t scale_pool_bytes = 0; // 8-bit slots: uint16 per (row, kv head), all slots
     size_t slot_bytes = 0;       // bytes of one slot inside a pool
     const int32_t *block_table = nullptr;
+    const int32_t *evict_sink = nullptr, *evict_first = nullptr; // borrowed device arrays, both or neither
     int32_t max_blocks_per_seq = 0;
     int32_t block_shift = 0;
     uint32_t *faults = nullptr;  // device word
@@ -333,6 +334,13 @@ skv_status_t skv_cache_set_block_table(skv_cache_t *c, const int32_t *table, int
     return SKV_OK;
 }
 
+skv_status_t skv_cache_set_eviction(skv_cache_t *c, const int32_t *sink_len, const int32_t *first_pos) {
+    if (!c || (sink_len == nullptr) != (first_pos == nullptr)) return SKV_ERR_INVALID_ARG;
+    c->evict_sink = sink_len;
+    c->evict_first = first_pos;
+    return SKV_OK;
+}
+
 skv_status_t skv_cache_device_faults(skv_cache_t *c, uint32_t *faults) {
     if (!c || !faults) return SKV_ERR_INVALID_ARG;
     hipError_t e = hipDeviceSynchronize();
@@ -447,6 +455,9 @@ skv_status_t skv_attn_decode_range(skv_cache_t *c, int32_t layer, int32_t seq_be
         if (view.scales != nullptr) view.scales += (size_t)seq_begin * view.max_ctx * c->d.n_kv_heads;
     }
 
+    const int g = c->d.n_q_heads / c->d.n_kv_heads;
+    const bool mfma = skv::decode_mfma_supported(c->d.dtype, c->d.head_dim, g);
+    if (c->evict_first != nullptr && !mfma) return SKV_ERR_UNSUPPORTED; // eviction: 16-bit and 8-bit slots only
     skv::AttnArgs a;
     a.lse = nullptr;
     a.cache = view;
@@ -454,6 +465,8 @@ skv_status_t skv_attn_decode_range(skv_cache_t *c, int32_t layer, int32_t seq_be
     a.out = out;
     a.q_lens = nullptr;
     a.kv_lens = kv_lens;
+    a.evict_sink = c->evict_sink ? c->evict_sink + seq_begin : nullptr;
+    a.evict_first = c->evict_first ? c->evict_first + seq_begin : nullptr;
     a.batch = seq_count;
     a.max_q = 1;
     a.n_q_heads = c->d.n_q_heads;
@@ -466,9 +479,8 @@ skv_status_t skv_attn_decode_range(skv_cache_t *c, int32_t layer, int32_t seq_be
     a.part_o = (float *)((char *)workspace + kCounterBytes);
     a.part_ml = a.part_o + (size_t)seq_count * c->d.n_q_heads * a.n_splits * c->d.head_dim;
 
-    const int g = c->d.n_q_heads / c->d.n_kv_heads;
     hipError_t e;
-    if (skv::decode_mfma_supported(c->d.dtype, c->d.head_dim, g))
+    if (mfma)
         e = skv::launch_decode_mfma(a, c->d.dtype, c->d.head_dim, g, (hipStream_t)stream);
     else
         e = skv::launch_attn_valu(a, c->d.dtype, c->d.head_dim, g, (hipStream_t)stream);
@@ -537,10 +549,12 @@ skv_status_t skv_attn_prefill(skv_cache_t *c, int32_t layer, const void *q, void
     if (layer < 0 || layer >= c->d.n_layers || max_q <= 0 || max_kv_len <= 0) return SKV_ERR_INVALID_ARG;
     if (!(scale > 0.f)) return SKV_ERR_INVALID_ARG;
     if (!paged_ready(c)) return SKV_ERR_INVALID_ARG;
+    if (c->evict_first != nullptr) return SKV_ERR_UNSUPPORTED; // pre-fill over an evicted cache is not built
     const skv::SlotView view = view_of(c, c->slot[layer]);
     if (max_kv_len > view.max_ctx) return SKV_ERR_CAPACITY;
 
     skv::AttnArgs a;
+    a.evict_sink = a.evict_first = nullptr;
     a.lse = nullptr;
     a.cache = view;
     a.q = q;
@@ -636,6 +650,7 @@ skv_status_t skv_train_attn_fwd(const void *q, const void *k, const void *v, voi
     // the source layer's activations are laid out exactly like one contiguous cache slot of
     // capacity seq, so the pre-fill kernels run on them unchanged
     skv::AttnArgs a;
+    a.evict_sink = a.evict_first = nullptr;
     a.cache.k = k;
     a.cache.v = v;
     a.cache.scales = nullptr;

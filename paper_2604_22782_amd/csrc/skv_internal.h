@@ -68,6 +68,8 @@ struct AttnArgs {
     void *out;              // same
     const int32_t *q_lens;  // nullptr for decode (one row per sequence)
     const int32_t *kv_lens; // [batch]
+    const int32_t *evict_sink;  // decode only, both or neither: positions [evict_sink[b], evict_first[b]) of
+    const int32_t *evict_first; //   sequence b were evicted and are never read
     float *part_o;          // split partials [rows*n_q_heads][n_splits][head_dim]
     float *part_ml;         // [rows*n_q_heads][n_splits][2]  (max, sum)
     int32_t *work_counters; // one device word (256-byte block): next work item of the persistent launch shape
@@ -81,6 +83,25 @@ struct AttnArgs {
     float scale_log2e;      // softmax scale * log2(e)
     float *lse;             // pre-fill only, may be nullptr: [batch][n_q_heads][max_q] log-sum-exp of the scaled scores
 };
+
+// Keys sequence b attends to in a decode call.  Without eviction: positions 0 .. kv_lens[b] - 1.
+// With it the positions [sink, first) are gone; the kernels walk the survivors as one compact range
+// of sink + (kv_lens[b] - first) keys, key c sitting at position c (c < sink) or c + gap with
+// gap = first - sink.  sink is a multiple of the 32-key tile and first a multiple of the block
+// size, so a tile never straddles the gap.  Returns -1 for values the host promised not to pass.
+__device__ __forceinline__ int decode_keys(const AttnArgs &a, int b, int &sink, int &gap) {
+    const int len = a.kv_lens[b];
+    sink = 0;
+    gap = 0;
+    if (a.evict_first != nullptr) {
+        const int s = a.evict_sink[b], f = a.evict_first[b];
+        if (s < 0 || (s & 31) || f < s || f > len) return -1;
+        sink = s;
+        gap = f - s;
+    }
+    const int m = len - gap;
+    return (len >= 1 && m >= 1 && m <= a.max_kv_len && len <= a.cache.max_ctx) ? m : -1;
+}
 
 // Launchers (each returns the hipError_t of its launch).
 hipError_t launch_append(const SlotView &slot, int dtype, const void *k_new, const void *v_new,

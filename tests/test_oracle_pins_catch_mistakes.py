@@ -170,3 +170,30 @@ def test_decoder_oracle_pins_catch(old, new, monkeypatch):
              lambda: pins.test_identity_route_is_a_standard_decoder_built_from_library_routines(True),
              pins.test_a_layer_reads_the_layer_its_route_names_not_the_latest_cache]
     assert _pins_fail(pins, "D", _mutant("decoder_oracle", old, new), tests, monkeypatch), (old, new)
+
+
+QUANT_MISTAKES = [
+    ("return s * (1.0 + m / 8.0) * 2.0 ** (e - 7)", "return s * (1.0 + m / 8.0) * 2.0 ** (e - 8)"),     # exponent bias of the other 8-bit format
+    ("return s * (m / 8.0) * 2.0 ** -6", "return s * (m / 8.0) * 2.0 ** -7"),                            # subnormal scale
+    ("if e == 0xF and m == 0x7:", "if e == 0xF:"),                                                        # a whole binade lost to NaN
+    ("e = k - 9 if f <= 0.875 else k - 8", "e = k - 9 if f < 0.875 else k - 8"),                          # 448 itself gets the larger scale
+    ("e = k - 9 if f <= 0.875 else k - 8", "e = k - 8"),                                                  # always the larger scale
+    ("e = np.where(f <= 0.875, k - 9, k - 8)", "e = np.where(f <= 0.875, k - 8, k - 7)"),                 # the array form disagrees with the rule
+    ("np.where(lo % 2 == 0, lo, hi)", "hi"),                                                              # ties away from zero
+    ("codes = round_to_e4m3(np.ldexp(flat, -e[:, None]))", "codes = round_to_e4m3(np.ldexp(flat, -e[:, None] - 1))"),   # scaled once too often
+    ("return np.ldexp(E4M3_TABLE[codes], e[..., None])", "return np.ldexp(E4M3_TABLE[codes], e[..., None] + 1)"),       # dequantised with the wrong exponent
+    ("np.concatenate([np.arange(0, sink), np.arange(first, n)])", "np.concatenate([np.arange(0, sink), np.arange(first + 1, n)])"),   # window starts late
+    ("    Ks, Vs = K[positions], V[positions]\n", "    Ks, Vs = K, V\n"),                                  # eviction ignored
+    ("    s = scale * (Ks @ q)\n", "    s = Ks @ q\n"),                                                     # scale dropped
+]
+
+
+@pytest.mark.parametrize("old,new", QUANT_MISTAKES)
+def test_quantisation_and_eviction_oracle_pins_catch(old, new, monkeypatch):
+    from tests import test_kv_quant_oracle_pins as pins
+    tests = [pins.test_e4m3_table_matches_the_format, pins.test_e4m3_table_and_rounding_match_torch_float8,
+             pins.test_ties_go_to_the_even_code, pins.test_scale_exponent_closed_forms,
+             lambda: pins.test_round_trip_error_bounds(0.5), lambda: pins.test_round_trip_error_bounds(300.0),
+             pins.test_identity_on_representable_rows, pins.test_dequantised_values_are_exact_in_bfloat16,
+             pins.test_eviction_reading]
+    assert _pins_fail(pins, "Q", _mutant("kv_quant_oracle", old, new), tests, monkeypatch), (old, new)
