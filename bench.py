@@ -624,6 +624,7 @@ def main():
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--decode-workload", default="llama3_decode", choices=["llama3_decode", "qwen3_paged", "llama2_mha"],
                     help="decode workload of the headline step (default: the one the metric is quoted on)")
+    ap.add_argument("--kv8", action="store_true", help="profiling aid: the headline decode workload over 8-bit slots")
     ap.add_argument("--mha-batch", type=int, default=32, help="batch of the llama2_mha workload when it is the headline")
     ap.add_argument("--fill-chunk-tokens", type=int, default=1 << 19,
                     help="tokens generated per append call while the cache is filled (bounds the temporaries)")
@@ -690,7 +691,11 @@ def main():
         w = configs.llama2_mha_decode(batch=args.mha_batch)
     else:
         w = configs.llama3_decode()
-    dec = run_decode(args, torch, skv, H, w, args.steps, args.warmup, headline=args.decode_workload == "llama3_decode")
+    if args.kv8:
+        w.kv8 = True
+        w.name += "_kv8"
+    dec = run_decode(args, torch, skv, H, w, args.steps, args.warmup,
+                     headline=args.decode_workload == "llama3_decode" and not args.kv8)
     line = {
         "metric": "routed decode attn HBM GB/s (% of peak) + prefill MFMA util %, 1 MI355X",
         "value": dec["value"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

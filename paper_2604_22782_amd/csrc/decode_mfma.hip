@@ -137,8 +137,8 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
     const int lrow = lane / LPR;   // row inside one wave-wide load
     const int lcol = lane % LPR;   // 16-byte piece inside the row
     constexpr int EB = KV8 ? 1 : 2; // bytes per slot element
-    const char *kp = (const char *)a.cache.k + ((int64_t)kvh * D) * EB + lcol * 16;
-    const char *vp = (const char *)a.cache.v + ((int64_t)kvh * D) * EB + lcol * 16;
+    const char *kp = (const char *)a.cache.k + ((int64_t)kvh * D) * EB; // uniform; the lane's part is lane_off
+    const char *vp = (const char *)a.cache.v + ((int64_t)kvh * D) * EB;
     const int64_t row_bytes = (int64_t)hkv * D * EB;
     const uint16_t *sp = KV8 ? a.cache.scales + kvh : nullptr; // 8-bit slots: exponent bytes of K (low) and V (high) per row
 
@@ -155,20 +155,25 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
             for (int u = 0; u < 4; ++u) blk[u] = row[min(first + u, a.cache.max_blocks_per_seq - 1)];
         }
     };
-    // Row number of this lane's key in load t of the tile at j0 (-1 = beyond the range / bad block id).
-    auto row_of = [&](int j0, const int32_t *blk, int t) -> int32_t {
-        const int c = j0 + RPL * t + lrow;
-        if (c >= k_end) return -1;
+    // Load t of the tile at j0 covers RPL consecutive keys, which lie inside one block (blocks hold at
+    // least RPL positions and tiles start on block boundaries): its first row is WAVE-UNIFORM, so the
+    // address of a lane is a scalar base (slot + first row of the load) plus a 32-bit lane offset that
+    // never changes (row inside the load, piece inside the row).  The address arithmetic of the 2 x NL
+    // loads of a tile is then scalar work; per lane only the bound check against k_end is left.
+    const uint32_t lane_off = (uint32_t)(lrow * (int)row_bytes + lcol * 16);
+    auto first_row_of = [&](int j0, const int32_t *blk, int t) -> int64_t { // -1: nothing to load
+        const int c0 = j0 + RPL * t;                  // first key of the load, uniform
+        if (c0 >= k_end) return -1;
         const int skip = j0 >= sink ? gap : 0;        // the whole tile lies on one side of the gap
-        const int key = c + skip;                     // position of the key
-        if (!paged) return b * a.cache.max_ctx + key;
-        const int u = (key >> shift) - ((j0 + skip) >> shift); // 0..3 (0 when a block holds 32 keys or more)
+        const int p0 = c0 + skip;                     // its position
+        if (!paged) return (int64_t)b * a.cache.max_ctx + p0;
+        const int u = (p0 >> shift) - ((j0 + skip) >> shift); // 0..3 (0 when a block holds 32 keys or more)
         const int32_t id = u == 0 ? blk[0] : u == 1 ? blk[1] : u == 2 ? blk[2] : blk[3];
         if ((uint32_t)id >= (uint32_t)a.cache.n_blocks) {
-            if (lcol == 0) atomicOr(a.cache.faults, (uint32_t)SKV_FAULT_BLOCK_ID);
+            if (lane == 0) atomicOr(a.cache.faults, (uint32_t)SKV_FAULT_BLOCK_ID);
             return -1;
         }
-        return (id << shift) + (key & ((1 << shift) - 1));
+        return ((int64_t)id << shift) + (p0 & ((1 << shift) - 1));
     };
     auto issue = [&](int j0, const int32_t *blk, uint4 *kr, uint4 *vr, uint16_t *sr) {
 #pragma unroll
@@ -176,17 +181,19 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
             kr[t] = make_uint4(0, 0, 0, 0);
             vr[t] = make_uint4(0, 0, 0, 0);
             if constexpr (KV8) sr[t] = 0x7f7f; // scale 1 for rows that are not loaded (their codes are zero)
-            const int32_t r = row_of(j0, blk, t);
-            if (r >= 0) {
+            const int64_t r0 = first_row_of(j0, blk, t);
+            if (r0 >= 0 && j0 + RPL * t + lrow < k_end) {
                 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+                const char *kb = kp + r0 * row_bytes, *vb = vp + r0 * row_bytes; // uniform part ...
+                const uint16_t *sb = KV8 ? sp + r0 * hkv : nullptr;
                 if constexpr (kStream) { // "nt" loads: +6..10 % bandwidth on launches far larger than the caches
-                    kr[t] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4 *)(kp + r * row_bytes)));
-                    vr[t] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4 *)(vp + r * row_bytes)));
-                    if constexpr (KV8) sr[t] = __builtin_nontemporal_load(sp + (int64_t)r * hkv);
+                    kr[t] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4 *)(kb + lane_off)));
+                    vr[t] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4 *)(vb + lane_off)));
+                    if constexpr (KV8) sr[t] = __builtin_nontemporal_load(sb + lrow * hkv);
                 } else {
-                    kr[t] = *(const uint4 *)(kp + r * row_bytes);
-                    vr[t] = *(const uint4 *)(vp + r * row_bytes);
-                    if constexpr (KV8) sr[t] = sp[(int64_t)r * hkv];
+                    kr[t] = *(const uint4 *)(kb + lane_off);
+                    vr[t] = *(const uint4 *)(vb + lane_off);
+                    if constexpr (KV8) sr[t] = sb[lrow * hkv];
                 }
             }
         }
@@ -209,8 +216,8 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
         return k_begin + t2 * kTile;
     };
 
-    // Two tiles per wave are in flight from HBM (register sets A and B) while a third is computed
-    // from LDS; the block ids run one more tile ahead.
+    // Two tiles per wave (three over 8-bit slots) are in flight from HBM (register sets A, B, C) while
+    // another is computed from LDS; the block ids run one more tile ahead.
     int32_t blk[4] = {0, 0, 0, 0};
     int tt_issue = wave; // next tile of this wave to request
     auto issue_next = [&](uint4 *kr, uint4 *vr, uint16_t *sr) {
@@ -220,11 +227,16 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
             if (tt_issue < n_tiles) blocks_of(tile_j0(tt_issue), blk);
         }
     };
-    uint4 krA[NL], vrA[NL], krB[NL], vrB[NL];
-    uint16_t srA[KV8 ? NL : 1], srB[KV8 ? NL : 1];
+    // 8-bit slots: a tile is half the bytes and the same arithmetic, so the time a wave spends per byte
+    // on the arithmetic doubles; a third tile in flight (its registers are there: a set is half as
+    // large) keeps the loads ahead of it.
+    constexpr int kSets = 2;
+    uint4 krA[NL], vrA[NL], krB[NL], vrB[NL], krC[kSets > 2 ? NL : 1], vrC[kSets > 2 ? NL : 1];
+    uint16_t srA[KV8 ? NL : 1], srB[KV8 ? NL : 1], srC[KV8 ? NL : 1];
     if (wave < n_tiles) blocks_of(tile_j0(wave), blk);
     issue_next(krA, vrA, srA);
     issue_next(krB, vrB, srB);
+    if constexpr (kSets > 2) issue_next(krC, vrC, srC);
 
     auto process = [&](int tt, uint4 *kr, uint4 *vr, uint16_t *sr) {
         const int j0 = tile_j0(tt);
@@ -310,9 +322,11 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); // reads of this tile before the next tile's writes
         __builtin_amdgcn_wave_barrier();
     };
-    for (int tt = wave; tt < n_tiles; tt += 2 * kWaves) {
+    for (int tt = wave; tt < n_tiles; tt += kSets * kWaves) {
         process(tt, krA, vrA, srA);
         if (tt + kWaves < n_tiles) process(tt + kWaves, krB, vrB, srB);
+        if constexpr (kSets > 2)
+            if (tt + 2 * kWaves < n_tiles) process(tt + 2 * kWaves, krC, vrC, srC);
     }
 
     // ---- merge the four waves through LDS --------------------------------------------------
