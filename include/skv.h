@@ -201,7 +201,7 @@ skv_status_t skv_kv_append(skv_cache_t *cache, int32_t layer, const void *k_new,
  * workspace: device scratch of skv_kv_project_workspace_bytes(cache, max_new, hidden) bytes (0 for
  * large prompts: launches too small to fill the chip -- one decode token per sequence, or a prompt
  * of a few thousand tokens -- split the hidden axis over work groups and keep fp32 partial sums
- * there); may be NULL when that is 0.
+ * there; launches of at most 64 token rows always do); may be NULL when that is 0.
  * SKV_ERR_NOT_OWNER for a layer without a slot (nothing is computed: that is the saving);
  * SKV_ERR_UNSUPPORTED unless the cache is 16-bit, head_dim 64 or 128 and hidden a multiple of 64. */
 skv_status_t skv_kv_project_workspace_bytes(const skv_cache_t *cache, int32_t max_new, int32_t hidden,
@@ -265,7 +265,9 @@ skv_status_t skv_attn_decode_static(skv_cache_t *cache, int32_t layer, const voi
  * kv_lens[b] - q_lens[b] + i and sees cached positions 0..that position of the routed slot.
  * q, out: device [batch][max_q][n_q_heads][head_dim]; rows i >= q_lens[b] are neither read nor
  * written.  q_lens, kv_lens: device int32[batch], 0 <= q_lens[b] <= min(max_q, kv_lens[b]),
- * kv_lens[b] <= max_kv_len. */
+ * kv_lens[b] <= max_kv_len.  A sequence whose lengths break these rules sets SKV_FAULT_KV_LEN and
+ * nothing is written for it, whatever the dtype (skv_attn_decode zero-fills the output row of such a
+ * sequence instead). */
 skv_status_t skv_attn_prefill(skv_cache_t *cache, int32_t layer, const void *q, void *out,
                               const int32_t *q_lens, const int32_t *kv_lens, int32_t max_q,
                               int32_t max_kv_len, float scale, void *stream);

@@ -110,7 +110,8 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void attn_valu_kernel(AttnArgs
 
     if (bad) { // lengths the host promised not to pass: define the output, record the fault
         if (lane == 0 && split == 0 && kvh == 0) atomicOr(a.cache.faults, (uint32_t)SKV_FAULT_KV_LEN);
-        if (split == 0 && grp == 0 && (a.q_lens == nullptr || i < a.max_q)) {
+        // decode: the sequence's output row is zeroed; pre-fill: nothing is written (as in the MFMA kernels)
+        if (split == 0 && grp == 0 && a.q_lens == nullptr) {
             float z[EPL] = {};
 #pragma unroll
             for (int h = 0; h < G; ++h)

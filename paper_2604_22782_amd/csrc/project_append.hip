@@ -545,6 +545,91 @@ __global__ __launch_bounds__(256, 1) void project_append_tile_kernel(ProjArgs a)
     }
 }
 
+// Few token rows (one decode token per sequence: at most 64 rows, where the launch is a stream of
+// the weights and nothing else).  Every wave is a work group of its own: wave (fb, s) forms the 32
+// features of feature block fb of the [K heads, V heads] list for all token rows (two blocks of 32)
+// over the hidden columns of split s.  No LDS and no barrier: both MFMA operands come straight from
+// memory in operand layout -- lane (c, hh) owns row c (a weight row / a token row) and, of every 64
+// columns, the 32 contiguous ones 32 hh .. 32 hh + 31 (the order of the contraction is free as long
+// as both operands use it), i.e. 64 contiguous bytes per row and tile, two lanes per 128-byte line.
+// Loads run three tiles ahead in a register ring.  The fp32 partial sums of a split go to the
+// workspace in the layout project_finish_kernel reads.  Four splits at hidden 4096 and 8 kv heads of
+// 128 (256 waves, one per compute unit): 4 MiB of partial traffic beside the 17 MiB of weights and
+// rows, where the one-head kernel above needed sixteen splits (16 MiB) to fill the chip.
+constexpr int kSmallTokens = 64;
+template <typename M, int D>
+__global__ __launch_bounds__(64) void project_small_kernel(ProjArgs a, int n_splits) {
+    using vec8 = typename M::vec8;
+    constexpr int NB = D / 32;
+    const int lane = threadIdx.x, c = lane & 31, hh = lane >> 5;
+    const int hkv = a.slot.n_kv_heads;
+    const int kh = (int)blockIdx.x / NB, nb = (int)blockIdx.x % NB; // head in the [K, V] list, feature block of it
+    const bool is_v = kh >= hkv;
+    const int head = is_v ? kh - hkv : kh;
+    const int n_tok = a.batch * a.max_new;                           // <= kSmallTokens (checked by the launcher)
+    const int cols = a.hidden / n_splits;
+    const int64_t col0 = (int64_t)blockIdx.y * cols + 32 * hh;
+    const uint16_t *w = (const uint16_t *)(is_v ? a.w_v : a.w_k) + ((int64_t)head * D + 32 * nb + c) * a.hidden + col0;
+    // token rows past the last one repeat it (their results are not stored)
+    const uint16_t *x0 = (const uint16_t *)a.x + (int64_t)min(c, n_tok - 1) * a.hidden + col0;
+    const uint16_t *x1 = (const uint16_t *)a.x + (int64_t)min(32 + c, n_tok - 1) * a.hidden + col0;
+    const bool two = n_tok > 32;
+
+    struct Slot {
+        uint4 w[4], x0[4], x1[4];
+    };
+    auto issue = [&](int kt, Slot &q) {
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            q.w[st] = *(const uint4 *)(w + kt * 64 + 8 * st);
+            q.x0[st] = *(const uint4 *)(x0 + kt * 64 + 8 * st);
+            if (two) q.x1[st] = *(const uint4 *)(x1 + kt * 64 + 8 * st);
+        }
+    };
+    f32x16 acc0, acc1;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc0[r] = acc1[r] = 0.f;
+    auto compute = [&](const Slot &q) {
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            const vec8 wa = __builtin_bit_cast(vec8, q.w[st]);
+            acc0 = M::mfma(wa, __builtin_bit_cast(vec8, q.x0[st]), acc0);
+            if (two) acc1 = M::mfma(wa, __builtin_bit_cast(vec8, q.x1[st]), acc1);
+        }
+    };
+    const int n_kt = cols / 64;
+    Slot s0, s1, s2;
+#pragma unroll
+    for (int st = 0; st < 4; ++st) s0.x1[st] = s1.x1[st] = s2.x1[st] = make_uint4(0, 0, 0, 0);
+    issue(0, s0);
+    if (1 < n_kt) issue(1, s1);
+    if (2 < n_kt) issue(2, s2);
+    for (int base = 0; base < n_kt; base += 3) { // ring slots named explicitly: fixed registers
+        compute(s0);
+        if (base + 3 < n_kt) issue(base + 3, s0);
+        if (base + 1 < n_kt) {
+            compute(s1);
+            if (base + 4 < n_kt) issue(base + 4, s1);
+        }
+        if (base + 2 < n_kt) {
+            compute(s2);
+            if (base + 5 < n_kt) issue(base + 5, s2);
+        }
+    }
+    // lane owns token c (acc0) and 32 + c (acc1); element r is feature 32 nb + 8 (r/4) + 4 hh + r%4 of the head
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+        const int m = 32 * tb + c;
+        if (m >= n_tok) continue;
+        const f32x16 &acc = tb == 0 ? acc0 : acc1;
+        float *part = a.partial + (((int64_t)blockIdx.y * n_tok + m) * 2 * hkv + kh) * D + 32 * nb + 4 * hh;
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4)
+            *(float4 *)(part + 8 * g4) = make_float4(acc[4 * g4], acc[4 * g4 + 1], acc[4 * g4 + 2], acc[4 * g4 + 3]);
+    }
+}
+
+
 // Adds up the partial sums of the splits.  One thread per (token, K or V head, half hh, feature
 // block nb < NB/2, group g4): the four features 32 nb + 8 g4 + 4 hh .. + 3 of the head and their
 // rotary partners d/2 further on, i.e. what finish_token needs together.
@@ -627,6 +712,12 @@ __global__ __launch_bounds__(256) void project_finish_kernel(ProjArgs a, int n_s
 
 // The tile kernel takes the launches whose (head, 256-token tile) grid the one-head kernel would
 // run unsplit, on shapes whose [K heads, V heads] list divides into tiles of 256 features.
+// The few-rows kernel takes launches of at most 64 token rows (it always leaves fp32 partial sums
+// for project_finish_kernel, also with a single split).
+bool small_kernel_takes(int64_t n_tokens, int hidden) {
+    return n_tokens >= 1 && n_tokens <= kSmallTokens && hidden % 64 == 0 && !tuning().project_wide;
+}
+
 bool tile_kernel_takes(int n_kv_heads, int head_dim, int64_t n_tokens, int hidden) {
     const int64_t tiles = (n_tokens + kTokens - 1) / kTokens;
     return 2 * (int64_t)n_kv_heads * tiles >= 128 && (2 * n_kv_heads * head_dim) % kGT == 0 && hidden % kSub == 0 &&
@@ -638,6 +729,15 @@ template <typename M, int D> hipError_t launch_j(const ProjArgs &a, int n_splits
     const int64_t tiles = (n_tok + kTokens - 1) / kTokens;
     if (tiles > 65535 || 2 * a.slot.n_kv_heads > 65535) return hipErrorInvalidValue;
     hipError_t e = hipSuccess;
+    if (small_kernel_takes(n_tok, a.hidden)) {
+        const dim3 grid((unsigned)(2 * a.slot.n_kv_heads * (D / 32)), (unsigned)n_splits);
+        project_small_kernel<M, D><<<grid, 64, 0, stream>>>(a, n_splits);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        const int64_t threads = n_tok * 2 * a.slot.n_kv_heads * 2 * (D / 64) * 4;
+        project_finish_kernel<M, D><<<dim3((unsigned)((threads + 255) / 256)), 256, 0, stream>>>(a, n_splits);
+        return hipGetLastError();
+    }
     if (tile_kernel_takes(a.slot.n_kv_heads, D, n_tok, a.hidden)) {
         const int64_t groups = ((n_tok + kGT - 1) / kGT) * (2 * a.slot.n_kv_heads * D / kGT);
         if (groups > 0x7fffffff) return hipErrorInvalidValue;
@@ -673,6 +773,11 @@ int project_append_splits(int n_kv_heads, int head_dim, int64_t n_tokens, int hi
     const int want = tuning().project_splits; // developer knob: a power of two that divides the tiles of the hidden axis
     if (want >= 1 && (want & (want - 1)) == 0 && hidden / kKT % want == 0) return want;
     int splits = 1;
+    if (small_kernel_takes(n_tokens, hidden)) { // one wave per (32 features, split): about one per compute unit, splits at least 256 wide
+        const int64_t waves = 2 * (int64_t)n_kv_heads * (head_dim / 32);
+        while (waves * splits < 256 && hidden / 64 % (2 * splits) == 0 && hidden / (2 * splits) >= 256) splits *= 2;
+        return splits;
+    }
     if (tile_kernel_takes(n_kv_heads, head_dim, n_tokens, hidden)) {
         const int64_t groups = ((n_tokens + kGT - 1) / kGT) * (2 * n_kv_heads * head_dim / kGT);
         while (groups * splits < 192 && hidden / kSub % (2 * splits) == 0 && hidden / (2 * splits) >= 512) splits *= 2;
@@ -687,6 +792,8 @@ int project_append_splits(int n_kv_heads, int head_dim, int64_t n_tokens, int hi
 
 size_t project_append_workspace_bytes(int n_kv_heads, int head_dim, int64_t n_tokens, int hidden) {
     const int splits = project_append_splits(n_kv_heads, head_dim, n_tokens, hidden);
+    if (small_kernel_takes(n_tokens, hidden)) // partial sums also with a single split
+        return (size_t)splits * (size_t)n_tokens * 2 * n_kv_heads * head_dim * sizeof(float);
     return splits == 1 ? 0 : (size_t)splits * (size_t)n_tokens * 2 * n_kv_heads * head_dim * sizeof(float);
 }
 

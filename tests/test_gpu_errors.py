@@ -104,3 +104,30 @@ def test_device_side_bad_lengths_and_block_ids_are_contained():
     skv.skv_kv_append(cache, 0, k, k, torch.zeros(2, dtype=torch.int32, device="cuda"), four, 4)
     assert skv.skv_cache_device_faults(cache) & 2
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dtype,d,kernel", [("f32", 64, "attn_valu_kernel"), ("bf16", 64, "prefill_mfma_kernel"),
+                                            ("bf16", 128, "prefill_pipe_kernel")])
+def test_prefill_writes_nothing_for_a_sequence_with_impossible_lengths(dtype, d, kernel):
+    """The three pre-fill kernels contain impossible device-side lengths the same way: the fault word
+    is raised, the sequence's output stays untouched, the other sequences are computed."""
+    from oracle import skv_oracle as O
+    from tests.test_gpu_parity_small import _small
+    from workloads import gen
+    lens = np.array([96, 96, 96], dtype=np.int32)
+    w = _small(dtype, 4, 2, d, 3, lens, [0, 0])
+    cache, _ = H.alloc_cache(w)
+    H.fill_by_append(cache, w)
+    oc = H.oracle_cache(w)
+    q = w.q_prefill(1, 0, 3, 0, 96, "cuda")
+    for bad_q, bad_kv in (([96, 97, 96], [96, 96, 96]), ([96, 50, 96], [96, 40, 96]), ([96, 96, 96], [96, 0, 96])):
+        out = torch.full_like(q, 7.0)
+        skv.skv_attn_prefill(cache, 1, q, out, torch.tensor(bad_q, dtype=torch.int32, device="cuda"),
+                             torch.tensor(bad_kv, dtype=torch.int32, device="cuda"), 96, 96, w.scale)
+        assert skv.skv_last_kernel_name() == kernel
+        assert skv.skv_cache_device_faults(cache) & 4
+        assert (out[1] == 7.0).all()
+        want = O.prefill(oc, 1, gen.to_f64(q), [96, 0, 96], [96, 1, 96], w.scale)
+        got = gen.to_f64(out)
+        assert np.abs(got[[0, 2]] - want[[0, 2]]).max() <= H.TOL[dtype]
+    cache.free()

@@ -121,12 +121,12 @@ def test_position_beyond_the_table_or_capacity_is_dropped_and_reported():
     d_cos, d_sin = torch.from_numpy(cos.astype(np.float32)).cuda(), torch.from_numpy(sin.astype(np.float32)).cuda()
     zero = torch.zeros(1, dtype=torch.int32, device="cuda")
     eight = torch.full((1,), 8, dtype=torch.int32, device="cuda")
-    assert skv.skv_kv_project_workspace_bytes(cache, 8, 64) == 0
-    skv.skv_kv_project_append(cache, 0, x, wk, wk, d_cos, d_sin, zero, eight, 8)     # table has 4 positions
+    ws = torch.empty(max(skv.skv_kv_project_workspace_bytes(cache, 8, 64), 4) // 4, dtype=torch.float32, device="cuda")
+    skv.skv_kv_project_append(cache, 0, x, wk, wk, d_cos, d_sin, zero, eight, 8, ws)  # table has 4 positions
     assert skv.skv_cache_device_faults(cache) == 1                                    # SKV_FAULT_APPEND_RANGE
     k_pool, v_pool = H.pool_tensors(cache, w)
     assert k_pool[0, :4].any() and not k_pool[0, 4:].any()                            # K rows 4..7 dropped
-    skv.skv_kv_project_append(cache, 0, x, wk, wk, None, None, torch.full((1,), 28, dtype=torch.int32, device="cuda"), eight, 8)
+    skv.skv_kv_project_append(cache, 0, x, wk, wk, None, None, torch.full((1,), 28, dtype=torch.int32, device="cuda"), eight, 8, ws)
     assert skv.skv_cache_device_faults(cache) == 1                                    # positions 32..35 exceed the capacity
     with pytest.raises(skv.SkvError) as e:
         skv.skv_kv_project_append(cache, 0, x[:, :, :48].contiguous(), wk[:, :48].contiguous(), wk[:, :48].contiguous(),
