@@ -41,21 +41,22 @@ KERNEL_SOURCES = {
     "prefill_pipe_kernel": ["prefill_pipe.hip", "gen_prefill_pipe.py"],
     "dkdv_kernel": ["train_bwd.hip"], "dq_kernel": ["train_bwd.hip"], "delta_kernel": ["train_bwd.hip"],
     "project_append_tile_kernel": ["project_append.hip"], "project_append_kernel": ["project_append.hip"],
-    "project_finish_kernel": ["project_append.hip"],
+    "project_finish_kernel": ["project_append.hip"], "project_small_kernel": ["project_append.hip"],
 }
 
 
 def source_sha(kernel):
     import hashlib
     h = hashlib.sha256()
-    for f in KERNEL_SOURCES.get(kernel, []):
+    for f in KERNEL_SOURCES.get(kernel.split("@")[0], []):
         h.update(open(os.path.join(ROOT, "paper_2604_22782_amd", "csrc", f), "rb").read())
     return h.hexdigest()[:16]
 
 
 def measured_traffic(kernel):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None if
-    there is none for the kernel's present sources."""
+    """HBM bytes per launch of `kernel` (or "kernel@workload" for a launch shape other than the
+    headline's) from the committed rocprofv3 counter summary, or None if there is none for the
+    kernel's present sources."""
     try:
         t = json.load(open(os.path.join(ROOT, TRAFFIC_FILE)))[kernel]
         if t.get("source_sha16") != source_sha(kernel):
@@ -179,8 +180,7 @@ def run_decode(args, torch, skv, H, w, steps, warmup, headline=False):
     achieved = layer_bytes / (call_ms * 1e-3) / 1e9
     roof = {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4)}
-    # the committed counter summary was taken on the headline workload only
-    roof.update(traffic_fields([kernel_name]) if headline else {"traffic": None})
+    roof.update(traffic_fields([kernel_name if headline else f"{kernel_name}@{w.name}_b{w.batch}"]))
     roof.update({"launch_us": round(call_ms * 1e3, 2), "algorithmic_bytes_per_launch": layer_bytes})
     res = {"value": round(value, 1), "ms_per_step": round(ms_per_step, 4), "steps": steps, "roofline": roof,
            "config": {"workload": w.name, "batch": w.batch, "max_context": ctx, "layers": w.n_layers,
@@ -227,7 +227,8 @@ def run_append(args, torch, skv, H, configs):
         out[regime] = {"workload": w.name, "rows": w.batch * new, "launch_us": round(us, 2),
                        "roofline": {"bound": "hbm", "kernel": "append_rows_kernel", "achieved": round(gbs, 1),
                                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
-                                    "traffic": None, "algorithmic_bytes_per_launch": nbytes}}
+                                    **traffic_fields([f"append_rows_kernel@{regime}"]),
+                                    "algorithmic_bytes_per_launch": nbytes}}
         log(f"[bench] append {regime}: {us:.1f} us, {gbs:.0f} GB/s")
         cache.free()
         del k_new, v_new
@@ -472,9 +473,9 @@ def run_project(args, torch, skv, H, configs):
                              **traffic_fields(["project_append_tile_kernel"]),
                              "algorithmic_flops_per_launch": flops}
         else:
-            r["roofline"] = {"bound": "hbm", "kernel": "project_append_kernel + project_finish_kernel", "achieved": r["gbs"],
+            r["roofline"] = {"bound": "hbm", "kernel": "project_small_kernel + project_finish_kernel", "achieved": r["gbs"],
                              "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(r["gbs"] / HBM_PEAK_GBS, 4),
-                             **traffic_fields(["project_append_kernel", "project_finish_kernel"]),
+                             **traffic_fields(["project_small_kernel", "project_finish_kernel"]),
                              "algorithmic_bytes_per_launch": nbytes}
         out[regime] = r
         cache.free()

@@ -41,10 +41,15 @@
  *     e = the smallest integer with max|x| * 2^-e <= 448, clamped to [-127, 127] (0 if all x are 0),
  *     code_i = x_i * 2^-e rounded to the nearest e4m3 number, ties to the even code; byte = e + 127.
  * skv_kv_append does this conversion; attention reads code * 2^e, which is exact in bf16 / fp16,
- * so Eq. (3.1) is evaluated on the stored values exactly as on a 16-bit cache.  The K and V pools
- * then have 1-byte elements in the layouts above, and a third pool holds the exponent bytes as
- * uint16 [n_slots][rows][n_kv_heads] (low byte: K, high byte: V; rows as in the K / V pools).
- * head_dim must be 64 or 128.
+ * so Eq. (3.1) is evaluated on the stored values exactly as on a 16-bit cache.
+ * Layout of 8-bit slots: 1-byte elements, and the rows of one kv head lie together in groups of
+ * R consecutive rows, so that a reader of one kv head streams R * head_dim contiguous bytes
+ * (strided 64- or 128-byte pieces cost a good part of the HBM rate):
+ *   contiguous:  K and V pools are [n_slots][batch][ceil(max_ctx / 128)][n_kv_heads][128][head_dim]   (R = 128)
+ *   paged:       K and V pools are [n_slots][n_blocks][block_size / R][n_kv_heads][R][head_dim],
+ *                R = min(block_size, 128); block_size must be at least 16
+ * and a third pool holds the exponent bytes as uint16 in the same order without the last axis
+ * ([...][n_kv_heads][R]; low byte: K, high byte: V).  head_dim must be 64 or 128.
  */
 #ifndef SKV_H
 #define SKV_H
@@ -161,8 +166,9 @@ skv_status_t skv_cache_set_block_table(skv_cache_t *cache, const int32_t *table_
  * |S| slots instead of L), their rows and, for a paged cache, their block-table entries are never
  * read again and may hold anything.  sink_len, first_pos: device int32[batch], borrowed until they
  * are replaced; both NULL switches eviction off.  sink_len[b] must be a multiple of 32, first_pos[b]
- * a multiple of the block size (any value for a contiguous cache), 0 <= sink_len[b] <= first_pos[b]
- * <= kv_lens[b]; other values set SKV_FAULT_KV_LEN and zero the sequence's output.
+ * a multiple of the block size (any value for a contiguous cache of 16-bit elements; a multiple of
+ * the group size R of an 8-bit slot), 0 <= sink_len[b] <= first_pos[b] <= kv_lens[b]; other values
+ * set SKV_FAULT_KV_LEN and zero the sequence's output.
  * While eviction is on, skv_attn_decode / _range / _static attend over the surviving positions
  * only, and their max_kv_len bounds the number of SURVIVING positions per sequence (kv_lens[b]
  * itself is bounded by the capacity); skv_attn_prefill returns SKV_ERR_UNSUPPORTED, and so does

@@ -106,7 +106,8 @@ __global__ __launch_bounds__(256) void append_quant_kernel(SlotView c, const uin
         return;
     }
     const int64_t src_piece = (row * hkv + head) * LPH + li;
-    const int64_t dst_piece = (dst_row * hkv + head) * LPH + li; // 8 codes = 8 bytes per lane
+    const int64_t dst_head_row = kv8_head_row(c, dst_row, head); // the slot is head-major inside groups of rows
+    const int64_t dst_piece = dst_head_row * LPH + li;           // 8 codes = 8 bytes per lane
     uint32_t ebytes = 0;
 #pragma unroll
     for (int which = 0; which < 2; ++which) {
@@ -144,7 +145,7 @@ __global__ __launch_bounds__(256) void append_quant_kernel(SlotView c, const uin
         *dst = make_uint2(lo, hi);
         ebytes |= (uint32_t)(e + 127) << (8 * which);
     }
-    if (li == 0) ((uint16_t *)c.scales)[dst_row * hkv + head] = (uint16_t)ebytes;
+    if (li == 0) ((uint16_t *)c.scales)[dst_head_row] = (uint16_t)ebytes;
 }
 
 hipError_t launch_append(const SlotView &slot, int dtype, const void *k_new, const void *v_new,

@@ -4,9 +4,9 @@
 // The kernel is bound by streaming K and V rows from HBM exactly once.  Work group = 4 waves =
 // one (sequence, kv head, key-axis split); the waves take 32-key tiles round-robin.  Per tile a
 // wave
-//   1. has the tile's K and V rows in registers from coalesced 128-bit global loads issued one
-//      tile ahead (16 lanes cover one 256-byte row, a wave-wide load covers 4 whole rows),
-//   2. parks them in its private LDS region and at once issues the loads of its next tile,
+//   1. has the tile's K and V rows in registers from coalesced 128-bit buffer loads issued two
+//      tiles ahead (16 lanes cover one 256-byte row, a wave-wide load covers 4 whole rows),
+//   2. parks them in its private LDS region and at once issues the loads of the tile after next,
 //   3. S^T[key][head] = K . Q^T on the matrix cores (v_mfma_f32_16x16x32): the G <= 16 query heads
 //      of the GQA group are the 16 columns, so a K/V tile is read once for the whole group and
 //      16-bit data feeds the MFMA without unpacking,
@@ -83,6 +83,28 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const char *p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(p));
 }
 
+// A tile is fetched with BUFFER loads: the descriptor (wave-uniform base, byte count) bounds every lane,
+// so rows beyond the end of the range read as zero without a branch.  Every tile therefore issues
+// the same number of load instructions whatever its length, and the wait before a tile is parked
+// counts exactly the loads issued after it: the loads of the following tile stay in flight across
+// it.  (With predicated loads the count of later loads has no lower bound and the wait drains them all.)
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t uniform_rsrc(const void *base, uint32_t bytes) {
+    const uint64_t p = (uint64_t)base;
+    // (the builtin returns a signed int: widen each half as unsigned, or bit 31 of the low half smears over the high one)
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)p);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(p >> 32));
+    const uint64_t u = ((uint64_t)hi << 32) | (uint64_t)lo;
+    // stride 0 (raw), byte count, 32-bit untyped data
+    return __builtin_amdgcn_make_buffer_rsrc((void *)u, 0, (int)__builtin_amdgcn_readfirstlane(bytes), 0x00020000);
+}
+template <bool kStream> __device__ __forceinline__ uint4 buffer_load_16(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+    return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, kStream ? 2 : 0)); // 2: non-temporal
+}
+template <bool kStream> __device__ __forceinline__ uint16_t buffer_load_2(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+    return (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, (int)off, 0, kStream ? 2 : 0);
+}
+
 // kStream: the K/V loads carry the non-temporal hint (every byte is used once: stream it past the
 // caches).  Without it the rows are cached as usual, which is what lets the next layer of a sharing
 // group find a small slot slice on chip.
@@ -137,19 +159,25 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
     const int lrow = lane / LPR;   // row inside one wave-wide load
     const int lcol = lane % LPR;   // 16-byte piece inside the row
     constexpr int EB = KV8 ? 1 : 2; // bytes per slot element
-    const char *kp = (const char *)a.cache.k + ((int64_t)kvh * D) * EB; // uniform; the lane's part is lane_off
-    const char *vp = (const char *)a.cache.v + ((int64_t)kvh * D) * EB;
-    const int64_t row_bytes = (int64_t)hkv * D * EB;
-    const uint16_t *sp = KV8 ? a.cache.scales + kvh : nullptr; // 8-bit slots: exponent bytes of K (low) and V (high) per row
+    // 16-bit slots are row-major ([row][kv head][d]): the lane's part of an address is its row inside
+    // the load times the row size plus its piece.  8-bit slots keep the rows of a kv head together
+    // (kv8_head_row): the RPL rows of a load are contiguous and the lane's part is 16 x lane.
+    const char *kp = (const char *)a.cache.k + (KV8 ? 0 : ((int64_t)kvh * D) * EB); // uniform; the lane's part is lane_off
+    const char *vp = (const char *)a.cache.v + (KV8 ? 0 : ((int64_t)kvh * D) * EB);
+    const int64_t row_bytes = KV8 ? (int64_t)D : (int64_t)hkv * D * EB; // distance of consecutive rows of this kv head inside a load
+    const uint16_t *sp = KV8 ? a.cache.scales : nullptr; // 8-bit slots: exponent bytes of K (low) and V (high) per (row, kv head)
 
     // Paged caches: the (at most four) block ids a 32-key tile touches are fetched with SCALAR loads
     // one tile ahead.  They have a counter of their own, so waiting for them never drains the
-    // vector loads of the K/V tiles that are still in flight.
+    // vector loads of the K/V tiles that are still in flight.  (The table is not written while the
+    // kernel runs: reading it through the constant address space is what makes the loads scalar even
+    // after the stores of an earlier work item.)
     const bool paged = a.cache.block_table != nullptr;
     const int shift = a.cache.block_shift;
     auto blocks_of = [&](int j0, int32_t *blk) {
         if (paged) {
-            const int32_t *row = a.cache.block_table + (int64_t)b * a.cache.max_blocks_per_seq;
+            typedef const __attribute__((address_space(4))) int32_t table_word;
+            table_word *row = (table_word *)(uintptr_t)(a.cache.block_table + (int64_t)b * a.cache.max_blocks_per_seq);
             const int first = (j0 + (j0 >= sink ? gap : 0)) >> shift;
 #pragma unroll
             for (int u = 0; u < 4; ++u) blk[u] = row[min(first + u, a.cache.max_blocks_per_seq - 1)];
@@ -159,14 +187,15 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
     // least RPL positions and tiles start on block boundaries): its first row is WAVE-UNIFORM, so the
     // address of a lane is a scalar base (slot + first row of the load) plus a 32-bit lane offset that
     // never changes (row inside the load, piece inside the row).  The address arithmetic of the 2 x NL
-    // loads of a tile is then scalar work; per lane only the bound check against k_end is left.
+    // loads of a tile is then scalar work, and the bound against k_end is the byte count of the
+    // load's buffer descriptor: nothing is left to do per lane.
     const uint32_t lane_off = (uint32_t)(lrow * (int)row_bytes + lcol * 16);
     auto first_row_of = [&](int j0, const int32_t *blk, int t) -> int64_t { // -1: nothing to load
         const int c0 = j0 + RPL * t;                  // first key of the load, uniform
         if (c0 >= k_end) return -1;
         const int skip = j0 >= sink ? gap : 0;        // the whole tile lies on one side of the gap
         const int p0 = c0 + skip;                     // its position
-        if (!paged) return (int64_t)b * a.cache.max_ctx + p0;
+        if (!paged) return (int64_t)b * a.cache.seq_rows + p0;
         const int u = (p0 >> shift) - ((j0 + skip) >> shift); // 0..3 (0 when a block holds 32 keys or more)
         const int32_t id = u == 0 ? blk[0] : u == 1 ? blk[1] : u == 2 ? blk[2] : blk[3];
         if ((uint32_t)id >= (uint32_t)a.cache.n_blocks) {
@@ -175,27 +204,22 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
         }
         return ((int64_t)id << shift) + (p0 & ((1 << shift) - 1));
     };
+    const uint32_t lane_soff = (uint32_t)(lrow * 2); // 8-bit slots: the lane's row inside the load's exponent byte pairs
     auto issue = [&](int j0, const int32_t *blk, uint4 *kr, uint4 *vr, uint16_t *sr) {
 #pragma unroll
         for (int t = 0; t < NL; ++t) {
-            kr[t] = make_uint4(0, 0, 0, 0);
-            vr[t] = make_uint4(0, 0, 0, 0);
-            if constexpr (KV8) sr[t] = 0x7f7f; // scale 1 for rows that are not loaded (their codes are zero)
             const int64_t r0 = first_row_of(j0, blk, t);
-            if (r0 >= 0 && j0 + RPL * t + lrow < k_end) {
-                typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-                const char *kb = kp + r0 * row_bytes, *vb = vp + r0 * row_bytes; // uniform part ...
-                const uint16_t *sb = KV8 ? sp + r0 * hkv : nullptr;
-                if constexpr (kStream) { // "nt" loads: +6..10 % bandwidth on launches far larger than the caches
-                    kr[t] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4 *)(kb + lane_off)));
-                    vr[t] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4 *)(vb + lane_off)));
-                    if constexpr (KV8) sr[t] = __builtin_nontemporal_load(sb + lrow * hkv);
-                } else {
-                    kr[t] = *(const uint4 *)(kb + lane_off);
-                    vr[t] = *(const uint4 *)(vb + lane_off);
-                    if constexpr (KV8) sr[t] = sb[lrow * hkv];
-                }
-            }
+            const int rows = r0 < 0 ? 0 : min(RPL, k_end - (j0 + RPL * t)); // rows of the load inside the range
+            const int64_t rr = r0 < 0 ? 0 : r0;                             // a valid base in any case
+            // first row of the load, in rows of this kv head (8-bit slots: the load never leaves its group)
+            const int64_t hr = KV8 ? kv8_head_row(a.cache, rr, kvh) : rr;
+            const uint32_t bytes = (uint32_t)(rows * (int)row_bytes);
+            const __amdgpu_buffer_rsrc_t rk = uniform_rsrc(kp + hr * row_bytes, bytes);
+            const __amdgpu_buffer_rsrc_t rv = uniform_rsrc(vp + hr * row_bytes, bytes);
+            kr[t] = buffer_load_16<kStream>(rk, lane_off);
+            vr[t] = buffer_load_16<kStream>(rv, lane_off);
+            if constexpr (KV8) // rows that are not loaded read as codes 0 with exponent byte 0: zeros
+                sr[t] = buffer_load_2<kStream>(uniform_rsrc(sp + hr, (uint32_t)(rows * 2)), lane_soff);
         }
     };
 
@@ -216,27 +240,33 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
         return k_begin + t2 * kTile;
     };
 
-    // Two tiles per wave (three over 8-bit slots) are in flight from HBM (register sets A, B, C) while
-    // another is computed from LDS; the block ids run one more tile ahead.
+    // Two tiles per wave are in flight from HBM (register sets A, B) while another is computed from
+    // LDS; the block ids run one more tile ahead.
     int32_t blk[4] = {0, 0, 0, 0};
     int tt_issue = wave; // next tile of this wave to request
+    // Always issues a tile's worth of loads: past the last tile they carry an empty descriptor (no
+    // memory access, no address arithmetic), which keeps the number of loads in flight behind any
+    // tile a constant.
     auto issue_next = [&](uint4 *kr, uint4 *vr, uint16_t *sr) {
         if (tt_issue < n_tiles) {
             issue(tile_j0(tt_issue), blk, kr, vr, sr);
-            tt_issue += kWaves;
-            if (tt_issue < n_tiles) blocks_of(tile_j0(tt_issue), blk);
+        } else {
+            const __amdgpu_buffer_rsrc_t none = uniform_rsrc(kp, 0);
+#pragma unroll
+            for (int t = 0; t < NL; ++t) {
+                kr[t] = buffer_load_16<kStream>(none, lane_off);
+                vr[t] = buffer_load_16<kStream>(none, lane_off);
+                if constexpr (KV8) sr[t] = buffer_load_2<kStream>(none, lane_soff);
+            }
         }
+        tt_issue += kWaves;
+        if (tt_issue < n_tiles) blocks_of(tile_j0(tt_issue), blk);
     };
-    // 8-bit slots: a tile is half the bytes and the same arithmetic, so the time a wave spends per byte
-    // on the arithmetic doubles; a third tile in flight (its registers are there: a set is half as
-    // large) keeps the loads ahead of it.
-    constexpr int kSets = 2;
-    uint4 krA[NL], vrA[NL], krB[NL], vrB[NL], krC[kSets > 2 ? NL : 1], vrC[kSets > 2 ? NL : 1];
-    uint16_t srA[KV8 ? NL : 1], srB[KV8 ? NL : 1], srC[KV8 ? NL : 1];
+    uint4 krA[NL], vrA[NL], krB[NL], vrB[NL];
+    uint16_t srA[KV8 ? NL : 1], srB[KV8 ? NL : 1];
     if (wave < n_tiles) blocks_of(tile_j0(wave), blk);
     issue_next(krA, vrA, srA);
     issue_next(krB, vrB, srB);
-    if constexpr (kSets > 2) issue_next(krC, vrC, srC);
 
     auto process = [&](int tt, uint4 *kr, uint4 *vr, uint16_t *sr) {
         const int j0 = tile_j0(tt);
@@ -322,12 +352,12 @@ __global__ __launch_bounds__(64 * kWaves, 2) void decode_mfma_kernel(AttnArgs a,
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); // reads of this tile before the next tile's writes
         __builtin_amdgcn_wave_barrier();
     };
-    for (int tt = wave; tt < n_tiles; tt += kSets * kWaves) {
+    int tt = wave;
+    for (; tt + kWaves < n_tiles; tt += 2 * kWaves) { // both tiles exist: no load of the loop body is conditional
         process(tt, krA, vrA, srA);
-        if (tt + kWaves < n_tiles) process(tt + kWaves, krB, vrB, srB);
-        if constexpr (kSets > 2)
-            if (tt + 2 * kWaves < n_tiles) process(tt + 2 * kWaves, krC, vrC, srC);
+        process(tt + kWaves, krB, vrB, srB);
     }
+    if (tt < n_tiles) process(tt, krA, vrA, srA);
 
     // ---- merge the four waves through LDS --------------------------------------------------
     float l_tot = l_part + __shfl_xor(l_part, 16, 64);

@@ -147,9 +147,10 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_mfma_kernel(AttnArgs a
     }
 
     // cooperative tile loads: thread t moves pieces t, t + 512, ... (16 lanes per row => coalesced)
-    const char *kp = (const char *)a.cache.k + (int64_t)kvh * D * EB;
-    const char *vp = (const char *)a.cache.v + (int64_t)kvh * D * EB;
-    const int64_t row_bytes = (int64_t)hkv * D * EB;
+    // 16-bit slots are row-major; 8-bit slots keep the rows of a kv head together (kv8_head_row)
+    const char *kp = (const char *)a.cache.k + (KV8 ? 0 : (int64_t)kvh * D * EB);
+    const char *vp = (const char *)a.cache.v + (KV8 ? 0 : (int64_t)kvh * D * EB);
+    const int64_t row_bytes = KV8 ? (int64_t)D : (int64_t)hkv * D * EB;
     const bool loader = kAllLoad || tid < kBN * LPR;
     auto rows_of = [&](int j0, int32_t *rows) {
 #pragma unroll
@@ -170,10 +171,11 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_mfma_kernel(AttnArgs a
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             if (rows[i] >= 0) { // a bad block id keeps the previous (finite) piece
-                const int64_t off = rows[i] * row_bytes + (tid % LPR) * 16;
+                const int64_t hr = KV8 ? kv8_head_row(a.cache, rows[i], kvh) : rows[i];
+                const int64_t off = hr * row_bytes + (tid % LPR) * 16;
                 kr[i] = *(const uint4 *)(kp + off);
                 vr[i] = *(const uint4 *)(vp + off);
-                if constexpr (KV8) sr[i] = a.cache.scales[(int64_t)rows[i] * hkv + kvh];
+                if constexpr (KV8) sr[i] = a.cache.scales[hr];
             }
         }
     };

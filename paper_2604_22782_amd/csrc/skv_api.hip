@@ -74,6 +74,7 @@ skv_status_t check_desc(const skv_cache_desc_t *d, int32_t *n_slots, std::vector
     if (d->block_size < 0) return SKV_ERR_INVALID_ARG;
     if (d->block_size > 0) {
         if (ilog2_exact(d->block_size) < 3 || d->block_size > 256) return SKV_ERR_UNSUPPORTED;
+        if (skv::dtype_kv8(d->dtype) && d->block_size < 16) return SKV_ERR_UNSUPPORTED; // a wave-wide load of codes covers 16 rows of 64
         if (d->n_blocks <= 0) return SKV_ERR_INVALID_ARG;
     }
     if ((d->k_pool == nullptr) != (d->v_pool == nullptr)) return SKV_ERR_INVALID_ARG;
@@ -87,8 +88,24 @@ skv_status_t check_desc(const skv_cache_desc_t *d, int32_t *n_slots, std::vector
     return SKV_OK;
 }
 
+// 8-bit slots keep the rows of one kv head together in groups of this many consecutive rows: the
+// four 32-key tiles the waves of a decode work group take side by side, or a whole block where
+// blocks are smaller; 1 = row-major slot.  (Decode over the Llama-3-8B-shaped workload: groups of
+// 32 / 64 / 128 rows = runs of 4 / 8 / 16 KiB per kv head: 97 / 94 / 92 us per call; row-major: 106-111.)
+constexpr int kGroupRows = 128;
+int group_rows_of(const skv_cache_desc_t *d) {
+    if (!skv::dtype_kv8(d->dtype)) return 1;
+    return d->block_size > 0 ? std::min(d->block_size, kGroupRows) : kGroupRows;
+}
+
+// rows a contiguous slot holds per sequence: whole groups
+size_t seq_rows_of(const skv_cache_desc_t *d) {
+    const size_t g = (size_t)group_rows_of(d);
+    return ((size_t)d->max_ctx + g - 1) / g * g;
+}
+
 size_t slot_rows_of(const skv_cache_desc_t *d) {
-    return d->block_size > 0 ? (size_t)d->n_blocks * d->block_size : (size_t)d->batch * d->max_ctx;
+    return d->block_size > 0 ? (size_t)d->n_blocks * d->block_size : (size_t)d->batch * seq_rows_of(d);
 }
 
 size_t slot_bytes_of(const skv_cache_desc_t *d) {
@@ -113,6 +130,8 @@ skv::SlotView view_of(const skv_cache *c, int slot) {
     v.max_ctx = c->d.block_size > 0
                     ? (int32_t)std::min<int64_t>((int64_t)c->max_blocks_per_seq << c->block_shift, INT32_MAX)
                     : c->d.max_ctx;
+    v.seq_rows = (int32_t)seq_rows_of(&c->d);
+    v.group_shift = ilog2_exact(group_rows_of(&c->d));
     v.n_kv_heads = c->d.n_kv_heads;
     v.head_dim = c->d.head_dim;
     return v;
@@ -449,10 +468,10 @@ skv_status_t skv_attn_decode_range(skv_cache_t *c, int32_t layer, int32_t seq_be
     if (view.block_table != nullptr) {
         view.block_table += (size_t)seq_begin * view.max_blocks_per_seq;
     } else {
-        const size_t seq_bytes = (size_t)view.max_ctx * c->d.n_kv_heads * c->d.head_dim * elem_bytes(c->d.dtype);
+        const size_t seq_bytes = (size_t)view.seq_rows * c->d.n_kv_heads * c->d.head_dim * elem_bytes(c->d.dtype);
         view.k = (const char *)view.k + (size_t)seq_begin * seq_bytes;
         view.v = (const char *)view.v + (size_t)seq_begin * seq_bytes;
-        if (view.scales != nullptr) view.scales += (size_t)seq_begin * view.max_ctx * c->d.n_kv_heads;
+        if (view.scales != nullptr) view.scales += (size_t)seq_begin * view.seq_rows * c->d.n_kv_heads;
     }
 
     const int g = c->d.n_q_heads / c->d.n_kv_heads;
@@ -660,6 +679,8 @@ skv_status_t skv_train_attn_fwd(const void *q, const void *k, const void *v, voi
     a.cache.block_shift = 0;
     a.cache.n_blocks = 0;
     a.cache.max_ctx = seq;
+    a.cache.seq_rows = seq;
+    a.cache.group_shift = 0;
     a.cache.n_kv_heads = n_kv_heads;
     a.cache.head_dim = head_dim;
     a.q = q;

@@ -18,7 +18,9 @@ struct SlotView {
     int32_t max_blocks_per_seq; // paged
     int32_t block_shift;        // paged: log2(block_size)
     int32_t n_blocks;           // paged
-    int32_t max_ctx;            // contiguous: rows per sequence; paged: max_blocks_per_seq << block_shift
+    int32_t max_ctx;            // contiguous: positions per sequence; paged: max_blocks_per_seq << block_shift
+    int32_t seq_rows;           // contiguous: rows the slot holds per sequence (max_ctx, rounded up to whole groups)
+    int32_t group_shift;        // 8-bit slots: log2 of the rows of one kv head that lie together (0: row-major slot)
     int32_t n_kv_heads;
     int32_t head_dim;
 };
@@ -26,10 +28,20 @@ struct SlotView {
 // Row number (in units of one [n_kv_heads][head_dim] row) of logical (b, pos) inside the slot,
 // or -1 if a paged lookup hits a block id outside the pool.  pos must be < max_ctx.
 __device__ __forceinline__ int64_t slot_row(const SlotView &c, int b, int pos) {
-    if (c.block_table == nullptr) return (int64_t)b * c.max_ctx + pos;
+    if (c.block_table == nullptr) return (int64_t)b * c.seq_rows + pos;
     const int blk = c.block_table[(int64_t)b * c.max_blocks_per_seq + (pos >> c.block_shift)];
     if ((unsigned)blk >= (unsigned)c.n_blocks) return -1;
     return ((int64_t)blk << c.block_shift) + (pos & ((1 << c.block_shift) - 1));
+}
+
+// 8-bit slots are head-major inside groups of R = 1 << group_shift consecutive rows (a group never
+// straddles a sequence or a block): the head_dim codes of (row, kv head) start at element
+// kv8_head_row(c, row, kvh) * head_dim of the slot, and the pair of exponent bytes is scale word
+// kv8_head_row(c, row, kvh).  A reader of one kv head then streams R * head_dim contiguous bytes
+// per group instead of head_dim bytes per row: strided 128-byte pieces cost 12-15 % of the HBM rate.
+__device__ __forceinline__ int64_t kv8_head_row(const SlotView &c, int64_t row, int kvh) {
+    const int gs = c.group_shift;
+    return ((((row >> gs) * c.n_kv_heads) + kvh) << gs) + (row & ((1 << gs) - 1));
 }
 
 // Descriptor dtypes 3 and 4: 16-bit activations over slots of 8-bit codes with power-of-two scales.
@@ -95,7 +107,7 @@ __device__ __forceinline__ int decode_keys(const AttnArgs &a, int b, int &sink, 
     gap = 0;
     if (a.evict_first != nullptr) {
         const int s = a.evict_sink[b], f = a.evict_first[b];
-        if (s < 0 || (s & 31) || f < s || f > len) return -1;
+        if (s < 0 || (s & 31) || f < s || f > len || ((f - s) & ((1 << a.cache.group_shift) - 1))) return -1;
         sink = s;
         gap = f - s;
     }

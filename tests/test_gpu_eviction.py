@@ -49,11 +49,12 @@ def test_decode_attends_over_surviving_positions_only(dtype, paged, kv8, many_sp
     oc = H.oracle_cache(w)
     # windows: nothing evicted, sinks of 0 / 32 / 64 positions, windows that start right at the end
     sink = np.array([(0, 32, 64, 0)[b % 4] for b in range(B)], dtype=np.int32)
-    first = np.array([min(max(int(sink[b]), (int(lens[b]) * (b % 5) // 5) // 16 * 16), int(lens[b]) // 16 * 16)
+    gr = 128 if (kv8 and not paged) else 16           # a window starts on a block (8-bit slots: row group) boundary
+    first = np.array([min(max(int(sink[b]), (int(lens[b]) * (b % 5) // 5) // gr * gr), int(lens[b]) // gr * gr)
                       for b in range(B)], dtype=np.int32)
     sink = np.minimum(sink, first // 32 * 32).astype(np.int32)
     first[3 % B] = sink[3 % B]                       # one sequence with nothing evicted
-    assert (sink % 32 == 0).all() and (first % 16 == 0).all() and (sink <= first).all() and (first <= lens).all()
+    assert (sink % 32 == 0).all() and (first % gr == 0).all() and (sink <= first).all() and (first <= lens).all()
     if paged:                                        # dropped blocks: their table entries are poison
         table = w.block_table.copy()
         for b in range(B):

@@ -180,8 +180,14 @@ def test_8bit_slot_descriptor_rules():
     base = dict(n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=128, batch=2, max_ctx=64, route=[0, 0])
     total = skv.skv_cache_bytes(dtype=skv.SKV_BF16_KV8, **base)
     kvb, scb = skv.skv_cache_pool_bytes(dtype=skv.SKV_BF16_KV8, **base)
-    assert kvb == 1 * 2 * 64 * 2 * 128 and scb == 1 * 2 * 64 * 2 * 2 and total == 2 * kvb + scb
-    assert skv.skv_cache_pool_bytes(dtype=skv.SKV_BF16, **base) == (2 * kvb, 0)
+    # an 8-bit slot holds whole groups of 128 rows per sequence: 64 positions take 128 rows
+    assert kvb == 1 * 2 * 128 * 2 * 128 and scb == 1 * 2 * 128 * 2 * 2 and total == 2 * kvb + scb
+    assert skv.skv_cache_pool_bytes(dtype=skv.SKV_BF16, **base) == (2 * 1 * 2 * 64 * 2 * 128, 0)
+    paged = dict(base, block_size=16, n_blocks=10)
+    assert skv.skv_cache_pool_bytes(dtype=skv.SKV_BF16_KV8, **paged) == (10 * 16 * 2 * 128, 10 * 16 * 2 * 2)
+    with pytest.raises(skv.SkvError) as e:                       # a wave-wide load of codes needs blocks of 16 rows
+        skv.skv_cache_bytes(dtype=skv.SKV_BF16_KV8, **dict(base, block_size=8, n_blocks=10))
+    assert e.value.status == 6
     with pytest.raises(skv.SkvError) as e:                       # head_dim 256 has no 8-bit path
         skv.skv_cache_bytes(dtype=skv.SKV_F16_KV8, **{**base, "head_dim": 256})
     assert e.value.status == 6

@@ -47,7 +47,19 @@ def pool_tensors(cache, w):
         host = torch.empty(sb, dtype=torch.uint8)
         rc = hip.hipMemcpy(ctypes.c_void_p(host.data_ptr()), ctypes.c_void_p(sp), ctypes.c_size_t(sb), 2)
         assert rc == 0, rc
-        return [o.view(shape) for o in outs] + [host.view(n_slots, rows, w.n_kv_heads, 2)]
+        # An 8-bit slot is head-major inside groups of R consecutive rows ([group][kv head][row in group][d],
+        # R = 128, or the block size where blocks are smaller; a contiguous slot holds whole groups per
+        # sequence): bring the three pools back to row order.
+        R = min(w.block_size, 128) if w.block_size else 128
+        seq_rows = -(-w.max_ctx // R) * R
+        phys = w.n_blocks * w.block_size if w.block_size else w.batch * seq_rows
+
+        def row_order(t, width):
+            x = t.view(n_slots, phys // R, w.n_kv_heads, R, width).permute(0, 1, 3, 2, 4).reshape(n_slots, phys, w.n_kv_heads, width)
+            if not w.block_size:
+                x = x.view(n_slots, w.batch, seq_rows, w.n_kv_heads, width)[:, :, : w.max_ctx]
+            return x.reshape(n_slots, rows, w.n_kv_heads, width).contiguous()
+        return [row_order(o, w.head_dim) for o in outs] + [row_order(host, 2)]
     view = {2: torch.int16, 4: torch.int32}[w.elem_bytes]
     return [o.view(view).view(shape) for o in outs]
 
