@@ -29,9 +29,19 @@ tile t-1, last read in the first half); one barrier per tile, placed after every
 for its own loads of tile t+1 and for its last reads of tile t-1, publishes the former and
 releases the latter.  A load is in flight for about 1.75 tiles before anybody waits for it.
 
+bf16 only: tiles entirely below a wave's diagonal run a FAST copy of the loop body first.  It
+multiplies K with a second copy of Q^T that carries scale x log2(e) (rounded to bf16 once more), so
+the accumulators hold the exponents of the weights, and takes weight = 2^score without a running
+maximum (bf16 weights have the exponent range of fp32): per score one v_exp, one v_add and half a
+v_cvt_pk instead of v_max3 / v_fma / v_exp / v_add / v_cvt_pk.  After every half tile each lane's
+sum of the half tile is checked against [2^-40, 2^14]; outside it the wave leaves, out of line, for
+the general stream, which forms the scores again from the caller's Q and scales them in fp32 (so
+nothing a result depends on was computed from the twice-rounded copy outside the checked range).
+
 Register map (per lane):
   a[0:127]    O^T accumulators  [nq][d block of 32][16]
   a[128:191]  Q^T as MFMA B operand [nq][k step of 16][4]
+  a[192:255]  bf16: Q^T x scale x log2(e), rounded to bf16 again (operand of the fast bodies)
   v[32:63], v[64:95]    S^T of even / odd half tiles [nq][16]
   v[96:111], v[112:127] P^T (16-bit pairs) of even / odd half tiles [nq][k step of 16 keys][4]
   v[128:...]  rings of K / V^T operands read from LDS, then softmax state, lane constants, addresses
