@@ -134,3 +134,21 @@ def test_null_handles_and_no_device_behaviour():
         with pytest.raises(skv.SkvError) as e:
             skv.skv_cache_alloc(**_desc())
         assert e.value.status == 7 and skv.skv_last_hip_error() != 0
+
+
+def test_8bit_slot_sizes_follow_the_documented_row_groups():
+    """8-bit slots hold whole groups of R rows per kv head (R = 128; a paged slot: min(block, 128)), so a
+    contiguous slot rounds its positions per sequence up to 128; 16-bit slots are row-major and do not."""
+    base = dict(n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=128, batch=3, route=[0, 1])
+    for max_ctx in (1, 127, 128, 129, 1000):
+        rows = -(-max_ctx // 128) * 128
+        kvb, scb = skv.skv_cache_pool_bytes(dtype=skv.SKV_BF16_KV8, max_ctx=max_ctx, **base)
+        assert kvb == 2 * 3 * rows * 2 * 128 and scb == 2 * 3 * rows * 2 * 2
+        assert skv.skv_cache_bytes(dtype=skv.SKV_BF16_KV8, max_ctx=max_ctx, **base) == 2 * kvb + scb
+        assert skv.skv_cache_pool_bytes(dtype=skv.SKV_BF16, max_ctx=max_ctx, **base) == (2 * 3 * max_ctx * 2 * 128 * 2, 0)
+    for block in (16, 64, 256):
+        kvb, scb = skv.skv_cache_pool_bytes(dtype=skv.SKV_F16_KV8, max_ctx=1000, block_size=block, n_blocks=7, **base)
+        assert kvb == 2 * 7 * block * 2 * 128 and scb == 2 * 7 * block * 2 * 2
+    with pytest.raises(skv.SkvError) as e:
+        skv.skv_cache_pool_bytes(dtype=skv.SKV_F16_KV8, max_ctx=1000, block_size=8, n_blocks=7, **base)
+    assert e.value.status == 6

@@ -31,7 +31,8 @@ def _oracle_decode(oc, w, layer, q64, lens, sink, first):
 
 
 @pytest.mark.parametrize("dtype,paged,kv8,many_splits", [("bf16", True, False, True), ("bf16", True, True, False),
-                                                        ("f16", False, False, False), ("bf16", True, False, False)])
+                                                        ("f16", False, False, False), ("bf16", True, False, False),
+                                                        ("f16", False, True, False)])
 def test_decode_attends_over_surviving_positions_only(dtype, paged, kv8, many_splits):
     rng = np.random.default_rng(9)
     if many_splits:   # ragged batch, work-queue launch shape
@@ -49,12 +50,13 @@ def test_decode_attends_over_surviving_positions_only(dtype, paged, kv8, many_sp
     oc = H.oracle_cache(w)
     # windows: nothing evicted, sinks of 0 / 32 / 64 positions, windows that start right at the end
     sink = np.array([(0, 32, 64, 0)[b % 4] for b in range(B)], dtype=np.int32)
-    gr = 128 if (kv8 and not paged) else 16           # a window starts on a block (8-bit slots: row group) boundary
-    first = np.array([min(max(int(sink[b]), (int(lens[b]) * (b % 5) // 5) // gr * gr), int(lens[b]) // gr * gr)
+    first = np.array([min(max(int(sink[b]), (int(lens[b]) * (b % 5) // 5) // 16 * 16), int(lens[b]) // 16 * 16)
                       for b in range(B)], dtype=np.int32)
     sink = np.minimum(sink, first // 32 * 32).astype(np.int32)
+    if kv8 and not paged:                            # a contiguous 8-bit slot: the gap is whole groups of 128 rows
+        first = (sink + (first - sink) // 128 * 128).astype(np.int32)
     first[3 % B] = sink[3 % B]                       # one sequence with nothing evicted
-    assert (sink % 32 == 0).all() and (first % gr == 0).all() and (sink <= first).all() and (first <= lens).all()
+    assert (sink % 32 == 0).all() and ((first - sink) % 16 == 0).all() and (sink <= first).all() and (first <= lens).all()
     if paged:                                        # dropped blocks: their table entries are poison
         table = w.block_table.copy()
         for b in range(B):
@@ -113,6 +115,31 @@ def test_impossible_windows_are_contained():
     s_ok, f_ok = sink.copy(), first.copy()
     f_ok[1:] = s_ok[1:] = 0
     want = _oracle_decode(oc, w, 1, gen.to_f64(q), lens, s_ok, f_ok)
+    assert np.abs(got[0] - want[0]).max() <= H.TOL["bf16"]
+    cache.free()
+
+
+def test_window_off_the_row_groups_of_an_8bit_slot_is_contained():
+    """A contiguous 8-bit slot keeps the rows of a kv head together in groups of 128 rows: a window whose
+    gap is not whole groups would put a 32-key tile across two groups, so it is refused like any other
+    impossible window (fault word, zero output), while a gap of whole groups is served."""
+    lens = np.array([700, 700], dtype=np.int32)
+    w = _small("bf16", 8, 2, 128, 2, lens, [0, 0], False, seed=47)
+    w.kv8 = True
+    cache, _ = H.alloc_cache(w)
+    H.fill_by_append(cache, w)
+    oc = H.oracle_cache(w)
+    sink = np.array([64, 64], dtype=np.int32)
+    first = np.array([64 + 256, 64 + 160], dtype=np.int32)     # gaps of 256 (two groups) and 160 (no multiple of 128)
+    skv.skv_cache_set_eviction(cache, torch.from_numpy(sink).cuda(), torch.from_numpy(first).cuda())
+    q = w.q_decode(1, "cuda")
+    out = torch.full_like(q, 7.0)
+    ws = H.workspace_for(cache, 700)
+    skv.skv_attn_decode(cache, 1, q, out, torch.from_numpy(lens).cuda(), 700, w.scale, ws)
+    assert skv.skv_cache_device_faults(cache) & 4
+    got = gen.to_f64(out)
+    assert not got[1].any()
+    want = _oracle_decode(oc, w, 1, gen.to_f64(q), lens, sink, np.array([320, 64]))
     assert np.abs(got[0] - want[0]).max() <= H.TOL["bf16"]
     cache.free()
 
