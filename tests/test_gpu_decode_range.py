@@ -17,11 +17,13 @@ pytestmark = pytest.mark.gpu
 RANGES = [(0, 5), (1, 3), (4, 1), (2, 2), (0, 1)]
 
 
-@pytest.mark.parametrize("dtype,hq,hkv,d,paged", [("bf16", 8, 2, 128, False), ("f16", 4, 4, 128, True),
-                                                  ("f32", 4, 2, 64, False), ("bf16", 16, 1, 64, True)])
-def test_range_decode_matches_oracle(dtype, hq, hkv, d, paged):
+@pytest.mark.parametrize("dtype,hq,hkv,d,paged,kv8", [("bf16", 8, 2, 128, False, False), ("f16", 4, 4, 128, True, False),
+                                                      ("f32", 4, 2, 64, False, False), ("bf16", 16, 1, 64, True, False),
+                                                      ("bf16", 8, 2, 128, False, True), ("f16", 8, 4, 64, True, True)])
+def test_range_decode_matches_oracle(dtype, hq, hkv, d, paged, kv8):
     lens = [700, 33, 1, 2049, 256]
     w = _small(dtype, hq, hkv, d, len(lens), lens, [0, 0, 2, 2], paged, seed=31)
+    w.kv8 = kv8      # 8-bit slots: a contiguous slot holds whole row groups per sequence, the range view moves by those
     cache, _ = H.alloc_cache(w)
     H.fill_by_append(cache, w)
     oc = H.oracle_cache(w)
