@@ -173,9 +173,9 @@ def test_full_size_pass_layer_on_a_sampled_slice():
         assert not dk[b, n:].any() and not dv[b, n:].any()
 
 
-def test_forward_log_sum_exp_from_the_eight_wave_shape(monkeypatch):
-    """The pipelined kernel's other shape (8 waves of 32 rows) writes the same log-sum-exp."""
-    monkeypatch.setenv("SKV_PREFILL_WAVES", "8")
+def test_forward_log_sum_exp_of_a_ragged_batch_from_the_pipelined_kernel():
+    """Lengths off every tile boundary (333 and 97 rows): the pipelined kernel writes the log-sum-exp of the
+    rows that exist and nothing behind them."""
     B, S, Hq, Hkv, D = 2, 333, 4, 2, 128
     qs, ks, vs, _ = _inputs("bf16", B, S, Hq, Hkv, D, seed=8)
     lens = [333, 97]
