@@ -95,7 +95,7 @@ typedef struct {
     int32_t max_ctx;     /* capacity in positions per sequence (contiguous: pool extent;
                             paged: max_blocks_per_seq * block_size is the effective bound) */
     int32_t dtype;       /* skv_dtype_t */
-    int32_t block_size;  /* 0 = contiguous, else tokens per physical block (power of two, 8..256) */
+    int32_t block_size;  /* 0 = contiguous, else tokens per physical block (power of two, 8..256; 8-bit slots: 16..256) */
     int32_t n_blocks;    /* paged: physical blocks per slot pool; ignored when contiguous */
     const int32_t *route; /* host, n_layers entries, copied by skv_cache_alloc */
     void *k_pool;        /* device, optional caller-owned storage for K; NULL = library allocates */
@@ -123,7 +123,9 @@ skv_status_t skv_route_validate(const int32_t *route, int32_t n_layers, int32_t 
 /* Total bytes of the K and V pools together:
  * 2 * n_slots * batch * max_ctx * n_kv_heads * head_dim * sizeof(dtype)   (contiguous)
  * 2 * n_slots * n_blocks * block_size * n_kv_heads * head_dim * sizeof(dtype)   (paged)
- * i.e. the footprint M = L x (T + t) x S of Sec. 3.1.1 with L replaced by |S|. */
+ * i.e. the footprint M = L x (T + t) x S of Sec. 3.1.1 with L replaced by |S|.  8-bit slots: one byte
+ * per element plus the pool of exponent bytes, and a contiguous slot holds max_ctx rounded up to a
+ * multiple of 128 rows per sequence (see "8-bit slots" above). */
 skv_status_t skv_cache_bytes(const skv_cache_desc_t *desc, size_t *total_bytes);
 
 /* The parts of skv_cache_bytes: bytes of the K pool (the V pool has the same size) and of the pool
