@@ -1,8 +1,12 @@
 // Pre-fill-phase routed attention (paper Sec. 3.1.1 "Pre-fill", Eq. (3.1)) for 16-bit contiguous
 // caches with head_dim 128: the software-pipelined kernel.
 //
-// Work group = 4 waves = 256 consecutive query rows of one (sequence, query head); wave w owns
-// rows 64w..64w+63 as two blocks of 32, so every K / V^T operand read from LDS feeds two MFMAs.
+// Work group = 4 waves, each owning 64 query rows of one query head as two blocks of 32, so that
+// every K / V^T operand read from LDS feeds two MFMAs.  The waves share the K/V tiles of one kv head:
+// with a GQA group of 4 (or a multiple) they are the SAME 64 rows of four query heads of the group --
+// all four reach their diagonal in the same tile, where 256 consecutive rows of one head reach it one
+// tile after the other and leave SIMDs idle for 1.5 tiles per work group (2.3 % of a launch at 8192
+// positions); a group of 2 gives two heads x 128 rows, a single head 256 consecutive rows.
 // One wave per SIMD holds ~400 registers: O^T and Q^T in AGPRs, two S^T and two P^T buffers in
 // VGPRs.  K/V tiles of 64 keys travel from HBM straight into a ring of four LDS stages
 // (buffer_load ... lds), requested almost two tiles before their first use.  The instruction
@@ -23,7 +27,6 @@ namespace {
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-constexpr int kRowsPerGroup = 256;
 constexpr int kD = 128;
 
 __device__ __forceinline__ uint32_t uni(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
@@ -40,48 +43,53 @@ __device__ __forceinline__ u32x4 make_srd(const void *base, uint32_t bytes) {
 }
 
 template <bool BF16, int NQ, bool PAGED>
-__global__ __launch_bounds__(512 / NQ, 1) void prefill_pipe_kernel(AttnArgs a, int G, int n_qt, int xcd_map) {
+__global__ __launch_bounds__(512 / NQ, 1) void prefill_pipe_kernel(AttnArgs a, int G, int gh, int n_qt, int xcd_map) {
     static_assert(SKV_PIPE2_THREADS == 256 && SKV_PIPE2P_THREADS == 256 && SKV_PIPE2P_LDS_BYTES == SKV_PIPE2_LDS_BYTES);
     __shared__ __attribute__((aligned(16))) char lds[SKV_PIPE2_LDS_BYTES];
     constexpr int kRowsPerWave = 32 * NQ;
 
     const int hkv = a.cache.n_kv_heads;
-    // block -> (query tile, head, sequence): heavy (late) query tiles first; with xcd_map the G
+    // A work group takes gh heads of the group (gh = 4, 2 or 1 divides G) x 256 / gh rows: wave w owns
+    // head w % gh of them and the 64 rows of row block w / gh.
+    // block -> (query tile, heads, sequence): heavy (late) query tiles first; with xcd_map the
     // heads of a kv head and neighbouring query tiles land on one XCD and share its L2
-    int qt, head, b;
+    const int wave = (int)uni(threadIdx.x >> 6);
+    const int rows_per_group = 256 / gh;
+    const int hg = G / gh; // sets of gh heads per kv head
+    int qt, hset, kvh, b;
     {
         const int id = blockIdx.x;
         int pair, rem;
         if (xcd_map) {
-            const int per_pair = G * n_qt;
+            const int per_pair = hg * n_qt;
             const int k = id >> 3;
             pair = (id & 7) + 8 * (k / per_pair);
             rem = k % per_pair;
         } else {
-            pair = id / (G * n_qt);
-            rem = id % (G * n_qt);
+            pair = id / (hg * n_qt);
+            rem = id % (hg * n_qt);
         }
-        qt = n_qt - 1 - rem / G;
-        head = (pair % hkv) * G + rem % G;
+        qt = n_qt - 1 - rem / hg;
+        hset = rem % hg;
+        kvh = pair % hkv;
         b = pair / hkv;
     }
-    const int kvh = head / G;
+    const int head = kvh * G + hset * gh + wave % gh;
 
     const int nq = a.q_lens[b];
     const int n = a.kv_lens[b];
     if (nq < 0 || nq > a.max_q || n < 1 || n > a.max_kv_len || nq > n) {
-        if (threadIdx.x == 0 && qt == 0 && head == 0) atomicOr(a.cache.faults, (uint32_t)SKV_FAULT_KV_LEN);
+        if (threadIdx.x == 0 && qt == 0 && kvh == 0 && hset == 0) atomicOr(a.cache.faults, (uint32_t)SKV_FAULT_KV_LEN);
         return; // nothing is written for a sequence with impossible lengths
     }
-    const int q_begin = qt * kRowsPerGroup;
+    const int q_begin = qt * rows_per_group;
     if (q_begin >= nq) return;
     const int offset = n - nq;
-    const int q_last = min(q_begin + kRowsPerGroup, nq) - 1;
+    const int q_last = min(q_begin + rows_per_group, nq) - 1;
     const int n_keys = offset + q_last + 1; // keys the work group needs
     const int n_tiles = (n_keys + 63) >> 6;
 
-    const int wave = (int)uni(threadIdx.x >> 6);
-    const int r0 = q_begin + kRowsPerWave * wave;
+    const int r0 = q_begin + kRowsPerWave * (wave / gh);
     const int rows_valid = nq - r0;
     const bool active = rows_valid > 0;
     const int p0 = offset + r0;
@@ -164,14 +172,16 @@ bool prefill_pipe_supported(const AttnArgs &a, int dtype, int head_dim) {
 }
 
 hipError_t launch_prefill_pipe(const AttnArgs &a, int dtype, int group, hipStream_t stream) {
-    const int n_qt = (a.max_q + kRowsPerGroup - 1) / kRowsPerGroup;
+    const int gh = group % 4 == 0 ? 4 : group % 2 == 0 ? 2 : 1; // heads of the group that share a work group
+    const int rows_per_group = 256 / gh;
+    const int n_qt = (a.max_q + rows_per_group - 1) / rows_per_group;
     const int pairs = a.batch * a.cache.n_kv_heads;
-    const int64_t blocks = (int64_t)pairs * group * n_qt;
+    const int64_t blocks = (int64_t)pairs * (group / gh) * n_qt;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     const int xcd_map = (pairs % 8) == 0;
     const dim3 grid((unsigned)blocks);
     const bool paged = a.cache.block_table != nullptr;
-#define SKV_PIPE_LAUNCH(BF, NQ_, PG) prefill_pipe_kernel<BF, NQ_, PG><<<grid, 512 / NQ_, 0, stream>>>(a, group, n_qt, xcd_map)
+#define SKV_PIPE_LAUNCH(BF, NQ_, PG) prefill_pipe_kernel<BF, NQ_, PG><<<grid, 512 / NQ_, 0, stream>>>(a, group, gh, n_qt, xcd_map)
     if (dtype == SKV_BF16) { if (paged) SKV_PIPE_LAUNCH(true, 2, true); else SKV_PIPE_LAUNCH(true, 2, false); }
     else { if (paged) SKV_PIPE_LAUNCH(false, 2, true); else SKV_PIPE_LAUNCH(false, 2, false); }
 #undef SKV_PIPE_LAUNCH
