@@ -43,7 +43,7 @@ __device__ __forceinline__ u32x4 make_srd(const void *base, uint32_t bytes) {
 }
 
 template <bool BF16, int NQ, bool PAGED>
-__global__ __launch_bounds__(512 / NQ, 1) void prefill_pipe_kernel(AttnArgs a, int G, int gh, int n_qt, int xcd_map) {
+__global__ __launch_bounds__(512 / NQ, 1) void prefill_pipe_kernel(AttnArgs a, int G, int gh, int n_qt, int n_pairs, int xcd_map) {
     static_assert(SKV_PIPE2_THREADS == 256 && SKV_PIPE2P_THREADS == 256 && SKV_PIPE2P_LDS_BYTES == SKV_PIPE2_LDS_BYTES);
     __shared__ __attribute__((aligned(16))) char lds[SKV_PIPE2_LDS_BYTES];
     constexpr int kRowsPerWave = 32 * NQ;
@@ -51,25 +51,31 @@ __global__ __launch_bounds__(512 / NQ, 1) void prefill_pipe_kernel(AttnArgs a, i
     const int hkv = a.cache.n_kv_heads;
     // A work group takes gh heads of the group (gh = 4, 2 or 1 divides G) x 256 / gh rows: wave w owns
     // head w % gh of them and the 64 rows of row block w / gh.
-    // block -> (query tile, heads, sequence): heavy (late) query tiles first; with xcd_map the
-    // heads of a kv head and neighbouring query tiles land on one XCD and share its L2
+    // A work group walks PAIRS of query tiles one after the other, tile u from the end and tile u from
+    // the start: under the causal mask their key tiles add up to the same number for every u, so all
+    // work groups of a launch are equally long, and starting a work group costs a compute unit about
+    // 1.6 us.  n_pairs pairs per work group: u = u0, u0 + n_half / n_pairs, ...
+    // block -> (pair of query tiles, heads, sequence); with xcd_map the heads of a kv head and
+    // neighbouring query tiles land on one XCD and share its L2
     const int wave = (int)uni(threadIdx.x >> 6);
     const int rows_per_group = 256 / gh;
     const int hg = G / gh; // sets of gh heads per kv head
-    int qt, hset, kvh, b;
+    const int n_half = (n_qt + 1) / 2;
+    const int n_u0 = n_half / n_pairs; // n_pairs divides n_half (launcher)
+    int u0, hset, kvh, b;
     {
         const int id = blockIdx.x;
         int pair, rem;
         if (xcd_map) {
-            const int per_pair = hg * n_qt;
+            const int per_pair = hg * n_u0;
             const int k = id >> 3;
             pair = (id & 7) + 8 * (k / per_pair);
             rem = k % per_pair;
         } else {
-            pair = id / (hg * n_qt);
-            rem = id % (hg * n_qt);
+            pair = id / (hg * n_u0);
+            rem = id % (hg * n_u0);
         }
-        qt = n_qt - 1 - rem / hg;
+        u0 = rem / hg;
         hset = rem % hg;
         kvh = pair % hkv;
         b = pair / hkv;
@@ -79,11 +85,18 @@ __global__ __launch_bounds__(512 / NQ, 1) void prefill_pipe_kernel(AttnArgs a, i
     const int nq = a.q_lens[b];
     const int n = a.kv_lens[b];
     if (nq < 0 || nq > a.max_q || n < 1 || n > a.max_kv_len || nq > n) {
-        if (threadIdx.x == 0 && qt == 0 && kvh == 0 && hset == 0) atomicOr(a.cache.faults, (uint32_t)SKV_FAULT_KV_LEN);
+        if (threadIdx.x == 0 && u0 == 0 && kvh == 0 && hset == 0) atomicOr(a.cache.faults, (uint32_t)SKV_FAULT_KV_LEN);
         return; // nothing is written for a sequence with impossible lengths
     }
+    bool first = true;
+    for (int pass = 0; pass < 2 * n_pairs; ++pass) {
+    const int u = u0 + (pass >> 1) * n_u0;
+    const int qt = (pass & 1) == 0 ? n_qt - 1 - u : u;
+    if ((pass & 1) == 1 && u >= n_qt - 1 - u) continue; // an odd count: the middle tile was the pass before
     const int q_begin = qt * rows_per_group;
-    if (q_begin >= nq) return;
+    if (q_begin >= nq) continue;
+    if (!first) __syncthreads(); // every wave has left the last tile's LDS stages (its memory operations are complete)
+    first = false;
     const int offset = n - nq;
     const int q_last = min(q_begin + rows_per_group, nq) - 1;
     const int n_keys = offset + q_last + 1; // keys the work group needs
@@ -150,6 +163,7 @@ __global__ __launch_bounds__(512 / NQ, 1) void prefill_pipe_kernel(AttnArgs a, i
 #pragma clang diagnostic pop
 #undef SKV_PIPE_RUN
 #undef SKV_PIPE_OPERANDS
+    } // pass
 }
 
 } // namespace
@@ -176,12 +190,20 @@ hipError_t launch_prefill_pipe(const AttnArgs &a, int dtype, int group, hipStrea
     const int rows_per_group = 256 / gh;
     const int n_qt = (a.max_q + rows_per_group - 1) / rows_per_group;
     const int pairs = a.batch * a.cache.n_kv_heads;
-    const int64_t blocks = (int64_t)pairs * (group / gh) * n_qt;
+    // pairs of query tiles per work group: as many as leave four work groups per compute unit
+    const int n_half = (n_qt + 1) / 2;
+    int n_pairs = 1;
+#ifdef SKV_PIPE_PAIRS
+    n_pairs = SKV_PIPE_PAIRS;
+#else
+    while (n_half % (2 * n_pairs) == 0 && (int64_t)pairs * (group / gh) * (n_half / (2 * n_pairs)) >= 4 * 256) n_pairs *= 2;
+#endif
+    const int64_t blocks = (int64_t)pairs * (group / gh) * (n_half / n_pairs);
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     const int xcd_map = (pairs % 8) == 0;
     const dim3 grid((unsigned)blocks);
     const bool paged = a.cache.block_table != nullptr;
-#define SKV_PIPE_LAUNCH(BF, NQ_, PG) prefill_pipe_kernel<BF, NQ_, PG><<<grid, 512 / NQ_, 0, stream>>>(a, group, gh, n_qt, xcd_map)
+#define SKV_PIPE_LAUNCH(BF, NQ_, PG) prefill_pipe_kernel<BF, NQ_, PG><<<grid, 512 / NQ_, 0, stream>>>(a, group, gh, n_qt, n_pairs, xcd_map)
     if (dtype == SKV_BF16) { if (paged) SKV_PIPE_LAUNCH(true, 2, true); else SKV_PIPE_LAUNCH(true, 2, false); }
     else { if (paged) SKV_PIPE_LAUNCH(false, 2, true); else SKV_PIPE_LAUNCH(false, 2, false); }
 #undef SKV_PIPE_LAUNCH
