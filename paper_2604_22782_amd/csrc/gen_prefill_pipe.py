@@ -943,6 +943,12 @@ def generator(nq: int = 2, paged: bool = False):
         half_step(A, 0, qk=None, pv=(VA_CUR, 1, PB), sm=None, nxt=None, extra=[], tagid="dr")
         for _ in range(3):  # the accumulators are read by the vector ALU next
             e("s_nop 7")
+        # Every K/V request of this wave has landed before its first output store is issued: loads and
+        # stores may retire out of order, so afterwards only "everything" could be waited for, and the
+        # stores' trip to memory would be spent idle.  With the loads out of the way a wave whose work
+        # group has no tile left leaves the statement with its stores in flight (nothing reads them,
+        # and waits of a later pass only become longer by stores that are older than its loads).
+        e("s_waitcnt vmcnt(0)")
 
         A.c("row sums of both lane halves, normalise, store")
         for q in range(NQ):
@@ -998,6 +1004,10 @@ def generator(nq: int = 2, paged: bool = False):
                     e(f"global_store_dwordx2 {vr(O_OFF[q])}, {vr(t[4], 2)}, %[op] offset:{64 * db + 16 * g4}")
             e(f"s_mov_b64 exec, {sr(S_EXEC, 2)}")
 
+        e("s_waitcnt lgkmcnt(0)")
+        e(f"s_cmp_ge_i32 {sr(S_T)}, %[nt]")
+        e("s_cbranch_scc1 L_DONE_%=")       # the usual case: the waves of a work group end in the same tile
+
         A.c("remaining tiles of the work group: staging and barriers only")
         e("L_STAGE_%=:")
         e("s_waitcnt vmcnt(0) lgkmcnt(0)")  # also the output stores: loads and stores may retire out of order
@@ -1021,6 +1031,7 @@ def generator(nq: int = 2, paged: bool = False):
             bad_block_paths(A, ["last", "p0", "p1", "p2", "g", "m", "s"] + (["f"] if fast else []))
         e("L_END_%=:")
         e("s_waitcnt vmcnt(0) lgkmcnt(0)")
+        e("L_DONE_%=:")
         return A.lines
 
 

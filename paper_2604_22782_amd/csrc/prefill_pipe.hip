@@ -95,7 +95,7 @@ __global__ __launch_bounds__(512 / NQ, 1) void prefill_pipe_kernel(AttnArgs a, i
     if ((pass & 1) == 1 && u >= n_qt - 1 - u) continue; // an odd count: the middle tile was the pass before
     const int q_begin = qt * rows_per_group;
     if (q_begin >= nq) continue;
-    if (!first) __syncthreads(); // every wave has left the last tile's LDS stages (its memory operations are complete)
+    if (!first) __syncthreads(); // every wave has left the last tile's LDS stages (its K/V requests have landed; output stores may still be on their way)
     first = false;
     const int offset = n - nq;
     const int q_last = min(q_begin + rows_per_group, nq) - 1;
