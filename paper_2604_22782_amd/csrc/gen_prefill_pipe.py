@@ -71,7 +71,12 @@ def generator(nq: int = 2, paged: bool = False):
     T_BYTES = 16 * CHUNK      # one tensor (K or V) of a 64-key tile
     STAGE = 2 * T_BYTES       # K then V
     N_STAGE = 4
-    LDS_BYTES = N_STAGE * STAGE
+    LDS_RING = N_STAGE * STAGE
+    # Output rows leave through a private region per wave behind the ring (NQ = 2 only): 16 rows of 256 bytes,
+    # 272 bytes apart, so that the 64-bit writes of 16 rows x 2 lane halves and the 128-bit reads of 4 rows x
+    # 16 pieces each touch every bank once.
+    OUT_ROW = 272
+    OUT_REGION = 16 * OUT_ROW
 
     # ---- shape ------------------------------------------------------------------------------------------
     # NQ = row blocks of 32 per wave.  NQ = 2: 4 waves per work group, one per SIMD, ~400 registers per
@@ -87,6 +92,7 @@ def generator(nq: int = 2, paged: bool = False):
     WAVES = 8 // NQ                       # waves per work group (256 query rows)
     THREADS = 64 * WAVES
     CPW = 16 // WAVES                     # 1 KiB chunks per wave, tile and tensor
+    LDS_BYTES = LDS_RING + (WAVES * OUT_REGION if NQ == 2 else 0)
     NEL = 16 * NQ                         # scores per lane and half tile
 
     # ---- register names ---------------------------------------------------------------------------
@@ -653,6 +659,80 @@ def generator(nq: int = 2, paged: bool = False):
         A.e(f"s_branch {resume}")
 
 
+    def store_rows_through_lds(A: Asm):
+        """O^T / l, rounded, to memory.  A lane holds, of ITS row, 4 consecutive features per (d block, group
+        of 8): stored as they lie, an instruction would write 16-byte pieces of 32 rows, and the memory
+        pipeline takes such an instruction piece by piece (4-6 us per pass for the 32 instructions of a
+        wave, with the four waves of the work group queueing at it).  So 16 rows at a time go through the
+        wave's private LDS region and leave as whole rows: a lane reads 16 bytes, 16 lanes a row, one
+        instruction writes 4 rows of 256 contiguous bytes.  Nothing of the ring is touched, so the other
+        waves may still be reading it.  Scratch: S^T and P^T registers (dead by now), TMP[8:15]."""
+        e, dt = A.e, A.dt
+        W_ADDR, R_ADDR, G_OFF, L16, T_ROW, T_ADR = TMP[8], TMP[9], TMP[10], TMP[11], TMP[12], TMP[13]
+        OB = (SA, SB)            # rounded output of row block q: 2 registers per (d block, group of 8)
+        RB = PA                  # 16 registers: the four 128-bit reads of a round
+        e(f"s_mov_b64 {sr(S_EXEC, 2)}, exec")
+        e(f"s_mul_i32 {sr(S_TMP)}, %[wv], {OUT_REGION}")
+        e(f"s_add_u32 {sr(S_TMP)}, {sr(S_TMP)}, %[lds]")
+        e(f"s_add_u32 {sr(S_TMP)}, {sr(S_TMP)}, {LDS_RING}")
+        # write address: row c % 16 of the region, 8 hh (+ 64 db + 16 g4 per instruction)
+        e(f"v_and_b32_e32 {vr(TMP[0])}, 15, {vr(COL)}")
+        e(f"v_mul_u32_u24_e32 {vr(TMP[0])}, {OUT_ROW}, {vr(TMP[0])}")
+        e(f"v_lshl_add_u32 {vr(TMP[0])}, {vr(HH)}, 3, {vr(TMP[0])}")
+        e(f"v_add_u32_e32 {vr(W_ADDR)}, {sr(S_TMP)}, {vr(TMP[0])}")
+        # read address: row L / 16 (+ 4 i per instruction), piece L % 16; the same split addresses memory
+        e(f"v_lshrrev_b32_e32 {vr(L16)}, 4, {vr(LANE)}")
+        e(f"v_and_b32_e32 {vr(TMP[1])}, 15, {vr(LANE)}")
+        e(f"v_mul_u32_u24_e32 {vr(TMP[0])}, {OUT_ROW}, {vr(L16)}")
+        e(f"v_lshl_add_u32 {vr(TMP[0])}, {vr(TMP[1])}, 4, {vr(TMP[0])}")
+        e(f"v_add_u32_e32 {vr(R_ADDR)}, {sr(S_TMP)}, {vr(TMP[0])}")
+        e(f"v_mul_u32_u24_e32 {vr(TMP[0])}, %[qrs], {vr(L16)}")
+        e(f"v_lshl_add_u32 {vr(G_OFF)}, {vr(TMP[1])}, 4, {vr(TMP[0])}")
+        e(f"v_cmp_gt_u32_e32 vcc, 16, {vr(COL)}")              # lanes of the first 16 rows of a row block
+        e(f"s_mov_b64 {sr(S_CMP, 2)}, vcc")
+        for q in range(NQ):
+            for db in range(4):
+                for g4 in range(4):
+                    t = TMP[0:4]
+                    base = A_O + 64 * q + 16 * db + 4 * g4
+                    o = OB[q] + 2 * (4 * db + g4)
+                    for k in range(4):
+                        e(f"v_accvgpr_read_b32 {vr(t[k])}, {ar(base + k)}")
+                    for k in range(4):
+                        e(f"v_mul_f32_e32 {vr(t[k])}, {vr(t[k])}, {vr(L_SUM[q])}")
+                    if dt == "bf16":
+                        e(f"v_cvt_pk_bf16_f32 {vr(o)}, {vr(t[0])}, {vr(t[1])}")
+                        e(f"v_cvt_pk_bf16_f32 {vr(o + 1)}, {vr(t[2])}, {vr(t[3])}")
+                    else:
+                        for k in range(4):
+                            e(f"v_cvt_f16_f32_e32 {vr(t[k])}, {vr(t[k])}")
+                        e(f"v_pack_b32_f16 {vr(o)}, {vr(t[0])}, {vr(t[1])}")
+                        e(f"v_pack_b32_f16 {vr(o + 1)}, {vr(t[2])}, {vr(t[3])}")
+            for h in range(2):
+                if h == 0:
+                    e(f"s_mov_b64 exec, {sr(S_CMP, 2)}")
+                else:
+                    e(f"s_andn2_b64 exec, {sr(S_EXEC, 2)}, {sr(S_CMP, 2)}")
+                for db in range(4):
+                    for g4 in range(4):
+                        o = OB[q] + 2 * (4 * db + g4)
+                        e(f"ds_write_b64 {vr(W_ADDR)}, {vr(o, 2)} offset:{64 * db + 16 * g4}")
+                e(f"s_mov_b64 exec, {sr(S_EXEC, 2)}")
+                e("s_waitcnt lgkmcnt(0)")
+                for i in range(4):
+                    e(f"ds_read_b128 {vr(RB + 4 * i, 4)}, {vr(R_ADDR)} offset:{4 * OUT_ROW * i}")
+                e("s_waitcnt lgkmcnt(0)")          # also: the region is free for the next round's writes
+                for i in range(4):
+                    r0 = 32 * q + 16 * h + 4 * i
+                    e(f"v_add_u32_e32 {vr(T_ROW)}, {r0}, {vr(L16)}")
+                    e(f"s_mul_i32 {sr(S_J0)}, %[qrs], {r0}")
+                    e(f"v_cmp_gt_i32_e32 vcc, %[rvs], {vr(T_ROW)}")
+                    e(f"v_add_u32_e32 {vr(T_ADR)}, {sr(S_J0)}, {vr(G_OFF)}")
+                    e("s_and_b64 exec, exec, vcc")
+                    e(f"global_store_dwordx4 {vr(T_ADR)}, {vr(RB + 4 * i, 4)}, %[op]")
+                    e(f"s_mov_b64 exec, {sr(S_EXEC, 2)}")
+
+
     def body_stage_only(A: Asm):
         rotate_addresses(A, vector=False)
         A.e(f"s_waitcnt vmcnt({2 * CPW + TBL})")
@@ -796,6 +876,41 @@ def generator(nq: int = 2, paged: bool = False):
         for q in range(NQ):
             e(f"v_mad_u32_u24 {vr(O_OFF[q])}, {vr(ROW[q])}, %[qrs], {vr(TMP[2])}")
 
+        def tile_request(x):
+            """Request of tile x (0, 1, 2) as chunks of instructions, one load each (the first with the set-up)."""
+            pre = []
+            if PAGED:
+                if x == 2:   # the id of tile 3 joins the queue before the loads of tile 2, as in the loop
+                    pre.append(f"s_add_u32 {sr(S_R0)}, {sr(S_R0W)}, 128")
+                    pre += paged_request_id(64)
+                pre += [f"v_readfirstlane_b32 {sr(S_BLK)}, {vr(TMP[9 + x])}",
+                        f"s_cmp_lt_u32 {sr(S_BLK)}, %[nblk]",
+                        f"s_cbranch_scc0 L_BADBLK_p{x}_%=", f"L_BADRET_p{x}_%=:",
+                        f"s_add_u32 {sr(S_R0)}, {sr(S_R0W)}, {64 * x}",
+                        f"s_and_b32 {sr(S_T2)}, {sr(S_R0)}, %[bsm1]",
+                        f"s_lshl_b32 {sr(S_SOFF)}, {sr(S_BLK)}, %[shift]",
+                        f"s_add_u32 {sr(S_SOFF)}, {sr(S_SOFF)}, {sr(S_T2)}",
+                        f"s_mul_i32 {sr(S_SOFF)}, {sr(S_SOFF)}, %[krb]"]
+            else:
+                pre.append(f"s_mul_i32 {sr(S_SOFF)}, %[krb], {64 * x}")
+            pre += clamped_offsets()
+            pre.append(f"s_add_u32 {sr(S_STW)}, {sr(S_WBASE)}, {x * STAGE}")
+            chunks = []
+            for i in range(CPW):
+                for which in ("k", "v"):
+                    m0w, ld = tile_load(which, i, S_STW)
+                    chunks.append(pre + [m0w, "s_nop 0", ld])
+                    pre = []
+            return chunks
+
+        A.c("tile 0 requested right behind Q: both are needed first.  Tiles 1 and 2 follow once Q has landed")
+        A.c("(a compute unit moves a burst of this size at about 45 bytes per clock: 64 KiB of Q and 96 KiB of")
+        A.c("tiles in one go keep every wave at the memory pipeline for 4 us; tiles 1, 2 are not needed before")
+        A.c("the second and third tile step)")
+        for chunk in tile_request(0):
+            for ins in chunk:
+                e(ins)
+
         A.c("state")
         for i in range(64 * NQ):
             e(f"v_accvgpr_write_b32 {ar(A_O + i)}, 0")
@@ -808,35 +923,6 @@ def generator(nq: int = 2, paged: bool = False):
             e(f"v_mov_b32_e32 {vr(NEG_MC[q])}, 0")
         e(f"s_mov_b32 {sr(S_FLAG)}, 0")
         e(f"s_mov_b32 {sr(S_T)}, 0")
-
-        A.c("tiles 0, 1, 2 requested")
-        for x in range(3):
-            if PAGED:
-                if x == 2:   # the id of tile 3 joins the queue before the loads of tile 2, as in the loop
-                    e(f"s_add_u32 {sr(S_R0)}, {sr(S_R0W)}, 128")
-                    for ins in paged_request_id(64):
-                        e(ins)
-                e(f"v_readfirstlane_b32 {sr(S_BLK)}, {vr(TMP[9 + x])}")
-                e(f"s_cmp_lt_u32 {sr(S_BLK)}, %[nblk]")
-                e(f"s_cbranch_scc0 L_BADBLK_p{x}_%=\nL_BADRET_p{x}_%=:")
-                e(f"s_add_u32 {sr(S_R0)}, {sr(S_R0W)}, {64 * x}")
-                e(f"s_and_b32 {sr(S_T2)}, {sr(S_R0)}, %[bsm1]")
-                e(f"s_lshl_b32 {sr(S_SOFF)}, {sr(S_BLK)}, %[shift]")
-                e(f"s_add_u32 {sr(S_SOFF)}, {sr(S_SOFF)}, {sr(S_T2)}")
-                e(f"s_mul_i32 {sr(S_SOFF)}, {sr(S_SOFF)}, %[krb]")
-            else:
-                e(f"s_mul_i32 {sr(S_SOFF)}, %[krb], {64 * x}")
-            for ins in clamped_offsets():
-                e(ins)
-            e(f"s_add_u32 {sr(S_STW)}, {sr(S_WBASE)}, {x * STAGE}")
-            for i in range(CPW):
-                for which in ("k", "v"):
-                    m0w, ld = tile_load(which, i, S_STW)
-                    e(m0w)
-                    e("s_nop 0")
-                    e(ld)
-        for i in range(CPW):   # the loop adds a scalar offset to these as long as whole tiles are in range
-            e(f"v_mov_b32_e32 {vr(VOFF[i])}, {vr(VBO[i])}")
         A.c("stage offsets before the first rotation: tile -1 in stage 3, tile 0 in stage 0")
         e(f"s_mov_b32 {sr(S_ST_CUR)}, {3 * STAGE}")
         e(f"s_mov_b32 {sr(S_ST_NXT)}, 0")
@@ -851,11 +937,14 @@ def generator(nq: int = 2, paged: bool = False):
         for i in range(full):
             e(f"ds_write_b128 {vr(TMP[0])}, {vr(PB, 4)} offset:{16 * THREADS * i}")
         e(f"ds_write_b128 {vr(TMP[1])}, {vr(PB, 4)} offset:{16 * THREADS * full}")
+
+        late = tile_request(1) + tile_request(2)
         if dt == "bf16":
-            A.c("Q has landed once only the tile loads are outstanding: a second copy, multiplied by scale x log2(e)")
-            A.c("and rounded to bf16 again, for the fast bodies (runs while tiles 0..2 are in flight)")
-            e(f"s_waitcnt vmcnt({6 * CPW + TBL})")
-            for base in range(0, 32 * NQ, 4):
+            A.c("Q has landed once only tile 0's loads are outstanding: a second copy, multiplied by scale x log2(e)")
+            A.c("and rounded to bf16 again, for the fast bodies; the requests of tiles 1 and 2 go out between its steps")
+            e(f"s_waitcnt vmcnt({2 * CPW})")
+            steps = list(range(0, 32 * NQ, 4))
+            for it, base in enumerate(steps):
                 for k in range(4):
                     e(f"v_accvgpr_read_b32 {vr(TMP[k])}, {ar(A_Q + base + k)}")
                 for k in range(4):
@@ -868,6 +957,16 @@ def generator(nq: int = 2, paged: bool = False):
                     e(f"v_cvt_pk_bf16_f32 {vr(TMP[k])}, {vr(TMP[4 + k])}, {vr(TMP[k])}")
                 for k in range(4):
                     e(f"v_accvgpr_write_b32 {ar(A_QS + base + k)}, {vr(TMP[k])}")
+                for chunk in late[it * len(late) // len(steps):(it + 1) * len(late) // len(steps)]:
+                    for ins in chunk:
+                        e(ins)
+        else:
+            A.c("tiles 1, 2 requested")
+            for chunk in late:
+                for ins in chunk:
+                    e(ins)
+        for i in range(CPW):   # the loop adds a scalar offset to these as long as whole tiles are in range
+            e(f"v_mov_b32_e32 {vr(VOFF[i])}, {vr(VBO[i])}")
         A.c("tile 0 has landed once at most the newest loads (tiles 1, 2) are outstanding")
         e(f"s_waitcnt vmcnt({4 * CPW + TBL}) lgkmcnt(0)")
         e("s_barrier")
@@ -980,7 +1079,9 @@ def generator(nq: int = 2, paged: bool = False):
         for q in range(NQ):
             e(f"v_rcp_f32_e32 {vr(L_SUM[q])}, {vr(L_SUM[q])}")
         e("s_nop 1")
-        for q in range(NQ):
+        if NQ == 2:
+            store_rows_through_lds(A)
+        for q in range(NQ if NQ != 2 else 0):
             e(f"v_cmp_gt_i32_e32 vcc, %[rvs], {vr(ROW[q])}")
             e(f"s_and_saveexec_b64 {sr(S_EXEC, 2)}, vcc")
             n = 0
