@@ -140,6 +140,8 @@ skv::SlotView view_of(const skv_cache *c, int slot) {
 // Key-axis chunk covered by one work item of the decode kernels.  Deterministic in
 // (batch, n_kv_heads, max_kv_len) so that the workspace size and the launch agree.
 constexpr int64_t kMaxKeysPerSplit = 4096;
+// Distance of a library-owned V pool from its K pool, modulo 1 KiB (see skv_cache_alloc).
+constexpr size_t kPoolSkew = 384;
 // The workspace of a decode call starts with the work counters of the persistent launch shape.
 constexpr size_t kCounterBytes = 256;
 
@@ -284,8 +286,16 @@ skv_status_t skv_cache_alloc(const skv_cache_desc_t *desc, skv_cache_t **out) {
         c->scale_pool = scale_bytes ? desc->scale_pool : nullptr;
     } else {
         c->owns_pools = true;
-        e = hipMalloc(&c->k_pool, each);
-        if (e == hipSuccess) e = hipMalloc(&c->v_pool, each);
+        // One allocation, the V pool kPoolSkew bytes past a multiple of 1 KiB behind the start of the K pool.
+        // The decode kernel streams the K and the V rows of the same positions at the same time; when the
+        // two pools are a multiple of 1 KiB apart (separate allocations are: both start on a 2 MiB boundary)
+        // the two streams meet in the same memory channels.  Measured on 64 sequences x 4096 positions, 8
+        // kv heads x 128, bf16: 173 us per call at distance = 0 mod 1 KiB, 161 us at 256 or 384 (171 at 128,
+        // 166 at 512, 209 at 64: rows off the 128-byte lines); 32 kv heads and paged pools gain 1-1.5 % at
+        // 384, 8-bit slots are indifferent.
+        const size_t v_off = (each + 1023) / 1024 * 1024 + kPoolSkew;
+        e = hipMalloc(&c->k_pool, v_off + each);
+        if (e == hipSuccess) c->v_pool = (char *)c->k_pool + v_off;
         if (e == hipSuccess && scale_bytes) e = hipMalloc(&c->scale_pool, scale_bytes);
         if (e == hipSuccess) e = hipMemset(c->k_pool, 0, each);
         if (e == hipSuccess) e = hipMemset(c->v_pool, 0, each);
@@ -293,8 +303,7 @@ skv_status_t skv_cache_alloc(const skv_cache_desc_t *desc, skv_cache_t **out) {
         if (e == hipSuccess && scale_bytes) e = hipMemset(c->scale_pool, 127, scale_bytes);
         if (e == hipSuccess) e = hipDeviceSynchronize();
         if (e != hipSuccess) {
-            if (c->k_pool) (void)hipFree(c->k_pool);
-            if (c->v_pool) (void)hipFree(c->v_pool);
+            if (c->k_pool) (void)hipFree(c->k_pool); // the V pool is part of this allocation
             if (c->scale_pool) (void)hipFree(c->scale_pool);
             (void)hipFree(c->faults);
             delete c;
@@ -309,10 +318,9 @@ skv_status_t skv_cache_free(skv_cache_t *c) {
     if (!c) return SKV_OK;
     skv_status_t st = SKV_OK;
     if (c->owns_pools) {
-        hipError_t e1 = hipFree(c->k_pool), e2 = hipFree(c->v_pool);
+        hipError_t e1 = hipFree(c->k_pool); // K and V pools are one allocation
         hipError_t e3 = c->scale_pool ? hipFree(c->scale_pool) : hipSuccess;
         if (e1 != hipSuccess) st = hip_fail(e1);
-        if (e2 != hipSuccess) st = hip_fail(e2);
         if (e3 != hipSuccess) st = hip_fail(e3);
     }
     hipError_t e = hipFree(c->faults);

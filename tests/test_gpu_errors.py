@@ -131,3 +131,21 @@ def test_prefill_writes_nothing_for_a_sequence_with_impossible_lengths(dtype, d,
         got = gen.to_f64(out)
         assert np.abs(got[[0, 2]] - want[[0, 2]]).max() <= H.TOL[dtype]
     cache.free()
+
+
+@pytest.mark.parametrize("kv8,paged", [(False, False), (True, False), (False, True)])
+def test_library_pools_are_one_allocation_with_the_documented_distance(kv8, paged):
+    """skv_cache_alloc places the V pool 384 bytes past a multiple of 1 KiB behind the start of the K pool
+    (the decode call streams both at once; pools a multiple of 1 KiB apart meet in the same memory channels)
+    and right behind it; appended rows still land where the documented layout says (the pool images
+    of the exhaustive tests are read through these pointers)."""
+    w = configs.Workload("placement", "bf16", 2, 8, 2, 128, 3, [0, 0], np.array([37, 5, 129], dtype=np.int32), 1.0, 0.5, seed=3)
+    w.kv8 = kv8
+    if paged:
+        table, n_blocks = configs._paged(w.kv_lens, 16, np.random.default_rng(1))
+        w.block_size, w.block_table, w.n_blocks, w.max_ctx = 16, table, n_blocks, table.shape[1] * 16
+    cache, _ = H.alloc_cache(w)
+    n_slots, kp, vp, each = skv.skv_cache_info(cache)
+    assert n_slots == 1 and kp % 256 == 0
+    assert (vp - kp) % 1024 == 384 and each <= vp - kp < each + 1024 + 384
+    cache.free()
