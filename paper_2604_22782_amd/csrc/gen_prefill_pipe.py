@@ -29,6 +29,14 @@ tile t-1, last read in the first half); one barrier per tile, placed after every
 for its own loads of tile t+1 and for its last reads of tile t-1, publishes the former and
 releases the latter.  A load is in flight for about 1.75 tiles before anybody waits for it.
 
+Boundaries of a row tile (a work group walks several, see prefill_pipe.hip).  What a wave pays there is
+time at the memory pipeline, not arithmetic, so their shape follows the pipeline: Q is requested first and
+tile 0 right behind it, tiles 1 and 2 only between the steps of the scaled copy (they are needed a tile
+step later each); the output rows do not leave as the lanes hold them (16-byte pieces of 32 rows per
+instruction) but through a private LDS region per wave behind the ring, 16 rows at a time, as whole rows
+(4 rows of 256 contiguous bytes per store instruction); and a wave whose work group has no tile left
+ends with its stores in flight.
+
 bf16 only: tiles entirely below a wave's diagonal run a FAST copy of the loop body first.  It
 multiplies K with a second copy of Q^T that carries scale x log2(e) (rounded to bf16 once more), so
 the accumulators hold the exponents of the weights, and takes weight = 2^score without a running
@@ -872,9 +880,10 @@ def generator(nq: int = 2, paged: bool = False):
             for s in range(8):
                 e(f"global_load_dwordx4 {ar(A_Q + 32 * q + 4 * s, 4)}, {vr(Q_OFF[q])}, %[qp] offset:{32 * s}")
         # output: element r of d block db is d = 32 db + 8 (r / 4) + 4 hh + (r % 4)
-        e(f"v_lshlrev_b32_e32 {vr(TMP[2])}, 3, {vr(HH)}")
-        for q in range(NQ):
-            e(f"v_mad_u32_u24 {vr(O_OFF[q])}, {vr(ROW[q])}, %[qrs], {vr(TMP[2])}")
+        if NQ != 2:     # NQ = 2 stores whole rows through LDS (store_rows_through_lds) and needs no lane offsets
+            e(f"v_lshlrev_b32_e32 {vr(TMP[2])}, 3, {vr(HH)}")
+            for q in range(NQ):
+                e(f"v_mad_u32_u24 {vr(O_OFF[q])}, {vr(ROW[q])}, %[qrs], {vr(TMP[2])}")
 
         def tile_request(x):
             """Request of tile x (0, 1, 2) as chunks of instructions, one load each (the first with the set-up)."""
