@@ -142,17 +142,12 @@ def run_decode(args, torch, skv, H, w, steps, warmup, headline=False):
     new_k = {l: _newest_rows(w, "k", l, ctx) for l in w.owner_layers}
     new_v = {l: _newest_rows(w, "v", l, ctx) for l in w.owner_layers}
     outs = [torch.empty_like(qs[0]) for _ in range(w.n_layers)]
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(w.n_layers)]
 
-    def step(timed_events=False):
+    def step():
         for l in range(w.n_layers):
             if l in new_k:
                 skv.skv_kv_append(cache, l, new_k[l], new_v[l], d_start, ones, 1)
-            if timed_events:
-                ev[l][0].record()
             skv.skv_attn_decode(cache, l, qs[l], outs[l], d_lens, ctx, w.scale, ws)
-            if timed_events:
-                ev[l][1].record()
 
     # Part of the set-up, like the fill: the first steps over a freshly written cache run up to 80 % slower
     # (5.2, 3.4, 3.1, 3.0, 2.9, 2.9 ... ms on the 8-bit headline workload) while memory clocks and address
@@ -168,13 +163,19 @@ def run_decode(args, torch, skv, H, w, steps, warmup, headline=False):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     kernel_name = skv.skv_last_kernel_name()
-    # dominant kernel: events around each layer's decode call (kernel + its small merge launch)
-    per_call = []
-    for _ in range(max(3, min(steps, 10))):
-        step(timed_events=True)
-        torch.cuda.synchronize()
-        per_call += [ev[l][0].elapsed_time(ev[l][1]) for l in range(w.n_layers)]
-    call_ms = float(np.mean(per_call))
+    # Dominant kernel: two HIP events on the launch stream around a region of back-to-back decode calls of
+    # all layers (each call = the kernel, plus the clearing and merge launches where the key axis is
+    # split), without the appends.  Events around every single call would add their own 3-5 us to a call
+    # of 90-160 us (the record is a packet of its own between two launches).
+    reps = max(3, min(steps, 10))
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        for l in range(w.n_layers):
+            skv.skv_attn_decode(cache, l, qs[l], outs[l], d_lens, ctx, w.scale, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    call_ms = e0.elapsed_time(e1) / (reps * w.n_layers)
     assert skv.skv_cache_device_faults(cache) == 0
     layer_bytes = w.decode_bytes_per_layer()
     # the new rows are read in the activation dtype and written in the slot's element type
