@@ -990,7 +990,11 @@ def generator(nq: int = 2, paged: bool = False):
         n_pro = len(A.lines)
         fast = dt == "bf16"
         if fast:
-            A.c("tiles entirely below the wave's diagonal, bf16: weights without a running maximum")
+            A.c("tiles entirely below the wave's diagonal, bf16: weights without a running maximum.  Not when the")
+            A.c("log-sum-exp is asked for (the training forward): it is the scores themselves, and the twice-rounded Q")
+            A.c("moves it by up to 4e-3; those calls take the general stream for every tile")
+            e("s_cmp_lg_u64 %[lsep], 0")
+            e("s_cbranch_scc1 L_FAST_END_%=")
             e("L_FAST_%=:")
             e(f"s_cmp_ge_i32 {sr(S_T)}, %[tms]")
             e("s_cbranch_scc1 L_FAST_END_%=")
@@ -1004,9 +1008,10 @@ def generator(nq: int = 2, paged: bool = False):
             for _ in range(2):
                 e("s_nop 7")
             recompute_scores(A, KA_NXT, 0, SA)
-            A.c("rows that went through the fast stream have weight relative to the reference point 0")
+            A.c("rows that went through the fast stream have weight relative to the reference point 0; a wave that")
+            A.c("has not run a fast tile goes on in the general loop (which ends at once unless the fast one was skipped)")
             e(f"s_cmp_eq_u32 {sr(S_T)}, 0")
-            e("s_cbranch_scc1 L_FULL_END_%=")
+            e("s_cbranch_scc1 L_FULL_%=")
             for q in range(NQ):
                 e(f"v_mov_b32_e32 {vr(M_RUN[q])}, 0")
             e("s_branch L_FULL_END_%=")

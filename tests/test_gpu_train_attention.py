@@ -186,3 +186,23 @@ def test_forward_log_sum_exp_of_a_ragged_batch_from_the_pipelined_kernel():
         assert np.abs(gen.to_f64(out)[b, :n] - want_o[b, :n]).max() <= H.TOL["bf16"]
         assert np.abs(lse.cpu().double().numpy()[b, :, :n] - want_l[b, :, :n]).max() <= 2e-3
         assert (lse.cpu().numpy()[b, :, n:] == 7.0).all()
+
+
+def test_log_sum_exp_in_bf16_does_not_go_through_the_twice_rounded_queries():
+    """Unit-variance inputs at scale 1.125 / sqrt(d), 15 query heads on 3 kv heads, ragged: a shape on which the
+    bf16 stream that multiplies K with a scaled, re-rounded copy of Q missed the log-sum-exp by 3.9e-3 at one
+    (head, row).  Calls that ask for the log-sum-exp take the stream that scales in fp32 for every tile."""
+    B, S, Hq, Hkv, D = 3, 255, 15, 3, 128
+    lens = [105, 255, 100]
+    g = torch.Generator().manual_seed(6)
+    q, k, v = (torch.randn(B, S, h, D, generator=g).to(torch.bfloat16) for h in (Hq, Hkv, Hkv))
+    scale = 1.125 / np.sqrt(D)
+    out, lse = _run_fwd(q, k, v, torch.tensor(lens, dtype=torch.int32, device="cuda"), scale)
+    assert skv.skv_last_kernel_name() == "prefill_pipe_kernel"
+    want_o, want_l = T.attn_fwd(gen.to_f64(q), gen.to_f64(k), gen.to_f64(v), scale, lens)
+    worst = 0.0
+    for b, n in enumerate(lens):
+        assert np.abs(gen.to_f64(out)[b, :n] - want_o[b, :n]).max() <= H.TOL["bf16"]
+        worst = max(worst, float(np.abs(lse.cpu().double().numpy()[b, :, :n] - want_l[b, :, :n]).max()))
+    print(f"worst log-sum-exp error {worst:.3e}", flush=True)
+    assert worst <= 1e-4
