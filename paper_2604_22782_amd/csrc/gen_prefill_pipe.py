@@ -42,7 +42,7 @@ multiplies K with a second copy of Q^T that carries scale x log2(e) (rounded to 
 the accumulators hold the exponents of the weights, and takes weight = 2^score without a running
 maximum (bf16 weights have the exponent range of fp32): per score one v_exp, one v_add and half a
 v_cvt_pk instead of v_max3 / v_fma / v_exp / v_add / v_cvt_pk.  After every half tile each lane's
-sum of the half tile is checked against [2^-40, 2^14]; outside it the wave leaves, out of line, for
+sum of the half tile is checked against [2^-40, 2^9]; outside it the wave leaves, out of line, for
 the general stream, which forms the scores again from the caller's Q and scales them in fp32 (so
 nothing a result depends on was computed from the twice-rounded copy outside the checked range).
 
@@ -143,6 +143,7 @@ def generator(nq: int = 2, paged: bool = False):
     assert LAST_V < 256 and PD < RING and TMP[4] % 2 == 0 and TMP[12] % 2 == 0
 
     A_O, A_Q = 0, 64 * NQ
+    FAST_SPAN = (9 + 40) << 23      # bit pattern of 2^9 minus that of 2^-40: the range of lane sums the fast stream keeps
     A_QS = 96 * NQ            # bf16: a second copy of Q^T, multiplied by scale x log2(e) (operand of the fast stream)
     # softmax software pipeline: element i gets its fma at step i, its exponential EXP_LAG steps later,
     # and is first read (row sum, 16-bit packing) USE_LAG steps later
@@ -222,8 +223,9 @@ def generator(nq: int = 2, paged: bool = False):
         the copy of Q that was multiplied by scale x log2(e) and rounded to bf16 again, so the
         accumulators hold the exponents; bf16 weights have the exponent range of fp32, so no
         reference point is needed for moderate scores.  half_step() checks after every half tile
-        that each lane's sum of the half tile lies in [2^-40, 2^14] (scores between about -40 and
-        +10 in log2 units, where the second rounding of Q moves a score by a few thousandths) and
+        that each lane's sum of the half tile lies in [2^-40, 2^9] (scores between about -40 and
+        +8 in log2 units; the second rounding of Q moves a score by up to 2^-9 of its size, which is why
+        the upper end is where it is and not at the 2^14 that overflow alone would allow) and
         otherwise leaves for the general stream, which recomputes the scores from the caller's Q and
         scales them in fp32.  Per score: v_exp, v_add, half a v_cvt_pk -- the maximum (v_max3 per two
         scores) and the multiply-subtract (one per score) of the general stream are gone."""
@@ -459,17 +461,17 @@ def generator(nq: int = 2, paged: bool = False):
             for ins in gaps[si]:
                 A.e(ins)
         if fast:
-            # every lane's sum of the half tile inside [2^-40, 2^14]?  One unsigned compare per row block:
-            # the bit pattern of a positive float minus that of 2^-40 is at most that of 2^14 minus that of
+            # every lane's sum of the half tile inside [2^-40, 2^9]?  One unsigned compare per row block:
+            # the bit pattern of a positive float minus that of 2^-40 is at most that of 2^9 minus that of
             # 2^-40 exactly then (smaller sums wrap around, infinities and NaNs are above).  Otherwise the
             # wave leaves for the general stream (out of line, never returns); else the sums join the
             # running row sums.
             for q in range(NQ):
                 A.e(f"v_subrev_u32_e32 {vr(TMP[q])}, 0x2b800000, {vr(P_SUM[q])}")
-            A.e(f"v_cmp_lt_u32_e32 vcc, 0x1b000000, {vr(TMP[0])}")
+            A.e(f"v_cmp_lt_u32_e32 vcc, 0x{FAST_SPAN:08x}, {vr(TMP[0])}")
             for q in range(1, NQ):
                 A.e(f"s_mov_b64 {sr(S_CMP, 2)}, vcc")
-                A.e(f"v_cmp_lt_u32_e32 vcc, 0x1b000000, {vr(TMP[q])}")
+                A.e(f"v_cmp_lt_u32_e32 vcc, 0x{FAST_SPAN:08x}, {vr(TMP[q])}")
                 A.e(f"s_or_b64 vcc, vcc, {sr(S_CMP, 2)}")
             A.e(f"s_cbranch_vccnz L_FALL_{tagid}_%=")
             for q in range(NQ):
