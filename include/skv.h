@@ -174,10 +174,12 @@ skv_status_t skv_cache_set_block_table(skv_cache_t *cache, const int32_t *table_
  * survive; the positions between were dropped from EVERY slot (one dropped block frees its rows in
  * |S| slots instead of L), their rows and, for a paged cache, their block-table entries are never
  * read again and may hold anything.  sink_len, first_pos: device int32[batch], borrowed until they
- * are replaced; both NULL switches eviction off.  sink_len[b] must be a multiple of 32, first_pos[b]
- * a multiple of the block size (any value for a contiguous cache of 16-bit elements; a multiple of
- * the group size R of an 8-bit slot), 0 <= sink_len[b] <= first_pos[b] <= kv_lens[b]; other values
- * set SKV_FAULT_KV_LEN and zero the sequence's output.
+ * are replaced; both NULL switches eviction off.  sink_len[b] must be a multiple of 32 and
+ * 0 <= sink_len[b] <= first_pos[b] <= kv_lens[b]; over 8-bit slots the number of dropped positions
+ * first_pos[b] - sink_len[b] must be a multiple of the group size R of the slot (whole groups are
+ * dropped); other values set SKV_FAULT_KV_LEN and zero the sequence's output.  A paged cache that wants
+ * its dropped blocks back drops whole blocks (first_pos[b] a multiple of the block size); the kernels
+ * do not ask for it.
  * While eviction is on, skv_attn_decode / _range / _static attend over the surviving positions
  * only, and their max_kv_len bounds the number of SURVIVING positions per sequence (kv_lens[b]
  * itself is bounded by the capacity); skv_attn_prefill returns SKV_ERR_UNSUPPORTED, and so does
