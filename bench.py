@@ -1,11 +1,11 @@
 #!/usr/bin/env python3
 """Benchmark of the routed-attention hot path on one MI355X.
 
-A "step" is one decode token of the Llama-3-8B-shaped workload (BASELINE config 2): for each of
+A "step" is one decode token of the Llama-3-8B-shaped workload (the second of the five workloads in workloads/configs.py): for each of
 the 32 layers, owner layers append the new token's K/V row to their slot (skv_kv_append), then
 every layer attends over the slot it is routed to (skv_attn_decode: split-K kernel + merge).
 `value` is the algorithmic HBM traffic of the step divided by its wall time.  The causal prefill
-workload (BASELINE config 3) is measured after it and reported in the "prefill" object of the
+workload (the third workload) is measured after it and reported in the "prefill" object of the
 same JSON line, because the metric names both.  A third object, "train", times one R-CLA
 training pass (Sec. 3.2: sampled route, forward and backward of the attention of every layer) on
 the same shape; it is a widening of the path and no part of `value`.
